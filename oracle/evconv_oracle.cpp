@@ -1,0 +1,634 @@
+// CPU oracle for incremental CNN inference on event-camera inputs (Ev-Conv).
+//
+// TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the HIP library is
+// checked against; only tests, the smoke check and the benchmark's cpu_baseline leg may load
+// it.  It shares no code, header, table or helper with the HIP path and never calls it.
+//
+// Two independent halves that must agree (Eq.2 of the paper, the telescoping sum
+// y(n) = y(n-m) + sum of increments):
+//   * dense_forward(): the plain definition - a regular forward pass of the whole network on a
+//     full input tensor (textbook convolution, ReLU, sigmoid, max-pool, bilinear x2, mean).
+//     "Refresh" (Drift Errors section) is exactly this pass, storing every accumulated tensor.
+//   * step(): the incremental algorithm in the paper's order: input increment (Eq.1), then per
+//     layer the increment operator of "Implementation of Increment Layers": linear ops on the
+//     increment alone (Eq.9-10), addition with OR-ed masks (Eq.11), activation through the
+//     accumulated input x_acc (Eq.12-14), and the output sum (Eq.2).
+//
+// Arithmetic is templated: T = double (reference state) or T = float (every operation in
+// binary32, used for bit-exact checks of elementwise kernels and for the drift study).  The
+// input increment itself is always one binary32 subtraction (Eq.1 on fp32 frames).
+//
+// Readings where the paper is silent (all mirrored in the project's design notes):
+//   * mask = per-site "any channel nonzero" set; a tile bitmap/occupancy word is derived from
+//     it for a given tile size and never influences a value (a mask may only skip zeros).
+//   * zero test is `!= 0` on the stored value: -0 is inactive, denormals and NaN are active.
+//   * after an activation / conv / max-pool the active set is value-pruned (sites whose output
+//     increment is zero in every channel are dropped); the un-pruned "touched" set (the paper's
+//     Eq.13 mask y_m = x_m pushed through the operator's footprint) is kept beside it.
+//     Bare add, concat, upsample and mean-pool keep the structural set (Eq.11b: OR).
+//   * bias enters only in the dense pass (the increment of a constant is zero).
+//   * padding is zero padding; max-pool pads with -inf; bilinear x2 uses half-pixel centres
+//     with clamped borders (weights 0.25 / 0.75).
+//   * a linear op without activation emits y_inc = theta_L(x_inc) itself (Eq.10), not the
+//     difference of the accumulated sums.
+//
+// Parity pins live in tests/ (CPU, "not gpu"): dense ops against PyTorch CPU fp64 routines,
+// Eq.2 invariant against the dense pass, linearity, zero increment, tile independence,
+// refresh equivalence, brute-force lists with exact integer arithmetic, closed-form touched
+// sets for a single active pixel.
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <limits>
+#include <vector>
+
+namespace {
+
+enum Op { OP_CONV = 0, OP_ADD, OP_CONCAT, OP_UP2X, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_ACT };
+enum Act { ACT_NONE = 0, ACT_RELU, ACT_SIGMOID };
+
+struct NodeDesc {
+  int op, act, in0, in1, c_in, c_out, k, stride, pad;
+  long long w_off, b_off;
+  int is_output;
+};
+constexpr int kDescInts = 12;  // ints per node in the marshalled description
+
+template <class T>
+T activate(int act, T v) {
+  if (act == ACT_RELU) return v > T(0) ? v : T(0);
+  if (act == ACT_SIGMOID) return T(1) / (T(1) + std::exp(-v));
+  return v;
+}
+
+struct Shape {
+  int c = 0, h = 0, w = 0;
+  size_t sites() const { return size_t(h) * w; }
+  size_t elems() const { return sites() * c; }
+};
+
+// bilinear x2, half-pixel centres: output index o reads source i0 (weight w0) and i1 (w1)
+inline void up2_src(int o, int n_in, int& i0, int& i1, double& w0, double& w1) {
+  int i = o >> 1;
+  if ((o & 1) == 0) { i0 = std::max(i - 1, 0); i1 = i; w0 = 0.25; w1 = 0.75; }
+  else { i0 = i; i1 = std::min(i + 1, n_in - 1); w0 = 0.75; w1 = 0.25; }
+}
+
+template <class T>
+struct NodeState {
+  Shape shp;                     // output shape
+  std::vector<T> z;              // accumulated pre-activation / accumulated linear result
+  std::vector<T> pool_in;        // max-pool: accumulated input (input shape)
+  std::vector<T> dy;             // this step's output increment, HWC, zero off the active set
+  std::vector<uint8_t> active;   // value-pruned (or structural) active set S
+  std::vector<uint8_t> touched;  // structural touched set T
+  std::vector<T> y;              // output nodes: running sum of increments (Eq.2)
+  std::vector<T> dz, da;         // dense pass: pre-activation and value of this node
+  bool keeps_z = false, structural = false;
+  double macs_site = 0, macs_dense = 0;
+};
+
+template <class T>
+struct Net {
+  std::vector<NodeDesc> nodes;
+  std::vector<double> weights;
+  Shape in;
+  std::vector<float> x_prev;          // CHW, the cached previous frame
+  std::vector<T> dx;                  // HWC input increment
+  std::vector<uint8_t> s0;            // input active set
+  std::vector<T> x_dense;             // HWC copy of the frame for the dense pass
+  std::vector<NodeState<T>> st;
+  bool has_state = false;
+
+  const Shape& shape_of(int i) const { return i < 0 ? in : st[i].shp; }
+  const std::vector<T>& dy_of(int i) const { return i < 0 ? dx : st[i].dy; }
+  const std::vector<uint8_t>& set_of(int i) const { return i < 0 ? s0 : st[i].active; }
+  const std::vector<T>& dense_of(int i) const { return i < 0 ? x_dense : st[i].da; }
+
+  // weights of conv/linear node i, re-laid as [ky][kx][ci][co] so that the innermost (output
+  // channel) loop of the contraction walks contiguous memory; row() is the c_out-vector of
+  // W[:, ci, ky, kx]
+  std::vector<std::vector<T>> w_taps;
+  inline const T* row(int i, const NodeDesc& nd, int ci, int ky, int kx) const {
+    return &w_taps[i][((size_t(ky) * nd.k + kx) * nd.c_in + ci) * nd.c_out];
+  }
+
+  int init(int n_nodes, const int* desc, const double* w, long long n_w, int c, int h, int wd) {
+    in.c = c; in.h = h; in.w = wd;
+    weights.assign(w, w + n_w);
+    nodes.resize(n_nodes);
+    st.resize(n_nodes);
+    w_taps.resize(n_nodes);
+    for (int i = 0; i < n_nodes; ++i) {
+      const int* d = desc + size_t(i) * kDescInts;
+      NodeDesc& nd = nodes[i];
+      nd.op = d[0]; nd.act = d[1]; nd.in0 = d[2]; nd.in1 = d[3]; nd.c_in = d[4]; nd.c_out = d[5];
+      nd.k = d[6]; nd.stride = d[7]; nd.pad = d[8]; nd.w_off = d[9]; nd.b_off = d[10];
+      nd.is_output = d[11];
+      if (nd.in0 >= i || nd.in1 >= i || nd.in0 < -1) return 1;
+      Shape a = shape_of(nd.in0), o;
+      switch (nd.op) {
+        case OP_CONV:
+          if (a.c != nd.c_in) return 2;
+          o.c = nd.c_out;
+          o.h = (a.h + 2 * nd.pad - nd.k) / nd.stride + 1;
+          o.w = (a.w + 2 * nd.pad - nd.k) / nd.stride + 1;
+          break;
+        case OP_MAXPOOL:
+          if (nd.act != ACT_NONE) return 3;
+          o.c = a.c;
+          o.h = (a.h + 2 * nd.pad - nd.k) / nd.stride + 1;
+          o.w = (a.w + 2 * nd.pad - nd.k) / nd.stride + 1;
+          break;
+        case OP_ADD: {
+          Shape b = shape_of(nd.in1);
+          if (b.c != a.c || b.h != a.h || b.w != a.w) return 4;
+          o = a;
+          break;
+        }
+        case OP_ACT: o = a; break;
+        case OP_CONCAT: {
+          Shape b = shape_of(nd.in1);
+          if (b.h != a.h || b.w != a.w) return 5;
+          o = a; o.c = a.c + b.c;
+          break;
+        }
+        case OP_UP2X: o.c = a.c; o.h = 2 * a.h; o.w = 2 * a.w; break;
+        case OP_GAP: o.c = a.c; o.h = 1; o.w = 1; break;
+        case OP_LINEAR:
+          if (a.h != 1 || a.w != 1 || a.c != nd.c_in) return 6;
+          o.c = nd.c_out; o.h = 1; o.w = 1;
+          break;
+        default: return 7;
+      }
+      if (o.h <= 0 || o.w <= 0) return 8;
+      NodeState<T>& s = st[i];
+      s.shp = o;
+      s.keeps_z = (nd.op == OP_CONV || nd.op == OP_LINEAR || nd.op == OP_GAP || nd.op == OP_ACT ||
+                   nd.act != ACT_NONE) && nd.op != OP_MAXPOOL;
+      s.structural = (nd.op == OP_ADD || nd.op == OP_CONCAT || nd.op == OP_UP2X || nd.op == OP_GAP) &&
+                     nd.act == ACT_NONE;
+      s.dy.assign(o.elems(), T(0));
+      s.active.assign(o.sites(), 0);
+      s.touched.assign(o.sites(), 0);
+      if (s.keeps_z) s.z.assign(o.elems(), T(0));
+      if (nd.op == OP_MAXPOOL) s.pool_in.assign(a.elems(), T(0));
+      if (nd.is_output) s.y.assign(o.elems(), T(0));
+      if (nd.op == OP_CONV || nd.op == OP_LINEAR) {
+        if (nd.w_off < 0 || nd.w_off + (long long)nd.c_out * nd.c_in * nd.k * nd.k > n_w) return 9;
+        w_taps[i].resize(size_t(nd.k) * nd.k * nd.c_in * nd.c_out);
+        for (int co = 0; co < nd.c_out; ++co)
+          for (int ci = 0; ci < nd.c_in; ++ci)
+            for (int ky = 0; ky < nd.k; ++ky)
+              for (int kx = 0; kx < nd.k; ++kx)
+                w_taps[i][((size_t(ky) * nd.k + kx) * nd.c_in + ci) * nd.c_out + co] =
+                    T(weights[nd.w_off + ((size_t(co) * nd.c_in + ci) * nd.k + ky) * nd.k + kx]);
+      }
+      if (nd.op == OP_CONV || nd.op == OP_LINEAR)
+        s.macs_dense = double(o.sites()) * nd.k * nd.k * nd.c_in * nd.c_out;  // upper bound (no border cut)
+    }
+    x_prev.assign(in.elems(), 0.f);
+    dx.assign(in.elems(), T(0));
+    s0.assign(in.sites(), 0);
+    return 0;
+  }
+
+  // ------------------------------------------------------------------ dense pass (definition)
+  void dense_forward(const float* x_chw) {
+    x_dense.resize(in.elems());
+    for (int c = 0; c < in.c; ++c)
+      for (size_t p = 0; p < in.sites(); ++p) x_dense[p * in.c + c] = T(x_chw[c * in.sites() + p]);
+    for (size_t i = 0; i < nodes.size(); ++i) dense_node(int(i));
+  }
+
+  void dense_node(int i) {
+    const NodeDesc& nd = nodes[i];
+    NodeState<T>& s = st[i];
+    const Shape a = shape_of(nd.in0), o = s.shp;
+    const std::vector<T>& xa = dense_of(nd.in0);
+    s.dz.assign(o.elems(), T(0));
+    switch (nd.op) {
+      case OP_CONV:
+      case OP_LINEAR: {
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int oy = 0; oy < o.h; ++oy) {
+          std::vector<T> acc(o.c);
+          for (int ox = 0; ox < o.w; ++ox) {
+            for (int co = 0; co < o.c; ++co) acc[co] = nd.b_off >= 0 ? T(weights[nd.b_off + co]) : T(0);
+            for (int ky = 0; ky < nd.k; ++ky) {
+              int iy = oy * nd.stride - nd.pad + ky;
+              if (iy < 0 || iy >= a.h) continue;  // zero padding
+              for (int kx = 0; kx < nd.k; ++kx) {
+                int ix = ox * nd.stride - nd.pad + kx;
+                if (ix < 0 || ix >= a.w) continue;
+                const T* xv = &xa[(size_t(iy) * a.w + ix) * a.c];
+                for (int ci = 0; ci < a.c; ++ci) {
+                  const T* wr = row(i, nd, ci, ky, kx);
+                  T xi = xv[ci];
+                  for (int co = 0; co < o.c; ++co) acc[co] += wr[co] * xi;
+                }
+              }
+            }
+            std::copy(acc.begin(), acc.end(), &s.dz[(size_t(oy) * o.w + ox) * o.c]);
+          }
+        }
+        break;
+      }
+      case OP_ADD: {
+        const std::vector<T>& xb = dense_of(nd.in1);
+        for (size_t e = 0; e < o.elems(); ++e) s.dz[e] = xa[e] + xb[e];
+        break;
+      }
+      case OP_ACT: s.dz = xa; break;
+      case OP_CONCAT: {
+        const Shape b = shape_of(nd.in1);
+        const std::vector<T>& xb = dense_of(nd.in1);
+        for (size_t p = 0; p < o.sites(); ++p) {
+          for (int c = 0; c < a.c; ++c) s.dz[p * o.c + c] = xa[p * a.c + c];
+          for (int c = 0; c < b.c; ++c) s.dz[p * o.c + a.c + c] = xb[p * b.c + c];
+        }
+        break;
+      }
+      case OP_UP2X:
+        for (int oy = 0; oy < o.h; ++oy)
+          for (int ox = 0; ox < o.w; ++ox) {
+            int y0, y1, x0, x1; double wy0, wy1, wx0, wx1;
+            up2_src(oy, a.h, y0, y1, wy0, wy1);
+            up2_src(ox, a.w, x0, x1, wx0, wx1);
+            for (int c = 0; c < o.c; ++c) {
+              auto at = [&](int y, int x) { return xa[(size_t(y) * a.w + x) * a.c + c]; };
+              s.dz[(size_t(oy) * o.w + ox) * o.c + c] =
+                  T(wy0) * (T(wx0) * at(y0, x0) + T(wx1) * at(y0, x1)) +
+                  T(wy1) * (T(wx0) * at(y1, x0) + T(wx1) * at(y1, x1));
+            }
+          }
+        break;
+      case OP_MAXPOOL:
+        for (int oy = 0; oy < o.h; ++oy)
+          for (int ox = 0; ox < o.w; ++ox)
+            for (int c = 0; c < o.c; ++c)
+              s.dz[(size_t(oy) * o.w + ox) * o.c + c] = window_max(xa, a, nd, oy, ox, c);
+        break;
+      case OP_GAP:
+        for (int c = 0; c < o.c; ++c) {
+          T sum = T(0);
+          for (size_t p = 0; p < a.sites(); ++p) sum += xa[p * a.c + c];
+          s.dz[c] = sum / T(a.sites());
+        }
+        break;
+    }
+    s.da.resize(o.elems());
+    for (size_t e = 0; e < o.elems(); ++e) s.da[e] = activate<T>(nd.act, s.dz[e]);
+  }
+
+  static T window_max(const std::vector<T>& v, const Shape& a, const NodeDesc& nd, int oy, int ox, int c) {
+    T m = -std::numeric_limits<T>::infinity();
+    for (int ky = 0; ky < nd.k; ++ky) {
+      int iy = oy * nd.stride - nd.pad + ky;
+      if (iy < 0 || iy >= a.h) continue;
+      for (int kx = 0; kx < nd.k; ++kx) {
+        int ix = ox * nd.stride - nd.pad + kx;
+        if (ix < 0 || ix >= a.w) continue;
+        m = std::max(m, v[(size_t(iy) * a.w + ix) * a.c + c]);
+      }
+    }
+    return m;
+  }
+
+  // refresh: regular forward pass that re-initialises every accumulated tensor
+  void reset(const float* x0) {
+    dense_forward(x0);
+    std::copy(x0, x0 + in.elems(), x_prev.begin());
+    std::fill(dx.begin(), dx.end(), T(0));
+    std::fill(s0.begin(), s0.end(), 0);
+    for (size_t i = 0; i < nodes.size(); ++i) {
+      NodeState<T>& s = st[i];
+      if (s.keeps_z) s.z = s.dz;
+      if (nodes[i].op == OP_MAXPOOL) s.pool_in = dense_of(nodes[i].in0);
+      if (nodes[i].is_output) s.y = s.da;
+      std::fill(s.dy.begin(), s.dy.end(), T(0));
+      std::fill(s.active.begin(), s.active.end(), 0);
+      std::fill(s.touched.begin(), s.touched.end(), 0);
+      s.macs_site = 0;
+    }
+    has_state = true;
+  }
+
+  // ------------------------------------------------------------------ incremental step
+  // Eq.1 on fp32 frames: one binary32 subtraction per element; the frame replaces x_prev.
+  void step_frame(const float* xt) {
+    for (size_t p = 0; p < in.sites(); ++p) {
+      uint8_t any = 0;
+      for (int c = 0; c < in.c; ++c) {
+        size_t e = c * in.sites() + p;
+        float dv = xt[e] - x_prev[e];
+        x_prev[e] = xt[e];
+        dx[p * in.c + c] = T(dv);
+        any |= (dv != 0.0f);
+      }
+      s0[p] = any;
+    }
+    propagate();
+  }
+
+  // the caller supplies the increment tensor itself
+  void step_increment(const float* inc) {
+    for (size_t p = 0; p < in.sites(); ++p) {
+      uint8_t any = 0;
+      for (int c = 0; c < in.c; ++c) {
+        size_t e = c * in.sites() + p;
+        float dv = inc[e];
+        x_prev[e] = x_prev[e] + dv;
+        dx[p * in.c + c] = T(dv);
+        any |= (dv != 0.0f);
+      }
+      s0[p] = any;
+    }
+    propagate();
+  }
+
+  void propagate() {
+    for (size_t i = 0; i < nodes.size(); ++i) incr_node(int(i));
+  }
+
+  // touched set of a windowed op (conv / max-pool): mark every output that reads an active,
+  // in-bounds input site through some tap
+  static void touched_windowed(const std::vector<uint8_t>& s_in, const Shape& a, const Shape& o,
+                               const NodeDesc& nd, std::vector<uint8_t>& t) {
+    std::fill(t.begin(), t.end(), 0);
+    for (int iy = 0; iy < a.h; ++iy)
+      for (int ix = 0; ix < a.w; ++ix) {
+        if (!s_in[size_t(iy) * a.w + ix]) continue;
+        for (int ky = 0; ky < nd.k; ++ky) {
+          int ny = iy + nd.pad - ky;
+          if (ny < 0 || ny % nd.stride) continue;
+          int oy = ny / nd.stride;
+          if (oy >= o.h) continue;
+          for (int kx = 0; kx < nd.k; ++kx) {
+            int nx = ix + nd.pad - kx;
+            if (nx < 0 || nx % nd.stride) continue;
+            int ox = nx / nd.stride;
+            if (ox >= o.w) continue;
+            t[size_t(oy) * o.w + ox] = 1;
+          }
+        }
+      }
+  }
+
+  void incr_node(int i) {
+    const NodeDesc& nd = nodes[i];
+    NodeState<T>& s = st[i];
+    const Shape a = shape_of(nd.in0), o = s.shp;
+    const std::vector<T>& da = dy_of(nd.in0);
+    const std::vector<uint8_t>& sa = set_of(nd.in0);
+    // clear last step's increment on its old support
+    for (size_t q = 0; q < o.sites(); ++q)
+      if (s.touched[q]) std::fill(&s.dy[q * o.c], &s.dy[q * o.c] + o.c, T(0));
+    std::vector<T> v;  // linear-part increment at touched sites, HWC dense-addressed
+    v.assign(o.elems(), T(0));
+    s.macs_site = 0;
+
+    switch (nd.op) {
+      case OP_CONV:
+      case OP_LINEAR: {
+        touched_windowed(sa, a, o, nd, s.touched);
+        std::vector<int> tl;
+        for (size_t q = 0; q < o.sites(); ++q) if (s.touched[q]) tl.push_back(int(q));
+        double macs = 0;
+#pragma omp parallel for schedule(dynamic, 16) reduction(+ : macs)
+        for (size_t n = 0; n < tl.size(); ++n) {
+          int q = tl[n], oy = q / o.w, ox = q % o.w;
+          T* acc = &v[size_t(q) * o.c];
+          for (int ky = 0; ky < nd.k; ++ky) {
+            int iy = oy * nd.stride - nd.pad + ky;
+            if (iy < 0 || iy >= a.h) continue;
+            for (int kx = 0; kx < nd.k; ++kx) {
+              int ix = ox * nd.stride - nd.pad + kx;
+              if (ix < 0 || ix >= a.w) continue;
+              size_t p = size_t(iy) * a.w + ix;
+              if (!sa[p]) continue;  // all-zero site: contributes nothing
+              macs += double(a.c) * o.c;
+              const T* xv = &da[p * a.c];
+              for (int ci = 0; ci < a.c; ++ci) {
+                const T* wr = row(i, nd, ci, ky, kx);
+                T xi = xv[ci];
+                for (int co = 0; co < o.c; ++co) acc[co] += wr[co] * xi;
+              }
+            }
+          }
+        }
+        s.macs_site = macs;
+        break;
+      }
+      case OP_ADD: {  // Eq.11
+        const std::vector<T>& db = dy_of(nd.in1);
+        const std::vector<uint8_t>& sb = set_of(nd.in1);
+        for (size_t q = 0; q < o.sites(); ++q) {
+          s.touched[q] = sa[q] | sb[q];
+          if (!s.touched[q]) continue;
+          for (int c = 0; c < o.c; ++c) v[q * o.c + c] = da[q * o.c + c] + db[q * o.c + c];
+        }
+        break;
+      }
+      case OP_ACT:
+        for (size_t q = 0; q < o.sites(); ++q) {
+          s.touched[q] = sa[q];
+          if (!s.touched[q]) continue;
+          for (int c = 0; c < o.c; ++c) v[q * o.c + c] = da[q * o.c + c];
+        }
+        break;
+      case OP_CONCAT: {
+        const Shape b = shape_of(nd.in1);
+        const std::vector<T>& db = dy_of(nd.in1);
+        const std::vector<uint8_t>& sb = set_of(nd.in1);
+        for (size_t q = 0; q < o.sites(); ++q) {
+          s.touched[q] = sa[q] | sb[q];
+          if (!s.touched[q]) continue;
+          for (int c = 0; c < a.c; ++c) v[q * o.c + c] = da[q * a.c + c];
+          for (int c = 0; c < b.c; ++c) v[q * o.c + a.c + c] = db[q * b.c + c];
+        }
+        break;
+      }
+      case OP_UP2X:  // linear => Eq.10 on the increment
+        for (int oy = 0; oy < o.h; ++oy)
+          for (int ox = 0; ox < o.w; ++ox) {
+            int y0, y1, x0, x1; double wy0, wy1, wx0, wx1;
+            up2_src(oy, a.h, y0, y1, wy0, wy1);
+            up2_src(ox, a.w, x0, x1, wx0, wx1);
+            size_t q = size_t(oy) * o.w + ox;
+            s.touched[q] = sa[size_t(y0) * a.w + x0] | sa[size_t(y0) * a.w + x1] |
+                           sa[size_t(y1) * a.w + x0] | sa[size_t(y1) * a.w + x1];
+            if (!s.touched[q]) continue;
+            for (int c = 0; c < o.c; ++c) {
+              auto at = [&](int y, int x) { return da[(size_t(y) * a.w + x) * a.c + c]; };
+              v[q * o.c + c] = T(wy0) * (T(wx0) * at(y0, x0) + T(wx1) * at(y0, x1)) +
+                               T(wy1) * (T(wx0) * at(y1, x0) + T(wx1) * at(y1, x1));
+            }
+          }
+        break;
+      case OP_MAXPOOL: {
+        // windowed nonlinearity with accumulated input (Eq.12 generalised): the output
+        // increment is max over the updated window minus max over the old window
+        touched_windowed(sa, a, o, nd, s.touched);
+        std::vector<T> old_max(o.elems(), T(0));
+        for (int oy = 0; oy < o.h; ++oy)
+          for (int ox = 0; ox < o.w; ++ox) {
+            size_t q = size_t(oy) * o.w + ox;
+            if (!s.touched[q]) continue;
+            for (int c = 0; c < o.c; ++c) old_max[q * o.c + c] = window_max(s.pool_in, a, nd, oy, ox, c);
+          }
+        for (size_t p = 0; p < a.sites(); ++p)
+          if (sa[p])
+            for (int c = 0; c < a.c; ++c) s.pool_in[p * a.c + c] += da[p * a.c + c];
+        for (int oy = 0; oy < o.h; ++oy)
+          for (int ox = 0; ox < o.w; ++ox) {
+            size_t q = size_t(oy) * o.w + ox;
+            if (!s.touched[q]) continue;
+            for (int c = 0; c < o.c; ++c)
+              v[q * o.c + c] = window_max(s.pool_in, a, nd, oy, ox, c) - old_max[q * o.c + c];
+          }
+        break;
+      }
+      case OP_GAP: {
+        bool any = false;
+        for (size_t p = 0; p < a.sites(); ++p) any |= bool(sa[p]);
+        s.touched[0] = any;
+        if (any)
+          for (int c = 0; c < o.c; ++c) {
+            T sum = T(0);
+            for (size_t p = 0; p < a.sites(); ++p)
+              if (sa[p]) sum += da[p * a.c + c];
+            v[c] = sum / T(a.sites());
+          }
+        break;
+      }
+    }
+
+    // accumulate, apply the activation increment (Eq.12-14) and derive the active set
+    for (size_t q = 0; q < o.sites(); ++q) {
+      s.active[q] = 0;
+      if (!s.touched[q]) continue;
+      uint8_t nz = 0;
+      for (int c = 0; c < o.c; ++c) {
+        size_t e = q * o.c + c;
+        T out = v[e];
+        if (s.keeps_z) {
+          T z_old = s.z[e];
+          T z_new = z_old + v[e];
+          s.z[e] = z_new;
+          if (nd.act != ACT_NONE) out = activate<T>(nd.act, z_new) - activate<T>(nd.act, z_old);
+        }
+        s.dy[e] = out;
+        nz |= (out != T(0));
+      }
+      s.active[q] = s.structural ? 1 : nz;
+      if (!s.active[q]) std::fill(&s.dy[q * o.c], &s.dy[q * o.c] + o.c, T(0));
+    }
+    if (nd.is_output)  // Eq.2
+      for (size_t q = 0; q < o.sites(); ++q)
+        if (s.active[q])
+          for (int c = 0; c < o.c; ++c) s.y[q * o.c + c] += s.dy[q * o.c + c];
+  }
+};
+
+struct Handle {
+  int fp32;
+  Net<double> d;
+  Net<float> f;
+};
+
+template <class T>
+void copy_out(const std::vector<T>& v, double* dst) {
+  for (size_t i = 0; i < v.size(); ++i) dst[i] = double(v[i]);
+}
+
+template <class T>
+long long get_tensor(Net<T>& n, int node, int kind, double* dst) {
+  // kind: 0 z, 1 dy, 2 y (outputs), 3 dense pre-activation, 4 dense value, 5 pool_in
+  if (node < 0) {
+    if (kind != 1) return -1;
+    if (dst) copy_out(n.dx, dst);
+    return (long long)n.dx.size();
+  }
+  NodeState<T>& s = n.st[node];
+  const std::vector<T>* v = nullptr;
+  switch (kind) {
+    case 0: v = &s.z; break;
+    case 1: v = &s.dy; break;
+    case 2: v = &s.y; break;
+    case 3: v = &s.dz; break;
+    case 4: v = &s.da; break;
+    case 5: v = &s.pool_in; break;
+    default: return -1;
+  }
+  if (dst) copy_out(*v, dst);
+  return (long long)v->size();
+}
+
+template <class T>
+long long get_set(Net<T>& n, int node, int kind, uint8_t* dst) {
+  // kind: 0 active set S, 1 touched set T   (dense H*W byte mask)
+  const std::vector<uint8_t>& v = node < 0 ? n.s0 : (kind == 0 ? n.st[node].active : n.st[node].touched);
+  if (dst) std::copy(v.begin(), v.end(), dst);
+  return (long long)v.size();
+}
+
+}  // namespace
+
+extern "C" {
+
+// desc: n_nodes x 12 int32 {op, act, in0, in1, c_in, c_out, k, stride, pad, w_off, b_off, is_output}
+void* evo_create(int n_nodes, const int* desc, const double* weights, long long n_weights,
+                 int in_c, int in_h, int in_w, int fp32_state) {
+  Handle* h = new Handle();
+  h->fp32 = fp32_state;
+  int rc = fp32_state ? h->f.init(n_nodes, desc, weights, n_weights, in_c, in_h, in_w)
+                      : h->d.init(n_nodes, desc, weights, n_weights, in_c, in_h, in_w);
+  if (rc) { delete h; return nullptr; }
+  return h;
+}
+void evo_destroy(void* h) { delete (Handle*)h; }
+void evo_dense_forward(void* h, const float* x) {
+  Handle* p = (Handle*)h;
+  if (p->fp32) p->f.dense_forward(x); else p->d.dense_forward(x);
+}
+void evo_reset(void* h, const float* x0) {
+  Handle* p = (Handle*)h;
+  if (p->fp32) p->f.reset(x0); else p->d.reset(x0);
+}
+void evo_step_frame(void* h, const float* xt) {
+  Handle* p = (Handle*)h;
+  if (p->fp32) p->f.step_frame(xt); else p->d.step_frame(xt);
+}
+void evo_step_increment(void* h, const float* inc) {
+  Handle* p = (Handle*)h;
+  if (p->fp32) p->f.step_increment(inc); else p->d.step_increment(inc);
+}
+long long evo_get_tensor(void* h, int node, int kind, double* dst) {
+  Handle* p = (Handle*)h;
+  return p->fp32 ? get_tensor(p->f, node, kind, dst) : get_tensor(p->d, node, kind, dst);
+}
+long long evo_get_set(void* h, int node, int kind, uint8_t* dst) {
+  Handle* p = (Handle*)h;
+  return p->fp32 ? get_set(p->f, node, kind, dst) : get_set(p->d, node, kind, dst);
+}
+void evo_get_shape(void* h, int node, int* chw) {
+  Handle* p = (Handle*)h;
+  Shape s = p->fp32 ? p->f.shape_of(node) : p->d.shape_of(node);
+  chw[0] = s.c; chw[1] = s.h; chw[2] = s.w;
+}
+void evo_get_x_prev(void* h, float* dst) {
+  Handle* p = (Handle*)h;
+  const std::vector<float>& v = p->fp32 ? p->f.x_prev : p->d.x_prev;
+  std::copy(v.begin(), v.end(), dst);
+}
+// executed multiply-accumulates of the last step at site granularity, and of a dense pass
+void evo_get_macs(void* h, int node, double* site, double* dense) {
+  Handle* p = (Handle*)h;
+  if (p->fp32) { *site = p->f.st[node].macs_site; *dense = p->f.st[node].macs_dense; }
+  else { *site = p->d.st[node].macs_site; *dense = p->d.st[node].macs_dense; }
+}
+
+}  // extern "C"
