@@ -1,0 +1,192 @@
+/* evconv.h - C ABI of the MI355X (gfx950) incremental-CNN library.
+ *
+ * Incremental CNN inference on event-camera inputs: each step runs the network on the sparse
+ * increment x_inc(n) = x(n) - x(n-1) (Eq.1) only where it is nonzero, adds the result into
+ * cached per-layer pre-activations (the x_acc of Eq.12-14) and returns the output together
+ * with its increment (Eq.2).  Every step of that path runs in HIP kernels of this library;
+ * the caller supplies device memory (one workspace) and a HIP stream, nothing else.
+ *
+ * Plain C: no C++ types, no exceptions cross this boundary.  Pointers are marked HOST or
+ * DEVICE.  One handle must be used from one host thread at a time.
+ *
+ * Data layout: public tensors are C x H x W fp32 (row-major, W fastest).  Site index means
+ * y*W + x.  Inside the workspace activations are H x W x C ("channels last", the notation of
+ * "Implementation of Increment Layers"); evconv_get_state returns that internal layout.
+ *
+ * Semantics of one node (input increment x_inc on active set S_in -> output increment y_inc on
+ * active set S_out); T is the touched set, the input mask pushed through the op's footprint:
+ *   CONV2D / LINEAR  y_lin = theta_L(x_inc) at T (Eq.10), no bias (bias enters in reset only).
+ *                    T = outputs with at least one tap on an active, in-bounds input site.
+ *   ADD              y_lin = a_inc + b_inc, T = S_a | S_b (Eq.11).
+ *   CONCAT           channel concatenation, T = S_a | S_b.
+ *   UPSAMPLE_BILINEAR2X  half-pixel centres, weights {0.25, 0.75}, clamped borders; T = outputs
+ *                    with an active source site.  Linear, so Eq.10 applies.
+ *   ACT              y_lin = x_inc, T = S_in (the activation increment layer, Eq.12-14).
+ *   GLOBAL_AVGPOOL   y_lin = mean over sites of x_inc (1 x 1 x C), T = {0} if S_in nonempty.
+ *   MAXPOOL          state a += x_inc; y_inc = max(window of a_new) - max(window of a_old) at
+ *                    windows containing an active site; padding value -inf; act must be NONE.
+ * A node keeps an accumulated tensor z (+= y_lin at T) if it is CONV2D, LINEAR,
+ * GLOBAL_AVGPOOL, ACT, or has an activation.  With an activation theta_a the output is
+ * y_inc = theta_a(z_new) - theta_a(z_old) (Eq.12), else y_inc = y_lin.
+ * S_out is T for ADD / CONCAT / UPSAMPLE / GLOBAL_AVGPOOL without activation (Eq.11b), otherwise
+ * the sites of T where some channel of y_inc is != 0 (-0 counts as zero, NaN as nonzero).
+ * Output nodes additionally keep y += y_inc on S_out (Eq.2).
+ */
+#ifndef EVCONV_H
+#define EVCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EVCONV_ABI_VERSION 1
+
+typedef struct evconv_net evconv_net; /* opaque, library-owned; freed by evconv_destroy */
+
+typedef enum {
+  EVCONV_OK = 0,
+  EVCONV_ERR_INVALID_ARG = 1, /* null pointer, bad enum value */
+  EVCONV_ERR_BAD_DESC = 2,    /* graph not topologically ordered, bad offsets, abi mismatch */
+  EVCONV_ERR_SHAPE = 3,       /* channel / spatial sizes of a node's inputs do not fit */
+  EVCONV_ERR_STATE = 4,       /* step before reset */
+  EVCONV_ERR_WORKSPACE = 5,   /* workspace too small or misaligned (256 bytes) */
+  EVCONV_ERR_HIP = 6,         /* a HIP call failed; text in evconv_last_error */
+  EVCONV_ERR_UNSUPPORTED = 7  /* valid request this build does not implement */
+} evconv_status;
+
+typedef enum {
+  EVCONV_OP_CONV2D = 0,
+  EVCONV_OP_ADD = 1,
+  EVCONV_OP_CONCAT = 2,
+  EVCONV_OP_UPSAMPLE_BILINEAR2X = 3,
+  EVCONV_OP_MAXPOOL = 4,
+  EVCONV_OP_GLOBAL_AVGPOOL = 5,
+  EVCONV_OP_LINEAR = 6,
+  EVCONV_OP_ACT = 7
+} evconv_op;
+
+typedef enum { EVCONV_ACT_NONE = 0, EVCONV_ACT_RELU = 1, EVCONV_ACT_SIGMOID = 2 } evconv_act;
+
+/* dtype of the weights and of the increments inside the channel contraction; accumulation and
+ * every cached tensor are always fp32 */
+typedef enum { EVCONV_F32 = 0, EVCONV_BF16 = 1 } evconv_dtype;
+
+typedef enum {
+  EVCONV_MODE_INCREMENTAL = 0,    /* the paper's method */
+  EVCONV_MODE_DENSE_RECOMPUTE = 1 /* regular forward pass of x(n) with the same kernels (the
+                                     refresh of "Drift Errors", used as the dense comparator) */
+} evconv_mode;
+
+/* One node.  Inputs are earlier node ids; -1 is the network input; in1 is ignored by one-input
+ * ops.  The activation is fused after the op. */
+typedef struct {
+  int32_t op;          /* evconv_op */
+  int32_t act;         /* evconv_act */
+  int32_t in0, in1;
+  int32_t c_in, c_out; /* CONV2D / LINEAR; other ops derive their channels */
+  int32_t kh, kw;      /* CONV2D, MAXPOOL; must be equal, 1..7 */
+  int32_t stride;      /* 1 or 2 */
+  int32_t pad;         /* zero padding (-inf for MAXPOOL), < kh */
+  int32_t wdtype;      /* evconv_dtype */
+  int32_t is_output;   /* nonzero: y and y_inc of this node are returned by reset / step */
+  int64_t weight_off;  /* byte offset into `weights`: fp32 [c_out][c_in][kh][kw]; -1 if none */
+  int64_t bias_off;    /* byte offset of fp32 [c_out]; -1 = no bias */
+} evconv_node_desc;
+
+typedef struct {
+  int32_t abi_version; /* EVCONV_ABI_VERSION */
+  int32_t n_nodes;
+  const evconv_node_desc* nodes; /* HOST, n_nodes entries, topological order */
+  int32_t in_c, in_h, in_w;
+  int32_t tile_h, tile_w; /* mask tile; 0 = default 8 x 8 (the only size this build accepts) */
+  float sparsify_tp;      /* lossy sparsification threshold; must be 0 (lossless) */
+  int32_t n_streams;      /* independent streams sharing the weights; must be 1 */
+} evconv_net_desc;
+
+/* Result of one output node.  All pointers are DEVICE memory inside the workspace, valid until
+ * the next reset / step / destroy on the same net, and written asynchronously on the net's
+ * stream: synchronise the stream before reading them. */
+typedef struct {
+  int32_t node, c, h, w;
+  const float* y;          /* C x H x W: y(n), the running sum of Eq.2 */
+  const float* dy;         /* C x H x W: y_inc(n), zero outside the active set */
+  const int32_t* dy_idx;   /* ascending active output sites (h*w entries allocated) */
+  const int32_t* dy_count; /* one int32: number of valid entries of dy_idx */
+} evconv_out;
+
+typedef struct {
+  int32_t n_sites, n_tiles;      /* of the node's output grid */
+  int32_t n_touched, n_active;   /* sites in T and in S_out after the last step */
+  int32_t n_touched_tiles;       /* tiles with at least one touched site */
+  double flops_executed;         /* 2 * MACs issued by the last step at tile granularity */
+  double flops_dense;            /* 2 * MACs of a regular forward pass of this node */
+} evconv_layer_stats;
+
+typedef enum {
+  EVCONV_STATE_Z = 0,           /* fp32 H x W x C accumulated tensor (nodes that keep one) */
+  EVCONV_STATE_DY = 1,          /* fp32 H x W x C increment buffer; meaningful on T only */
+  EVCONV_STATE_IDX = 2,         /* int32 ascending site list of S_out */
+  EVCONV_STATE_COUNT = 3,       /* int32 */
+  EVCONV_STATE_BITMAP = 4,      /* uint64 words, bit t%64 of word t/64 = tile t non-empty */
+  EVCONV_STATE_OCC = 5,         /* uint64 per tile: S_out, bit (y%8)*8 + x%8, tiles row-major */
+  EVCONV_STATE_OCC_TOUCHED = 6, /* uint64 per tile: T */
+  EVCONV_STATE_X_PREV = 7       /* node -1 only: fp32 C x H x W cached previous frame */
+} evconv_state_kind;
+
+/* Bytes of device workspace a net of this description needs.  No GPU work. */
+evconv_status evconv_query_workspace(const evconv_net_desc* desc, size_t* bytes);
+
+/* Builds a net.  `weights` is HOST memory (copied and re-laid out; the caller may free it on
+ * return).  `workspace` is DEVICE memory, 256-byte aligned, at least the queried size, owned by
+ * the caller and used exclusively by this net until evconv_destroy.  `hip_stream` is a
+ * hipStream_t (NULL = the default stream); all later work of this net is enqueued on it.
+ * Synchronous.  On error *out is untouched. */
+evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, size_t weight_bytes,
+                            void* workspace, size_t workspace_bytes, void* hip_stream,
+                            evconv_net** out);
+
+/* Number of output nodes (entries written to the `out` arrays below). */
+int32_t evconv_num_outputs(const evconv_net* net);
+
+/* Refresh ("Drift Errors"): regular forward pass of x0 (DEVICE, C x H x W fp32) that fills the
+ * previous-frame cache, every accumulated tensor and y(0).  `out` (HOST array of
+ * evconv_num_outputs entries, may be NULL) receives the pointers; dy is zero, count 0.
+ * Asynchronous on the net's stream. */
+evconv_status evconv_reset(evconv_net* net, const float* x0, evconv_out* out);
+
+/* One incremental step on a caller-supplied increment tensor (DEVICE, dense C x H x W fp32,
+ * zeros where nothing changed).  Asynchronous.  EVCONV_ERR_STATE before the first reset. */
+evconv_status evconv_step(evconv_net* net, const float* increment, evconv_out* out);
+
+/* One incremental step on the next frame x(n) (DEVICE, C x H x W fp32): the increment is
+ * formed against the cached previous frame with one fp32 subtraction per element (Eq.1). */
+evconv_status evconv_step_frame(evconv_net* net, const float* x_t, evconv_out* out);
+
+/* NULL is accepted.  Never frees the workspace.  Synchronises the net's stream first. */
+evconv_status evconv_destroy(evconv_net* net);
+
+evconv_status evconv_set_mode(evconv_net* net, int32_t mode /* evconv_mode */);
+
+/* Shape (c, h, w) of a node's output; node -1 is the network input. */
+evconv_status evconv_node_shape(const evconv_net* net, int32_t node, int32_t* chw /* HOST[3] */);
+
+/* Synchronous copy of internal state to HOST memory (parity checks, checkpoints).  `bytes`
+ * must be the exact size; node -1 addresses the input increment stage. */
+evconv_status evconv_get_state(evconv_net* net, int32_t node, int32_t kind, void* dst, size_t bytes);
+
+/* Synchronous; counts come from the occupancy words of the last step. */
+evconv_status evconv_get_stats(evconv_net* net, int32_t node, evconv_layer_stats* out);
+
+/* Name of the kernel family that executes a node ("conv_valu_f32", "conv_mfma_f32", ...). */
+const char* evconv_node_kernel(const evconv_net* net, int32_t node);
+
+/* Text of the last error on this net (or of the last failed create when net is NULL). */
+const char* evconv_last_error(const evconv_net* net);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EVCONV_H */

@@ -27,7 +27,7 @@ SET_ACTIVE, SET_TOUCHED = 0, 1
 def build_oracle(force: bool = False) -> str:
     """Compile the oracle with g++ (no fast-math, no FMA contraction, OpenMP)."""
     if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
-        cmd = ["g++", "-O3", "-march=native", "-fopenmp", "-ffp-contract=off", "-std=c++17",
+        cmd = ["g++", "-O3", "-march=x86-64-v3", "-fopenmp", "-ffp-contract=off", "-std=c++17",
                "-shared", "-fPIC", "-o", _SO, _SRC]
         subprocess.run(cmd, check=True)
     return _SO

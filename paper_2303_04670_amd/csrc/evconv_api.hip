@@ -1,0 +1,524 @@
+// Host side of the C ABI declared in include/evconv.h: description checking, workspace
+// layout, weight re-layout, and the per-step launch sequence.  No computation of the method
+// happens on the host; every step of the path is a kernel launch on the caller's stream.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/evconv.h"
+#include "evconv_kernels.h"
+
+using namespace evk;
+
+namespace {
+
+thread_local std::string g_create_error;
+
+enum KernelKind { kKernConvValu = 0, kKernConvMfmaF32, kKernElementwise, kKernGap, kKernPool };
+const char* const kKernelNames[] = {"conv_valu_f32", "conv_mfma_f32", "elementwise", "global_avgpool",
+                                    "maxpool"};
+
+struct NodePlan {
+  evconv_node_desc d;
+  Geo ga, gb, go;
+  bool keeps_z = false, structural = false;
+  int kernel = 0;
+  int c_out_pad = 0;
+  // workspace offsets (bytes); resolved to pointers at create
+  size_t off_z = 0, off_out = 0, off_pool = 0, off_occ = 0, off_touched = 0, off_idx = 0, off_count = 0,
+         off_bitmap = 0, off_w = 0, off_bias = 0, off_y = 0, off_dy = 0;
+  float *z = nullptr, *out = nullptr, *pool_in = nullptr, *bias = nullptr, *y = nullptr, *dy = nullptr;
+  void* w = nullptr;
+  uint64_t *occ = nullptr, *touched = nullptr, *bitmap = nullptr;
+  int32_t *idx = nullptr, *count = nullptr;
+};
+
+struct Layout {
+  std::vector<NodePlan> nodes;
+  Geo gin;
+  size_t off_x_prev = 0, off_dx = 0, off_occ_in = 0, off_idx_in = 0, off_count_in = 0, off_bitmap_in = 0;
+  size_t off_occ_nodes = 0, n_occ_words = 0;  // contiguous occupancy region of all nodes
+  size_t off_sets = 0;
+  size_t total = 0;
+  int max_ty = 0;
+};
+
+size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+struct Bump {
+  size_t cur = 0;
+  size_t take(size_t bytes) {
+    size_t o = cur;
+    cur = align_up(cur + bytes);
+    return o;
+  }
+};
+
+evconv_status fail(std::string* err, evconv_status st, const std::string& msg) {
+  if (err) *err = msg;
+  return st;
+}
+
+// Checks the description and lays the workspace out.  Pure host arithmetic.
+evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool check_weights, Layout* L,
+                          std::string* err) {
+  if (!desc || !desc->nodes) return fail(err, EVCONV_ERR_INVALID_ARG, "null description");
+  if (desc->abi_version != EVCONV_ABI_VERSION) return fail(err, EVCONV_ERR_BAD_DESC, "abi_version mismatch");
+  if (desc->n_nodes <= 0) return fail(err, EVCONV_ERR_BAD_DESC, "n_nodes must be positive");
+  if (desc->in_c <= 0 || desc->in_h <= 0 || desc->in_w <= 0) return fail(err, EVCONV_ERR_SHAPE, "bad input shape");
+  if ((desc->tile_h != 0 && desc->tile_h != kTile) || (desc->tile_w != 0 && desc->tile_w != kTile))
+    return fail(err, EVCONV_ERR_UNSUPPORTED, "only 8 x 8 mask tiles are built");
+  if (desc->sparsify_tp != 0.0f) return fail(err, EVCONV_ERR_UNSUPPORTED, "lossy sparsification is not built");
+  if (desc->n_streams != 0 && desc->n_streams != 1) return fail(err, EVCONV_ERR_UNSUPPORTED, "n_streams must be 1");
+  if ((long long)desc->in_h * desc->in_w > (1ll << 30)) return fail(err, EVCONV_ERR_SHAPE, "input too large");
+
+  L->gin = make_geo(desc->in_c, desc->in_h, desc->in_w);
+  L->nodes.resize(desc->n_nodes);
+  L->max_ty = L->gin.ty;
+  Bump b;
+  // occupancy words of all nodes first, contiguous: cleared in one sweep at the start of a step
+  L->off_occ_nodes = b.cur;
+  std::vector<size_t> occ_word_off(desc->n_nodes);
+  size_t words = 0;
+  for (int i = 0; i < desc->n_nodes; ++i) {
+    const evconv_node_desc& d = desc->nodes[i];
+    NodePlan& n = L->nodes[i];
+    n.d = d;
+    char where[64];
+    snprintf(where, sizeof where, "node %d: ", i);
+    if (d.op < 0 || d.op > EVCONV_OP_ACT) return fail(err, EVCONV_ERR_INVALID_ARG, std::string(where) + "bad op");
+    if (d.act < 0 || d.act > EVCONV_ACT_SIGMOID) return fail(err, EVCONV_ERR_INVALID_ARG, std::string(where) + "bad act");
+    if (d.in0 < -1 || d.in0 >= i) return fail(err, EVCONV_ERR_BAD_DESC, std::string(where) + "in0 is not an earlier node");
+    const bool two = d.op == EVCONV_OP_ADD || d.op == EVCONV_OP_CONCAT;
+    if (two && (d.in1 < -1 || d.in1 >= i)) return fail(err, EVCONV_ERR_BAD_DESC, std::string(where) + "in1 is not an earlier node");
+    n.ga = d.in0 < 0 ? L->gin : L->nodes[d.in0].go;
+    n.gb = two ? (d.in1 < 0 ? L->gin : L->nodes[d.in1].go) : n.ga;
+    int c = n.ga.c, h = n.ga.h, w = n.ga.w;
+    switch (d.op) {
+      case EVCONV_OP_CONV2D:
+      case EVCONV_OP_LINEAR:
+      case EVCONV_OP_MAXPOOL: {
+        int k = d.kh, s = d.stride, pad = d.pad;
+        if (d.op == EVCONV_OP_LINEAR) {
+          if (h != 1 || w != 1) return fail(err, EVCONV_ERR_SHAPE, std::string(where) + "LINEAR needs a 1 x 1 input");
+          k = 1; s = 1; pad = 0;
+          n.d.kh = n.d.kw = 1; n.d.stride = 1; n.d.pad = 0;
+        } else {
+          if (d.kh != d.kw || k < 1 || k > 7) return fail(err, EVCONV_ERR_UNSUPPORTED, std::string(where) + "kernel must be square, 1..7");
+          if (s < 1 || s > 2) return fail(err, EVCONV_ERR_UNSUPPORTED, std::string(where) + "stride must be 1 or 2");
+          if (pad < 0 || pad >= k) return fail(err, EVCONV_ERR_BAD_DESC, std::string(where) + "pad must be in [0, k)");
+        }
+        if (d.op == EVCONV_OP_MAXPOOL) {
+          if (d.act != EVCONV_ACT_NONE) return fail(err, EVCONV_ERR_UNSUPPORTED, std::string(where) + "MAXPOOL takes no activation");
+        } else {
+          if (d.c_in != c) return fail(err, EVCONV_ERR_SHAPE, std::string(where) + "c_in does not match the input node");
+          if (d.c_out <= 0) return fail(err, EVCONV_ERR_SHAPE, std::string(where) + "c_out must be positive");
+          if (d.wdtype != EVCONV_F32 && d.wdtype != EVCONV_BF16) return fail(err, EVCONV_ERR_INVALID_ARG, std::string(where) + "bad wdtype");
+          const size_t wb = (size_t)d.c_out * d.c_in * k * k * sizeof(float);
+          if (d.weight_off < 0 || (d.weight_off & 3)) return fail(err, EVCONV_ERR_BAD_DESC, std::string(where) + "bad weight_off");
+          if (check_weights && (size_t)d.weight_off + wb > weight_bytes) return fail(err, EVCONV_ERR_BAD_DESC, std::string(where) + "weights out of range");
+          if (d.bias_off >= 0 && ((d.bias_off & 3) || (check_weights && (size_t)d.bias_off + d.c_out * sizeof(float) > weight_bytes)))
+            return fail(err, EVCONV_ERR_BAD_DESC, std::string(where) + "bias out of range");
+          c = d.c_out;
+        }
+        const int ho = (h + 2 * pad - k) / s + 1, wo = (w + 2 * pad - k) / s + 1;
+        if (h + 2 * pad < k || w + 2 * pad < k || ho <= 0 || wo <= 0) return fail(err, EVCONV_ERR_SHAPE, std::string(where) + "empty output");
+        h = ho; w = wo;
+        break;
+      }
+      case EVCONV_OP_ADD:
+        if (n.gb.c != c || n.gb.h != h || n.gb.w != w) return fail(err, EVCONV_ERR_SHAPE, std::string(where) + "ADD inputs differ in shape");
+        break;
+      case EVCONV_OP_CONCAT:
+        if (n.gb.h != h || n.gb.w != w) return fail(err, EVCONV_ERR_SHAPE, std::string(where) + "CONCAT inputs differ in size");
+        c += n.gb.c;
+        break;
+      case EVCONV_OP_UPSAMPLE_BILINEAR2X: h *= 2; w *= 2; break;
+      case EVCONV_OP_GLOBAL_AVGPOOL: h = 1; w = 1; break;
+      case EVCONV_OP_ACT: break;
+    }
+    if ((long long)h * w > (1ll << 30)) return fail(err, EVCONV_ERR_SHAPE, std::string(where) + "output too large");
+    n.go = make_geo(c, h, w);
+    if (n.go.ty > L->max_ty) L->max_ty = n.go.ty;
+    const bool lin = d.op == EVCONV_OP_CONV2D || d.op == EVCONV_OP_LINEAR;
+    n.keeps_z = (lin || d.op == EVCONV_OP_GLOBAL_AVGPOOL || d.op == EVCONV_OP_ACT || d.act != EVCONV_ACT_NONE) &&
+                d.op != EVCONV_OP_MAXPOOL;
+    n.structural = (d.op == EVCONV_OP_ADD || d.op == EVCONV_OP_CONCAT || d.op == EVCONV_OP_UPSAMPLE_BILINEAR2X ||
+                    d.op == EVCONV_OP_GLOBAL_AVGPOOL) && d.act == EVCONV_ACT_NONE;
+    if (lin) {
+      n.kernel = kKernConvValu;
+      n.c_out_pad = (d.c_out + 31) / 32 * 32;
+    } else if (d.op == EVCONV_OP_GLOBAL_AVGPOOL) n.kernel = kKernGap;
+    else if (d.op == EVCONV_OP_MAXPOOL) n.kernel = kKernPool;
+    else n.kernel = kKernElementwise;
+    occ_word_off[i] = words;
+    words += 2 * (size_t)n.go.tiles();
+  }
+  L->n_occ_words = words;
+  b.take(words * sizeof(uint64_t));
+  for (int i = 0; i < desc->n_nodes; ++i) {
+    NodePlan& n = L->nodes[i];
+    n.off_occ = L->off_occ_nodes + occ_word_off[i] * sizeof(uint64_t);
+    n.off_touched = n.off_occ + (size_t)n.go.tiles() * sizeof(uint64_t);
+  }
+  // input stage
+  const size_t in_elems = (size_t)L->gin.c * L->gin.sites();
+  L->off_x_prev = b.take(in_elems * 4);
+  L->off_dx = b.take(in_elems * 4);
+  L->off_occ_in = b.take((size_t)L->gin.tiles() * 8);
+  L->off_idx_in = b.take((size_t)L->gin.sites() * 4);
+  L->off_count_in = b.take(4);
+  L->off_bitmap_in = b.take(((size_t)L->gin.tiles() + 63) / 64 * 8);
+  for (int i = 0; i < desc->n_nodes; ++i) {
+    NodePlan& n = L->nodes[i];
+    const size_t elems = (size_t)n.go.c * n.go.sites();
+    if (n.keeps_z || n.d.op == EVCONV_OP_MAXPOOL) n.off_z = b.take(elems * 4);
+    if (n.d.op == EVCONV_OP_MAXPOOL) n.off_pool = b.take((size_t)n.ga.c * n.ga.sites() * 4);
+    n.off_out = b.take(elems * 4);
+    n.off_idx = b.take((size_t)n.go.sites() * 4);
+    n.off_count = b.take(4);
+    n.off_bitmap = b.take(((size_t)n.go.tiles() + 63) / 64 * 8);
+    if (n.d.op == EVCONV_OP_CONV2D || n.d.op == EVCONV_OP_LINEAR) {
+      const int k = n.d.kh;
+      n.off_w = b.take((size_t)k * k * n.d.c_in * n.c_out_pad * 4);
+      if (n.d.bias_off >= 0) n.off_bias = b.take((size_t)n.d.c_out * 4);
+    }
+    if (n.d.is_output) {
+      n.off_y = b.take(elems * 4);
+      n.off_dy = b.take(elems * 4);
+    }
+  }
+  L->off_sets = b.take(sizeof(SetDesc) * (size_t)(desc->n_nodes + 1));
+  L->total = b.cur;
+  return EVCONV_OK;
+}
+
+}  // namespace
+
+struct evconv_net {
+  Layout L;
+  std::vector<evconv_node_desc> desc_nodes;
+  char* ws = nullptr;
+  hipStream_t stream = nullptr;
+  int mode = EVCONV_MODE_INCREMENTAL;
+  bool has_state = false;
+  std::string err;
+  std::vector<int> outputs;
+  float *x_prev = nullptr, *dx = nullptr;
+  uint64_t *occ_in = nullptr, *bitmap_in = nullptr, *occ_nodes = nullptr;
+  int32_t *idx_in = nullptr, *count_in = nullptr;
+  SetDesc* sets_dev = nullptr;
+};
+
+namespace {
+
+evconv_status hip_fail(evconv_net* net, hipError_t e, const char* what) {
+  net->err = std::string(what) + ": " + hipGetErrorString(e);
+  return EVCONV_ERR_HIP;
+}
+
+enum PassKind { kPassStep = 0, kPassReset = 1, kPassRecompute = 2 };
+
+// Enqueues one pass of the whole network.
+evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, PassKind pass) {
+  hipStream_t s = net->stream;
+  const int dense = pass != kPassStep;
+  BuilderParams bp;
+  bp.in = input; bp.x_prev = net->x_prev; bp.dx = net->dx; bp.occ = net->occ_in;
+  bp.clear = net->occ_nodes; bp.n_clear = (int)net->L.n_occ_words;
+  bp.g = net->L.gin; bp.mode = builder_mode;
+  launch_builder(bp, s);
+
+  for (size_t i = 0; i < net->L.nodes.size(); ++i) {
+    NodePlan& n = net->L.nodes[i];
+    const evconv_node_desc& d = n.d;
+    const float* a = d.in0 < 0 ? net->dx : net->L.nodes[d.in0].out;
+    const uint64_t* occ_a = d.in0 < 0 ? net->occ_in : net->L.nodes[d.in0].occ;
+    const bool two = d.op == EVCONV_OP_ADD || d.op == EVCONV_OP_CONCAT;
+    const float* bptr = two ? (d.in1 < 0 ? net->dx : net->L.nodes[d.in1].out) : nullptr;
+    const uint64_t* occ_b = two ? (d.in1 < 0 ? net->occ_in : net->L.nodes[d.in1].occ) : nullptr;
+    switch (n.kernel) {
+      case kKernConvValu:
+      case kKernConvMfmaF32: {
+        ConvParams p;
+        p.in = a; p.occ_in = occ_a; p.w = n.w; p.bias = n.bias; p.z = n.z; p.out = n.out;
+        p.occ_out = n.occ; p.occ_touched = n.touched; p.gi = n.ga; p.go = n.go; p.c_out_pad = n.c_out_pad;
+        p.k = d.kh; p.stride = d.stride; p.pad = d.pad; p.act = d.act; p.dense = dense;
+        if (n.kernel == kKernConvMfmaF32) launch_conv_mfma_f32(p, s);
+        else launch_conv_valu(p, s);
+        break;
+      }
+      case kKernElementwise: {
+        EwParams p;
+        p.op = d.op == EVCONV_OP_ADD ? kEwAdd : d.op == EVCONV_OP_CONCAT ? kEwConcat :
+               d.op == EVCONV_OP_UPSAMPLE_BILINEAR2X ? kEwUp2x : kEwAct;
+        p.act = d.act; p.dense = dense; p.keeps_z = n.keeps_z; p.structural = n.structural;
+        p.ga = n.ga; p.gb = n.gb; p.go = n.go; p.a = a; p.occ_a = occ_a; p.b = bptr; p.occ_b = occ_b;
+        p.z = n.z; p.out = n.out; p.occ_out = n.occ; p.occ_touched = n.touched;
+        p.k = 1; p.stride = 1; p.pad = 0;
+        launch_elementwise(p, s);
+        break;
+      }
+      case kKernPool: {
+        EwParams p;
+        p.act = kActNone; p.dense = dense; p.keeps_z = 0; p.structural = 0;
+        p.ga = n.ga; p.gb = n.ga; p.a = a; p.occ_a = occ_a; p.b = nullptr; p.occ_b = nullptr;
+        p.out = nullptr; p.occ_out = nullptr; p.occ_touched = nullptr;
+        p.k = d.kh; p.stride = d.stride; p.pad = d.pad;
+        p.op = kEwPoolAcc; p.go = n.ga; p.z = n.pool_in;  // a_acc += x_inc on S_in
+        launch_elementwise(p, s);
+        p.op = kEwPoolMax; p.go = n.go; p.a = n.pool_in; p.z = n.z; p.out = n.out;
+        p.occ_out = n.occ; p.occ_touched = n.touched;
+        launch_elementwise(p, s);
+        break;
+      }
+      case kKernGap: {
+        GapParams p;
+        p.a = a; p.occ_a = occ_a; p.ga = n.ga; p.z = n.z; p.out = n.out; p.occ_out = n.occ;
+        p.occ_touched = n.touched; p.act = d.act; p.dense = dense;
+        launch_gap(p, s);
+        break;
+      }
+    }
+    if (d.is_output) {
+      IntegrateParams ip;
+      ip.delta = n.out; ip.occ = n.occ; ip.y = n.y; ip.dy = n.dy; ip.g = n.go;
+      ip.mode = pass == kPassStep ? kIntStep : pass == kPassReset ? kIntReset : kIntRecompute;
+      launch_integrate(ip, s);
+    }
+  }
+  if (pass == kPassReset) launch_fill_u64(net->occ_nodes, net->L.n_occ_words, 0, s);
+  launch_build_lists(net->sets_dev, (int)net->L.nodes.size() + 1, net->L.max_ty, s);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(net, e, "kernel launch");
+  return EVCONV_OK;
+}
+
+void fill_outputs(evconv_net* net, evconv_out* out) {
+  if (!out) return;
+  for (size_t j = 0; j < net->outputs.size(); ++j) {
+    const NodePlan& n = net->L.nodes[net->outputs[j]];
+    out[j].node = net->outputs[j];
+    out[j].c = n.go.c; out[j].h = n.go.h; out[j].w = n.go.w;
+    out[j].y = n.y; out[j].dy = n.dy; out[j].dy_idx = n.idx; out[j].dy_count = n.count;
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+evconv_status evconv_query_workspace(const evconv_net_desc* desc, size_t* bytes) {
+  if (!bytes) return EVCONV_ERR_INVALID_ARG;
+  Layout L;
+  evconv_status st = make_layout(desc, 0, false, &L, &g_create_error);
+  if (st != EVCONV_OK) return st;
+  *bytes = L.total;
+  return EVCONV_OK;
+}
+
+evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, size_t weight_bytes,
+                            void* workspace, size_t workspace_bytes, void* hip_stream, evconv_net** out) {
+  if (!out || !workspace || (!weights && weight_bytes)) {
+    g_create_error = "null argument";
+    return EVCONV_ERR_INVALID_ARG;
+  }
+  evconv_net* net = new evconv_net();
+  evconv_status st = make_layout(desc, weight_bytes, true, &net->L, &g_create_error);
+  if (st != EVCONV_OK) { delete net; return st; }
+  if (((uintptr_t)workspace & 255) || workspace_bytes < net->L.total) {
+    g_create_error = "workspace too small or not 256-byte aligned";
+    delete net;
+    return EVCONV_ERR_WORKSPACE;
+  }
+  Layout& L = net->L;
+  net->ws = (char*)workspace;
+  net->stream = (hipStream_t)hip_stream;
+  net->desc_nodes.assign(desc->nodes, desc->nodes + desc->n_nodes);
+  char* ws = net->ws;
+  net->x_prev = (float*)(ws + L.off_x_prev);
+  net->dx = (float*)(ws + L.off_dx);
+  net->occ_in = (uint64_t*)(ws + L.off_occ_in);
+  net->idx_in = (int32_t*)(ws + L.off_idx_in);
+  net->count_in = (int32_t*)(ws + L.off_count_in);
+  net->bitmap_in = (uint64_t*)(ws + L.off_bitmap_in);
+  net->occ_nodes = (uint64_t*)(ws + L.off_occ_nodes);
+  net->sets_dev = (SetDesc*)(ws + L.off_sets);
+
+  hipError_t e = hipMemsetAsync(ws, 0, L.total, net->stream);
+  if (e != hipSuccess) { g_create_error = std::string("hipMemsetAsync: ") + hipGetErrorString(e); delete net; return EVCONV_ERR_HIP; }
+
+  std::vector<SetDesc> sets(L.nodes.size() + 1);
+  sets[0] = SetDesc{net->occ_in, net->idx_in, net->count_in, net->bitmap_in, L.gin.h, L.gin.w, L.gin.tx, L.gin.ty};
+  std::vector<float> staging;
+  for (size_t i = 0; i < L.nodes.size(); ++i) {
+    NodePlan& n = L.nodes[i];
+    const size_t elems = (size_t)n.go.c * n.go.sites();
+    (void)elems;
+    n.z = (n.keeps_z || n.d.op == EVCONV_OP_MAXPOOL) ? (float*)(ws + n.off_z) : nullptr;
+    n.pool_in = n.d.op == EVCONV_OP_MAXPOOL ? (float*)(ws + n.off_pool) : nullptr;
+    n.out = (float*)(ws + n.off_out);
+    n.occ = (uint64_t*)(ws + n.off_occ);
+    n.touched = (uint64_t*)(ws + n.off_touched);
+    n.idx = (int32_t*)(ws + n.off_idx);
+    n.count = (int32_t*)(ws + n.off_count);
+    n.bitmap = (uint64_t*)(ws + n.off_bitmap);
+    if (n.d.is_output) {
+      n.y = (float*)(ws + n.off_y);
+      n.dy = (float*)(ws + n.off_dy);
+      net->outputs.push_back((int)i);
+    }
+    sets[i + 1] = SetDesc{n.occ, n.idx, n.count, n.bitmap, n.go.h, n.go.w, n.go.tx, n.go.ty};
+    if (n.d.op == EVCONV_OP_CONV2D || n.d.op == EVCONV_OP_LINEAR) {
+      // re-lay [c_out][c_in][k][k] as [tap][c_in][c_out_pad] (zero padded output channels)
+      const int k = n.d.kh, ci_n = n.d.c_in, co_n = n.d.c_out, cop = n.c_out_pad;
+      const float* src = (const float*)((const char*)weights + n.d.weight_off);
+      staging.assign((size_t)k * k * ci_n * cop, 0.0f);
+      for (int co = 0; co < co_n; ++co)
+        for (int ci = 0; ci < ci_n; ++ci)
+          for (int t = 0; t < k * k; ++t)
+            staging[((size_t)t * ci_n + ci) * cop + co] = src[((size_t)co * ci_n + ci) * k * k + t];
+      n.w = ws + n.off_w;
+      e = hipMemcpyAsync(n.w, staging.data(), staging.size() * 4, hipMemcpyHostToDevice, net->stream);
+      if (e == hipSuccess) e = hipStreamSynchronize(net->stream);  // staging is reused
+      if (e == hipSuccess && n.d.bias_off >= 0) {
+        n.bias = (float*)(ws + n.off_bias);
+        e = hipMemcpy(n.bias, (const char*)weights + n.d.bias_off, (size_t)co_n * 4, hipMemcpyHostToDevice);
+      }
+      if (e != hipSuccess) { g_create_error = std::string("weight upload: ") + hipGetErrorString(e); delete net; return EVCONV_ERR_HIP; }
+      ConvParams probe;
+      probe.gi = n.ga; probe.go = n.go; probe.k = k; probe.stride = n.d.stride; probe.c_out_pad = cop;
+      if (n.d.wdtype == EVCONV_F32 && conv_mfma_f32_supported(probe)) n.kernel = kKernConvMfmaF32;
+    }
+  }
+  e = hipMemcpyAsync(net->sets_dev, sets.data(), sets.size() * sizeof(SetDesc), hipMemcpyHostToDevice, net->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(net->stream);
+  if (e != hipSuccess) { g_create_error = std::string("upload: ") + hipGetErrorString(e); delete net; return EVCONV_ERR_HIP; }
+  if (net->outputs.empty()) { g_create_error = "no output node"; delete net; return EVCONV_ERR_BAD_DESC; }
+  *out = net;
+  return EVCONV_OK;
+}
+
+int32_t evconv_num_outputs(const evconv_net* net) { return net ? (int32_t)net->outputs.size() : 0; }
+
+evconv_status evconv_reset(evconv_net* net, const float* x0, evconv_out* out) {
+  if (!net) return EVCONV_ERR_INVALID_ARG;
+  if (!x0) { net->err = "null x0"; return EVCONV_ERR_INVALID_ARG; }
+  evconv_status st = run_pass(net, x0, kBuildReset, kPassReset);
+  if (st != EVCONV_OK) return st;
+  net->has_state = true;
+  fill_outputs(net, out);
+  return EVCONV_OK;
+}
+
+static evconv_status step_common(evconv_net* net, const float* in, int builder_mode, evconv_out* out) {
+  if (!net) return EVCONV_ERR_INVALID_ARG;
+  if (!in) { net->err = "null input"; return EVCONV_ERR_INVALID_ARG; }
+  if (!net->has_state) { net->err = "step before reset"; return EVCONV_ERR_STATE; }
+  evconv_status st;
+  if (net->mode == EVCONV_MODE_DENSE_RECOMPUTE) {
+    // regular forward pass of x(n): the builder first folds the input into x_prev (and, for a
+    // supplied increment, adds it), then the dense pass reads the updated frame
+    st = run_pass(net, in, builder_mode == kBuildFrame ? kBuildReset : kBuildIncrementDense, kPassRecompute);
+  } else {
+    st = run_pass(net, in, builder_mode, kPassStep);
+  }
+  if (st != EVCONV_OK) return st;
+  fill_outputs(net, out);
+  return EVCONV_OK;
+}
+
+evconv_status evconv_step(evconv_net* net, const float* increment, evconv_out* out) {
+  return step_common(net, increment, kBuildIncrement, out);
+}
+
+evconv_status evconv_step_frame(evconv_net* net, const float* x_t, evconv_out* out) {
+  return step_common(net, x_t, kBuildFrame, out);
+}
+
+evconv_status evconv_destroy(evconv_net* net) {
+  if (!net) return EVCONV_OK;
+  hipStreamSynchronize(net->stream);
+  delete net;
+  return EVCONV_OK;
+}
+
+evconv_status evconv_set_mode(evconv_net* net, int32_t mode) {
+  if (!net) return EVCONV_ERR_INVALID_ARG;
+  if (mode != EVCONV_MODE_INCREMENTAL && mode != EVCONV_MODE_DENSE_RECOMPUTE) {
+    net->err = "bad mode";
+    return EVCONV_ERR_INVALID_ARG;
+  }
+  net->mode = mode;
+  return EVCONV_OK;
+}
+
+evconv_status evconv_node_shape(const evconv_net* net, int32_t node, int32_t* chw) {
+  if (!net || !chw || node < -1 || node >= (int)net->L.nodes.size()) return EVCONV_ERR_INVALID_ARG;
+  const Geo& g = node < 0 ? net->L.gin : net->L.nodes[node].go;
+  chw[0] = g.c; chw[1] = g.h; chw[2] = g.w;
+  return EVCONV_OK;
+}
+
+evconv_status evconv_get_state(evconv_net* net, int32_t node, int32_t kind, void* dst, size_t bytes) {
+  if (!net) return EVCONV_ERR_INVALID_ARG;
+  if (!dst || node < -1 || node >= (int)net->L.nodes.size()) { net->err = "bad node or null dst"; return EVCONV_ERR_INVALID_ARG; }
+  const Geo& g = node < 0 ? net->L.gin : net->L.nodes[node].go;
+  const NodePlan* n = node < 0 ? nullptr : &net->L.nodes[node];
+  const void* src = nullptr;
+  size_t need = 0;
+  const size_t elems = (size_t)g.c * g.sites();
+  switch (kind) {
+    case EVCONV_STATE_Z: src = n ? n->z : nullptr; need = elems * 4; break;
+    case EVCONV_STATE_DY: src = n ? (const void*)n->out : (const void*)net->dx; need = elems * 4; break;
+    case EVCONV_STATE_IDX: src = n ? n->idx : net->idx_in; need = (size_t)g.sites() * 4; break;
+    case EVCONV_STATE_COUNT: src = n ? n->count : net->count_in; need = 4; break;
+    case EVCONV_STATE_BITMAP: src = n ? n->bitmap : net->bitmap_in; need = ((size_t)g.tiles() + 63) / 64 * 8; break;
+    case EVCONV_STATE_OCC: src = n ? n->occ : net->occ_in; need = (size_t)g.tiles() * 8; break;
+    case EVCONV_STATE_OCC_TOUCHED: src = n ? n->touched : net->occ_in; need = (size_t)g.tiles() * 8; break;
+    case EVCONV_STATE_X_PREV: src = n ? nullptr : net->x_prev; need = elems * 4; break;
+    default: net->err = "bad state kind"; return EVCONV_ERR_INVALID_ARG;
+  }
+  if (!src) { net->err = "this node keeps no such state"; return EVCONV_ERR_INVALID_ARG; }
+  if (bytes != need) { net->err = "size mismatch: expected " + std::to_string(need) + " bytes"; return EVCONV_ERR_INVALID_ARG; }
+  hipError_t e = hipStreamSynchronize(net->stream);
+  if (e == hipSuccess) e = hipMemcpy(dst, src, need, hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return hip_fail(net, e, "get_state");
+  return EVCONV_OK;
+}
+
+evconv_status evconv_get_stats(evconv_net* net, int32_t node, evconv_layer_stats* out) {
+  if (!net || !out || node < 0 || node >= (int)net->L.nodes.size()) return EVCONV_ERR_INVALID_ARG;
+  const NodePlan& n = net->L.nodes[node];
+  const int tiles = n.go.tiles();
+  std::vector<uint64_t> words(2 * (size_t)tiles);
+  hipError_t e = hipStreamSynchronize(net->stream);
+  if (e == hipSuccess) e = hipMemcpy(words.data(), n.occ, words.size() * 8, hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return hip_fail(net, e, "get_stats");
+  memset(out, 0, sizeof *out);
+  out->n_sites = n.go.sites();
+  out->n_tiles = tiles;
+  for (int t = 0; t < tiles; ++t) {
+    out->n_active += __builtin_popcountll(words[t]);
+    out->n_touched += __builtin_popcountll(words[tiles + t]);
+    out->n_touched_tiles += words[tiles + t] != 0;
+  }
+  if (n.d.op == EVCONV_OP_CONV2D || n.d.op == EVCONV_OP_LINEAR) {
+    const double per_site = 2.0 * n.d.kh * n.d.kh * n.d.c_in * n.d.c_out;
+    out->flops_dense = per_site * n.go.sites();
+    out->flops_executed = per_site * 64.0 * out->n_touched_tiles;
+  }
+  return EVCONV_OK;
+}
+
+const char* evconv_node_kernel(const evconv_net* net, int32_t node) {
+  if (!net || node < 0 || node >= (int)net->L.nodes.size()) return "";
+  return kKernelNames[net->L.nodes[node].kernel];
+}
+
+const char* evconv_last_error(const evconv_net* net) { return net ? net->err.c_str() : g_create_error.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,105 @@
+// Internal interface between the host-side planner (evconv_api.hip) and the gfx950 kernels.
+// Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace evk {
+
+// Mask tile: 8 x 8 sites = 64 = one wavefront, so one ballot yields a tile's occupancy word.
+constexpr int kTile = 8;
+
+// Geometry of one H x W x C tensor and of its tile grid.
+struct Geo {
+  int h, w, c;
+  int tx, ty;  // tiles per row / per column
+  __host__ __device__ int sites() const { return h * w; }
+  __host__ __device__ int tiles() const { return tx * ty; }
+};
+inline Geo make_geo(int c, int h, int w) {
+  Geo g;
+  g.h = h; g.w = w; g.c = c;
+  g.tx = (w + kTile - 1) / kTile;
+  g.ty = (h + kTile - 1) / kTile;
+  return g;
+}
+
+enum Act { kActNone = 0, kActRelu = 1, kActSigmoid = 2 };
+
+// ---- increment builder (Eq.1 + mask) ---------------------------------------------------
+enum BuilderMode { kBuildFrame = 0, kBuildIncrement = 1, kBuildReset = 2, kBuildIncrementDense = 3 };
+struct BuilderParams {
+  const float* in;    // C x H x W: frame x(n), increment, or x0
+  float* x_prev;      // C x H x W cached previous frame
+  float* dx;          // H x W x C increment (full frame in reset mode)
+  uint64_t* occ;      // per-tile occupancy of the input increment
+  uint64_t* clear;    // words to zero before the layers run (all nodes' occupancy), or null
+  int n_clear;
+  Geo g;
+  int mode;
+};
+void launch_builder(const BuilderParams& p, hipStream_t s);
+
+// ---- sparse incremental convolution (Eq.10 at touched tiles, fused Eq.12-14) ------------
+struct ConvParams {
+  const float* in;          // H x W x C increment of the input node (full values if dense)
+  const uint64_t* occ_in;   // its occupancy words
+  const void* w;            // re-laid weights [k*k][c_in][c_out_pad] (fp32 or bf16)
+  const float* bias;        // fp32 [c_out] or null; used by the dense pass only
+  float* z;                 // H x W x C accumulated pre-activation
+  float* out;               // H x W x C output increment (value in dense mode)
+  uint64_t* occ_out;        // S_out words (pre-zeroed; OR-ed in)
+  uint64_t* occ_touched;    // T words
+  Geo gi, go;
+  int c_out_pad;
+  int k, stride, pad, act;
+  int dense;                // 1: regular forward pass (all sites, z overwritten with bias)
+};
+void launch_conv_valu(const ConvParams& p, hipStream_t s);
+// fp32 MFMA variant; requires c_in % 16 == 0 and c_out % 32 == 0
+bool conv_mfma_f32_supported(const ConvParams& p);
+void launch_conv_mfma_f32(const ConvParams& p, hipStream_t s);
+
+// ---- elementwise / structural increment operators ---------------------------------------
+enum EwOp { kEwAdd = 0, kEwAct, kEwConcat, kEwUp2x, kEwPoolAcc, kEwPoolMax };
+struct EwParams {
+  int op, act, dense, keeps_z, structural;
+  Geo ga, gb, go;
+  const float* a; const uint64_t* occ_a;
+  const float* b; const uint64_t* occ_b;
+  float* z;                 // accumulated tensor (pool: cached window max; pool-acc: pooled input)
+  float* out;
+  uint64_t* occ_out; uint64_t* occ_touched;
+  int k, stride, pad;       // pooling window
+};
+void launch_elementwise(const EwParams& p, hipStream_t s);
+
+// ---- global average pool -----------------------------------------------------------------
+struct GapParams {
+  const float* a; const uint64_t* occ_a; Geo ga;
+  float* z; float* out; uint64_t* occ_out; uint64_t* occ_touched;
+  int act, dense;
+};
+void launch_gap(const GapParams& p, hipStream_t s);
+
+// ---- output integration (Eq.2) -------------------------------------------------------------
+enum IntegrateMode { kIntStep = 0, kIntReset = 1, kIntRecompute = 2 };
+struct IntegrateParams {
+  const float* delta;       // H x W x C node output (increment, or value in reset/recompute)
+  const uint64_t* occ;      // S_out words
+  float* y; float* dy;      // C x H x W
+  Geo g; int mode;
+};
+void launch_integrate(const IntegrateParams& p, hipStream_t s);
+
+// ---- ordered compaction of occupancy words into ascending site lists -------------------------
+struct SetDesc {
+  const uint64_t* occ; int32_t* idx; int32_t* count; uint64_t* bitmap;
+  int h, w, tx, ty;
+};
+void launch_build_lists(const SetDesc* sets_dev, int n_sets, int max_ty, hipStream_t s);
+
+void launch_fill_u64(uint64_t* p, size_t n, uint64_t v, hipStream_t s);
+
+}  // namespace evk

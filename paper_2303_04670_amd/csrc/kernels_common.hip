@@ -1,0 +1,430 @@
+// gfx950 kernels: increment builder, elementwise / structural increment operators, global
+// average pool, output integration, ordered list compaction.
+//
+// Conventions: tensors are H x W x C fp32; a tile is 8 x 8 sites and its occupancy word has
+// bit (y%8)*8 + x%8 set for an active site; tiles are row-major.  Nothing here uses
+// floating-point atomics: every accumulated element has exactly one writer, so results are
+// run-to-run bit-reproducible.
+#include "evconv_kernels.h"
+
+namespace evk {
+
+namespace {
+
+__device__ __forceinline__ bool occ_bit(const uint64_t* __restrict__ occ, int tx, int y, int x) {
+  uint64_t w = occ[(y >> 3) * tx + (x >> 3)];
+  return (w >> (((y & 7) << 3) | (x & 7))) & 1ull;
+}
+
+__device__ __forceinline__ float apply_act(int act, float v) {
+  if (act == kActRelu) return fmaxf(v, 0.0f);
+  if (act == kActSigmoid) return 1.0f / (1.0f + expf(-v));
+  return v;
+}
+
+// in-bounds mask of tile (tile_y, tile_x) of an h x w grid, bit layout as the occupancy words
+__device__ __forceinline__ uint64_t inbounds_word(int h, int w, int tile_y, int tile_x) {
+  int rows = min(8, h - tile_y * 8), cols = min(8, w - tile_x * 8);
+  uint64_t row = (cols >= 8) ? 0xffull : ((1ull << cols) - 1);
+  uint64_t m = 0;
+  for (int r = 0; r < rows; ++r) m |= row << (8 * r);
+  return m;
+}
+
+}  // namespace
+
+// =============================================================================== builder
+// One workgroup = 8 wavefronts = an 8-row x 64-column strip (8 tiles).  Wave r reads row r with
+// 256-byte coalesced loads per channel; its ballot is the 64-column activity of that row.  The
+// eight ballots are transposed through LDS into eight tile occupancy words.
+__global__ __launch_bounds__(512) void builder_kernel(BuilderParams p) {
+  __shared__ uint64_t s_rows[8];
+  const int lane = threadIdx.x & 63;
+  const int r = threadIdx.x >> 6;
+  const int y = blockIdx.y * 8 + r;
+  const int x = blockIdx.x * 64 + lane;
+  const int hw = p.g.h * p.g.w;
+  const bool inb = (y < p.g.h) && (x < p.g.w);
+  bool any = false;
+  if (inb) {
+    const int site = y * p.g.w + x;
+    for (int c = 0; c < p.g.c; ++c) {
+      const int e = c * hw + site;
+      float d;
+      if (p.mode == kBuildFrame) {
+        const float xt = p.in[e];
+        d = xt - p.x_prev[e];          // Eq.1: one binary32 subtraction
+        p.x_prev[e] = xt;
+      } else if (p.mode == kBuildIncrement) {
+        d = p.in[e];
+        p.x_prev[e] = p.x_prev[e] + d;
+      } else if (p.mode == kBuildIncrementDense) {
+        d = p.x_prev[e] + p.in[e];     // dense recompute of a supplied increment: emit x(n)
+        p.x_prev[e] = d;
+      } else {
+        d = p.in[e];
+        p.x_prev[e] = d;
+      }
+      p.dx[(size_t)site * p.g.c + c] = d;
+      any |= (d != 0.0f);
+    }
+  }
+  const uint64_t row_mask = __ballot(any);
+  if (lane == 0) s_rows[r] = row_mask;
+  __syncthreads();
+  if (threadIdx.x < 8) {
+    const int j = threadIdx.x;
+    const int tile_x = blockIdx.x * 8 + j;
+    if (tile_x < p.g.tx) {
+      uint64_t word = 0;
+      for (int rr = 0; rr < 8; ++rr) word |= ((s_rows[rr] >> (8 * j)) & 0xffull) << (8 * rr);
+      if (p.mode >= kBuildReset) word = 0;
+      p.occ[blockIdx.y * p.g.tx + tile_x] = word;
+    }
+  }
+  // clear the per-node occupancy words that the layer kernels OR into
+  if (p.clear) {
+    const int nthreads = gridDim.x * gridDim.y * blockDim.x;
+    const int gtid = (blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x;
+    for (int i = gtid; i < p.n_clear; i += nthreads) p.clear[i] = 0;
+  }
+}
+
+void launch_builder(const BuilderParams& p, hipStream_t s) {
+  dim3 grid((p.g.w + 63) / 64, (p.g.h + 7) / 8);
+  hipLaunchKernelGGL(builder_kernel, grid, dim3(512), 0, s, p);
+}
+
+// =============================================================================== elementwise
+// One workgroup per output tile.  Wave 0 derives the tile's touched word and the list of
+// touched sites; then the 256 threads walk (touched site, channel vector) pairs with the
+// channel index fastest, so global accesses are contiguous runs of C floats per site.
+template <int VEC>
+__global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
+  __shared__ int s_sites[64];
+  __shared__ unsigned s_flags[2];
+  __shared__ uint64_t s_word, s_wa, s_wb;
+  const int tid = threadIdx.x;
+  const int tile = blockIdx.x;
+  const int tile_y = tile / p.go.tx, tile_x = tile - tile_y * p.go.tx;
+
+  if (tid < 64) {
+    const int ly = tid >> 3, lx = tid & 7;
+    const int oy = tile_y * 8 + ly, ox = tile_x * 8 + lx;
+    const bool inb = oy < p.go.h && ox < p.go.w;
+    bool t = false;
+    uint64_t wa = 0, wb = 0;
+    if (p.dense) {
+      t = inb;
+      wa = wb = ~0ull;
+    } else if (p.op == kEwAdd || p.op == kEwConcat) {
+      wa = p.occ_a[tile];
+      wb = p.occ_b[tile];
+      t = ((wa | wb) >> tid) & 1ull;
+    } else if (p.op == kEwAct || p.op == kEwPoolAcc) {
+      wa = p.occ_a[tile];
+      t = (wa >> tid) & 1ull;
+    } else if (p.op == kEwUp2x) {
+      if (inb) {
+        const int iy = oy >> 1, ix = ox >> 1;
+        const int y0 = (oy & 1) ? iy : max(iy - 1, 0), y1 = (oy & 1) ? min(iy + 1, p.ga.h - 1) : iy;
+        const int x0 = (ox & 1) ? ix : max(ix - 1, 0), x1 = (ox & 1) ? min(ix + 1, p.ga.w - 1) : ix;
+        t = occ_bit(p.occ_a, p.ga.tx, y0, x0) | occ_bit(p.occ_a, p.ga.tx, y0, x1) |
+            occ_bit(p.occ_a, p.ga.tx, y1, x0) | occ_bit(p.occ_a, p.ga.tx, y1, x1);
+      }
+    } else {  // kEwPoolMax: windows that contain an active input site
+      if (inb) {
+        for (int ky = 0; ky < p.k; ++ky) {
+          const int iy = oy * p.stride - p.pad + ky;
+          if ((unsigned)iy >= (unsigned)p.ga.h) continue;
+          for (int kx = 0; kx < p.k; ++kx) {
+            const int ix = ox * p.stride - p.pad + kx;
+            if ((unsigned)ix >= (unsigned)p.ga.w) continue;
+            t |= occ_bit(p.occ_a, p.ga.tx, iy, ix);
+          }
+        }
+      }
+    }
+    const uint64_t word = __ballot(t);
+    if (t) s_sites[__popcll(word & ((1ull << tid) - 1))] = tid;
+    if (tid == 0) { s_word = word; s_wa = wa; s_wb = wb; s_flags[0] = 0; s_flags[1] = 0; }
+  }
+  __syncthreads();
+  const uint64_t word = s_word;
+  if (word == 0) return;
+  const uint64_t wa = s_wa, wb = s_wb;
+  const int n_sites = __popcll(word);
+  const int C = p.go.c;
+  const int cv = C / VEC;
+  const int total = n_sites * cv;
+
+  for (int e = tid; e < total; e += 256) {
+    const int r = e / cv, v = e - r * cv;
+    const int site = s_sites[r];
+    const int oy = tile_y * 8 + (site >> 3), ox = tile_x * 8 + (site & 7);
+    const size_t q = (size_t)oy * p.go.w + ox;
+    const int c = v * VEC;
+    float lin[VEC];
+    if (p.op == kEwAdd) {
+      const bool on_a = (wa >> site) & 1ull, on_b = (wb >> site) & 1ull;
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) {
+        const float va = on_a ? p.a[q * C + c + i] : 0.0f;
+        const float vb = on_b ? p.b[q * C + c + i] : 0.0f;
+        lin[i] = va + vb;
+      }
+    } else if (p.op == kEwAct || p.op == kEwPoolAcc) {
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) lin[i] = p.a[q * C + c + i];
+    } else if (p.op == kEwConcat) {
+      const bool on_a = (wa >> site) & 1ull, on_b = (wb >> site) & 1ull;
+      const int ca = p.ga.c, cb = p.gb.c;
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) {
+        const int cc = c + i;
+        lin[i] = cc < ca ? (on_a ? p.a[q * ca + cc] : 0.0f) : (on_b ? p.b[q * cb + cc - ca] : 0.0f);
+      }
+    } else if (p.op == kEwUp2x) {
+      const int iy = oy >> 1, ix = ox >> 1;
+      const int y0 = (oy & 1) ? iy : max(iy - 1, 0), y1 = (oy & 1) ? min(iy + 1, p.ga.h - 1) : iy;
+      const int x0 = (ox & 1) ? ix : max(ix - 1, 0), x1 = (ox & 1) ? min(ix + 1, p.ga.w - 1) : ix;
+      const float wy0 = (oy & 1) ? 0.75f : 0.25f, wy1 = 1.0f - wy0;
+      const float wx0 = (ox & 1) ? 0.75f : 0.25f, wx1 = 1.0f - wx0;
+      const bool o00 = p.dense || occ_bit(p.occ_a, p.ga.tx, y0, x0);
+      const bool o01 = p.dense || occ_bit(p.occ_a, p.ga.tx, y0, x1);
+      const bool o10 = p.dense || occ_bit(p.occ_a, p.ga.tx, y1, x0);
+      const bool o11 = p.dense || occ_bit(p.occ_a, p.ga.tx, y1, x1);
+      const size_t b00 = ((size_t)y0 * p.ga.w + x0) * C + c, b01 = ((size_t)y0 * p.ga.w + x1) * C + c;
+      const size_t b10 = ((size_t)y1 * p.ga.w + x0) * C + c, b11 = ((size_t)y1 * p.ga.w + x1) * C + c;
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) {
+        const float v00 = o00 ? p.a[b00 + i] : 0.0f, v01 = o01 ? p.a[b01 + i] : 0.0f;
+        const float v10 = o10 ? p.a[b10 + i] : 0.0f, v11 = o11 ? p.a[b11 + i] : 0.0f;
+        lin[i] = wy0 * (wx0 * v00 + wx1 * v01) + wy1 * (wx0 * v10 + wx1 * v11);
+      }
+    } else {  // kEwPoolMax: p.a is the accumulated pool input, p.z the cached window maximum
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) lin[i] = -INFINITY;
+      for (int ky = 0; ky < p.k; ++ky) {
+        const int iy = oy * p.stride - p.pad + ky;
+        if ((unsigned)iy >= (unsigned)p.ga.h) continue;
+        for (int kx = 0; kx < p.k; ++kx) {
+          const int ix = ox * p.stride - p.pad + kx;
+          if ((unsigned)ix >= (unsigned)p.ga.w) continue;
+          const size_t bi = ((size_t)iy * p.ga.w + ix) * C + c;
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) lin[i] = fmaxf(lin[i], p.a[bi + i]);
+        }
+      }
+    }
+
+    bool nz = false;
+    if (p.op == kEwPoolAcc) {
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) p.z[q * C + c + i] = p.dense ? lin[i] : p.z[q * C + c + i] + lin[i];
+      continue;
+    }
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+      float o;
+      if (p.op == kEwPoolMax) {
+        const float m_old = p.z[q * C + c + i];
+        p.z[q * C + c + i] = lin[i];
+        o = p.dense ? lin[i] : lin[i] - m_old;
+      } else if (p.keeps_z) {
+        if (p.dense) {
+          p.z[q * C + c + i] = lin[i];
+          o = apply_act(p.act, lin[i]);
+        } else {
+          const float z_old = p.z[q * C + c + i];
+          const float z_new = z_old + lin[i];
+          p.z[q * C + c + i] = z_new;
+          o = (p.act == kActNone) ? lin[i] : apply_act(p.act, z_new) - apply_act(p.act, z_old);
+        }
+      } else {
+        o = lin[i];
+      }
+      p.out[q * C + c + i] = o;
+      nz |= (o != 0.0f);
+    }
+    if (nz && !p.structural) atomicOr(&s_flags[site >> 5], 1u << (site & 31));
+  }
+  if (p.op == kEwPoolAcc) return;
+  __syncthreads();
+  if (tid == 0) {
+    const uint64_t flags = (uint64_t)s_flags[0] | ((uint64_t)s_flags[1] << 32);
+    p.occ_touched[tile] = word;
+    p.occ_out[tile] = (p.structural || p.dense) ? word : flags;
+  }
+}
+
+void launch_elementwise(const EwParams& p, hipStream_t s) {
+  bool vec4 = (p.go.c % 4) == 0;
+  if (p.op == kEwConcat) vec4 = vec4 && (p.ga.c % 4) == 0;
+  dim3 grid(p.go.tiles());
+  if (vec4) hipLaunchKernelGGL(elementwise_kernel<4>, grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL(elementwise_kernel<1>, grid, dim3(256), 0, s, p);
+}
+
+// =============================================================================== global avg pool
+// One thread per channel; active sites are visited in tile order (ascending tiles, ascending
+// bits), a fixed order, so the fp32 sum is reproducible.
+__global__ __launch_bounds__(256) void gap_kernel(GapParams p) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  const int C = p.ga.c;
+  bool any = false;
+  float sum = 0.0f;
+  for (int t = 0; t < p.ga.tiles(); ++t) {
+    const int tile_y = t / p.ga.tx, tile_x = t - tile_y * p.ga.tx;
+    uint64_t w = p.dense ? inbounds_word(p.ga.h, p.ga.w, tile_y, tile_x) : p.occ_a[t];
+    any |= (w != 0);
+    while (w) {
+      const int bit = __ffsll((unsigned long long)w) - 1;
+      w &= w - 1;
+      const int y = tile_y * 8 + (bit >> 3), x = tile_x * 8 + (bit & 7);
+      if (c < C) sum += p.a[((size_t)y * p.ga.w + x) * C + c];
+    }
+  }
+  if (!any) return;
+  bool nz = false;
+  if (c < C) {
+    const float lin = sum / (float)(p.ga.h * p.ga.w);
+    float o;
+    if (p.dense) {
+      p.z[c] = lin;
+      o = apply_act(p.act, lin);
+    } else {
+      const float z_old = p.z[c], z_new = z_old + lin;
+      p.z[c] = z_new;
+      o = (p.act == kActNone) ? lin : apply_act(p.act, z_new) - apply_act(p.act, z_old);
+    }
+    p.out[c] = o;
+    nz = (o != 0.0f);
+  }
+  const bool structural = (p.act == kActNone) || p.dense;
+  const uint64_t b = __ballot(nz);
+  if ((threadIdx.x & 63) == 0) {
+    if (structural) { if (c == 0) p.occ_out[0] = 1ull; }
+    else if (b) atomicOr((unsigned long long*)p.occ_out, 1ull);
+    if (c == 0) p.occ_touched[0] = 1ull;
+  }
+}
+
+void launch_gap(const GapParams& p, hipStream_t s) {
+  hipLaunchKernelGGL(gap_kernel, dim3((p.ga.c + 255) / 256), dim3(256), 0, s, p);
+}
+
+// =============================================================================== Eq.2
+__global__ __launch_bounds__(256) void integrate_kernel(IntegrateParams p) {
+  const int site = blockIdx.x * 256 + threadIdx.x;
+  const int hw = p.g.h * p.g.w;
+  if (site >= hw) return;
+  const int y = site / p.g.w, x = site - y * p.g.w;
+  const bool on = p.mode != kIntStep || occ_bit(p.occ, p.g.tx, y, x);
+  for (int c = 0; c < p.g.c; ++c) {
+    const int e = c * hw + site;
+    const float v = on ? p.delta[(size_t)site * p.g.c + c] : 0.0f;
+    if (p.mode == kIntStep) {
+      if (on) p.y[e] += v;
+      p.dy[e] = v;
+    } else if (p.mode == kIntReset) {
+      p.y[e] = v;
+      p.dy[e] = 0.0f;
+    } else {
+      p.dy[e] = v - p.y[e];
+      p.y[e] = v;
+    }
+  }
+}
+
+void launch_integrate(const IntegrateParams& p, hipStream_t s) {
+  hipLaunchKernelGGL(integrate_kernel, dim3((p.g.sites() + 255) / 256), dim3(256), 0, s, p);
+}
+
+// =============================================================================== ordered lists
+// Workgroup (strip, set): strip = one row of tiles = 8 image rows.  Its first list position is
+// the number of active sites in all earlier strips (a reduction over their occupancy words);
+// inside the strip wave r owns image row r and scans the per-tile byte popcounts with a
+// wave-wide prefix sum, so indices come out strictly ascending in y*W + x.
+__global__ __launch_bounds__(512) void build_lists_kernel(const SetDesc* sets) {
+  __shared__ int s_part[8];
+  __shared__ int s_rowcnt[8];
+  const SetDesc d = sets[blockIdx.y];
+  const int strip = blockIdx.x;
+  if (strip >= d.ty) return;
+  const int tid = threadIdx.x, lane = tid & 63, r = tid >> 6;
+
+  int cnt = 0;
+  for (int t = tid; t < strip * d.tx; t += 512) cnt += __popcll(d.occ[t]);
+  for (int o = 32; o > 0; o >>= 1) cnt += __shfl_down(cnt, o);
+  if (lane == 0) s_part[r] = cnt;
+
+  // row r of this strip: per-tile 8-bit masks
+  int row_total = 0;
+  for (int j0 = 0; j0 < d.tx; j0 += 64) {
+    const int j = j0 + lane;
+    const unsigned byte = j < d.tx ? (unsigned)((d.occ[strip * d.tx + j] >> (8 * r)) & 0xffull) : 0u;
+    int c = __popc(byte);
+    for (int o = 32; o > 0; o >>= 1) c += __shfl_down(c, o);
+    row_total += __shfl(c, 0);
+  }
+  if (lane == 0) s_rowcnt[r] = row_total;
+  __syncthreads();
+
+  int base = 0;
+  for (int i = 0; i < 8; ++i) base += s_part[i];
+  int strip_total = 0;
+  for (int i = 0; i < 8; ++i) {
+    if (i < r) base += s_rowcnt[i];
+    strip_total += s_rowcnt[i];
+  }
+  const int total_before = base;  // list position of the first active site of row r
+  int running = total_before;
+  const int y = strip * 8 + r;
+  for (int j0 = 0; j0 < d.tx; j0 += 64) {
+    const int j = j0 + lane;
+    unsigned byte = j < d.tx ? (unsigned)((d.occ[strip * d.tx + j] >> (8 * r)) & 0xffull) : 0u;
+    const int c = __popc(byte);
+    int incl = c;  // inclusive wave scan
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_up(incl, o);
+      if (lane >= o) incl += v;
+    }
+    int pos = running + incl - c;
+    while (byte) {
+      const int bit = __ffs(byte) - 1;
+      byte &= byte - 1;
+      d.idx[pos++] = y * d.w + j * 8 + bit;
+    }
+    running += __shfl(incl, 63);
+  }
+  if (strip == d.ty - 1 && tid == 0) {
+    int s = 0;
+    for (int i = 0; i < 8; ++i) s += s_part[i];
+    *d.count = s + strip_total;
+  }
+  if (strip == 0) {  // tile bitmap: one ballot per 64 tiles
+    const int n_tiles = d.tx * d.ty;
+    for (int w0 = r * 64; w0 < n_tiles; w0 += 512) {
+      const int t = w0 + lane;
+      const uint64_t b = __ballot(t < n_tiles && d.occ[t] != 0);
+      if (lane == 0) d.bitmap[w0 >> 6] = b;
+    }
+  }
+}
+
+void launch_build_lists(const SetDesc* sets_dev, int n_sets, int max_ty, hipStream_t s) {
+  hipLaunchKernelGGL(build_lists_kernel, dim3(max_ty, n_sets), dim3(512), 0, s, sets_dev);
+}
+
+__global__ void fill_u64_kernel(uint64_t* p, size_t n, uint64_t v) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+void launch_fill_u64(uint64_t* p, size_t n, uint64_t v, hipStream_t s) {
+  if (!n) return;
+  int blocks = (int)((n + 255) / 256);
+  if (blocks > 1024) blocks = 1024;
+  hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks), dim3(256), 0, s, p, n, v);
+}
+
+}  // namespace evk

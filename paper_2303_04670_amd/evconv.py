@@ -1,0 +1,239 @@
+"""Thin ctypes binding of libevconv.so (the C ABI of include/evconv.h).
+
+Argument marshalling only: every step of the incremental path runs inside the HIP library.
+PyTorch appears solely as the owner of device memory (the workspace, inputs) and of the stream.
+There is no CPU fallback: if the library is missing, importing the entry points raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libevconv.so")
+
+ABI_VERSION = 1
+OK = 0
+STATUS_NAMES = ["OK", "ERR_INVALID_ARG", "ERR_BAD_DESC", "ERR_SHAPE", "ERR_STATE", "ERR_WORKSPACE",
+                "ERR_HIP", "ERR_UNSUPPORTED"]
+(ERR_INVALID_ARG, ERR_BAD_DESC, ERR_SHAPE, ERR_STATE, ERR_WORKSPACE, ERR_HIP, ERR_UNSUPPORTED) = range(1, 8)
+MODE_INCREMENTAL, MODE_DENSE_RECOMPUTE = 0, 1
+(STATE_Z, STATE_DY, STATE_IDX, STATE_COUNT, STATE_BITMAP, STATE_OCC, STATE_OCC_TOUCHED,
+ STATE_X_PREV) = range(8)
+
+EXPORTS = ["evconv_query_workspace", "evconv_create", "evconv_num_outputs", "evconv_reset", "evconv_step",
+           "evconv_step_frame", "evconv_destroy", "evconv_set_mode", "evconv_node_shape", "evconv_get_state",
+           "evconv_get_stats", "evconv_node_kernel", "evconv_last_error"]
+
+
+class NodeDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("op", "act", "in0", "in1", "c_in", "c_out", "kh", "kw", "stride", "pad", "wdtype", "is_output")] + \
+               [("weight_off", ctypes.c_int64), ("bias_off", ctypes.c_int64)]
+
+
+class NetDesc(ctypes.Structure):
+    _fields_ = [("abi_version", ctypes.c_int32), ("n_nodes", ctypes.c_int32),
+                ("nodes", ctypes.POINTER(NodeDesc)),
+                ("in_c", ctypes.c_int32), ("in_h", ctypes.c_int32), ("in_w", ctypes.c_int32),
+                ("tile_h", ctypes.c_int32), ("tile_w", ctypes.c_int32),
+                ("sparsify_tp", ctypes.c_float), ("n_streams", ctypes.c_int32)]
+
+
+class Out(ctypes.Structure):
+    _fields_ = [("node", ctypes.c_int32), ("c", ctypes.c_int32), ("h", ctypes.c_int32), ("w", ctypes.c_int32),
+                ("y", ctypes.c_void_p), ("dy", ctypes.c_void_p), ("dy_idx", ctypes.c_void_p),
+                ("dy_count", ctypes.c_void_p)]
+
+
+class LayerStats(ctypes.Structure):
+    _fields_ = [("n_sites", ctypes.c_int32), ("n_tiles", ctypes.c_int32), ("n_touched", ctypes.c_int32),
+                ("n_active", ctypes.c_int32), ("n_touched_tiles", ctypes.c_int32),
+                ("flops_executed", ctypes.c_double), ("flops_dense", ctypes.c_double)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libevconv.so.  Raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2303_04670_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32 = ctypes.c_void_p, ctypes.c_int32
+        L.evconv_query_workspace.argtypes = [ctypes.POINTER(NetDesc), ctypes.POINTER(ctypes.c_size_t)]
+        L.evconv_create.argtypes = [ctypes.POINTER(NetDesc), vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp,
+                                    ctypes.POINTER(vp)]
+        L.evconv_num_outputs.argtypes = [vp]
+        L.evconv_reset.argtypes = [vp, vp, ctypes.POINTER(Out)]
+        L.evconv_step.argtypes = [vp, vp, ctypes.POINTER(Out)]
+        L.evconv_step_frame.argtypes = [vp, vp, ctypes.POINTER(Out)]
+        L.evconv_destroy.argtypes = [vp]
+        L.evconv_set_mode.argtypes = [vp, i32]
+        L.evconv_node_shape.argtypes = [vp, i32, ctypes.POINTER(i32)]
+        L.evconv_get_state.argtypes = [vp, i32, i32, vp, ctypes.c_size_t]
+        L.evconv_get_stats.argtypes = [vp, i32, ctypes.POINTER(LayerStats)]
+        L.evconv_node_kernel.argtypes = [vp, i32]
+        L.evconv_node_kernel.restype = ctypes.c_char_p
+        L.evconv_last_error.argtypes = [vp]
+        L.evconv_last_error.restype = ctypes.c_char_p
+        for name in EXPORTS:
+            if getattr(L, name).restype is ctypes.c_int:
+                getattr(L, name).restype = ctypes.c_int32
+        _lib = L
+    return _lib
+
+
+class EvConvError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"evconv {STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else status}: {text}")
+        self.status = status
+
+
+def marshal_desc(net, tile=(0, 0), sparsify_tp=0.0, n_streams=1):
+    """workloads.Net -> (NetDesc, keep-alive node array).  Element offsets become byte offsets."""
+    nodes = (NodeDesc * len(net.nodes))()
+    for i, nd in enumerate(net.nodes):
+        n = nodes[i]
+        n.op, n.act, n.in0, n.in1 = nd.op, nd.act, nd.in0, max(nd.in1, -1)
+        n.c_in, n.c_out, n.kh, n.kw, n.stride, n.pad = nd.c_in, nd.c_out, nd.k, nd.k, nd.stride, nd.pad
+        n.wdtype, n.is_output = nd.wdtype, nd.is_output
+        n.weight_off = nd.w_off * 4 if nd.w_off >= 0 else -1
+        n.bias_off = nd.b_off * 4 if nd.b_off >= 0 else -1
+    d = NetDesc(ABI_VERSION, len(net.nodes), nodes, net.in_c, net.in_h, net.in_w, tile[0], tile[1],
+                sparsify_tp, n_streams)
+    return d, nodes
+
+
+def evconv_query_workspace(desc: NetDesc) -> int:
+    n = ctypes.c_size_t(0)
+    st = lib().evconv_query_workspace(ctypes.byref(desc), ctypes.byref(n))
+    if st != OK:
+        raise EvConvError(st, lib().evconv_last_error(None).decode())
+    return n.value
+
+
+class EvConvNet:
+    """Owns one evconv_net handle plus the torch tensors that back it."""
+
+    def __init__(self, net, device="cuda:0", stream=None, **desc_kw):
+        import torch
+        self.torch = torch
+        self.net = net
+        self.device = torch.device(device)
+        desc, self._nodes_keep = marshal_desc(net, **desc_kw)
+        self._desc = desc
+        nbytes = evconv_query_workspace(desc)
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        base = self.workspace.data_ptr()
+        self._ws_ptr = (base + 255) // 256 * 256
+        self.workspace_bytes = nbytes
+        self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        w = np.ascontiguousarray(net.weights, dtype=np.float32)
+        h = ctypes.c_void_p()
+        with torch.cuda.device(self.device):
+            st = lib().evconv_create(ctypes.byref(desc), w.ctypes.data_as(ctypes.c_void_p), w.nbytes,
+                                     ctypes.c_void_p(self._ws_ptr), nbytes,
+                                     ctypes.c_void_p(self.stream.cuda_stream), ctypes.byref(h))
+        if st != OK:
+            raise EvConvError(st, lib().evconv_last_error(None).decode())
+        self._h = h
+        self.n_outputs = lib().evconv_num_outputs(self._h)
+        self._outs = (Out * self.n_outputs)()
+
+    # ---- the four calls
+    def _check(self, st):
+        if st != OK:
+            raise EvConvError(st, lib().evconv_last_error(self._h).decode())
+
+    def _dev_ptr(self, t):
+        torch = self.torch
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
+        assert tuple(t.shape) == (self.net.in_c, self.net.in_h, self.net.in_w)
+        return ctypes.c_void_p(t.data_ptr())
+
+    def reset(self, x0):
+        self._check(lib().evconv_reset(self._h, self._dev_ptr(x0), self._outs))
+
+    def step(self, increment):
+        self._check(lib().evconv_step(self._h, self._dev_ptr(increment), self._outs))
+
+    def step_frame(self, x_t):
+        self._check(lib().evconv_step_frame(self._h, self._dev_ptr(x_t), self._outs))
+
+    def destroy(self):
+        if getattr(self, "_h", None):
+            lib().evconv_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def set_mode(self, mode):
+        self._check(lib().evconv_set_mode(self._h, mode))
+
+    # ---- observability
+    def shape(self, node):
+        s = (ctypes.c_int32 * 3)()
+        self._check(lib().evconv_node_shape(self._h, node, s))
+        return int(s[0]), int(s[1]), int(s[2])
+
+    def state(self, node, kind) -> np.ndarray:
+        c, h, w = self.shape(node)
+        tiles = (-(-h // 8)) * (-(-w // 8))
+        if kind in (STATE_Z, STATE_DY):
+            a = np.empty((h, w, c), np.float32)
+        elif kind == STATE_X_PREV:
+            a = np.empty((c, h, w), np.float32)
+        elif kind == STATE_IDX:
+            a = np.empty(h * w, np.int32)
+        elif kind == STATE_COUNT:
+            a = np.empty(1, np.int32)
+        elif kind == STATE_BITMAP:
+            a = np.empty(-(-tiles // 64), np.uint64)
+        else:
+            a = np.empty(tiles, np.uint64)
+        self._check(lib().evconv_get_state(self._h, node, kind, a.ctypes.data_as(ctypes.c_void_p), a.nbytes))
+        return a
+
+    def site_list(self, node) -> np.ndarray:
+        n = int(self.state(node, STATE_COUNT)[0])
+        return self.state(node, STATE_IDX)[:n].copy()
+
+    def stats(self, node) -> LayerStats:
+        s = LayerStats()
+        self._check(lib().evconv_get_stats(self._h, node, ctypes.byref(s)))
+        return s
+
+    def kernel_name(self, node) -> str:
+        return lib().evconv_node_kernel(self._h, node).decode()
+
+    def outputs(self):
+        """Per output node: dict of torch views (y, dy as C x H x W; idx; count), valid until the
+        next call on this net.  The caller synchronises the stream before reading."""
+        torch = self.torch
+        res = []
+        base = self._ws_ptr
+        raw = self.workspace
+        off0 = base - raw.data_ptr()
+
+        def view(ptr, nbytes, dtype, shape):
+            o = ptr - base + off0
+            return raw[o:o + nbytes].view(dtype).view(*shape)
+        for j in range(self.n_outputs):
+            o = self._outs[j]
+            n = o.c * o.h * o.w
+            res.append(dict(node=o.node,
+                            y=view(o.y, n * 4, torch.float32, (o.c, o.h, o.w)),
+                            dy=view(o.dy, n * 4, torch.float32, (o.c, o.h, o.w)),
+                            idx=view(o.dy_idx, o.h * o.w * 4, torch.int32, (o.h * o.w,)),
+                            count=view(o.dy_count, 4, torch.int32, (1,))))
+        return res

@@ -1,0 +1,88 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, sizes workspaces, and rejects bad descriptions before any GPU work."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2303_04670_amd import evconv as ev
+from paper_2303_04670_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "evconv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(evconv_[a-z_]+)\s*\(", text))
+    assert declared == set(ev.EXPORTS)
+    L = ev.lib()
+    for name in sorted(declared):
+        assert hasattr(L, name), name
+
+
+@pytest.mark.parametrize("make", [wl.net_single_conv, wl.net_conv_stack, wl.net_unet_depth, wl.net_resnet18,
+                                  wl.net_flow], ids=lambda f: f.__name__)
+def test_query_workspace_all_workloads(make):
+    net = make()
+    desc, keep = ev.marshal_desc(net)
+    n = ev.evconv_query_workspace(desc)
+    shapes = net.node_shapes()
+    lower = sum(c * h * w * 4 for c, h, w in shapes)   # at least one increment buffer per node
+    assert lower < n < 40 * lower + (64 << 20)
+
+
+def _status(desc):
+    n = ctypes.c_size_t(0)
+    return ev.lib().evconv_query_workspace(ctypes.byref(desc), ctypes.byref(n))
+
+
+def test_bad_descriptions_are_rejected():
+    net = wl.net_conv_stack(1, h=16, w=16)
+    desc, nodes = ev.marshal_desc(net)
+    assert _status(desc) == ev.OK
+    desc.abi_version = 99
+    assert _status(desc) == ev.ERR_BAD_DESC
+    desc.abi_version = ev.ABI_VERSION
+    nodes[1].in0 = 3                       # forward reference
+    assert _status(desc) == ev.ERR_BAD_DESC
+    nodes[1].in0 = 0
+    nodes[1].c_in = 7                      # channel mismatch
+    assert _status(desc) == ev.ERR_SHAPE
+    nodes[1].c_in = 32
+    nodes[2].kh = 9
+    assert _status(desc) == ev.ERR_UNSUPPORTED
+    nodes[2].kh = 3
+    nodes[0].op = 42
+    assert _status(desc) == ev.ERR_INVALID_ARG
+    nodes[0].op = wl.OP_CONV2D
+    desc.sparsify_tp = 0.1                 # lossy sparsification is a later row
+    assert _status(desc) == ev.ERR_UNSUPPORTED
+    desc.sparsify_tp = 0.0
+    desc.tile_h, desc.tile_w = 6, 6
+    assert _status(desc) == ev.ERR_UNSUPPORTED
+    desc.tile_h, desc.tile_w = 8, 8
+    assert _status(desc) == ev.OK
+    assert ev.lib().evconv_query_workspace(None, None) == ev.ERR_INVALID_ARG
+    assert b"" != ev.lib().evconv_last_error(None)
+
+
+def test_null_handles():
+    L = ev.lib()
+    assert L.evconv_destroy(None) == ev.OK
+    assert L.evconv_num_outputs(None) == 0
+    assert L.evconv_reset(None, None, None) == ev.ERR_INVALID_ARG
+    assert L.evconv_step(None, None, None) == ev.ERR_INVALID_ARG
+    assert L.evconv_set_mode(None, 0) == ev.ERR_INVALID_ARG
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2303_04670_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith(".py"):
+                src = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle", src, flags=re.M), f
+                assert "libevconv_oracle" not in src, f

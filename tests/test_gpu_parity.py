@@ -1,0 +1,227 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element, on the
+same seeded inputs.  Integer products bit-exact (with counted rounding flips of value-pruned
+sets, see oracle/compare.py); fp32 tensors within 1e-4 * max|tensor| of the fp64 oracle."""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import compare as cmp
+from oracle.oracle import Oracle
+from paper_2303_04670_amd import evconv as ev
+from paper_2303_04670_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def run_stream(net, x0, inputs, kind, check_nodes_at=None, tol=TOL, exact_sets=False, max_flips=0,
+               fp32_oracle=False, label=""):
+    """kind: 'frame' or 'increment'.  check_nodes_at: steps (1-based) at which every node is
+    compared (None = every step); outputs and the input stage are compared at every step."""
+    gpu = ev.EvConvNet(net)
+    ora = Oracle(net, fp32_state=fp32_oracle)
+    rep = cmp.Report()
+    gpu.reset(_dev(x0))
+    ora.reset(x0)
+    cmp.compare_outputs(gpu, ora, rep, tol)
+    for i in range(len(net.nodes)):
+        if ora.tensor(i, 0).size:
+            z = gpu.state(i, ev.STATE_Z).astype(np.float64)
+            zr = ora.z(i)
+            assert np.abs(z - zr).max() <= tol * max(np.abs(zr).max(), 1e-30), f"reset: node {i} z"
+    for step, inp in enumerate(inputs, 1):
+        if kind == "frame":
+            gpu.step_frame(_dev(inp))
+            ora.step_frame(inp)
+        else:
+            gpu.step(_dev(inp))
+            ora.step_increment(inp)
+        cmp.compare_input_stage(gpu, ora, rep)
+        cmp.compare_outputs(gpu, ora, rep, tol)
+        if check_nodes_at is None or step in check_nodes_at:
+            for i in range(len(net.nodes)):
+                cmp.compare_node(gpu, ora, i, rep, tol=tol, exact_sets=exact_sets)
+        if step % 10 == 0:
+            _say(f"[{label}] step {step}: flips {rep.flips} max rel z err {rep.max_rel_z:.2e} y err {rep.max_rel_y:.2e}")
+    assert rep.flips <= max_flips, f"{rep.flips} rounding flips of value-pruned sets"
+    gpu.destroy()
+    return rep
+
+
+def test_workload1_single_conv_10_steps():
+    _say("workload 1: single conv3x3 16->16 on 16x64x64, 10 increments at 2 %")
+    net = wl.net_single_conv()
+    x0, incs = wl.stream_line_increments()
+    rep = run_stream(net, x0, incs, "increment", label="w1", max_flips=2)
+    assert rep.nodes_checked == 10
+
+
+def test_workload2_conv_stack_100_steps():
+    _say("workload 2: 4-layer conv stack on 5x180x240, 100 frames at 1-5 %")
+    net = wl.net_conv_stack()
+    frames = list(wl.stream_voxel(1002, 180, 240, 100, wl.density_sweep_1_5))
+    run_stream(net, frames[0], frames[1:], "frame", check_nodes_at={1, 2, 3, 25, 50, 75, 100}, label="w2",
+               max_flips=8)
+
+
+@pytest.mark.parametrize("seed", [7, 8, 9])
+def test_every_op_small_ragged_graph(seed):
+    _say(f"small graph touching every op, seed {seed}")
+    kw = {} if seed == 7 else dict(in_c=2, h=9, w=19, bias=(seed == 8))
+    net = wl.net_random_small(seed, **kw)
+    rng = np.random.default_rng(seed)
+    x0 = rng.standard_normal((net.in_c, net.in_h, net.in_w)).astype(np.float32)
+    frames, x = [], x0
+    for t in range(12):
+        m = rng.random((net.in_h, net.in_w)) < (0.02 + 0.08 * (t % 4))
+        x = (x + rng.standard_normal(x.shape).astype(np.float32) * m[None]).astype(np.float32)
+        frames.append(x)
+    run_stream(net, x0, frames, "frame", label=f"small{seed}", max_flips=4)
+
+
+def test_unet_reduced_all_nodes_every_step():
+    _say("UNet depth net, reduced 5x64x96 width 8, 30 frames, all nodes every step")
+    net = wl.net_unet_depth(1003, h=64, w=96, width=8)
+    frames = list(wl.stream_voxel(1003, 64, 96, 30, 0.02, n_prim=6))
+    run_stream(net, frames[0], frames[1:], "frame", label="unet-small", max_flips=8)
+
+
+def test_flow_net_reduced_concat_upsample():
+    _say("flow encoder-decoder, reduced 4x64x64 width 8, density sweep, all nodes every step")
+    net = wl.net_flow(1005, h=64, w=64, width=8)
+    frames = list(wl.stream_count_timestamp(1005, 64, 64, densities=[0.001, 0.01, 0.05, 0.2], steps_per=4))
+    run_stream(net, frames[0], frames[1:], "frame", label="flow-small", max_flips=8)
+
+
+def test_resnet_reduced_pool_gap_linear():
+    _say("ResNet-18-style classifier, reduced 2x64x64 width 8")
+    net = wl.net_resnet18(1004, h=64, w=64, n_classes=11, width=8)
+    frames = list(wl.stream_histogram(1004, 64, 64, steps=16))
+    run_stream(net, frames[0], frames[1:], "frame", label="resnet-small", max_flips=8)
+
+
+def test_edge_cases_zero_full_corner_special_values():
+    _say("edge cases: zero increment, every site active, corner pixels, -0.0, denormal, NaN-free inf-free")
+    net = wl.net_conv_stack(77, h=21, w=27)
+    rng = np.random.default_rng(77)
+    x0 = rng.standard_normal((5, 21, 27)).astype(np.float32)
+    incs = []
+    incs.append(np.zeros_like(x0))                                   # nothing changes
+    incs.append(rng.standard_normal(x0.shape).astype(np.float32))    # everything changes
+    for (y, x) in [(0, 0), (0, 26), (20, 0), (20, 26)]:              # single corner pixels
+        d = np.zeros_like(x0)
+        d[2, y, x] = 1.25
+        incs.append(d)
+    d = np.zeros_like(x0)
+    d[:, 3, 3] = -0.0                                                 # negative zero: inactive
+    d[1, 10, 10] = np.float32(1e-42)                                  # denormal: active
+    incs.append(d)
+    incs.append(np.zeros_like(x0))
+    rep = run_stream(net, x0, incs, "increment", label="edge", exact_sets=False, max_flips=4)
+    # explicit expectations on the input stage for the special values
+    gpu = ev.EvConvNet(net)
+    gpu.reset(_dev(x0))
+    gpu.step(_dev(d))
+    assert list(gpu.site_list(-1)) == [10 * 27 + 10]
+    gpu.step(_dev(np.zeros_like(x0)))
+    assert gpu.site_list(-1).size == 0
+    for i in range(4):
+        assert gpu.site_list(i).size == 0
+        assert not gpu.state(i, ev.STATE_OCC_TOUCHED).any()
+    gpu.destroy()
+
+
+def test_elementwise_kernels_bit_exact_against_fp32_oracle():
+    """Activation increment (Eq.12-14) and addition (Eq.11) are single-rounded fp32 operations, so
+    the GPU must match the oracle's binary32 mode bit for bit (tol = 0, exact sets)."""
+    _say("bit-exact elementwise: ACT(relu) and ADD+relu nets against the binary32 oracle")
+    nodes = [wl.Node(wl.OP_ACT, wl.ACT_RELU, -1, -2, 4, 4),
+             wl.Node(wl.OP_ADD, wl.ACT_RELU, 0, -1, 4, 4),
+             wl.Node(wl.OP_ADD, wl.ACT_NONE, 1, 0, 4, 4, is_output=1)]
+    net = wl.Net("elementwise", 4, 19, 23, nodes, np.zeros(0, np.float32))
+    rng = np.random.default_rng(5)
+    x0 = rng.standard_normal((4, 19, 23)).astype(np.float32)
+    frames, x = [], x0
+    for t in range(8):
+        m = rng.random((19, 23)) < 0.2
+        x = (x + rng.standard_normal(x.shape).astype(np.float32) * m[None]).astype(np.float32)
+        frames.append(x)
+    run_stream(net, x0, frames, "frame", tol=0.0, exact_sets=True, fp32_oracle=True, label="ew-bits")
+
+
+def test_reset_equals_stepped_state_and_dense_recompute_mode():
+    """Refresh equivalence on the GPU: after k steps, reset(x_t) and DENSE_RECOMPUTE give the same
+    accumulated tensors and output as the incremental path (within fp32 tolerance)."""
+    _say("refresh equivalence and dense-recompute mode")
+    net = wl.net_unet_depth(21, h=32, w=48, width=8)
+    frames = list(wl.stream_voxel(21, 32, 48, 12, 0.05, n_prim=4))
+    a, b, c = ev.EvConvNet(net), ev.EvConvNet(net), ev.EvConvNet(net)
+    a.reset(_dev(frames[0]))
+    c.reset(_dev(frames[0]))
+    c.set_mode(ev.MODE_DENSE_RECOMPUTE)
+    for f in frames[1:]:
+        a.step_frame(_dev(f))
+        c.step_frame(_dev(f))
+    b.reset(_dev(frames[-1]))
+    import torch
+    torch.cuda.synchronize()
+    for i, nd in enumerate(net.nodes):
+        if nd.op == wl.OP_CONV2D or nd.act != wl.ACT_NONE:
+            za, zb, zc = (n.state(i, ev.STATE_Z) for n in (a, b, c))
+            s = np.abs(zb).max()
+            assert np.abs(za - zb).max() <= TOL * s, f"node {i}"
+            np.testing.assert_array_equal(zb, zc)
+    ya, yb, yc = (n.outputs()[0]["y"].cpu().numpy() for n in (a, b, c))
+    assert np.abs(ya - yb).max() <= TOL
+    np.testing.assert_array_equal(yb, yc)
+
+
+def test_run_to_run_bit_reproducible():
+    _say("determinism: the same stream twice gives identical bits")
+    net = wl.net_unet_depth(31, h=40, w=56, width=8)
+    frames = list(wl.stream_voxel(31, 40, 56, 10, 0.03, n_prim=4))
+    res = []
+    for _ in range(2):
+        g = ev.EvConvNet(net)
+        g.reset(_dev(frames[0]))
+        for f in frames[1:]:
+            g.step_frame(_dev(f))
+        import torch
+        torch.cuda.synchronize()
+        res.append([g.state(i, ev.STATE_DY).copy() for i in range(len(net.nodes))] +
+                   [g.outputs()[0]["y"].cpu().numpy()] + [g.site_list(i) for i in range(len(net.nodes))])
+        g.destroy()
+    for u, v in zip(*res):
+        np.testing.assert_array_equal(u, v)
+
+
+def test_step_before_reset_is_an_error():
+    net = wl.net_single_conv(3, c=4, h=8, w=8)
+    g = ev.EvConvNet(net)
+    with pytest.raises(ev.EvConvError) as e:
+        g.step(_dev(np.zeros((4, 8, 8), np.float32)))
+    assert e.value.status == ev.ERR_STATE
+    g.destroy()
+
+
+@pytest.mark.timeout(900)
+def test_workload3_unet_full_size_100_steps():
+    """Full-size UNet depth net (5x256x352), 100 consecutive frames at 2 % changed pixels, in the
+    configuration bench.py times.  Outputs and the input stage are compared at every step, every
+    node at steps 1, 2, 50 and 100."""
+    _say("workload 3: UNet depth net 5x256x352, 100 frames at 2 %")
+    net = wl.net_unet_depth()
+    gen = wl.stream_voxel(1003, 256, 352, 100, 0.02)
+    x0 = next(gen)
+    run_stream(net, x0, gen, "frame", check_nodes_at={1, 2, 50, 100}, label="w3", max_flips=16)
