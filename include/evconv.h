@@ -180,6 +180,16 @@ evconv_status evconv_get_state(evconv_net* net, int32_t node, int32_t kind, void
 /* Synchronous; counts come from the occupancy words of the last step. */
 evconv_status evconv_get_stats(evconv_net* net, int32_t node, evconv_layer_stats* out);
 
+/* Per-node kernel timing with HIP events recorded on the net's stream around each node's
+ * launches.  profile_begin allocates `max_records` event pairs and arms recording for the
+ * following reset / step calls (recording stops silently when the pairs run out);
+ * profile_end synchronises the stream and accumulates the elapsed times; get_node_time returns
+ * the accumulated milliseconds and number of timed launches of a node since profile_begin. */
+evconv_status evconv_profile_begin(evconv_net* net, int32_t max_records);
+evconv_status evconv_profile_end(evconv_net* net);
+evconv_status evconv_get_node_time(const evconv_net* net, int32_t node, double* ms_total /* HOST */,
+                                   int64_t* launches /* HOST */);
+
 /* Name of the kernel family that executes a node ("conv_valu_f32", "conv_mfma_f32", ...). */
 const char* evconv_node_kernel(const evconv_net* net, int32_t node);
 

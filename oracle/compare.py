@@ -31,6 +31,7 @@ class Report:
     max_rel_z: float = 0.0
     max_rel_y: float = 0.0
     nodes_checked: int = 0
+    flips_by_node: dict = dataclasses.field(default_factory=dict)
 
 
 def _check_set(name, gpu_mask, ref_mask, gpu_mag, ref_mag, tol_abs, rep: Report):
@@ -44,7 +45,9 @@ def _check_set(name, gpu_mask, ref_mask, gpu_mag, ref_mag, tol_abs, rep: Report)
     assert not bad_g.any() and not bad_r.any(), (
         f"{name}: active sets differ at sites carrying non-negligible increments "
         f"(gpu-only {int(bad_g.sum())}, oracle-only {int(bad_r.sum())}, tol {tol_abs:g})")
-    rep.flips += int(only_gpu.sum() + only_ref.sum())
+    n = int(only_gpu.sum() + only_ref.sum())
+    rep.flips += n
+    rep.flips_by_node[name] = rep.flips_by_node.get(name, 0) + n
 
 
 def compare_input_stage(gpu, ora: Oracle, rep: Report):

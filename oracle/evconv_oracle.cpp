@@ -388,6 +388,7 @@ struct Net {
       if (s.touched[q]) std::fill(&s.dy[q * o.c], &s.dy[q * o.c] + o.c, T(0));
     std::vector<T> v;  // linear-part increment at touched sites, HWC dense-addressed
     v.assign(o.elems(), T(0));
+    std::vector<float> v32;  // max-pool only: the increment formed from binary32-rounded maxima
     s.macs_site = 0;
 
     switch (nd.op) {
@@ -473,6 +474,7 @@ struct Net {
         // increment is max over the updated window minus max over the old window
         touched_windowed(sa, a, o, nd, s.touched);
         std::vector<T> old_max(o.elems(), T(0));
+        v32.assign(o.elems(), 0.f);
         for (int oy = 0; oy < o.h; ++oy)
           for (int ox = 0; ox < o.w; ++ox) {
             size_t q = size_t(oy) * o.w + ox;
@@ -486,8 +488,11 @@ struct Net {
           for (int ox = 0; ox < o.w; ++ox) {
             size_t q = size_t(oy) * o.w + ox;
             if (!s.touched[q]) continue;
-            for (int c = 0; c < o.c; ++c)
-              v[q * o.c + c] = window_max(s.pool_in, a, nd, oy, ox, c) - old_max[q * o.c + c];
+            for (int c = 0; c < o.c; ++c) {
+              T new_max = window_max(s.pool_in, a, nd, oy, ox, c);
+              v[q * o.c + c] = new_max - old_max[q * o.c + c];
+              v32[q * o.c + c] = float(new_max) - float(old_max[q * o.c + c]);
+            }
           }
         break;
       }
@@ -514,14 +519,21 @@ struct Net {
       for (int c = 0; c < o.c; ++c) {
         size_t e = q * o.c + c;
         T out = v[e];
+        // out32: the same increment evaluated on binary32-rounded operands.  Whether a site is
+        // kept is an integer decided by floating point; it is taken in binary32, the precision
+        // the cached tensors of the method are held in.
+        float out32 = v32.empty() ? float(v[e]) : v32[e];
         if (s.keeps_z) {
           T z_old = s.z[e];
           T z_new = z_old + v[e];
           s.z[e] = z_new;
-          if (nd.act != ACT_NONE) out = activate<T>(nd.act, z_new) - activate<T>(nd.act, z_old);
+          if (nd.act != ACT_NONE) {
+            out = activate<T>(nd.act, z_new) - activate<T>(nd.act, z_old);
+            out32 = activate<float>(nd.act, float(z_new)) - activate<float>(nd.act, float(z_old));
+          }
         }
         s.dy[e] = out;
-        nz |= (out != T(0));
+        nz |= (out32 != 0.0f);
       }
       s.active[q] = s.structural ? 1 : nz;
       if (!s.active[q]) std::fill(&s.dy[q * o.c], &s.dy[q * o.c] + o.c, T(0));

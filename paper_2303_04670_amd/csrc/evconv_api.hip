@@ -211,6 +211,12 @@ struct evconv_net {
   uint64_t *occ_in = nullptr, *bitmap_in = nullptr, *occ_nodes = nullptr;
   int32_t *idx_in = nullptr, *count_in = nullptr;
   SetDesc* sets_dev = nullptr;
+  // optional per-node timing with HIP events on the net's stream
+  bool prof = false;
+  std::vector<hipEvent_t> prof_ev;
+  std::vector<int> prof_node;
+  std::vector<double> node_ms;
+  std::vector<long long> node_launches;
 };
 
 namespace {
@@ -240,6 +246,8 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
     const bool two = d.op == EVCONV_OP_ADD || d.op == EVCONV_OP_CONCAT;
     const float* bptr = two ? (d.in1 < 0 ? net->dx : net->L.nodes[d.in1].out) : nullptr;
     const uint64_t* occ_b = two ? (d.in1 < 0 ? net->occ_in : net->L.nodes[d.in1].occ) : nullptr;
+    const bool timed = net->prof && 2 * (net->prof_node.size() + 1) <= net->prof_ev.size();
+    if (timed) (void)hipEventRecord(net->prof_ev[2 * net->prof_node.size()], s);
     switch (n.kernel) {
       case kKernConvValu:
       case kKernConvMfmaF32: {
@@ -282,6 +290,10 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
         launch_gap(p, s);
         break;
       }
+    }
+    if (timed) {
+      (void)hipEventRecord(net->prof_ev[2 * net->prof_node.size() + 1], s);
+      net->prof_node.push_back((int)i);
     }
     if (d.is_output) {
       IntegrateParams ip;
@@ -441,7 +453,8 @@ evconv_status evconv_step_frame(evconv_net* net, const float* x_t, evconv_out* o
 
 evconv_status evconv_destroy(evconv_net* net) {
   if (!net) return EVCONV_OK;
-  hipStreamSynchronize(net->stream);
+  (void)hipStreamSynchronize(net->stream);
+  for (hipEvent_t e : net->prof_ev) (void)hipEventDestroy(e);
   delete net;
   return EVCONV_OK;
 }
@@ -511,6 +524,48 @@ evconv_status evconv_get_stats(evconv_net* net, int32_t node, evconv_layer_stats
     out->flops_dense = per_site * n.go.sites();
     out->flops_executed = per_site * 64.0 * out->n_touched_tiles;
   }
+  return EVCONV_OK;
+}
+
+evconv_status evconv_profile_begin(evconv_net* net, int32_t max_records) {
+  if (!net || max_records <= 0) return EVCONV_ERR_INVALID_ARG;
+  for (hipEvent_t e : net->prof_ev) (void)hipEventDestroy(e);
+  net->prof_ev.assign(2 * (size_t)max_records, nullptr);
+  for (hipEvent_t& e : net->prof_ev) {
+    hipError_t err = hipEventCreate(&e);
+    if (err != hipSuccess) return hip_fail(net, err, "hipEventCreate");
+  }
+  net->prof_node.clear();
+  net->node_ms.assign(net->L.nodes.size(), 0.0);
+  net->node_launches.assign(net->L.nodes.size(), 0);
+  net->prof = true;
+  return EVCONV_OK;
+}
+
+evconv_status evconv_profile_end(evconv_net* net) {
+  if (!net) return EVCONV_ERR_INVALID_ARG;
+  if (!net->prof) { net->err = "profiling was not started"; return EVCONV_ERR_STATE; }
+  net->prof = false;
+  hipError_t e = hipStreamSynchronize(net->stream);
+  if (e != hipSuccess) return hip_fail(net, e, "profile_end");
+  for (size_t r = 0; r < net->prof_node.size(); ++r) {
+    float ms = 0.f;
+    e = hipEventElapsedTime(&ms, net->prof_ev[2 * r], net->prof_ev[2 * r + 1]);
+    if (e != hipSuccess) return hip_fail(net, e, "hipEventElapsedTime");
+    net->node_ms[net->prof_node[r]] += ms;
+    net->node_launches[net->prof_node[r]] += 1;
+  }
+  for (hipEvent_t ev : net->prof_ev) (void)hipEventDestroy(ev);
+  net->prof_ev.clear();
+  net->prof_node.clear();
+  return EVCONV_OK;
+}
+
+evconv_status evconv_get_node_time(const evconv_net* net, int32_t node, double* ms_total, int64_t* launches) {
+  if (!net || !ms_total || !launches || node < 0 || node >= (int)net->L.nodes.size()) return EVCONV_ERR_INVALID_ARG;
+  if (net->node_ms.empty()) { *ms_total = 0; *launches = 0; return EVCONV_OK; }
+  *ms_total = net->node_ms[node];
+  *launches = net->node_launches[node];
   return EVCONV_OK;
 }
 

@@ -26,7 +26,8 @@ MODE_INCREMENTAL, MODE_DENSE_RECOMPUTE = 0, 1
 
 EXPORTS = ["evconv_query_workspace", "evconv_create", "evconv_num_outputs", "evconv_reset", "evconv_step",
            "evconv_step_frame", "evconv_destroy", "evconv_set_mode", "evconv_node_shape", "evconv_get_state",
-           "evconv_get_stats", "evconv_node_kernel", "evconv_last_error"]
+           "evconv_get_stats", "evconv_node_kernel", "evconv_last_error", "evconv_profile_begin",
+           "evconv_profile_end", "evconv_get_node_time"]
 
 
 class NodeDesc(ctypes.Structure):
@@ -82,9 +83,10 @@ def lib() -> ctypes.CDLL:
         L.evconv_node_kernel.restype = ctypes.c_char_p
         L.evconv_last_error.argtypes = [vp]
         L.evconv_last_error.restype = ctypes.c_char_p
-        for name in EXPORTS:
-            if getattr(L, name).restype is ctypes.c_int:
-                getattr(L, name).restype = ctypes.c_int32
+        L.evconv_profile_begin.argtypes = [vp, i32]
+        L.evconv_profile_end.argtypes = [vp]
+        L.evconv_get_node_time.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double),
+                                           ctypes.POINTER(ctypes.c_int64)]
         _lib = L
     return _lib
 
@@ -212,6 +214,18 @@ class EvConvNet:
         s = LayerStats()
         self._check(lib().evconv_get_stats(self._h, node, ctypes.byref(s)))
         return s
+
+    def profile_begin(self, max_records):
+        self._check(lib().evconv_profile_begin(self._h, max_records))
+
+    def profile_end(self):
+        self._check(lib().evconv_profile_end(self._h))
+
+    def node_time(self, node):
+        """(total milliseconds, launches) of a node's kernels since profile_begin."""
+        ms, n = ctypes.c_double(), ctypes.c_int64()
+        self._check(lib().evconv_get_node_time(self._h, node, ctypes.byref(ms), ctypes.byref(n)))
+        return ms.value, n.value
 
     def kernel_name(self, node) -> str:
         return lib().evconv_node_kernel(self._h, node).decode()
