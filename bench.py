@@ -1,0 +1,137 @@
+#!/usr/bin/env python3
+"""Benchmark of the incremental-inference hot path on one MI355X.
+
+A step = one evconv_step_frame call: increment builder, every layer's increment kernel, output
+integration and list compaction, on one frame of a synthetic event-voxel stream that is already
+resident in HBM.  Workload: the UNet depth network on 5x256x352 at 2 % changed pixels per step.
+
+Prints ONE JSON line (see the fields below).  Extra keys: `dense_recompute` (the same frames run as
+regular forward passes through the same kernels), `roofline` (dominant kernel family, timed with
+HIP events on the library's stream inside the timed region) and `cpu_baseline` (the CPU oracle on
+a bounded sample of the same frames).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAKS = {  # MI355X published dense peaks
+    "conv_mfma_f32": ("mfma", 157.3, "TFLOP/s"),
+    "conv_mfma_bf16": ("mfma", 2500.0, "TFLOP/s"),
+    # vector ALU fp32: 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2 (dual-issue/packed) x 2.4 GHz
+    "conv_valu_f32": ("alu", 157.3, "TFLOP/s"),
+}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--density", type=float, default=0.02)
+    ap.add_argument("--variant", choices=["f32", "bf16"], default="f32")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-steps", type=int, default=20)
+    ap.add_argument("--no-dense", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (one event stream per device, no collectives); "
+                 "--gpus must be 1")
+
+    import numpy as np
+    import torch
+    from paper_2303_04670_amd import evconv as ev
+    from paper_2303_04670_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    H, W = 256, 352
+    net = wl.net_unet_depth(1003, h=H, w=W, bf16=(args.variant == "bf16"))
+    n_frames = args.warmup + args.steps
+    frames = list(wl.stream_voxel(1003, H, W, n_frames, args.density))
+    dens = float(np.mean([wl.changed_fraction(frames[i], frames[i + 1]) for i in range(args.warmup, n_frames)]))
+    dframes = [torch.from_numpy(f).to(dev) for f in frames]
+    torch.cuda.synchronize()
+
+    def timed_run(mode, profile):
+        g = ev.EvConvNet(net, device="cuda:0")
+        g.set_mode(mode)
+        g.reset(dframes[0])
+        for i in range(1, args.warmup + 1):
+            g.step_frame(dframes[i])
+        torch.cuda.synchronize()
+        if profile:
+            g.profile_begin(args.steps * len(net.nodes))
+        t0 = time.perf_counter()
+        for i in range(args.warmup + 1, n_frames + 1):
+            g.step_frame(dframes[i])
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        if profile:
+            g.profile_end()
+        return g, dt
+
+    g, dt = timed_run(ev.MODE_INCREMENTAL, profile=True)
+    ms_per_step = dt / args.steps * 1e3
+
+    # per kernel family: accumulated event time, launches, algorithmic flops of the timed launches
+    fam = {}
+    layers = []
+    for i, nd in enumerate(net.nodes):
+        ms, n = g.node_time(i)
+        name = g.kernel_name(i)
+        st = g.stats(i)
+        per_site = 2.0 * nd.k * nd.k * nd.c_in * nd.c_out if nd.op in (wl.OP_CONV2D, wl.OP_LINEAR) else 0.0
+        flops = per_site * st.n_touched            # algorithmic: touched output sites of the last step
+        f = fam.setdefault(name, dict(ms=0.0, launches=0, flops=0.0))
+        f["ms"] += ms
+        f["launches"] += n
+        f["flops"] += flops * n
+        layers.append(dict(node=i, kernel=name, ms_avg=ms / max(n, 1), touched=st.n_touched, sites=st.n_sites,
+                           active=st.n_active, touched_tiles=st.n_touched_tiles, tiles=st.n_tiles,
+                           gflop_alg=flops / 1e9))
+    dom = max((k for k in fam if k.startswith("conv")), key=lambda k: fam[k]["ms"])
+    bound, peak, unit = PEAKS[dom]
+    achieved = fam[dom]["flops"] / (fam[dom]["ms"] * 1e-3) / 1e12 if fam[dom]["ms"] > 0 else 0.0
+    roofline = dict(kernel=dom, bound=bound, achieved=achieved, peak=peak, unit=unit, frac=achieved / peak,
+                    traffic=None, avg_launch_ms=fam[dom]["ms"] / max(fam[dom]["launches"], 1),
+                    launches=fam[dom]["launches"], share_of_step=fam[dom]["ms"] / (dt * 1e3))
+    g.destroy()
+
+    out = {
+        "metric": "incremental steps/sec at 2% density (UNet depth net)",
+        "value": args.steps / dt, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if args.variant == "f32" else "bf16", "data": "synthetic",
+        "config": {"workload": f"unet_depth_5x{H}x{W}_voxel_stream", "changed_pixel_fraction": round(dens, 5),
+                   "weights": args.variant, "mode": "incremental", "batch": 1},
+        "roofline": roofline,
+    }
+    if not args.no_dense:
+        g2, dt2 = timed_run(ev.MODE_DENSE_RECOMPUTE, profile=False)
+        g2.destroy()
+        out["dense_recompute"] = {"value": args.steps / dt2, "unit": "steps/s", "ms_per_step": dt2 / args.steps * 1e3,
+                                  "incremental_speedup": dt2 / dt}
+    if not args.no_cpu_baseline:
+        from oracle.oracle import Oracle
+        ora = Oracle(net)
+        ora.reset(frames[0])
+        k = min(args.cpu_steps, n_frames)
+        t0 = time.perf_counter()
+        for i in range(1, k + 1):
+            ora.step_frame(frames[i])
+        cdt = time.perf_counter() - t0
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        out["cpu_baseline"] = {"value": k / cdt, "unit": "steps/s", "cores": cores, "kind": "oracle",
+                               "sample": f"first {k} frames of the same stream, fp64, OpenMP"}
+    out["layers"] = layers
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

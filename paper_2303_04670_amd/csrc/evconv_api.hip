@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -385,14 +386,27 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
     }
     sets[i + 1] = SetDesc{n.occ, n.idx, n.count, n.bitmap, n.go.h, n.go.w, n.go.tx, n.go.ty};
     if (n.d.op == EVCONV_OP_CONV2D || n.d.op == EVCONV_OP_LINEAR) {
-      // re-lay [c_out][c_in][k][k] as [tap][c_in][c_out_pad] (zero padded output channels)
       const int k = n.d.kh, ci_n = n.d.c_in, co_n = n.d.c_out, cop = n.c_out_pad;
+      ConvParams probe;
+      probe.gi = n.ga; probe.go = n.go; probe.k = k; probe.stride = n.d.stride; probe.c_out_pad = cop;
+      const bool force_valu = getenv("EVCONV_FORCE_VALU") != nullptr;
+      if (!force_valu && n.d.wdtype == EVCONV_F32 && conv_mfma_f32_supported(probe)) n.kernel = kKernConvMfmaF32;
       const float* src = (const float*)((const char*)weights + n.d.weight_off);
       staging.assign((size_t)k * k * ci_n * cop, 0.0f);
-      for (int co = 0; co < co_n; ++co)
-        for (int ci = 0; ci < ci_n; ++ci)
-          for (int t = 0; t < k * k; ++t)
-            staging[((size_t)t * ci_n + ci) * cop + co] = src[((size_t)co * ci_n + ci) * k * k + t];
+      if (n.kernel == kKernConvMfmaF32) {
+        // matrix-core layout [tap][c_in/4][c_out][4]: a lane's 4 input channels are 16 bytes
+        for (int co = 0; co < co_n; ++co)
+          for (int ci = 0; ci < ci_n; ++ci)
+            for (int t = 0; t < k * k; ++t)
+              staging[(((size_t)t * (ci_n / 4) + ci / 4) * cop + co) * 4 + (ci & 3)] =
+                  src[((size_t)co * ci_n + ci) * k * k + t];
+      } else {
+        // vector-ALU layout [tap][c_in][c_out_pad] (zero padded output channels)
+        for (int co = 0; co < co_n; ++co)
+          for (int ci = 0; ci < ci_n; ++ci)
+            for (int t = 0; t < k * k; ++t)
+              staging[((size_t)t * ci_n + ci) * cop + co] = src[((size_t)co * ci_n + ci) * k * k + t];
+      }
       n.w = ws + n.off_w;
       e = hipMemcpyAsync(n.w, staging.data(), staging.size() * 4, hipMemcpyHostToDevice, net->stream);
       if (e == hipSuccess) e = hipStreamSynchronize(net->stream);  // staging is reused
@@ -401,9 +415,6 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
         e = hipMemcpy(n.bias, (const char*)weights + n.d.bias_off, (size_t)co_n * 4, hipMemcpyHostToDevice);
       }
       if (e != hipSuccess) { g_create_error = std::string("weight upload: ") + hipGetErrorString(e); delete net; return EVCONV_ERR_HIP; }
-      ConvParams probe;
-      probe.gi = n.ga; probe.go = n.go; probe.k = k; probe.stride = n.d.stride; probe.c_out_pad = cop;
-      if (n.d.wdtype == EVCONV_F32 && conv_mfma_f32_supported(probe)) n.kernel = kKernConvMfmaF32;
     }
   }
   e = hipMemcpyAsync(net->sets_dev, sets.data(), sets.size() * sizeof(SetDesc), hipMemcpyHostToDevice, net->stream);

@@ -97,6 +97,37 @@ def test_unet_reduced_all_nodes_every_step():
     run_stream(net, frames[0], frames[1:], "frame", label="unet-small", max_flips=8)
 
 
+def test_unet_full_width_reduced_size_matrix_core_layers():
+    _say("UNet depth net, full width (32..256 channels) on 5x64x96: matrix-core conv layers, all nodes every step")
+    net = wl.net_unet_depth(1003, h=64, w=96)
+    g = ev.EvConvNet(net)
+    names = [g.kernel_name(i) for i in range(len(net.nodes))]
+    g.destroy()
+    assert names.count("conv_mfma_f32") == 10 and names[0] == "conv_valu_f32", names
+    frames = list(wl.stream_voxel(1003, 64, 96, 20, 0.02, n_prim=6))
+    run_stream(net, frames[0], frames[1:], "frame", label="unet-wide", max_flips=40)
+
+
+def test_matrix_core_conv_shapes():
+    """Every (kernel, stride, channel-chunk) variant of the matrix-core conv on ragged sizes, with
+    bias, dense and sparse increments."""
+    _say("matrix-core conv variants: k in {1,3,5,7}, stride {1,2}, c_in in {16,32,48,64}")
+    for k, s, ci, co in [(3, 1, 32, 32), (3, 2, 16, 64), (5, 1, 64, 32), (5, 2, 48, 96), (7, 2, 16, 32), (1, 1, 32, 64)]:
+        b = wl._NetBuilder(f"conv{k}s{s}", ci, 21, 27, 100 + k * 10 + s, bias=True)
+        b.conv(-1, co, k, s, act=wl.ACT_RELU, out=1)
+        net = b.finish()
+        rng = np.random.default_rng(k + s)
+        x0 = rng.standard_normal((ci, 21, 27)).astype(np.float32)
+        incs = []
+        for t in range(4):
+            m = rng.random((21, 27)) < (0.03 if t < 3 else 1.0)
+            incs.append(rng.standard_normal(x0.shape).astype(np.float32) * m[None])
+        g = ev.EvConvNet(net)
+        assert g.kernel_name(0) == "conv_mfma_f32"
+        g.destroy()
+        run_stream(net, x0, incs, "increment", label=f"mfma k{k}s{s}", max_flips=2)
+
+
 def test_flow_net_reduced_concat_upsample():
     _say("flow encoder-decoder, reduced 4x64x64 width 8, density sweep, all nodes every step")
     net = wl.net_flow(1005, h=64, w=64, width=8)
