@@ -113,7 +113,10 @@ def main():
         "roofline": roofline,
     }
     if not args.no_dense:
-        g2, dt2 = timed_run(ev.MODE_DENSE_RECOMPUTE, profile=False)
+        g2, dt2 = timed_run(ev.MODE_DENSE_RECOMPUTE, profile=True)
+        for i, l in enumerate(layers):
+            ms, n = g2.node_time(i)
+            l["dense_ms_avg"] = ms / max(n, 1)
         g2.destroy()
         out["dense_recompute"] = {"value": args.steps / dt2, "unit": "steps/s", "ms_per_step": dt2 / args.steps * 1e3,
                                   "incremental_speedup": dt2 / dt}

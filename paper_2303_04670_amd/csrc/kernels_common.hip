@@ -99,6 +99,8 @@ void launch_builder(const BuilderParams& p, hipStream_t s) {
 // One workgroup per output tile.  Wave 0 derives the tile's touched word and the list of
 // touched sites; then the 256 threads walk (touched site, channel vector) pairs with the
 // channel index fastest, so global accesses are contiguous runs of C floats per site.
+constexpr int kEwVecPerBlock = 16;  // channel vectors per workgroup: wide layers split over blockIdx.y
+
 template <int VEC>
 __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
   __shared__ int s_sites[64];
@@ -155,11 +157,14 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
   const uint64_t wa = s_wa, wb = s_wb;
   const int n_sites = __popcll(word);
   const int C = p.go.c;
-  const int cv = C / VEC;
+  // channel vectors [v0, v0 + cv) of every touched site belong to this workgroup
+  const int cv_all = C / VEC;
+  const int v0 = blockIdx.y * kEwVecPerBlock;
+  const int cv = min(kEwVecPerBlock, cv_all - v0);
   const int total = n_sites * cv;
 
   for (int e = tid; e < total; e += 256) {
-    const int r = e / cv, v = e - r * cv;
+    const int r = e / cv, v = v0 + (e - r * cv);
     const int site = s_sites[r];
     const int oy = tile_y * 8 + (site >> 3), ox = tile_x * 8 + (site & 7);
     const size_t q = (size_t)oy * p.go.w + ox;
@@ -253,15 +258,20 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
   __syncthreads();
   if (tid == 0) {
     const uint64_t flags = (uint64_t)s_flags[0] | ((uint64_t)s_flags[1] << 32);
-    p.occ_touched[tile] = word;
-    p.occ_out[tile] = (p.structural || p.dense) ? word : flags;
+    if (p.structural || p.dense) {
+      if (blockIdx.y == 0) p.occ_out[tile] = word;
+    } else if (flags) {
+      atomicOr((unsigned long long*)&p.occ_out[tile], (unsigned long long)flags);  // pre-zeroed word
+    }
+    if (blockIdx.y == 0) p.occ_touched[tile] = word;
   }
 }
 
 void launch_elementwise(const EwParams& p, hipStream_t s) {
   bool vec4 = (p.go.c % 4) == 0;
   if (p.op == kEwConcat) vec4 = vec4 && (p.ga.c % 4) == 0;
-  dim3 grid(p.go.tiles());
+  const int cv_all = p.go.c / (vec4 ? 4 : 1);
+  dim3 grid(p.go.tiles(), (cv_all + kEwVecPerBlock - 1) / kEwVecPerBlock);
   if (vec4) hipLaunchKernelGGL(elementwise_kernel<4>, grid, dim3(256), 0, s, p);
   else hipLaunchKernelGGL(elementwise_kernel<1>, grid, dim3(256), 0, s, p);
 }

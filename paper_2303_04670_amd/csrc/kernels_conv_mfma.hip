@@ -4,15 +4,17 @@
 // Implicit GEMM per touched output tile: M = 64 sites (two 32-row blocks: tile rows 0-3 and
 // 4-7), N = 32 output channels per workgroup, K = taps x c_in.
 //
-// Workgroup = 4 wavefronts that split K: the (tap, 8-channel group) units of every channel chunk
-// are dealt round-robin to the waves; each wave keeps both 32 x 32 accumulators (32 VGPRs) and
-// the four partial sums are added through LDS at the end.  K-splitting (rather than N-splitting)
-// is what fills the chip on the low-resolution layers, where a layer has only 24-88 tiles.
+// Workgroup = NW (4 or 8) wavefronts that split K: the (tap, 8-channel group) units of every
+// channel chunk are dealt round-robin to the waves; each wave keeps both 32 x 32 accumulators
+// (32 VGPRs) and the partial sums are added through LDS at the end.  K-splitting (rather than
+// N-splitting) is what fills the chip on the low-resolution layers, where a layer has only
+// 24-88 tiles; those layers run with 8 waves.
 //   A operand: the input halo patch of the current chunk, gathered once per workgroup into LDS
-//     (zeros for inactive / out-of-image sites, never fetched); a lane reads 4 consecutive
-//     channels of its site with one ds_read_b128.
+//     (zeros for inactive / out-of-image sites, which are never fetched).  The next chunk's
+//     patch is fetched into registers while the current one is being contracted.  A lane
+//     reads 4 consecutive channels of its site with one ds_read_b128.
 //   B operand: weights re-laid as [tap][c_in/4][c_out][4] so that a lane's 4 channels of its
-//     output column are one 16-byte global load (L2-resident), prefetched one unit ahead.
+//     output column are one 16-byte global load (L2-resident), prefetched two units ahead.
 //   K order inside an 8-channel group: MFMA j contracts channels {j, 4+j}; lanes 0-31 hold
 //     channel j, lanes 32-63 channel 4+j, for both operands.
 // Epilogue: lane = output channel, so every z / increment access is a 128-byte row segment.
@@ -30,10 +32,17 @@ __device__ __forceinline__ float act_m(int act, float v) {
   return v;
 }
 
-template <int CHUNK>
-__global__ __launch_bounds__(256) void conv_mfma_f32_kernel(ConvParams p) {
+// largest halo patch: 32-channel chunks are used with stride 1 only (14 x 14 for 7 x 7 taps),
+// 16-channel chunks also with stride 2 (21 x 21)
+constexpr int max_patch_sites(int chunk) { return chunk == 32 ? 14 * 14 : 21 * 21; }
+
+template <int CHUNK, int NW>
+__global__ __launch_bounds__(NW * 64) void conv_mfma_f32_kernel(ConvParams p) {
+  constexpr int NT = NW * 64;
   constexpr int CS = CHUNK + 4;  // LDS site stride in floats: CS/4 odd => conflict-free b128 reads
   constexpr int KG = CHUNK / 8;  // 8-channel groups per chunk
+  constexpr int NV = CHUNK / 4;  // float4 per patch site
+  constexpr int MAXV = (max_patch_sites(CHUNK) * NV + NT - 1) / NT;  // patch float4 per thread, upper bound
   extern __shared__ __align__(16) float s_mem[];
   __shared__ uint64_t s_occ[16];
   __shared__ unsigned s_nz[2];
@@ -59,7 +68,7 @@ __global__ __launch_bounds__(256) void conv_mfma_f32_kernel(ConvParams p) {
   if (tid < 2) s_nz[tid] = 0;
   __syncthreads();
 
-  // touched word of the tile (identical in all four waves)
+  // touched word of the tile (identical in all waves)
   uint64_t touched_word;
   {
     const int oy = tile_y * 8 + (lane >> 3), ox = tile_x * 8 + (lane & 7);
@@ -84,6 +93,40 @@ __global__ __launch_bounds__(256) void conv_mfma_f32_kernel(ConvParams p) {
   }
   if (touched_word == 0) return;
 
+  // ---- patch gather: thread-private list of (LDS offset, global offset or -1) fixed per tile
+  const int total_v = P * P * NV;
+  int lds_off[MAXV];
+  int g_off[MAXV];  // element offset of channel 0 of the site, < 0: site contributes zeros
+#pragma unroll
+  for (int j = 0; j < MAXV; ++j) {
+    const int e = tid + j * NT;
+    lds_off[j] = -1;
+    g_off[j] = -1;
+    if (e < total_v) {
+      const int site = e / NV, v = e - site * NV;
+      const int py = site / P, px = site - py * P;
+      const int iy = iy0 + py, ix = ix0 + px;
+      lds_off[j] = site * CS + v * 4;
+      if ((unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W) {
+        const uint64_t w = s_occ[((iy >> 3) - rty0) * 4 + ((ix >> 3) - rtx0)];
+        if ((w >> (((iy & 7) << 3) | (ix & 7))) & 1ull) g_off[j] = (iy * W + ix) * Cin + v * 4;
+      }
+    }
+  }
+  float4 pre[MAXV];
+  auto fetch = [&](int c0) {
+#pragma unroll
+    for (int j = 0; j < MAXV; ++j) {
+      pre[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (g_off[j] >= 0) pre[j] = *(const float4*)&p.in[(size_t)g_off[j] + c0];
+    }
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int j = 0; j < MAXV; ++j)
+      if (lds_off[j] >= 0) *(float4*)&s_mem[lds_off[j]] = pre[j];
+  };
+
   floatx16 acc0, acc1;
 #pragma unroll
   for (int i = 0; i < 16; ++i) { acc0[i] = 0.0f; acc1[i] = 0.0f; }
@@ -93,46 +136,33 @@ __global__ __launch_bounds__(256) void conv_mfma_f32_kernel(ConvParams p) {
   const int cop = p.c_out_pad;
   const int n_units = K * K * KG;
   const int cin4 = Cin >> 2;
-  const float4* __restrict__ wq = (const float4*)p.w;
   const int a_lane_off = (mly * s * P + mlx * s) * CS + half * 4;
   const int a_blk1 = 4 * s * P * CS;
+  const float4* __restrict__ wlane = (const float4*)p.w + (size_t)half * cop + co0 + m;
 
+  fetch(0);
   for (int c0 = 0; c0 < Cin; c0 += CHUNK) {
     __syncthreads();  // all waves are done reading the previous chunk
-    {
-      constexpr int NV = CHUNK / 4;
-      const int total = P * P * NV;
-      for (int e = tid; e < total; e += 256) {
-        const int site = e / NV, v = e - site * NV;
-        const int py = site / P, px = site - py * P;
-        const int iy = iy0 + py, ix = ix0 + px;
-        float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-        if ((unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W) {
-          const uint64_t w = s_occ[((iy >> 3) - rty0) * 4 + ((ix >> 3) - rtx0)];
-          if ((w >> (((iy & 7) << 3) | (ix & 7))) & 1ull)
-            val = *(const float4*)&p.in[((size_t)iy * W + ix) * Cin + c0 + v * 4];
-        }
-        *(float4*)&s_mem[site * CS + v * 4] = val;
-      }
-    }
+    stash();
     __syncthreads();
-
-    const int cq = (c0 >> 2) + half;  // float4 row of this lane's channels inside a tap
-    int u = wave;
-    float4 b_next = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (u < n_units) {
-      const int tap = u / KG, kg = u - tap * KG;
-      b_next = wq[((size_t)tap * cin4 + cq + kg * 2) * cop + co0 + m];
-    }
-    for (; u < n_units; u += 4) {
-      const int tap = u / KG, kg = u - tap * KG;
-      const int ky = tap / K, kx = tap - ky * K;
-      const float4 b = b_next;
-      const int un = u + 4;
-      if (un < n_units) {
-        const int tapn = un / KG, kgn = un - tapn * KG;
-        b_next = wq[((size_t)tapn * cin4 + cq + kgn * 2) * cop + co0 + m];
-      }
+    // units u = wave, wave + NW, ...: (tap, kg) advanced without divisions
+    int tap = wave / KG, kg = wave % KG;
+    int ky = tap / K, kx = tap - ky * K;
+    const float4* wchunk = wlane + (size_t)(c0 >> 2) * cop;
+    auto b_addr = [&](int t, int g) { return wchunk + ((size_t)t * cin4 + g * 2) * cop; };
+    // two-deep weight prefetch
+    int tap1 = tap + (kg + NW) / KG, kg1 = (kg + NW) % KG;
+    float4 b0 = make_float4(0.f, 0.f, 0.f, 0.f), b1 = b0;
+    if (wave < n_units) b0 = *b_addr(tap, kg);
+    if (wave + NW < n_units) b1 = *b_addr(tap1, kg1);
+    // next chunk's patch: issued after the first weight loads (vector loads complete in order),
+    // in flight during the contraction below
+    if (c0 + CHUNK < Cin) fetch(c0 + CHUNK);
+    for (int u = wave; u < n_units; u += NW) {
+      const float4 b = b0;
+      b0 = b1;
+      const int tap2 = tap1 + (kg1 + NW) / KG, kg2 = (kg1 + NW) % KG;
+      if (u + 2 * NW < n_units) b1 = *b_addr(tap2, kg2);
       const float* ap = &s_mem[a_lane_off + (ky * P + kx) * CS + kg * 8];
       const float4 a0 = *(const float4*)ap;
       const float4 a1 = *(const float4*)(ap + a_blk1);
@@ -144,12 +174,36 @@ __global__ __launch_bounds__(256) void conv_mfma_f32_kernel(ConvParams p) {
       acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.z, b.z, acc1, 0, 0, 0);
       acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.w, b.w, acc0, 0, 0, 0);
       acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.w, b.w, acc1, 0, 0, 0);
+      // advance (tap, kg) -> next unit of this wave, and its (ky, kx)
+      kx += tap1 - tap;
+      while (kx >= K) { kx -= K; ++ky; }
+      tap = tap1; kg = kg1;
+      tap1 = tap2; kg1 = kg2;
     }
   }
 
-  // partial sums -> LDS: [wave][block*16 + reg][lane]
+  // ---- reduce the NW partial sums through LDS: slots [4][block*16 + reg][lane]
   __syncthreads();
-  {
+  if (NW == 8) {
+    if (wave >= 4) {
+      float* part = s_mem + (wave - 4) * (32 * 64);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        part[i * 64 + lane] = acc0[i];
+        part[(16 + i) * 64 + lane] = acc1[i];
+      }
+    }
+    __syncthreads();
+    if (wave < 4) {
+      const float* part = s_mem + wave * (32 * 64);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        acc0[i] += part[i * 64 + lane];
+        acc1[i] += part[(16 + i) * 64 + lane];
+      }
+    }
+  }
+  if (wave < 4) {
     float* part = s_mem + wave * (32 * 64);
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -159,12 +213,13 @@ __global__ __launch_bounds__(256) void conv_mfma_f32_kernel(ConvParams p) {
   }
   __syncthreads();
 
-  // epilogue: thread -> (output channel = tid % 32, 8 sites); accumulator element (block b,
-  // register i, lane l) is site b*32 + 8*(i/4) + 4*(l/32) + i%4, channel l%32
+  // epilogue: thread -> (output channel = tid % 32, 64 / (NT / 32) sites); accumulator element
+  // (block b, register i, lane l) is site b*32 + 8*(i/4) + 4*(l/32) + i%4, channel l%32
   const int co = tid & 31;
   uint64_t nz_sites = 0;
-  for (int it = 0; it < 8; ++it) {
-    const int site = it * 8 + (tid >> 5);
+  constexpr int SITES_PER_IT = NT / 32;
+  for (int it = 0; it < 64 / SITES_PER_IT; ++it) {
+    const int site = it * SITES_PER_IT + (tid >> 5);
     if (!((touched_word >> site) & 1ull)) continue;
     const int b = site >> 5, r = site & 31;
     const int reg = (r >> 3) * 4 + (r & 3);
@@ -206,20 +261,31 @@ __global__ __launch_bounds__(256) void conv_mfma_f32_kernel(ConvParams p) {
 
 int chunk_for(const ConvParams& p) { return (p.gi.c % 32 == 0 && p.stride == 1) ? 32 : 16; }
 
+template <int CHUNK, int NW>
+void launch_variant(const ConvParams& p, hipStream_t s) {
+  const int P = 7 * p.stride + p.k;
+  size_t lds = (size_t)P * P * (CHUNK + 4) * sizeof(float);
+  if (lds < 4 * 32 * 64 * sizeof(float)) lds = 4 * 32 * 64 * sizeof(float);  // partial sums reuse it
+  dim3 grid(p.go.tiles(), p.go.c / 32);
+  hipLaunchKernelGGL((conv_mfma_f32_kernel<CHUNK, NW>), grid, dim3(NW * 64), lds, s, p);
+}
+
 }  // namespace
 
 bool conv_mfma_f32_supported(const ConvParams& p) {
-  return p.gi.c % 16 == 0 && p.go.c % 32 == 0 && p.c_out_pad == p.go.c;
+  return p.gi.c % 16 == 0 && p.go.c % 32 == 0 && p.c_out_pad == p.go.c &&
+         (long long)p.gi.h * p.gi.w * p.gi.c < (1ll << 31);
 }
 
 void launch_conv_mfma_f32(const ConvParams& p, hipStream_t s) {
-  const int P = 7 * p.stride + p.k;
   const int chunk = chunk_for(p);
-  size_t lds = (size_t)P * P * (chunk + 4) * sizeof(float);
-  if (lds < 4 * 32 * 64 * sizeof(float)) lds = 4 * 32 * 64 * sizeof(float);  // partial sums reuse it
-  dim3 grid(p.go.tiles(), p.go.c / 32);
-  if (chunk == 32) hipLaunchKernelGGL(conv_mfma_f32_kernel<32>, grid, dim3(256), lds, s, p);
-  else hipLaunchKernelGGL(conv_mfma_f32_kernel<16>, grid, dim3(256), lds, s, p);
+  // low-resolution layers have few workgroups: give each one 8 waves to split K further
+  const bool wide = (long long)p.go.tiles() * (p.go.c / 32) < 512;
+  if (chunk == 32) {
+    if (wide) launch_variant<32, 8>(p, s); else launch_variant<32, 4>(p, s);
+  } else {
+    if (wide) launch_variant<16, 8>(p, s); else launch_variant<16, 4>(p, s);
+  }
 }
 
 }  // namespace evk

@@ -94,7 +94,7 @@ def test_unet_reduced_all_nodes_every_step():
     _say("UNet depth net, reduced 5x64x96 width 8, 30 frames, all nodes every step")
     net = wl.net_unet_depth(1003, h=64, w=96, width=8)
     frames = list(wl.stream_voxel(1003, 64, 96, 30, 0.02, n_prim=6))
-    run_stream(net, frames[0], frames[1:], "frame", label="unet-small", max_flips=8)
+    run_stream(net, frames[0], frames[1:], "frame", label="unet-small", max_flips=40)
 
 
 def test_unet_full_width_reduced_size_matrix_core_layers():
