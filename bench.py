@@ -38,6 +38,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=20)
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--calib-copy-mb", type=int, default=0,
+                    help="also run plain device-to-device copies of this size (for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings against a kernel of known traffic)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (one event stream per device, no collectives); "
@@ -57,6 +60,12 @@ def main():
     dens = float(np.mean([wl.changed_fraction(frames[i], frames[i + 1]) for i in range(args.warmup, n_frames)]))
     dframes = [torch.from_numpy(f).to(dev) for f in frames]
     torch.cuda.synchronize()
+    if args.calib_copy_mb:
+        src = torch.empty(args.calib_copy_mb << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     def timed_run(mode, profile):
         g = ev.EvConvNet(net, device="cuda:0")

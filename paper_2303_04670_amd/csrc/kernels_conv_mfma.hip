@@ -93,15 +93,18 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_f32_kernel(ConvParams p) {
   }
   if (touched_word == 0) return;
 
-  // ---- patch gather: thread-private list of (LDS offset, global offset or -1) fixed per tile
+  // ---- patch gather: per thread a fixed list of (LDS offset, byte offset into the input).
+  // Inactive and out-of-image sites get an offset beyond the buffer: the hardware bounds check
+  // of the buffer load returns zeros for them without touching memory (conditioned fetch).
+  constexpr unsigned kOob = 0x80000000u;
   const int total_v = P * P * NV;
   int lds_off[MAXV];
-  int g_off[MAXV];  // element offset of channel 0 of the site, < 0: site contributes zeros
+  unsigned g_off[MAXV];
 #pragma unroll
   for (int j = 0; j < MAXV; ++j) {
     const int e = tid + j * NT;
     lds_off[j] = -1;
-    g_off[j] = -1;
+    g_off[j] = kOob;
     if (e < total_v) {
       const int site = e / NV, v = e - site * NV;
       const int py = site / P, px = site - py * P;
@@ -109,17 +112,17 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_f32_kernel(ConvParams p) {
       lds_off[j] = site * CS + v * 4;
       if ((unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W) {
         const uint64_t w = s_occ[((iy >> 3) - rty0) * 4 + ((ix >> 3) - rtx0)];
-        if ((w >> (((iy & 7) << 3) | (ix & 7))) & 1ull) g_off[j] = (iy * W + ix) * Cin + v * 4;
+        if ((w >> (((iy & 7) << 3) | (ix & 7))) & 1ull) g_off[j] = (unsigned)(((iy * W + ix) * Cin + v * 4) * 4);
       }
     }
   }
+  const __amdgpu_buffer_rsrc_t in_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc((void*)p.in, 0, H * W * Cin * 4, 0x00020000);
   float4 pre[MAXV];
   auto fetch = [&](int c0) {
 #pragma unroll
-    for (int j = 0; j < MAXV; ++j) {
-      pre[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (g_off[j] >= 0) pre[j] = *(const float4*)&p.in[(size_t)g_off[j] + c0];
-    }
+    for (int j = 0; j < MAXV; ++j)
+      pre[j] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(in_rsrc, g_off[j], c0 * 4, 0));
   };
   auto stash = [&]() {
 #pragma unroll
@@ -139,31 +142,36 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_f32_kernel(ConvParams p) {
   const int a_lane_off = (mly * s * P + mlx * s) * CS + half * 4;
   const int a_blk1 = 4 * s * P * CS;
   const float4* __restrict__ wlane = (const float4*)p.w + (size_t)half * cop + co0 + m;
+  // units of this wave: u_j = wave + j * NW, j < n_mine
+  const int n_mine = (n_units - wave + NW - 1) / NW;
+  const int last = n_mine - 1;
+  const int k_magic = (65536 + K - 1) / K;  // tap / K == (tap * k_magic) >> 16 for tap < 49
 
   fetch(0);
   for (int c0 = 0; c0 < Cin; c0 += CHUNK) {
     __syncthreads();  // all waves are done reading the previous chunk
     stash();
     __syncthreads();
-    // units u = wave, wave + NW, ...: (tap, kg) advanced without divisions
-    int tap = wave / KG, kg = wave % KG;
-    int ky = tap / K, kx = tap - ky * K;
+    if (n_mine <= 0) {  // more waves than units (1 x 1 taps): only help with the gather
+      if (c0 + CHUNK < Cin) fetch(c0 + CHUNK);
+      continue;
+    }
     const float4* wchunk = wlane + (size_t)(c0 >> 2) * cop;
-    auto b_addr = [&](int t, int g) { return wchunk + ((size_t)t * cin4 + g * 2) * cop; };
-    // two-deep weight prefetch
-    int tap1 = tap + (kg + NW) / KG, kg1 = (kg + NW) % KG;
-    float4 b0 = make_float4(0.f, 0.f, 0.f, 0.f), b1 = b0;
-    if (wave < n_units) b0 = *b_addr(tap, kg);
-    if (wave + NW < n_units) b1 = *b_addr(tap1, kg1);
-    // next chunk's patch: issued after the first weight loads (vector loads complete in order),
-    // in flight during the contraction below
-    if (c0 + CHUNK < Cin) fetch(c0 + CHUNK);
-    for (int u = wave; u < n_units; u += NW) {
-      const float4 b = b0;
-      b0 = b1;
-      const int tap2 = tap1 + (kg1 + NW) / KG, kg2 = (kg1 + NW) % KG;
-      if (u + 2 * NW < n_units) b1 = *b_addr(tap2, kg2);
-      const float* ap = &s_mem[a_lane_off + (ky * P + kx) * CS + kg * 8];
+    // unit j -> LDS offset of its A fragment and address of its B fragment (clamped to the last
+    // unit so that look-ahead loads stay unconditional and in bounds)
+    auto b_ptr = [&](int j) {
+      const int u = wave + min(j, last) * NW;
+      const int tap = u / KG, kg = u % KG;
+      return wchunk + ((size_t)tap * cin4 + kg * 2) * cop;
+    };
+    auto a_off = [&](int j) {
+      const int u = wave + j * NW;
+      const int tap = u / KG, kg = u % KG;
+      const int ky = (tap * k_magic) >> 16, kx = tap - ky * K;
+      return a_lane_off + (ky * P + kx) * CS + kg * 8;
+    };
+    auto unit = [&](int j, const float4& b) {
+      const float* ap = &s_mem[a_off(j)];
       const float4 a0 = *(const float4*)ap;
       const float4 a1 = *(const float4*)(ap + a_blk1);
       acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.x, b.x, acc0, 0, 0, 0);
@@ -174,14 +182,25 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_f32_kernel(ConvParams p) {
       acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.z, b.z, acc1, 0, 0, 0);
       acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.w, b.w, acc0, 0, 0, 0);
       acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.w, b.w, acc1, 0, 0, 0);
-      // advance (tap, kg) -> next unit of this wave, and its (ky, kx)
-      kx += tap1 - tap;
-      while (kx >= K) { kx -= K; ++ky; }
-      tap = tap1; kg = kg1;
-      tap1 = tap2; kg1 = kg2;
+    };
+    // ring of three weight fragments, two units of look-ahead, no register copies: vector loads
+    // complete in order, so each wait only covers loads issued two units earlier
+    float4 bq0 = *b_ptr(0);
+    float4 bq1 = *b_ptr(1);
+    float4 bq2;
+    if (c0 + CHUNK < Cin) fetch(c0 + CHUNK);  // next chunk's patch, in flight during the contraction
+    int j = 0;
+    for (; j + 3 <= n_mine; j += 3) {
+      bq2 = *b_ptr(j + 2);
+      unit(j, bq0);
+      bq0 = *b_ptr(j + 3);
+      unit(j + 1, bq1);
+      bq1 = *b_ptr(j + 4);
+      unit(j + 2, bq2);
     }
+    if (j < n_mine) unit(j, bq0);
+    if (j + 1 < n_mine) unit(j + 1, bq1);
   }
-
   // ---- reduce the NW partial sums through LDS: slots [4][block*16 + reg][lane]
   __syncthreads();
   if (NW == 8) {
@@ -274,7 +293,7 @@ void launch_variant(const ConvParams& p, hipStream_t s) {
 
 bool conv_mfma_f32_supported(const ConvParams& p) {
   return p.gi.c % 16 == 0 && p.go.c % 32 == 0 && p.c_out_pad == p.go.c &&
-         (long long)p.gi.h * p.gi.w * p.gi.c < (1ll << 31);
+         (long long)p.gi.h * p.gi.w * p.gi.c * 4 < (1ll << 31);  // byte offsets of the gather fit 31 bits
 }
 
 void launch_conv_mfma_f32(const ConvParams& p, hipStream_t s) {
