@@ -28,6 +28,9 @@ struct NodePlan {
   bool keeps_z = false, structural = false;
   int kernel = 0;
   int c_out_pad = 0;
+  int fused_into = -1;      // ADD node executed in the epilogue of that conv node
+  int n_fused = 0;          // conv node: ADD nodes it executes, in order
+  int fused_nodes[kMaxFusedAdds] = {-1, -1};
   // workspace offsets (bytes); resolved to pointers at create
   size_t off_z = 0, off_out = 0, off_pool = 0, off_occ = 0, off_touched = 0, off_idx = 0, off_count = 0,
          off_bitmap = 0, off_w = 0, off_bias = 0, off_y = 0, off_dy = 0;
@@ -247,6 +250,15 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
     const bool two = d.op == EVCONV_OP_ADD || d.op == EVCONV_OP_CONCAT;
     const float* bptr = two ? (d.in1 < 0 ? net->dx : net->L.nodes[d.in1].out) : nullptr;
     const uint64_t* occ_b = two ? (d.in1 < 0 ? net->occ_in : net->L.nodes[d.in1].occ) : nullptr;
+    if (n.fused_into >= 0) {  // computed by the producing conv's epilogue
+      if (d.is_output) {
+        IntegrateParams ip;
+        ip.delta = n.out; ip.occ = n.occ; ip.y = n.y; ip.dy = n.dy; ip.g = n.go;
+        ip.mode = pass == kPassStep ? kIntStep : pass == kPassReset ? kIntReset : kIntRecompute;
+        launch_integrate(ip, s);
+      }
+      continue;
+    }
     const bool timed = net->prof && 2 * (net->prof_node.size() + 1) <= net->prof_ev.size();
     if (timed) (void)hipEventRecord(net->prof_ev[2 * net->prof_node.size()], s);
     switch (n.kernel) {
@@ -256,6 +268,18 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
         p.in = a; p.occ_in = occ_a; p.w = n.w; p.bias = n.bias; p.z = n.z; p.out = n.out;
         p.occ_out = n.occ; p.occ_touched = n.touched; p.gi = n.ga; p.go = n.go; p.c_out_pad = n.c_out_pad;
         p.k = d.kh; p.stride = d.stride; p.pad = d.pad; p.act = d.act; p.dense = dense;
+        p.n_fused = n.n_fused;
+        for (int f = 0; f < n.n_fused; ++f) {
+          const NodePlan& a_node = net->L.nodes[n.fused_nodes[f]];
+          // the ADD's other input: the one that is not the previous stage
+          const int prev = f == 0 ? (int)i : n.fused_nodes[f - 1];
+          const int other = a_node.d.in0 == prev ? a_node.d.in1 : a_node.d.in0;
+          FusedAdd& fa = p.fused[f];
+          fa.skip = other < 0 ? net->dx : net->L.nodes[other].out;
+          fa.occ_skip = other < 0 ? net->occ_in : net->L.nodes[other].occ;
+          fa.z = a_node.z; fa.out = a_node.out; fa.occ_out = a_node.occ; fa.occ_touched = a_node.touched;
+          fa.act = a_node.d.act; fa.keeps_z = a_node.keeps_z; fa.structural = a_node.structural;
+        }
         if (n.kernel == kKernConvMfmaF32) launch_conv_mfma_f32(p, s);
         else launch_conv_valu(p, s);
         break;
@@ -421,6 +445,24 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
   if (e == hipSuccess) e = hipStreamSynchronize(net->stream);
   if (e != hipSuccess) { g_create_error = std::string("upload: ") + hipGetErrorString(e); delete net; return EVCONV_ERR_HIP; }
   if (net->outputs.empty()) { g_create_error = "no output node"; delete net; return EVCONV_ERR_BAD_DESC; }
+  // Fold ADD nodes into the epilogue of the matrix-core conv that produces their later input
+  // (residual add + activation, skip adds).  Every buffer of the ADD node is still written.
+  if (!getenv("EVCONV_NO_FUSION")) {
+    for (size_t i = 0; i < L.nodes.size(); ++i) {
+      NodePlan& a_node = L.nodes[i];
+      if (a_node.d.op != EVCONV_OP_ADD) continue;
+      const int later = a_node.d.in0 > a_node.d.in1 ? a_node.d.in0 : a_node.d.in1;
+      const int other = a_node.d.in0 > a_node.d.in1 ? a_node.d.in1 : a_node.d.in0;
+      if (later < 0 || later == other) continue;
+      const int host = L.nodes[later].fused_into >= 0 ? L.nodes[later].fused_into : later;
+      NodePlan& c_node = L.nodes[host];
+      if (c_node.kernel != kKernConvMfmaF32 || c_node.n_fused >= kMaxFusedAdds) continue;
+      if (host != later && c_node.fused_nodes[c_node.n_fused - 1] != later) continue;  // chain must be contiguous
+      if (other >= host) continue;  // the other input must exist before the conv runs
+      c_node.fused_nodes[c_node.n_fused++] = (int)i;
+      a_node.fused_into = host;
+    }
+  }
   *out = net;
   return EVCONV_OK;
 }
@@ -582,6 +624,7 @@ evconv_status evconv_get_node_time(const evconv_net* net, int32_t node, double* 
 
 const char* evconv_node_kernel(const evconv_net* net, int32_t node) {
   if (!net || node < 0 || node >= (int)net->L.nodes.size()) return "";
+  if (net->L.nodes[node].fused_into >= 0) return "fused_into_conv_epilogue";
   return kKernelNames[net->L.nodes[node].kernel];
 }
 

@@ -42,6 +42,20 @@ struct BuilderParams {
 void launch_builder(const BuilderParams& p, hipStream_t s);
 
 // ---- sparse incremental convolution (Eq.10 at touched tiles, fused Eq.12-14) ------------
+// An ADD node folded into the epilogue of the conv that produces one of its inputs (residual
+// add + activation, or skip add): y_lin = conv_out + skip, then the usual accumulate /
+// activation-increment / mask logic of the ADD node, written to the ADD node's own buffers.
+struct FusedAdd {
+  const float* skip;        // increment of the other input (same geometry as the conv output)
+  const uint64_t* occ_skip; // its occupancy words
+  float* z;                 // accumulated tensor of the ADD node (null if it keeps none)
+  float* out;               // its increment buffer
+  uint64_t* occ_out;        // its S words (pre-zeroed; OR-ed in)
+  uint64_t* occ_touched;    // its T words (pre-zeroed; OR-ed in)
+  int act, keeps_z, structural;
+};
+constexpr int kMaxFusedAdds = 2;
+
 struct ConvParams {
   const float* in;          // H x W x C increment of the input node (full values if dense)
   const uint64_t* occ_in;   // its occupancy words
@@ -55,6 +69,8 @@ struct ConvParams {
   int c_out_pad;
   int k, stride, pad, act;
   int dense;                // 1: regular forward pass (all sites, z overwritten with bias)
+  int n_fused;              // matrix-core kernel only: ADD nodes applied in the epilogue, in order
+  FusedAdd fused[kMaxFusedAdds];
 };
 void launch_conv_valu(const ConvParams& p, hipStream_t s);
 // fp32 MFMA variant; requires c_in % 16 == 0 and c_out % 32 == 0

@@ -101,9 +101,37 @@ void launch_builder(const BuilderParams& p, hipStream_t s) {
 // channel index fastest, so global accesses are contiguous runs of C floats per site.
 constexpr int kEwVecPerBlock = 16;  // channel vectors per workgroup: wide layers split over blockIdx.y
 
+template <int VEC> struct VecT { float v[VEC]; };
+template <int VEC> __device__ __forceinline__ VecT<VEC> ldv(const float* ptr) {
+  VecT<VEC> r;
+  if (VEC == 4) {
+    const float4 t = *(const float4*)ptr;  // channel counts are multiples of 4 and buffers 256-byte aligned
+    r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
+  } else {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) r.v[i] = ptr[i];
+  }
+  return r;
+}
+template <int VEC> __device__ __forceinline__ void stv(float* ptr, const VecT<VEC>& x) {
+  if (VEC == 4) {
+    *(float4*)ptr = make_float4(x.v[0], x.v[1], x.v[2], x.v[3]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) ptr[i] = x.v[i];
+  }
+}
+template <int VEC> __device__ __forceinline__ VecT<VEC> zerov() {
+  VecT<VEC> r;
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) r.v[i] = 0.0f;
+  return r;
+}
+
 template <int VEC>
 __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
   __shared__ int s_sites[64];
+  __shared__ unsigned char s_src[64];  // upsample: which of the four source sites are active
   __shared__ unsigned s_flags[2];
   __shared__ uint64_t s_word, s_wa, s_wb;
   const int tid = threadIdx.x;
@@ -116,6 +144,7 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
     const bool inb = oy < p.go.h && ox < p.go.w;
     bool t = false;
     uint64_t wa = 0, wb = 0;
+    unsigned src = 15;
     if (p.dense) {
       t = inb;
       wa = wb = ~0ull;
@@ -127,12 +156,14 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
       wa = p.occ_a[tile];
       t = (wa >> tid) & 1ull;
     } else if (p.op == kEwUp2x) {
+      src = 0;
       if (inb) {
         const int iy = oy >> 1, ix = ox >> 1;
         const int y0 = (oy & 1) ? iy : max(iy - 1, 0), y1 = (oy & 1) ? min(iy + 1, p.ga.h - 1) : iy;
         const int x0 = (ox & 1) ? ix : max(ix - 1, 0), x1 = (ox & 1) ? min(ix + 1, p.ga.w - 1) : ix;
-        t = occ_bit(p.occ_a, p.ga.tx, y0, x0) | occ_bit(p.occ_a, p.ga.tx, y0, x1) |
-            occ_bit(p.occ_a, p.ga.tx, y1, x0) | occ_bit(p.occ_a, p.ga.tx, y1, x1);
+        src = (unsigned)occ_bit(p.occ_a, p.ga.tx, y0, x0) | ((unsigned)occ_bit(p.occ_a, p.ga.tx, y0, x1) << 1) |
+              ((unsigned)occ_bit(p.occ_a, p.ga.tx, y1, x0) << 2) | ((unsigned)occ_bit(p.occ_a, p.ga.tx, y1, x1) << 3);
+        t = src != 0;
       }
     } else {  // kEwPoolMax: windows that contain an active input site
       if (inb) {
@@ -147,6 +178,7 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
         }
       }
     }
+    s_src[tid] = (unsigned char)src;
     const uint64_t word = __ballot(t);
     if (t) s_sites[__popcll(word & ((1ull << tid) - 1))] = tid;
     if (tid == 0) { s_word = word; s_wa = wa; s_wb = wb; s_flags[0] = 0; s_flags[1] = 0; }
@@ -169,25 +201,27 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
     const int oy = tile_y * 8 + (site >> 3), ox = tile_x * 8 + (site & 7);
     const size_t q = (size_t)oy * p.go.w + ox;
     const int c = v * VEC;
-    float lin[VEC];
+    VecT<VEC> lin;
     if (p.op == kEwAdd) {
       const bool on_a = (wa >> site) & 1ull, on_b = (wb >> site) & 1ull;
+      const VecT<VEC> va = on_a ? ldv<VEC>(&p.a[q * C + c]) : zerov<VEC>();
+      const VecT<VEC> vb = on_b ? ldv<VEC>(&p.b[q * C + c]) : zerov<VEC>();
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) {
-        const float va = on_a ? p.a[q * C + c + i] : 0.0f;
-        const float vb = on_b ? p.b[q * C + c + i] : 0.0f;
-        lin[i] = va + vb;
-      }
+      for (int i = 0; i < VEC; ++i) lin.v[i] = va.v[i] + vb.v[i];
     } else if (p.op == kEwAct || p.op == kEwPoolAcc) {
-#pragma unroll
-      for (int i = 0; i < VEC; ++i) lin[i] = p.a[q * C + c + i];
+      lin = ldv<VEC>(&p.a[q * C + c]);
     } else if (p.op == kEwConcat) {
       const bool on_a = (wa >> site) & 1ull, on_b = (wb >> site) & 1ull;
       const int ca = p.ga.c, cb = p.gb.c;
+      if (VEC == 4) {  // c_a % 4 == 0: a vector never straddles the two inputs
+        lin = c < ca ? (on_a ? ldv<VEC>(&p.a[q * ca + c]) : zerov<VEC>())
+                     : (on_b ? ldv<VEC>(&p.b[q * cb + c - ca]) : zerov<VEC>());
+      } else {
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) {
-        const int cc = c + i;
-        lin[i] = cc < ca ? (on_a ? p.a[q * ca + cc] : 0.0f) : (on_b ? p.b[q * cb + cc - ca] : 0.0f);
+        for (int i = 0; i < VEC; ++i) {
+          const int cc = c + i;
+          lin.v[i] = cc < ca ? (on_a ? p.a[q * ca + cc] : 0.0f) : (on_b ? p.b[q * cb + cc - ca] : 0.0f);
+        }
       }
     } else if (p.op == kEwUp2x) {
       const int iy = oy >> 1, ix = ox >> 1;
@@ -195,63 +229,69 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
       const int x0 = (ox & 1) ? ix : max(ix - 1, 0), x1 = (ox & 1) ? min(ix + 1, p.ga.w - 1) : ix;
       const float wy0 = (oy & 1) ? 0.75f : 0.25f, wy1 = 1.0f - wy0;
       const float wx0 = (ox & 1) ? 0.75f : 0.25f, wx1 = 1.0f - wx0;
-      const bool o00 = p.dense || occ_bit(p.occ_a, p.ga.tx, y0, x0);
-      const bool o01 = p.dense || occ_bit(p.occ_a, p.ga.tx, y0, x1);
-      const bool o10 = p.dense || occ_bit(p.occ_a, p.ga.tx, y1, x0);
-      const bool o11 = p.dense || occ_bit(p.occ_a, p.ga.tx, y1, x1);
-      const size_t b00 = ((size_t)y0 * p.ga.w + x0) * C + c, b01 = ((size_t)y0 * p.ga.w + x1) * C + c;
-      const size_t b10 = ((size_t)y1 * p.ga.w + x0) * C + c, b11 = ((size_t)y1 * p.ga.w + x1) * C + c;
+      const unsigned src = s_src[site];
+      const VecT<VEC> v00 = (src & 1) ? ldv<VEC>(&p.a[((size_t)y0 * p.ga.w + x0) * C + c]) : zerov<VEC>();
+      const VecT<VEC> v01 = (src & 2) ? ldv<VEC>(&p.a[((size_t)y0 * p.ga.w + x1) * C + c]) : zerov<VEC>();
+      const VecT<VEC> v10 = (src & 4) ? ldv<VEC>(&p.a[((size_t)y1 * p.ga.w + x0) * C + c]) : zerov<VEC>();
+      const VecT<VEC> v11 = (src & 8) ? ldv<VEC>(&p.a[((size_t)y1 * p.ga.w + x1) * C + c]) : zerov<VEC>();
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) {
-        const float v00 = o00 ? p.a[b00 + i] : 0.0f, v01 = o01 ? p.a[b01 + i] : 0.0f;
-        const float v10 = o10 ? p.a[b10 + i] : 0.0f, v11 = o11 ? p.a[b11 + i] : 0.0f;
-        lin[i] = wy0 * (wx0 * v00 + wx1 * v01) + wy1 * (wx0 * v10 + wx1 * v11);
-      }
+      for (int i = 0; i < VEC; ++i)
+        lin.v[i] = wy0 * (wx0 * v00.v[i] + wx1 * v01.v[i]) + wy1 * (wx0 * v10.v[i] + wx1 * v11.v[i]);
     } else {  // kEwPoolMax: p.a is the accumulated pool input, p.z the cached window maximum
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) lin[i] = -INFINITY;
+      for (int i = 0; i < VEC; ++i) lin.v[i] = -INFINITY;
       for (int ky = 0; ky < p.k; ++ky) {
         const int iy = oy * p.stride - p.pad + ky;
         if ((unsigned)iy >= (unsigned)p.ga.h) continue;
         for (int kx = 0; kx < p.k; ++kx) {
           const int ix = ox * p.stride - p.pad + kx;
           if ((unsigned)ix >= (unsigned)p.ga.w) continue;
-          const size_t bi = ((size_t)iy * p.ga.w + ix) * C + c;
+          const VecT<VEC> t = ldv<VEC>(&p.a[((size_t)iy * p.ga.w + ix) * C + c]);
 #pragma unroll
-          for (int i = 0; i < VEC; ++i) lin[i] = fmaxf(lin[i], p.a[bi + i]);
+          for (int i = 0; i < VEC; ++i) lin.v[i] = fmaxf(lin.v[i], t.v[i]);
         }
       }
     }
 
-    bool nz = false;
+    float* zq = p.z ? &p.z[q * C + c] : nullptr;
     if (p.op == kEwPoolAcc) {
+      VecT<VEC> acc = lin;
+      if (!p.dense) {
+        const VecT<VEC> old = ldv<VEC>(zq);
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) p.z[q * C + c + i] = p.dense ? lin[i] : p.z[q * C + c + i] + lin[i];
+        for (int i = 0; i < VEC; ++i) acc.v[i] = old.v[i] + lin.v[i];
+      }
+      stv<VEC>(zq, acc);
       continue;
     }
+    VecT<VEC> o;
+    bool nz = false;
+    if (p.op == kEwPoolMax) {
+      const VecT<VEC> m_old = ldv<VEC>(zq);
+      stv<VEC>(zq, lin);
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) {
-      float o;
-      if (p.op == kEwPoolMax) {
-        const float m_old = p.z[q * C + c + i];
-        p.z[q * C + c + i] = lin[i];
-        o = p.dense ? lin[i] : lin[i] - m_old;
-      } else if (p.keeps_z) {
-        if (p.dense) {
-          p.z[q * C + c + i] = lin[i];
-          o = apply_act(p.act, lin[i]);
-        } else {
-          const float z_old = p.z[q * C + c + i];
-          const float z_new = z_old + lin[i];
-          p.z[q * C + c + i] = z_new;
-          o = (p.act == kActNone) ? lin[i] : apply_act(p.act, z_new) - apply_act(p.act, z_old);
-        }
+      for (int i = 0; i < VEC; ++i) o.v[i] = p.dense ? lin.v[i] : lin.v[i] - m_old.v[i];
+    } else if (p.keeps_z) {
+      if (p.dense) {
+        stv<VEC>(zq, lin);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) o.v[i] = apply_act(p.act, lin.v[i]);
       } else {
-        o = lin[i];
+        const VecT<VEC> z_old = ldv<VEC>(zq);
+        VecT<VEC> z_new;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+          z_new.v[i] = z_old.v[i] + lin.v[i];
+          o.v[i] = (p.act == kActNone) ? lin.v[i] : apply_act(p.act, z_new.v[i]) - apply_act(p.act, z_old.v[i]);
+        }
+        stv<VEC>(zq, z_new);
       }
-      p.out[q * C + c + i] = o;
-      nz |= (o != 0.0f);
+    } else {
+      o = lin;
     }
+    stv<VEC>(&p.out[q * C + c], o);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) nz |= (o.v[i] != 0.0f);
     if (nz && !p.structural) atomicOr(&s_flags[site >> 5], 1u << (site & 31));
   }
   if (p.op == kEwPoolAcc) return;

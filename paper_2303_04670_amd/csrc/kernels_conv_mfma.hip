@@ -6,18 +6,23 @@
 //
 // Workgroup = NW (4 or 8) wavefronts that split K: the (tap, 8-channel group) units of every
 // channel chunk are dealt round-robin to the waves; each wave keeps both 32 x 32 accumulators
-// (32 VGPRs) and the partial sums are added through LDS at the end.  K-splitting (rather than
-// N-splitting) is what fills the chip on the low-resolution layers, where a layer has only
+// (32 registers) and the partial sums are added through LDS at the end.  K-splitting (rather
+// than N-splitting) is what fills the chip on the low-resolution layers, where a layer has only
 // 24-88 tiles; those layers run with 8 waves.
+//   Masks: the occupancy words of the input tiles under the halo are turned into one bit row per
+//     patch row in LDS; the touched word of the tile and the gather predicates come from those.
 //   A operand: the input halo patch of the current chunk, gathered once per workgroup into LDS
-//     (zeros for inactive / out-of-image sites, which are never fetched).  The next chunk's
-//     patch is fetched into registers while the current one is being contracted.  A lane
-//     reads 4 consecutive channels of its site with one ds_read_b128.
+//     with buffer loads whose offset is pushed out of range for inactive / out-of-image sites:
+//     the hardware bounds check returns zeros without a memory access (conditioned fetch).  The
+//     next chunk's patch is fetched into registers while the current one is being contracted.
+//     A lane reads 4 consecutive channels of its site with one ds_read_b128.
 //   B operand: weights re-laid as [tap][c_in/4][c_out][4] so that a lane's 4 channels of its
-//     output column are one 16-byte global load (L2-resident), prefetched two units ahead.
+//     output column are one 16-byte global load (L2-resident), held in a three-register ring
+//     two units ahead, across chunk boundaries.
 //   K order inside an 8-channel group: MFMA j contracts channels {j, 4+j}; lanes 0-31 hold
 //     channel j, lanes 32-63 channel 4+j, for both operands.
-// Epilogue: lane = output channel, so every z / increment access is a 128-byte row segment.
+// Epilogue: lane = output channel, so every z / increment access is a 128-byte row segment; the
+// old z values are requested before the contraction starts.
 #include "evconv_kernels.h"
 
 namespace evk {
@@ -32,9 +37,9 @@ __device__ __forceinline__ float act_m(int act, float v) {
   return v;
 }
 
-// largest halo patch: 32-channel chunks are used with stride 1 only (14 x 14 for 7 x 7 taps),
-// 16-channel chunks also with stride 2 (21 x 21)
-constexpr int max_patch_sites(int chunk) { return chunk == 32 ? 14 * 14 : 21 * 21; }
+// largest halo patch edge: 32-channel chunks are used with stride 1 only (7 + 7), 16-channel
+// chunks also with stride 2 (14 + 7)
+constexpr int max_patch_edge(int chunk) { return chunk == 32 ? 14 : 21; }
 
 template <int CHUNK, int NW>
 __global__ __launch_bounds__(NW * 64) void conv_mfma_f32_kernel(ConvParams p) {
@@ -42,10 +47,14 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_f32_kernel(ConvParams p) {
   constexpr int CS = CHUNK + 4;  // LDS site stride in floats: CS/4 odd => conflict-free b128 reads
   constexpr int KG = CHUNK / 8;  // 8-channel groups per chunk
   constexpr int NV = CHUNK / 4;  // float4 per patch site
-  constexpr int MAXV = (max_patch_sites(CHUNK) * NV + NT - 1) / NT;  // patch float4 per thread, upper bound
+  constexpr int MAXP = max_patch_edge(CHUNK);
+  constexpr int MAXV = (MAXP * MAXP * NV + NT - 1) / NT;  // patch float4 per thread, upper bound
+  constexpr int EP_SITES = NT / 32;                       // sites per epilogue pass
+  constexpr int EP_ITERS = 64 / EP_SITES;
   extern __shared__ __align__(16) float s_mem[];
   __shared__ uint64_t s_occ[16];
-  __shared__ unsigned s_nz[2];
+  __shared__ unsigned s_rows[24];  // bit px of s_rows[py]: patch site (py, px) is active
+  __shared__ unsigned s_nz[2 * (1 + kMaxFusedAdds)];  // nonzero-site bits: conv, then each fused ADD
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int tile = blockIdx.x;
@@ -65,39 +74,70 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_f32_kernel(ConvParams p) {
       w = p.dense ? ~0ull : p.occ_in[ty * p.gi.tx + tx];
     s_occ[tid] = w;
   }
-  if (tid < 2) s_nz[tid] = 0;
+  if (tid < 2 * (1 + kMaxFusedAdds)) s_nz[tid] = 0;
+  __syncthreads();
+  if (tid < P) {  // one bit row per patch row; out-of-image sites are 0
+    const int iy = iy0 + tid;
+    unsigned bits = 0;
+    if ((unsigned)iy < (unsigned)H) {
+      const int ry = (iy >> 3) - rty0;
+      // 32 consecutive columns starting at image column rtx0 * 8
+      uint64_t span = 0;
+#pragma unroll
+      for (int rx = 0; rx < 4; ++rx)
+        span |= ((s_occ[ry * 4 + rx] >> ((iy & 7) * 8)) & 0xffull) << (8 * rx);
+      bits = (unsigned)(span >> (ix0 - rtx0 * 8));
+      // clear columns outside the image (dense mode sets every bit) and beyond the patch
+      const int lo = max(0, -ix0), hi = min(P, W - ix0);  // valid px in [lo, hi)
+      unsigned m = hi >= 32 ? ~0u : ((1u << max(hi, 0)) - 1u);
+      m &= ~((1u << lo) - 1u);
+      bits &= m;
+    }
+    s_rows[tid] = bits;
+  }
   __syncthreads();
 
-  // touched word of the tile (identical in all waves)
+  // touched word of the tile (identical in all waves): OR of the K rows, dilated by K columns
   uint64_t touched_word;
   {
-    const int oy = tile_y * 8 + (lane >> 3), ox = tile_x * 8 + (lane & 7);
-    bool touched = false;
-    if (oy < p.go.h && ox < p.go.w) {
-      if (p.dense) {
-        touched = true;
-      } else {
-        for (int ky = 0; ky < K; ++ky) {
-          const int iy = oy * s - p.pad + ky;
-          if ((unsigned)iy >= (unsigned)H) continue;
-          for (int kx = 0; kx < K; ++kx) {
-            const int ix = ox * s - p.pad + kx;
-            if ((unsigned)ix >= (unsigned)W) continue;
-            const uint64_t w = s_occ[((iy >> 3) - rty0) * 4 + ((ix >> 3) - rtx0)];
-            touched |= (w >> (((iy & 7) << 3) | (ix & 7))) & 1ull;
-          }
-        }
-      }
-    }
+    const int ly = lane >> 3, lx = lane & 7;
+    const int oy = tile_y * 8 + ly, ox = tile_x * 8 + lx;
+    unsigned rows = 0;
+    for (int ky = 0; ky < K; ++ky) rows |= s_rows[ly * s + ky];
+    const unsigned win = (rows >> (lx * s)) & ((1u << K) - 1u);
+    const bool touched = (oy < p.go.h) && (ox < p.go.w) && (p.dense || win != 0);
     touched_word = __ballot(touched);
   }
-  if (touched_word == 0) return;
+  // fused ADD nodes: their other input may be active where the conv is not
+  uint64_t skip_word[kMaxFusedAdds];
+  uint64_t site_word = touched_word;  // sites this workgroup has to visit in the epilogue
+#pragma unroll
+  for (int f = 0; f < kMaxFusedAdds; ++f) {
+    skip_word[f] = 0;
+    if (f < p.n_fused) skip_word[f] = p.dense ? touched_word : p.fused[f].occ_skip[tile];
+    site_word |= skip_word[f];
+  }
+  if (site_word == 0) return;
+  const bool conv_on = touched_word != 0;
 
-  // ---- patch gather: per thread a fixed list of (LDS offset, byte offset into the input).
-  // Inactive and out-of-image sites get an offset beyond the buffer: the hardware bounds check
-  // of the buffer load returns zeros for them without touching memory (conditioned fetch).
+  // old z values of the epilogue, requested now so that they arrive during the contraction
+  const int co = tid & 31;
+  const int co0 = blockIdx.y * 32;
+  float z_old[EP_ITERS];
+#pragma unroll
+  for (int it = 0; it < EP_ITERS; ++it) {
+    const int site = it * EP_SITES + (tid >> 5);
+    z_old[it] = 0.0f;
+    if (!p.dense && ((touched_word >> site) & 1ull)) {
+      const int oy = tile_y * 8 + (site >> 3), ox = tile_x * 8 + (site & 7);
+      z_old[it] = p.z[((size_t)oy * p.go.w + ox) * Cout + co0 + co];
+    }
+  }
+
+  // ---- patch gather: per thread a fixed list of (LDS offset, byte offset into the input)
   constexpr unsigned kOob = 0x80000000u;
   const int total_v = P * P * NV;
+  const int p_magic = (65536 + P - 1) / P;  // site / P == (site * p_magic) >> 16 for site < 441
   int lds_off[MAXV];
   unsigned g_off[MAXV];
 #pragma unroll
@@ -107,13 +147,9 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_f32_kernel(ConvParams p) {
     g_off[j] = kOob;
     if (e < total_v) {
       const int site = e / NV, v = e - site * NV;
-      const int py = site / P, px = site - py * P;
-      const int iy = iy0 + py, ix = ix0 + px;
+      const int py = (site * p_magic) >> 16, px = site - py * P;
       lds_off[j] = site * CS + v * 4;
-      if ((unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W) {
-        const uint64_t w = s_occ[((iy >> 3) - rty0) * 4 + ((ix >> 3) - rtx0)];
-        if ((w >> (((iy & 7) << 3) | (ix & 7))) & 1ull) g_off[j] = (unsigned)(((iy * W + ix) * Cin + v * 4) * 4);
-      }
+      if ((s_rows[py] >> px) & 1u) g_off[j] = (unsigned)((((iy0 + py) * W + ix0 + px) * Cin + v * 4) * 4);
     }
   }
   const __amdgpu_buffer_rsrc_t in_rsrc =
@@ -135,7 +171,6 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_f32_kernel(ConvParams p) {
   for (int i = 0; i < 16; ++i) { acc0[i] = 0.0f; acc1[i] = 0.0f; }
   const int half = lane >> 5, m = lane & 31;
   const int mly = m >> 3, mlx = m & 7;  // site of this lane inside a 32-row block
-  const int co0 = blockIdx.y * 32;
   const int cop = p.c_out_pad;
   const int n_units = K * K * KG;
   const int cin4 = Cin >> 2;
@@ -147,60 +182,69 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_f32_kernel(ConvParams p) {
   const int last = n_mine - 1;
   const int k_magic = (65536 + K - 1) / K;  // tap / K == (tap * k_magic) >> 16 for tap < 49
 
-  fetch(0);
-  for (int c0 = 0; c0 < Cin; c0 += CHUNK) {
+  // unit j of the chunk starting at channel c0 -> address of its B fragment (j clamped to the
+  // last unit so that look-ahead loads stay unconditional and in bounds)
+  auto b_ptr = [&](int c0, int j) {
+    const int u = wave + min(j, last) * NW;
+    const int tap = u / KG, kg = u % KG;
+    return wlane + ((size_t)tap * cin4 + (c0 >> 2) + kg * 2) * cop;
+  };
+  // ... and LDS offset of its A fragment
+  auto a_off = [&](int j) {
+    const int u = wave + j * NW;
+    const int tap = u / KG, kg = u % KG;
+    const int ky = (tap * k_magic) >> 16, kx = tap - ky * K;
+    return a_lane_off + (ky * P + kx) * CS + kg * 8;
+  };
+  auto unit = [&](int j, const float4& b) {
+    const float* ap = &s_mem[a_off(j)];
+    const float4 a0 = *(const float4*)ap;
+    const float4 a1 = *(const float4*)(ap + a_blk1);
+    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.x, b.x, acc0, 0, 0, 0);
+    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.x, b.x, acc1, 0, 0, 0);
+    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.y, b.y, acc0, 0, 0, 0);
+    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.y, b.y, acc1, 0, 0, 0);
+    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.z, b.z, acc0, 0, 0, 0);
+    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.z, b.z, acc1, 0, 0, 0);
+    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.w, b.w, acc0, 0, 0, 0);
+    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.w, b.w, acc1, 0, 0, 0);
+  };
+
+  // Ring of three weight fragments, two units of look-ahead, no register copies: vector loads
+  // complete in order, so each wait only covers loads issued two units earlier.  The first two
+  // fragments of a chunk are requested before the barriers that precede it.
+  float4 bq0 = make_float4(0.f, 0.f, 0.f, 0.f), bq1 = bq0, bq2 = bq0;
+  if (conv_on) {
+    fetch(0);
+    if (n_mine > 0) {
+      bq0 = *b_ptr(0, 0);
+      bq1 = *b_ptr(0, 1);
+    }
+  }
+  for (int c0 = 0; conv_on && c0 < Cin; c0 += CHUNK) {
     __syncthreads();  // all waves are done reading the previous chunk
     stash();
     __syncthreads();
-    if (n_mine <= 0) {  // more waves than units (1 x 1 taps): only help with the gather
-      if (c0 + CHUNK < Cin) fetch(c0 + CHUNK);
-      continue;
-    }
-    const float4* wchunk = wlane + (size_t)(c0 >> 2) * cop;
-    // unit j -> LDS offset of its A fragment and address of its B fragment (clamped to the last
-    // unit so that look-ahead loads stay unconditional and in bounds)
-    auto b_ptr = [&](int j) {
-      const int u = wave + min(j, last) * NW;
-      const int tap = u / KG, kg = u % KG;
-      return wchunk + ((size_t)tap * cin4 + kg * 2) * cop;
-    };
-    auto a_off = [&](int j) {
-      const int u = wave + j * NW;
-      const int tap = u / KG, kg = u % KG;
-      const int ky = (tap * k_magic) >> 16, kx = tap - ky * K;
-      return a_lane_off + (ky * P + kx) * CS + kg * 8;
-    };
-    auto unit = [&](int j, const float4& b) {
-      const float* ap = &s_mem[a_off(j)];
-      const float4 a0 = *(const float4*)ap;
-      const float4 a1 = *(const float4*)(ap + a_blk1);
-      acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.x, b.x, acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.x, b.x, acc1, 0, 0, 0);
-      acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.y, b.y, acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.y, b.y, acc1, 0, 0, 0);
-      acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.z, b.z, acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.z, b.z, acc1, 0, 0, 0);
-      acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.w, b.w, acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.w, b.w, acc1, 0, 0, 0);
-    };
-    // ring of three weight fragments, two units of look-ahead, no register copies: vector loads
-    // complete in order, so each wait only covers loads issued two units earlier
-    float4 bq0 = *b_ptr(0);
-    float4 bq1 = *b_ptr(1);
-    float4 bq2;
-    if (c0 + CHUNK < Cin) fetch(c0 + CHUNK);  // next chunk's patch, in flight during the contraction
+    const bool more = c0 + CHUNK < Cin;
+    if (more) fetch(c0 + CHUNK);  // next chunk's patch, in flight during the contraction
+    if (n_mine <= 0) continue;    // more waves than units (1 x 1 taps): only help with the gather
     int j = 0;
     for (; j + 3 <= n_mine; j += 3) {
-      bq2 = *b_ptr(j + 2);
+      bq2 = *b_ptr(c0, j + 2);
       unit(j, bq0);
-      bq0 = *b_ptr(j + 3);
+      bq0 = *b_ptr(c0, j + 3);
       unit(j + 1, bq1);
-      bq1 = *b_ptr(j + 4);
+      bq1 = *b_ptr(c0, j + 4);
       unit(j + 2, bq2);
     }
     if (j < n_mine) unit(j, bq0);
     if (j + 1 < n_mine) unit(j + 1, bq1);
+    if (more) {
+      bq0 = *b_ptr(c0 + CHUNK, 0);
+      bq1 = *b_ptr(c0 + CHUNK, 1);
+    }
   }
+
   // ---- reduce the NW partial sums through LDS: slots [4][block*16 + reg][lane]
   __syncthreads();
   if (NW == 8) {
@@ -232,49 +276,86 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_f32_kernel(ConvParams p) {
   }
   __syncthreads();
 
-  // epilogue: thread -> (output channel = tid % 32, 64 / (NT / 32) sites); accumulator element
+  // epilogue: thread -> (output channel = tid % 32, EP_ITERS sites); accumulator element
   // (block b, register i, lane l) is site b*32 + 8*(i/4) + 4*(l/32) + i%4, channel l%32
-  const int co = tid & 31;
   uint64_t nz_sites = 0;
-  constexpr int SITES_PER_IT = NT / 32;
-  for (int it = 0; it < 64 / SITES_PER_IT; ++it) {
-    const int site = it * SITES_PER_IT + (tid >> 5);
-    if (!((touched_word >> site) & 1ull)) continue;
-    const int b = site >> 5, r = site & 31;
-    const int reg = (r >> 3) * 4 + (r & 3);
-    const int l = ((r >> 2) & 1) * 32 + co;
-    const int off = (b * 16 + reg) * 64 + l;
-    const float v = (s_mem[off] + s_mem[off + 2048]) + (s_mem[off + 4096] + s_mem[off + 6144]);
+  uint64_t nz_fused[kMaxFusedAdds] = {0, 0};
+#pragma unroll
+  for (int it = 0; it < EP_ITERS; ++it) {
+    const int site = it * EP_SITES + (tid >> 5);
+    if (!((site_word >> site) & 1ull)) continue;
     const int oy = tile_y * 8 + (site >> 3), ox = tile_x * 8 + (site & 7);
     const size_t q = ((size_t)oy * p.go.w + ox) * Cout + co0 + co;
-    float o;
-    if (p.dense) {
-      const float z = v + (p.bias ? p.bias[co0 + co] : 0.0f);
-      p.z[q] = z;
-      o = act_m(p.act, z);
-    } else {
-      const float z_old = p.z[q];
-      const float z_new = z_old + v;
-      p.z[q] = z_new;
-      o = (p.act == kActNone) ? v : act_m(p.act, z_new) - act_m(p.act, z_old);
+    float o = 0.0f;
+    if ((touched_word >> site) & 1ull) {
+      const int b = site >> 5, r = site & 31;
+      const int reg = (r >> 3) * 4 + (r & 3);
+      const int l = ((r >> 2) & 1) * 32 + co;
+      const int off = (b * 16 + reg) * 64 + l;
+      const float v = (s_mem[off] + s_mem[off + 2048]) + (s_mem[off + 4096] + s_mem[off + 6144]);
+      if (p.dense) {
+        const float z = v + (p.bias ? p.bias[co0 + co] : 0.0f);
+        p.z[q] = z;
+        o = act_m(p.act, z);
+      } else {
+        const float z_new = z_old[it] + v;
+        p.z[q] = z_new;
+        o = (p.act == kActNone) ? v : act_m(p.act, z_new) - act_m(p.act, z_old[it]);
+      }
+      p.out[q] = o;
+      if (o != 0.0f) nz_sites |= 1ull << site;
     }
-    p.out[q] = o;
-    if (o != 0.0f) nz_sites |= 1ull << site;
+    // fused ADD nodes (Eq.11 followed by Eq.12-14): a = the value just produced, b = skip input
+#pragma unroll
+    for (int f = 0; f < kMaxFusedAdds; ++f) {
+      if (f >= p.n_fused) break;
+      const FusedAdd& fa = p.fused[f];
+      const float vb = ((skip_word[f] >> site) & 1ull) ? fa.skip[q] : 0.0f;
+      const float lin = o + vb;
+      if (fa.keeps_z) {
+        if (p.dense) {
+          fa.z[q] = lin;
+          o = act_m(fa.act, lin);
+        } else {
+          const float z2_old = fa.z[q];
+          const float z2_new = z2_old + lin;
+          fa.z[q] = z2_new;
+          o = (fa.act == kActNone) ? lin : act_m(fa.act, z2_new) - act_m(fa.act, z2_old);
+        }
+      } else {
+        o = lin;
+      }
+      fa.out[q] = o;
+      if (o != 0.0f) nz_fused[f] |= 1ull << site;
+    }
   }
-  if (!p.dense) {
-    if (nz_sites) {
-      if ((unsigned)nz_sites) atomicOr(&s_nz[0], (unsigned)nz_sites);
-      if ((unsigned)(nz_sites >> 32)) atomicOr(&s_nz[1], (unsigned)(nz_sites >> 32));
-    }
-    __syncthreads();
-    if (tid == 0) {
-      const uint64_t w = (uint64_t)s_nz[0] | ((uint64_t)s_nz[1] << 32);
-      if (w) atomicOr((unsigned long long*)&p.occ_out[tile], (unsigned long long)w);
-      if (blockIdx.y == 0) p.occ_touched[tile] = touched_word;
-    }
-  } else if (tid == 0) {
-    atomicOr((unsigned long long*)&p.occ_out[tile], (unsigned long long)touched_word);
+  auto lds_or = [&](int slot, uint64_t bits) {
+    if ((unsigned)bits) atomicOr(&s_nz[2 * slot], (unsigned)bits);
+    if ((unsigned)(bits >> 32)) atomicOr(&s_nz[2 * slot + 1], (unsigned)(bits >> 32));
+  };
+  lds_or(0, nz_sites);
+#pragma unroll
+  for (int f = 0; f < kMaxFusedAdds; ++f)
+    if (f < p.n_fused) lds_or(1 + f, nz_fused[f]);
+  __syncthreads();
+  if (tid == 0) {
+    auto glob_or = [](uint64_t* dst, uint64_t bits) {
+      if (bits) atomicOr((unsigned long long*)dst, (unsigned long long)bits);
+    };
+    // S of the producer as seen by this workgroup's channels; all words are pre-zeroed and the
+    // workgroups of the other channel blocks OR their share in
+    uint64_t s_prev = p.dense ? touched_word : ((uint64_t)s_nz[0] | ((uint64_t)s_nz[1] << 32));
+    glob_or(&p.occ_out[tile], s_prev);
     if (blockIdx.y == 0) p.occ_touched[tile] = touched_word;
+    for (int f = 0; f < p.n_fused; ++f) {
+      const FusedAdd& fa = p.fused[f];
+      const uint64_t t_f = s_prev | skip_word[f];  // Eq.11b
+      const uint64_t nz_f = (uint64_t)s_nz[2 + 2 * f] | ((uint64_t)s_nz[3 + 2 * f] << 32);
+      const uint64_t s_f = (fa.structural || p.dense) ? t_f : nz_f;
+      glob_or(&fa.occ_touched[tile], t_f);
+      glob_or(&fa.occ_out[tile], s_f);
+      s_prev = s_f;
+    }
   }
 }
 

@@ -104,8 +104,22 @@ def test_unet_full_width_reduced_size_matrix_core_layers():
     names = [g.kernel_name(i) for i in range(len(net.nodes))]
     g.destroy()
     assert names.count("conv_mfma_f32") == 10 and names[0] == "conv_valu_f32", names
+    assert names.count("fused_into_conv_epilogue") == 6, names   # 2 residual adds + 4 skip adds
     frames = list(wl.stream_voxel(1003, 64, 96, 20, 0.02, n_prim=6))
     run_stream(net, frames[0], frames[1:], "frame", label="unet-wide", max_flips=40)
+
+
+def test_unet_full_width_without_epilogue_fusion(monkeypatch):
+    """The same graph with ADD nodes run by their own kernels instead of the conv epilogues."""
+    _say("UNet depth net, full width on 5x64x96, ADD nodes unfused")
+    monkeypatch.setenv("EVCONV_NO_FUSION", "1")
+    net = wl.net_unet_depth(1003, h=64, w=96)
+    g = ev.EvConvNet(net)
+    names = [g.kernel_name(i) for i in range(len(net.nodes))]
+    g.destroy()
+    assert "fused_into_conv_epilogue" not in names
+    frames = list(wl.stream_voxel(1003, 64, 96, 8, 0.02, n_prim=6))
+    run_stream(net, frames[0], frames[1:], "frame", label="unet-wide-unfused", max_flips=40)
 
 
 def test_matrix_core_conv_shapes():
