@@ -9,8 +9,8 @@
 //   2. the input halo patch is gathered into LDS 16 channels at a time; inactive or
 //      out-of-image sites are written as zeros without touching global memory (conditioned
 //      fetch);
-//   3. weights are wave-uniform, so they arrive through scalar loads and each LDS read of an
-//      increment feeds 8 FMAs;
+//   3. the weights of one kernel row are staged in LDS; a wave reads its 8 channels with two
+//      broadcast ds_read_b128, so each LDS read of an increment feeds 8 FMAs;
 //   4. the epilogue read-modify-writes z at touched sites only, forms the activation
 //      increment (Eq.12) and ORs the per-site nonzero ballot into the output occupancy word.
 #include "evconv_kernels.h"
@@ -80,7 +80,8 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(ConvParams p) {
 #pragma unroll
   for (int j = 0; j < kCpt; ++j) acc[j] = 0.0f;
   const int co0 = blockIdx.y * (4 * kCpt) + wave * kCpt;
-  const float* __restrict__ wbase = (const float*)p.w + co0;
+  const float* __restrict__ wblock = (const float*)p.w + blockIdx.y * (4 * kCpt);
+  float* s_w = s_patch + P * P * kChunkPad;  // staged weights of one kernel row
   const int cop = p.c_out_pad;
   const bool vec_in = (Cin & 3) == 0;
 
@@ -115,30 +116,28 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(ConvParams p) {
         s_patch[site * kChunkPad + c] = val;
       }
     }
-    __syncthreads();
-    if (co0 < cop) {
-      for (int ky = 0; ky < K; ++ky) {
-        for (int kx = 0; kx < K; ++kx) {
-          const float* prow = &s_patch[((ly * s + ky) * P + lx * s + kx) * kChunkPad];
-          const float* wrow = wbase + ((size_t)(ky * K + kx) * Cin + c0) * cop;
-          if (vec_in) {
-            for (int c = 0; c < chn; c += 4) {
-              const float4 a = *(const float4*)&prow[c];
-#pragma unroll
-              for (int j = 0; j < kCpt; ++j) {
-                acc[j] = fmaf(a.x, wrow[(size_t)(c + 0) * cop + j], acc[j]);
-                acc[j] = fmaf(a.y, wrow[(size_t)(c + 1) * cop + j], acc[j]);
-                acc[j] = fmaf(a.z, wrow[(size_t)(c + 2) * cop + j], acc[j]);
-                acc[j] = fmaf(a.w, wrow[(size_t)(c + 3) * cop + j], acc[j]);
-              }
-            }
-          } else {
-            for (int c = 0; c < chn; ++c) {
-              const float a = prow[c];
-#pragma unroll
-              for (int j = 0; j < kCpt; ++j) acc[j] = fmaf(a, wrow[(size_t)c * cop + j], acc[j]);
-            }
-          }
+    // one kernel row at a time: its weights [kx][c][32 channels of this workgroup] are staged in
+    // LDS (wave-uniform reads are broadcasts), so the inner loop never waits on memory
+    for (int ky = 0; ky < K; ++ky) {
+      __syncthreads();  // patch complete (first row) / previous row's weights no longer read
+      const int wtotal = K * chn * 32;
+      for (int e = tid; e < wtotal; e += 256) {
+        const int j = e & 31, rc = e >> 5;
+        const int kx = rc / chn, c = rc - kx * chn;
+        s_w[e] = wblock[((size_t)(ky * K + kx) * Cin + c0 + c) * cop + j];
+      }
+      __syncthreads();
+      for (int kx = 0; kx < K; ++kx) {
+        const float* prow = &s_patch[((ly * s + ky) * P + lx * s + kx) * kChunkPad];
+        const float* wrow = &s_w[kx * chn * 32 + wave * kCpt];
+        for (int c = 0; c < chn; ++c) {
+          const float a = prow[c];
+          const float4 w0 = *(const float4*)&wrow[c * 32];
+          const float4 w1 = *(const float4*)&wrow[c * 32 + 4];
+          acc[0] = fmaf(a, w0.x, acc[0]); acc[1] = fmaf(a, w0.y, acc[1]);
+          acc[2] = fmaf(a, w0.z, acc[2]); acc[3] = fmaf(a, w0.w, acc[3]);
+          acc[4] = fmaf(a, w1.x, acc[4]); acc[5] = fmaf(a, w1.y, acc[5]);
+          acc[6] = fmaf(a, w1.z, acc[6]); acc[7] = fmaf(a, w1.w, acc[7]);
         }
       }
     }
@@ -179,7 +178,7 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(ConvParams p) {
 
 void launch_conv_valu(const ConvParams& p, hipStream_t s) {
   const int P = 7 * p.stride + p.k;
-  const size_t lds = (size_t)P * P * kChunkPad * sizeof(float);
+  const size_t lds = ((size_t)P * P * kChunkPad + (size_t)p.k * kChunk * 32) * sizeof(float);
   dim3 grid(p.go.tiles(), (p.go.c + 4 * kCpt - 1) / (4 * kCpt));
   hipLaunchKernelGGL(conv_valu_kernel, grid, dim3(256), lds, s, p);
 }
