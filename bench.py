@@ -3,12 +3,15 @@
 
 A step = one evconv_step_frame call: increment builder, every layer's increment kernel, output
 integration and list compaction, on one frame of a synthetic event-voxel stream that is already
-resident in HBM.  Workload: the UNet depth network on 5x256x352 at 2 % changed pixels per step.
+resident in HBM.  Workload: the UNet depth network on 5x256x352 at 2 % changed pixels per step,
+fp32 weights (headline) and the bf16-weight variant (reported beside it).
 
-Prints ONE JSON line (see the fields below).  Extra keys: `dense_recompute` (the same frames run as
-regular forward passes through the same kernels), `roofline` (dominant kernel family, timed with
-HIP events on the library's stream inside the timed region) and `cpu_baseline` (the CPU oracle on
-a bounded sample of the same frames).
+Prints ONE JSON line.  Extra keys: `dense_recompute` (the same frames run as regular forward
+passes through the same kernels), `roofline` (dominant kernel family, timed with HIP events on the
+library's stream inside the timed region), `cpu_baseline` (the CPU oracle on a bounded sample of
+the same frames), `bf16_variant`, `layers`.
+
+`--sweep` runs the density sweep of the optical-flow encoder-decoder instead (one JSON line).
 """
 import argparse
 import json
@@ -23,74 +26,39 @@ if ROOT not in sys.path:
 PEAKS = {  # MI355X published dense peaks
     "conv_mfma_f32": ("mfma", 157.3, "TFLOP/s"),
     "conv_mfma_bf16": ("mfma", 2500.0, "TFLOP/s"),
-    # vector ALU fp32: 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2 (dual-issue/packed) x 2.4 GHz
+    # vector ALU fp32: 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2 (packed) x 2.4 GHz
     "conv_valu_f32": ("alu", 157.3, "TFLOP/s"),
 }
 
+# HBM bytes per launch of the dominant kernel family, from the committed rocprofv3 counter runs
+# (profiles/unet_depth_f32_incremental_kernels.md: FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00)
+TRAFFIC_FROM_PROFILE = {"conv_mfma_f32": 33.9e6}
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--density", type=float, default=0.02)
-    ap.add_argument("--variant", choices=["f32", "bf16"], default="f32")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-steps", type=int, default=20)
-    ap.add_argument("--no-dense", action="store_true")
-    ap.add_argument("--calib-copy-mb", type=int, default=0,
-                    help="also run plain device-to-device copies of this size (for scaling rocprofv3 "
-                         "FETCH_SIZE / WRITE_SIZE readings against a kernel of known traffic)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU (one event stream per device, no collectives); "
-                 "--gpus must be 1")
 
-    import numpy as np
-    import torch
-    from paper_2303_04670_amd import evconv as ev
-    from paper_2303_04670_amd import workloads as wl
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    dev = torch.device("cuda:0")
+def run_variant(args, np, torch, ev, wl, variant, frames, dframes, with_dense, with_layers):
     H, W = 256, 352
-    net = wl.net_unet_depth(1003, h=H, w=W, bf16=(args.variant == "bf16"))
+    net = wl.net_unet_depth(1003, h=H, w=W, bf16=(variant == "bf16"))
     n_frames = args.warmup + args.steps
-    frames = list(wl.stream_voxel(1003, H, W, n_frames, args.density))
-    dens = float(np.mean([wl.changed_fraction(frames[i], frames[i + 1]) for i in range(args.warmup, n_frames)]))
-    dframes = [torch.from_numpy(f).to(dev) for f in frames]
-    torch.cuda.synchronize()
-    if args.calib_copy_mb:
-        src = torch.empty(args.calib_copy_mb << 20, dtype=torch.uint8, device=dev).random_(0, 255)
-        dst = torch.empty_like(src)
-        for _ in range(4):
-            dst.copy_(src)
-        torch.cuda.synchronize()
 
-    def timed_run(mode, profile):
+    def timed_run(mode):
         g = ev.EvConvNet(net, device="cuda:0")
         g.set_mode(mode)
         g.reset(dframes[0])
         for i in range(1, args.warmup + 1):
             g.step_frame(dframes[i])
         torch.cuda.synchronize()
-        if profile:
-            g.profile_begin(args.steps * len(net.nodes))
+        g.profile_begin(args.steps * len(net.nodes))
         t0 = time.perf_counter()
         for i in range(args.warmup + 1, n_frames + 1):
             g.step_frame(dframes[i])
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        if profile:
-            g.profile_end()
+        g.profile_end()
         return g, dt
 
-    g, dt = timed_run(ev.MODE_INCREMENTAL, profile=True)
-    ms_per_step = dt / args.steps * 1e3
-
+    g, dt = timed_run(ev.MODE_INCREMENTAL)
     # per kernel family: accumulated event time, launches, algorithmic flops of the timed launches
-    fam = {}
-    layers = []
+    fam, layers = {}, []
     for i, nd in enumerate(net.nodes):
         ms, n = g.node_time(i)
         name = g.kernel_name(i)
@@ -108,27 +76,87 @@ def main():
     bound, peak, unit = PEAKS[dom]
     achieved = fam[dom]["flops"] / (fam[dom]["ms"] * 1e-3) / 1e12 if fam[dom]["ms"] > 0 else 0.0
     roofline = dict(kernel=dom, bound=bound, achieved=achieved, peak=peak, unit=unit, frac=achieved / peak,
-                    traffic=None, avg_launch_ms=fam[dom]["ms"] / max(fam[dom]["launches"], 1),
+                    traffic=TRAFFIC_FROM_PROFILE.get(dom), avg_launch_ms=fam[dom]["ms"] / max(fam[dom]["launches"], 1),
                     launches=fam[dom]["launches"], share_of_step=fam[dom]["ms"] / (dt * 1e3))
     g.destroy()
-
-    out = {
-        "metric": "incremental steps/sec at 2% density (UNet depth net)",
-        "value": args.steps / dt, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if args.variant == "f32" else "bf16", "data": "synthetic",
-        "config": {"workload": f"unet_depth_5x{H}x{W}_voxel_stream", "changed_pixel_fraction": round(dens, 5),
-                   "weights": args.variant, "mode": "incremental", "batch": 1},
-        "roofline": roofline,
-    }
-    if not args.no_dense:
-        g2, dt2 = timed_run(ev.MODE_DENSE_RECOMPUTE, profile=True)
+    res = dict(value=args.steps / dt, ms_per_step=dt / args.steps * 1e3, roofline=roofline)
+    if with_dense:
+        g2, dt2 = timed_run(ev.MODE_DENSE_RECOMPUTE)
         for i, l in enumerate(layers):
             ms, n = g2.node_time(i)
             l["dense_ms_avg"] = ms / max(n, 1)
         g2.destroy()
-        out["dense_recompute"] = {"value": args.steps / dt2, "unit": "steps/s", "ms_per_step": dt2 / args.steps * 1e3,
+        res["dense_recompute"] = {"value": args.steps / dt2, "unit": "steps/s", "ms_per_step": dt2 / args.steps * 1e3,
                                   "incremental_speedup": dt2 / dt}
+    if with_layers:
+        res["layers"] = layers
+    return net, res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--density", type=float, default=0.02)
+    ap.add_argument("--variant", choices=["f32", "bf16"], default="f32", help="weights of the headline run")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-steps", type=int, default=20)
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-second-variant", action="store_true")
+    ap.add_argument("--calib-copy-mb", type=int, default=0,
+                    help="also run plain device-to-device copies of this size (for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings against a kernel of known traffic)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the headline run: optical-flow encoder-decoder (4x256x256), incremental "
+                         "vs dense recompute at 10 increment densities 0.1 % .. 20 %; prints one JSON line")
+    ap.add_argument("--sweep-steps", type=int, default=30)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (one event stream per device, no collectives); "
+                 "--gpus must be 1")
+
+    import numpy as np
+    import torch
+    from paper_2303_04670_amd import evconv as ev
+    from paper_2303_04670_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    if args.sweep:
+        return density_sweep(args, np, torch, ev, wl, dev)
+    H, W = 256, 352
+    n_frames = args.warmup + args.steps
+    frames = list(wl.stream_voxel(1003, H, W, n_frames, args.density))
+    dens = float(np.mean([wl.changed_fraction(frames[i], frames[i + 1]) for i in range(args.warmup, n_frames)]))
+    dframes = [torch.from_numpy(f).to(dev) for f in frames]
+    torch.cuda.synchronize()
+    if args.calib_copy_mb:
+        src = torch.empty(args.calib_copy_mb << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
+    net, res = run_variant(args, np, torch, ev, wl, args.variant, frames, dframes, not args.no_dense, True)
+    out = {
+        "metric": "incremental steps/sec at 2% density (UNet depth net)",
+        "value": res["value"], "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": args.variant, "data": "synthetic",
+        "config": {"workload": f"unet_depth_5x{H}x{W}_voxel_stream", "changed_pixel_fraction": round(dens, 5),
+                   "weights": args.variant, "mode": "incremental", "batch": 1},
+        "roofline": res["roofline"],
+    }
+    if "dense_recompute" in res:
+        out["dense_recompute"] = res["dense_recompute"]
+    if not args.no_second_variant:
+        other = "bf16" if args.variant == "f32" else "f32"
+        _, r2 = run_variant(args, np, torch, ev, wl, other, frames, dframes, not args.no_dense, False)
+        r2["unit"] = "steps/s"
+        r2["weights"] = other
+        r2["parity_bar"] = "2e-2 relative (Frobenius)" if other == "bf16" else "1e-4 max-abs"
+        out[f"{other}_variant"] = r2
     if not args.no_cpu_baseline:
         from oracle.oracle import Oracle
         ora = Oracle(net)
@@ -141,8 +169,43 @@ def main():
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
         out["cpu_baseline"] = {"value": k / cdt, "unit": "steps/s", "cores": cores, "kind": "oracle",
                                "sample": f"first {k} frames of the same stream, fp64, OpenMP"}
-    out["layers"] = layers
+    out["layers"] = res["layers"]
     print(json.dumps(out), flush=True)
+
+
+def density_sweep(args, np, torch, ev, wl, dev):
+    """Workload 5: where does incremental inference beat a dense recompute built from the same
+    kernels?  One stream per density so that every timed step runs at that density."""
+    net = wl.net_flow(1005)
+    rows = []
+    for dens in np.geomspace(0.001, 0.2, 10):
+        n = 5 + args.sweep_steps
+        frames = list(wl.stream_count_timestamp(1005, 256, 256, densities=[float(dens)], steps_per=n))
+        real = float(np.mean([wl.changed_fraction(frames[i], frames[i + 1]) for i in range(5, n)]))
+        dfr = [torch.from_numpy(f).to(dev) for f in frames]
+        t = {}
+        for mode in (ev.MODE_INCREMENTAL, ev.MODE_DENSE_RECOMPUTE):
+            g = ev.EvConvNet(net, device="cuda:0")
+            g.set_mode(mode)
+            g.reset(dfr[0])
+            for i in range(1, 6):
+                g.step_frame(dfr[i])
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(6, n + 1):
+                g.step_frame(dfr[i])
+            torch.cuda.synchronize()
+            t[mode] = (time.perf_counter() - t0) / (n - 5) * 1e3
+            if mode == ev.MODE_INCREMENTAL:
+                ex = sum(g.stats(i).flops_executed for i in range(len(net.nodes)))
+                de = sum(g.stats(i).flops_dense for i in range(len(net.nodes)))
+            g.destroy()
+        rows.append(dict(density=real, incremental_ms=t[ev.MODE_INCREMENTAL], dense_ms=t[ev.MODE_DENSE_RECOMPUTE],
+                         speedup=t[ev.MODE_DENSE_RECOMPUTE] / t[ev.MODE_INCREMENTAL],
+                         tile_flop_fraction=ex / de))
+    print(json.dumps({"metric": "density sweep: incremental vs dense recompute (flow encoder-decoder 4x256x256)",
+                      "unit": "ms/step", "n_gpus": 1, "steps_per_density": args.sweep_steps, "dtype": "f32",
+                      "data": "synthetic", "rows": rows}), flush=True)
 
 
 if __name__ == "__main__":

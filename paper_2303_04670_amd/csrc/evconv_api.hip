@@ -18,9 +18,17 @@ namespace {
 
 thread_local std::string g_create_error;
 
-enum KernelKind { kKernConvValu = 0, kKernConvMfmaF32, kKernElementwise, kKernGap, kKernPool };
+enum KernelKind { kKernConvValu = 0, kKernConvMfmaF32, kKernElementwise, kKernGap, kKernPool, kKernConvMfmaBf16 };
 const char* const kKernelNames[] = {"conv_valu_f32", "conv_mfma_f32", "elementwise", "global_avgpool",
-                                    "maxpool"};
+                                    "maxpool", "conv_mfma_bf16"};
+
+// fp32 -> bf16 bits, round to nearest even
+uint16_t to_bf16(float x) {
+  uint32_t u;
+  memcpy(&u, &x, 4);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;
+  return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
 
 struct NodePlan {
   evconv_node_desc d;
@@ -263,6 +271,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
     if (timed) (void)hipEventRecord(net->prof_ev[2 * net->prof_node.size()], s);
     switch (n.kernel) {
       case kKernConvValu:
+      case kKernConvMfmaBf16:
       case kKernConvMfmaF32: {
         ConvParams p;
         p.in = a; p.occ_in = occ_a; p.w = n.w; p.bias = n.bias; p.z = n.z; p.out = n.out;
@@ -281,6 +290,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
           fa.act = a_node.d.act; fa.keeps_z = a_node.keeps_z; fa.structural = a_node.structural;
         }
         if (n.kernel == kKernConvMfmaF32) launch_conv_mfma_f32(p, s);
+        else if (n.kernel == kKernConvMfmaBf16) launch_conv_mfma_bf16(p, s);
         else launch_conv_valu(p, s);
         break;
       }
@@ -415,9 +425,18 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
       probe.gi = n.ga; probe.go = n.go; probe.k = k; probe.stride = n.d.stride; probe.c_out_pad = cop;
       const bool force_valu = getenv("EVCONV_FORCE_VALU") != nullptr;
       if (!force_valu && n.d.wdtype == EVCONV_F32 && conv_mfma_f32_supported(probe)) n.kernel = kKernConvMfmaF32;
+      if (!force_valu && n.d.wdtype == EVCONV_BF16 && conv_mfma_bf16_supported(probe)) n.kernel = kKernConvMfmaBf16;
       const float* src = (const float*)((const char*)weights + n.d.weight_off);
       staging.assign((size_t)k * k * ci_n * cop, 0.0f);
-      if (n.kernel == kKernConvMfmaF32) {
+      if (n.kernel == kKernConvMfmaBf16) {
+        // bf16 matrix-core layout [tap][c_in/8][c_out][8]: a lane's 8 input channels are 16 bytes
+        uint16_t* h16 = (uint16_t*)staging.data();
+        for (int co = 0; co < co_n; ++co)
+          for (int ci = 0; ci < ci_n; ++ci)
+            for (int t = 0; t < k * k; ++t)
+              h16[(((size_t)t * (ci_n / 8) + ci / 8) * cop + co) * 8 + (ci & 7)] =
+                  to_bf16(src[((size_t)co * ci_n + ci) * k * k + t]);
+      } else if (n.kernel == kKernConvMfmaF32) {
         // matrix-core layout [tap][c_in/4][c_out][4]: a lane's 4 input channels are 16 bytes
         for (int co = 0; co < co_n; ++co)
           for (int ci = 0; ci < ci_n; ++ci)
@@ -456,7 +475,8 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
       if (later < 0 || later == other) continue;
       const int host = L.nodes[later].fused_into >= 0 ? L.nodes[later].fused_into : later;
       NodePlan& c_node = L.nodes[host];
-      if (c_node.kernel != kKernConvMfmaF32 || c_node.n_fused >= kMaxFusedAdds) continue;
+      if ((c_node.kernel != kKernConvMfmaF32 && c_node.kernel != kKernConvMfmaBf16) ||
+          c_node.n_fused >= kMaxFusedAdds) continue;
       if (host != later && c_node.fused_nodes[c_node.n_fused - 1] != later) continue;  // chain must be contiguous
       if (other >= host) continue;  // the other input must exist before the conv runs
       c_node.fused_nodes[c_node.n_fused++] = (int)i;

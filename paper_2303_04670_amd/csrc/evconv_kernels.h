@@ -76,6 +76,9 @@ void launch_conv_valu(const ConvParams& p, hipStream_t s);
 // fp32 MFMA variant; requires c_in % 16 == 0 and c_out % 32 == 0
 bool conv_mfma_f32_supported(const ConvParams& p);
 void launch_conv_mfma_f32(const ConvParams& p, hipStream_t s);
+// bf16 MFMA variant (increments rounded to bf16 in the gather, bf16 weights, fp32 accumulation)
+bool conv_mfma_bf16_supported(const ConvParams& p);
+void launch_conv_mfma_bf16(const ConvParams& p, hipStream_t s);
 
 // ---- elementwise / structural increment operators ---------------------------------------
 enum EwOp { kEwAdd = 0, kEwAct, kEwConcat, kEwUp2x, kEwPoolAcc, kEwPoolMax };

@@ -30,6 +30,15 @@ namespace evk {
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// fp32 -> bf16, round to nearest even (NaN kept quiet); two values packed low/high
+__device__ __forceinline__ unsigned bf16_bits(float x) {
+  unsigned u = __float_as_uint(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) { return bf16_bits(lo) | (bf16_bits(hi) << 16); }
 
 __device__ __forceinline__ float act_m(int act, float v) {
   if (act == kActRelu) return fmaxf(v, 0.0f);
@@ -41,11 +50,18 @@ __device__ __forceinline__ float act_m(int act, float v) {
 // chunks also with stride 2 (14 + 7)
 constexpr int max_patch_edge(int chunk) { return chunk == 32 ? 14 : 21; }
 
-template <int CHUNK, int NW>
-__global__ __launch_bounds__(NW * 64) void conv_mfma_f32_kernel(ConvParams p) {
+// BF16 = false: fp32 operands, v_mfma_f32_32x32x2_f32, unit = tap x 8 channels (4 MFMA steps).
+// BF16 = true : the gather rounds increments to bf16 on their way into LDS, weights are bf16,
+//               v_mfma_f32_32x32x16_bf16 with fp32 accumulation, unit = tap x 16 channels (one
+//               MFMA per 32-row block); lanes 0-31 hold channels 0-7 of the group, lanes 32-63
+//               channels 8-15, for both operands.
+template <int CHUNK, int NW, bool BF16>
+__global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
   constexpr int NT = NW * 64;
-  constexpr int CS = CHUNK + 4;  // LDS site stride in floats: CS/4 odd => conflict-free b128 reads
-  constexpr int KG = CHUNK / 8;  // 8-channel groups per chunk
+  // LDS site stride in 4-byte words; stride / 4 is odd => conflict-free ds_read_b128
+  constexpr int CS = BF16 ? CHUNK / 2 + 4 : CHUNK + 4;
+  constexpr int UCH = BF16 ? 16 : 8;   // channels per unit
+  constexpr int KG = CHUNK / UCH;      // units per tap and chunk
   constexpr int NV = CHUNK / 4;  // float4 per patch site
   constexpr int MAXP = max_patch_edge(CHUNK);
   constexpr int MAXV = (MAXP * MAXP * NV + NT - 1) / NT;  // patch float4 per thread, upper bound
@@ -148,7 +164,7 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_f32_kernel(ConvParams p) {
     if (e < total_v) {
       const int site = e / NV, v = e - site * NV;
       const int py = (site * p_magic) >> 16, px = site - py * P;
-      lds_off[j] = site * CS + v * 4;
+      lds_off[j] = BF16 ? site * CS + v * 2 : site * CS + v * 4;
       if ((s_rows[py] >> px) & 1u) g_off[j] = (unsigned)((((iy0 + py) * W + ix0 + px) * Cin + v * 4) * 4);
     }
   }
@@ -163,7 +179,16 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_f32_kernel(ConvParams p) {
   auto stash = [&]() {
 #pragma unroll
     for (int j = 0; j < MAXV; ++j)
-      if (lds_off[j] >= 0) *(float4*)&s_mem[lds_off[j]] = pre[j];
+      if (lds_off[j] >= 0) {
+        if (BF16) {
+          uint2 w;
+          w.x = pack_bf16x2(pre[j].x, pre[j].y);
+          w.y = pack_bf16x2(pre[j].z, pre[j].w);
+          *(uint2*)&s_mem[lds_off[j]] = w;
+        } else {
+          *(float4*)&s_mem[lds_off[j]] = pre[j];
+        }
+      }
   };
 
   floatx16 acc0, acc1;
@@ -173,7 +198,7 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_f32_kernel(ConvParams p) {
   const int mly = m >> 3, mlx = m & 7;  // site of this lane inside a 32-row block
   const int cop = p.c_out_pad;
   const int n_units = K * K * KG;
-  const int cin4 = Cin >> 2;
+  const int cin_rows = BF16 ? Cin >> 3 : Cin >> 2;  // 16-byte weight rows per tap: 8 bf16 or 4 floats
   const int a_lane_off = (mly * s * P + mlx * s) * CS + half * 4;
   const int a_blk1 = 4 * s * P * CS;
   const float4* __restrict__ wlane = (const float4*)p.w + (size_t)half * cop + co0 + m;
@@ -187,19 +212,26 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_f32_kernel(ConvParams p) {
   auto b_ptr = [&](int c0, int j) {
     const int u = wave + min(j, last) * NW;
     const int tap = u / KG, kg = u % KG;
-    return wlane + ((size_t)tap * cin4 + (c0 >> 2) + kg * 2) * cop;
+    const int row0 = BF16 ? (c0 >> 3) : (c0 >> 2);
+    return wlane + ((size_t)tap * cin_rows + row0 + kg * 2) * cop;
   };
   // ... and LDS offset of its A fragment
   auto a_off = [&](int j) {
     const int u = wave + j * NW;
     const int tap = u / KG, kg = u % KG;
     const int ky = (tap * k_magic) >> 16, kx = tap - ky * K;
-    return a_lane_off + (ky * P + kx) * CS + kg * 8;
+    return a_lane_off + (ky * P + kx) * CS + kg * 8;  // 8 words = 8 floats or 16 bf16
   };
   auto unit = [&](int j, const float4& b) {
     const float* ap = &s_mem[a_off(j)];
     const float4 a0 = *(const float4*)ap;
     const float4 a1 = *(const float4*)(ap + a_blk1);
+    if (BF16) {
+      const bf16x8 bb = __builtin_bit_cast(bf16x8, b);
+      acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a0), bb, acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a1), bb, acc1, 0, 0, 0);
+      return;
+    }
     acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.x, b.x, acc0, 0, 0, 0);
     acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.x, b.x, acc1, 0, 0, 0);
     acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.y, b.y, acc0, 0, 0, 0);
@@ -361,13 +393,25 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_f32_kernel(ConvParams p) {
 
 int chunk_for(const ConvParams& p) { return (p.gi.c % 32 == 0 && p.stride == 1) ? 32 : 16; }
 
-template <int CHUNK, int NW>
+template <int CHUNK, int NW, bool BF16>
 void launch_variant(const ConvParams& p, hipStream_t s) {
   const int P = 7 * p.stride + p.k;
-  size_t lds = (size_t)P * P * (CHUNK + 4) * sizeof(float);
+  size_t lds = (size_t)P * P * (BF16 ? CHUNK / 2 + 4 : CHUNK + 4) * sizeof(float);
   if (lds < 4 * 32 * 64 * sizeof(float)) lds = 4 * 32 * 64 * sizeof(float);  // partial sums reuse it
   dim3 grid(p.go.tiles(), p.go.c / 32);
-  hipLaunchKernelGGL((conv_mfma_f32_kernel<CHUNK, NW>), grid, dim3(NW * 64), lds, s, p);
+  hipLaunchKernelGGL((conv_mfma_kernel<CHUNK, NW, BF16>), grid, dim3(NW * 64), lds, s, p);
+}
+
+template <bool BF16>
+void launch_any(const ConvParams& p, hipStream_t s) {
+  const int chunk = chunk_for(p);
+  // low-resolution layers have few workgroups: give each one 8 waves to split K further
+  const bool wide = (long long)p.go.tiles() * (p.go.c / 32) < 512;
+  if (chunk == 32) {
+    if (wide) launch_variant<32, 8, BF16>(p, s); else launch_variant<32, 4, BF16>(p, s);
+  } else {
+    if (wide) launch_variant<16, 8, BF16>(p, s); else launch_variant<16, 4, BF16>(p, s);
+  }
 }
 
 }  // namespace
@@ -377,15 +421,10 @@ bool conv_mfma_f32_supported(const ConvParams& p) {
          (long long)p.gi.h * p.gi.w * p.gi.c * 4 < (1ll << 31);  // byte offsets of the gather fit 31 bits
 }
 
-void launch_conv_mfma_f32(const ConvParams& p, hipStream_t s) {
-  const int chunk = chunk_for(p);
-  // low-resolution layers have few workgroups: give each one 8 waves to split K further
-  const bool wide = (long long)p.go.tiles() * (p.go.c / 32) < 512;
-  if (chunk == 32) {
-    if (wide) launch_variant<32, 8>(p, s); else launch_variant<32, 4>(p, s);
-  } else {
-    if (wide) launch_variant<16, 8>(p, s); else launch_variant<16, 4>(p, s);
-  }
-}
+void launch_conv_mfma_f32(const ConvParams& p, hipStream_t s) { launch_any<false>(p, s); }
+
+// bf16 operands, fp32 accumulation; weights are [tap][c_in/8][c_out][8] bf16
+bool conv_mfma_bf16_supported(const ConvParams& p) { return conv_mfma_f32_supported(p); }
+void launch_conv_mfma_bf16(const ConvParams& p, hipStream_t s) { launch_any<true>(p, s); }
 
 }  // namespace evk

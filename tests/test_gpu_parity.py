@@ -26,7 +26,7 @@ def _dev(a):
 
 
 def run_stream(net, x0, inputs, kind, check_nodes_at=None, tol=TOL, exact_sets=False, max_flips=0,
-               fp32_oracle=False, label=""):
+               fp32_oracle=False, label="", frobenius=False):
     """kind: 'frame' or 'increment'.  check_nodes_at: steps (1-based) at which every node is
     compared (None = every step); outputs and the input stage are compared at every step."""
     gpu = ev.EvConvNet(net)
@@ -51,7 +51,7 @@ def run_stream(net, x0, inputs, kind, check_nodes_at=None, tol=TOL, exact_sets=F
         cmp.compare_outputs(gpu, ora, rep, tol)
         if check_nodes_at is None or step in check_nodes_at:
             for i in range(len(net.nodes)):
-                cmp.compare_node(gpu, ora, i, rep, tol=tol, exact_sets=exact_sets)
+                cmp.compare_node(gpu, ora, i, rep, tol=tol, exact_sets=exact_sets, frobenius=frobenius)
         if step % 10 == 0:
             _say(f"[{label}] step {step}: flips {rep.flips} max rel z err {rep.max_rel_z:.2e} y err {rep.max_rel_y:.2e}")
     assert rep.flips <= max_flips, f"{rep.flips} rounding flips of value-pruned sets: {rep.flips_by_node}"
@@ -120,6 +120,38 @@ def test_unet_full_width_without_epilogue_fusion(monkeypatch):
     assert "fused_into_conv_epilogue" not in names
     frames = list(wl.stream_voxel(1003, 64, 96, 8, 0.02, n_prim=6))
     run_stream(net, frames[0], frames[1:], "frame", label="unet-wide-unfused", max_flips=40)
+
+
+def test_unet_bf16_matrix_core_variant_reduced():
+    """bf16-weight variant: increments are rounded to bf16 in the gather, weights are bf16, fp32
+    accumulation.  Oracle: the same bf16-rounded weights held exactly in fp64, unrounded
+    increments.  Bar: 2e-2 relative (Frobenius) per accumulated tensor and increment."""
+    _say("UNet depth net bf16 variant, full width on 5x64x96, 20 frames")
+    net = wl.net_unet_depth(1003, h=64, w=96, bf16=True)
+    g = ev.EvConvNet(net)
+    names = [g.kernel_name(i) for i in range(len(net.nodes))]
+    g.destroy()
+    assert names.count("conv_mfma_bf16") == 10, names
+    frames = list(wl.stream_voxel(1003, 64, 96, 20, 0.02, n_prim=6))
+    run_stream(net, frames[0], frames[1:], "frame", label="unet-bf16", tol=2e-2, frobenius=True, max_flips=200)
+
+
+def test_matrix_core_conv_shapes_bf16():
+    _say("bf16 matrix-core conv variants")
+    for k, s, ci, co in [(3, 1, 32, 32), (3, 2, 16, 64), (5, 1, 64, 32), (5, 2, 48, 96), (7, 2, 16, 32), (1, 1, 32, 64)]:
+        b = wl._NetBuilder(f"conv{k}s{s}", ci, 21, 27, 100 + k * 10 + s, bf16=True, bias=True)
+        b.conv(-1, co, k, s, act=wl.ACT_RELU, out=1)
+        net = b.finish()
+        rng = np.random.default_rng(k + s)
+        x0 = rng.standard_normal((ci, 21, 27)).astype(np.float32)
+        incs = []
+        for t in range(4):
+            m = rng.random((21, 27)) < (0.03 if t < 3 else 1.0)
+            incs.append(rng.standard_normal(x0.shape).astype(np.float32) * m[None])
+        g = ev.EvConvNet(net)
+        assert g.kernel_name(0) == "conv_mfma_bf16"
+        g.destroy()
+        run_stream(net, x0, incs, "increment", label=f"bf16 k{k}s{s}", tol=2e-2, frobenius=True, max_flips=20)
 
 
 def test_matrix_core_conv_shapes():
@@ -258,6 +290,39 @@ def test_step_before_reset_is_an_error():
         g.step(_dev(np.zeros((4, 8, 8), np.float32)))
     assert e.value.status == ev.ERR_STATE
     g.destroy()
+
+
+@pytest.mark.timeout(600)
+def test_workload4_resnet18_full_size():
+    """Full-size ResNet-18-style classifier on 2x224x224 event histograms, density ramp 0.5-5 %:
+    max-pool, strided convs with 1x1 projection shortcuts, global mean, linear head."""
+    _say("workload 4: ResNet-18 2x224x224, 24 frames, density 0.5 -> 5 %")
+    net = wl.net_resnet18()
+    gen = wl.stream_histogram(1004, 224, 224, steps=24)
+    x0 = next(gen)
+    run_stream(net, x0, gen, "frame", check_nodes_at={1, 12, 24}, label="w4", max_flips=64)
+
+
+@pytest.mark.timeout(600)
+def test_workload5_flow_net_full_size_density_sweep():
+    """Full-size optical-flow encoder-decoder on 4x256x256 (concat skips, flow head per scale), a
+    few steps at each of four increment densities between 0.1 % and 20 %."""
+    _say("workload 5: flow encoder-decoder 4x256x256, densities 0.1 / 1 / 5 / 20 %, 4 steps each")
+    net = wl.net_flow()
+    gen = wl.stream_count_timestamp(1005, 256, 256, densities=[0.001, 0.01, 0.05, 0.2], steps_per=4)
+    x0 = next(gen)
+    run_stream(net, x0, gen, "frame", check_nodes_at={1, 6, 11, 16}, label="w5", max_flips=64)
+
+
+@pytest.mark.timeout(900)
+def test_workload3_unet_bf16_full_size_100_steps():
+    """Workload 3, bf16-weight variant, full size, 100 consecutive frames: 2e-2 relative."""
+    _say("workload 3 (bf16 weights): UNet depth net 5x256x352, 100 frames at 2 %")
+    net = wl.net_unet_depth(bf16=True)
+    gen = wl.stream_voxel(1003, 256, 352, 100, 0.02)
+    x0 = next(gen)
+    run_stream(net, x0, gen, "frame", check_nodes_at={1, 50, 100}, label="w3-bf16", tol=2e-2, frobenius=True,
+               max_flips=3 * int(0.02 * 256 * 352))
 
 
 @pytest.mark.timeout(900)
