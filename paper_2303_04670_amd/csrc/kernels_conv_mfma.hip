@@ -1,28 +1,36 @@
-// Sparse incremental convolution on the matrix cores, fp32 (v_mfma_f32_32x32x2_f32).
+// Sparse incremental convolution on the matrix cores.
 //
 // Used where the per-tile channel contraction is a dense GEMM: c_in % 16 == 0, c_out % 32 == 0.
-// Implicit GEMM per touched output tile: M = 64 sites (two 32-row blocks: tile rows 0-3 and
-// 4-7), N = 32 output channels per workgroup, K = taps x c_in.
+// Implicit GEMM per touched output tile (8 x 8 sites): M = 32 * MB sites (MB = 2: the whole
+// tile as two 32-row MFMA blocks, rows 0-3 and 4-7; MB = 1: one workgroup per half tile),
+// N = 32 output channels per workgroup, K = taps x c_in.
 //
-// Workgroup = NW (4 or 8) wavefronts that split K: the (tap, 8-channel group) units of every
-// channel chunk are dealt round-robin to the waves; each wave keeps both 32 x 32 accumulators
-// (32 registers) and the partial sums are added through LDS at the end.  K-splitting (rather
-// than N-splitting) is what fills the chip on the low-resolution layers, where a layer has only
-// 24-88 tiles; those layers run with 8 waves.
+//   BF16 = false: fp32 operands, v_mfma_f32_32x32x2_f32; a unit = one tap x 8 channels (4 MFMA
+//                 steps per block); MFMA j of a unit contracts channels {j, 4+j}: lanes 0-31 hold
+//                 channel j, lanes 32-63 channel 4+j, for both operands.
+//   BF16 = true : the gather rounds increments to bf16 on their way into LDS, weights are bf16,
+//                 v_mfma_f32_32x32x16_bf16 with fp32 accumulation; a unit = one tap x 16 channels
+//                 (one MFMA per block); lanes 0-31 hold channels 0-7, lanes 32-63 channels 8-15.
+//
+// Workgroup = NW (4 or 8) wavefronts that split K: the units of every channel chunk are dealt
+// round-robin to the waves; each wave keeps the MB accumulators and the partial sums are added
+// through LDS at the end.  K-splitting (rather than N-splitting), 8 waves and half tiles are what
+// spread the low-resolution layers (24-88 tiles) over 256 CUs; the launcher picks MB and NW from
+// the number of workgroups a layer yields.
 //   Masks: the occupancy words of the input tiles under the halo are turned into one bit row per
 //     patch row in LDS; the touched word of the tile and the gather predicates come from those.
 //   A operand: the input halo patch of the current chunk, gathered once per workgroup into LDS
 //     with buffer loads whose offset is pushed out of range for inactive / out-of-image sites:
 //     the hardware bounds check returns zeros without a memory access (conditioned fetch).  The
 //     next chunk's patch is fetched into registers while the current one is being contracted.
-//     A lane reads 4 consecutive channels of its site with one ds_read_b128.
-//   B operand: weights re-laid as [tap][c_in/4][c_out][4] so that a lane's 4 channels of its
-//     output column are one 16-byte global load (L2-resident), held in a three-register ring
-//     two units ahead, across chunk boundaries.
-//   K order inside an 8-channel group: MFMA j contracts channels {j, 4+j}; lanes 0-31 hold
-//     channel j, lanes 32-63 channel 4+j, for both operands.
+//     A lane reads its fragment with one ds_read_b128; the LDS site stride keeps that
+//     conflict-free for stride-1 layers.
+//   B operand: weights re-laid as [tap][c_in/4][c_out][4] (fp32) or [tap][c_in/8][c_out][8]
+//     (bf16) so that a lane's fragment is one 16-byte global load (L2-resident), held in a
+//     three-register ring two units ahead, across chunk boundaries.
 // Epilogue: lane = output channel, so every z / increment access is a 128-byte row segment; the
-// old z values are requested before the contraction starts.
+// old z values are requested before the contraction starts.  ADD nodes that consume the conv
+// output (residual add + activation, skip adds) run here as well, writing their own buffers.
 #include "evconv_kernels.h"
 
 namespace evk {
@@ -32,6 +40,12 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
+__device__ __forceinline__ float act_m(int act, float v) {
+  if (act == kActRelu) return fmaxf(v, 0.0f);
+  if (act == kActSigmoid) return 1.0f / (1.0f + expf(-v));
+  return v;
+}
+
 // fp32 -> bf16, round to nearest even (NaN kept quiet); two values packed low/high
 __device__ __forceinline__ unsigned bf16_bits(float x) {
   unsigned u = __float_as_uint(x);
@@ -40,47 +54,44 @@ __device__ __forceinline__ unsigned bf16_bits(float x) {
 }
 __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) { return bf16_bits(lo) | (bf16_bits(hi) << 16); }
 
-__device__ __forceinline__ float act_m(int act, float v) {
-  if (act == kActRelu) return fmaxf(v, 0.0f);
-  if (act == kActSigmoid) return 1.0f / (1.0f + expf(-v));
-  return v;
+// Largest halo patch (sites) a variant can meet: 64-channel chunks are used with stride 1 and
+// taps <= 3, 32-channel chunks with stride 1 (taps <= 7), 16-channel chunks also with stride 2.
+constexpr int max_patch_sites(int chunk, int mb) {
+  const int rows = 4 * mb - 1;
+  return chunk == 64 ? (rows + 3) * 10 : chunk == 32 ? (rows + 7) * 14 : (rows * 2 + 7) * 21;
 }
 
-// largest halo patch edge: 32-channel chunks are used with stride 1 only (7 + 7), 16-channel
-// chunks also with stride 2 (14 + 7)
-constexpr int max_patch_edge(int chunk) { return chunk == 32 ? 14 : 21; }
-
-// BF16 = false: fp32 operands, v_mfma_f32_32x32x2_f32, unit = tap x 8 channels (4 MFMA steps).
-// BF16 = true : the gather rounds increments to bf16 on their way into LDS, weights are bf16,
-//               v_mfma_f32_32x32x16_bf16 with fp32 accumulation, unit = tap x 16 channels (one
-//               MFMA per 32-row block); lanes 0-31 hold channels 0-7 of the group, lanes 32-63
-//               channels 8-15, for both operands.
-template <int CHUNK, int NW, bool BF16>
+template <int CHUNK, int NW, bool BF16, int MB>
 __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
   constexpr int NT = NW * 64;
   // LDS site stride in 4-byte words; stride / 4 is odd => conflict-free ds_read_b128
   constexpr int CS = BF16 ? CHUNK / 2 + 4 : CHUNK + 4;
-  constexpr int UCH = BF16 ? 16 : 8;   // channels per unit
-  constexpr int KG = CHUNK / UCH;      // units per tap and chunk
-  constexpr int NV = CHUNK / 4;  // float4 per patch site
-  constexpr int MAXP = max_patch_edge(CHUNK);
-  constexpr int MAXV = (MAXP * MAXP * NV + NT - 1) / NT;  // patch float4 per thread, upper bound
-  constexpr int EP_SITES = NT / 32;                       // sites per epilogue pass
-  constexpr int EP_ITERS = 64 / EP_SITES;
+  constexpr int UCH = BF16 ? 16 : 8;  // channels per unit
+  constexpr int KG = CHUNK / UCH;     // units per tap and chunk
+  constexpr int NV = CHUNK / 4;       // float4 per patch site
+  constexpr int MAXV = (max_patch_sites(CHUNK, MB) * NV + NT - 1) / NT;  // patch float4 per thread
+  constexpr int SUBS = 2 / MB;        // workgroups per tile
+  constexpr int NROWS = 4 * MB;       // output rows of this workgroup
+  constexpr int NSITES = 32 * MB;
+  constexpr int EP_SITES = NT / 32;   // sites per epilogue pass
+  constexpr int EP_ITERS = NSITES / EP_SITES;
+  constexpr int SLOT = MB * 16 * 64;  // floats per partial-sum slot
   extern __shared__ __align__(16) float s_mem[];
   __shared__ uint64_t s_occ[16];
   __shared__ unsigned s_rows[24];  // bit px of s_rows[py]: patch site (py, px) is active
   __shared__ unsigned s_nz[2 * (1 + kMaxFusedAdds)];  // nonzero-site bits: conv, then each fused ADD
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int tile = blockIdx.x;
+  const int tile = blockIdx.x / SUBS, sub = blockIdx.x % SUBS;
+  const int r0 = sub * NROWS;  // first tile row of this workgroup
+  const uint64_t row_mask = MB == 2 ? ~0ull : (0xffffffffull << (32 * sub));
   const int tile_y = tile / p.go.tx, tile_x = tile - tile_y * p.go.tx;
   const int s = p.stride, K = p.k;
   const int H = p.gi.h, W = p.gi.w, Cin = p.gi.c, Cout = p.go.c;
-  const int iy0 = tile_y * 8 * s - p.pad, ix0 = tile_x * 8 * s - p.pad;
-  const int P = 7 * s + K;
+  const int iy0 = (tile_y * 8 + r0) * s - p.pad, ix0 = tile_x * 8 * s - p.pad;
+  const int PH = (NROWS - 1) * s + K, PW = 7 * s + K;
   const int rty0 = iy0 >> 3, rtx0 = ix0 >> 3;
-  const int rny = ((iy0 + P - 1) >> 3) - rty0 + 1, rnx = ((ix0 + P - 1) >> 3) - rtx0 + 1;
+  const int rny = ((iy0 + PH - 1) >> 3) - rty0 + 1, rnx = ((ix0 + PW - 1) >> 3) - rtx0 + 1;
 
   if (tid < 16) {
     const int ry = tid >> 2, rx = tid & 3;
@@ -92,7 +103,7 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
   }
   if (tid < 2 * (1 + kMaxFusedAdds)) s_nz[tid] = 0;
   __syncthreads();
-  if (tid < P) {  // one bit row per patch row; out-of-image sites are 0
+  if (tid < PH) {  // one bit row per patch row; out-of-image sites are 0
     const int iy = iy0 + tid;
     unsigned bits = 0;
     if ((unsigned)iy < (unsigned)H) {
@@ -104,7 +115,7 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
         span |= ((s_occ[ry * 4 + rx] >> ((iy & 7) * 8)) & 0xffull) << (8 * rx);
       bits = (unsigned)(span >> (ix0 - rtx0 * 8));
       // clear columns outside the image (dense mode sets every bit) and beyond the patch
-      const int lo = max(0, -ix0), hi = min(P, W - ix0);  // valid px in [lo, hi)
+      const int lo = max(0, -ix0), hi = min(PW, W - ix0);  // valid px in [lo, hi)
       unsigned m = hi >= 32 ? ~0u : ((1u << max(hi, 0)) - 1u);
       m &= ~((1u << lo) - 1u);
       bits &= m;
@@ -113,15 +124,19 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
   }
   __syncthreads();
 
-  // touched word of the tile (identical in all waves): OR of the K rows, dilated by K columns
+  // touched word of this workgroup's rows (identical in all waves): OR of the K bit rows under a
+  // site, then any of the K columns
   uint64_t touched_word;
   {
     const int ly = lane >> 3, lx = lane & 7;
     const int oy = tile_y * 8 + ly, ox = tile_x * 8 + lx;
-    unsigned rows = 0;
-    for (int ky = 0; ky < K; ++ky) rows |= s_rows[ly * s + ky];
-    const unsigned win = (rows >> (lx * s)) & ((1u << K) - 1u);
-    const bool touched = (oy < p.go.h) && (ox < p.go.w) && (p.dense || win != 0);
+    const int lr = ly - r0;
+    bool touched = false;
+    if (lr >= 0 && lr < NROWS && oy < p.go.h && ox < p.go.w) {
+      unsigned rows = 0;
+      for (int ky = 0; ky < K; ++ky) rows |= s_rows[lr * s + ky];
+      touched = p.dense || ((rows >> (lx * s)) & ((1u << K) - 1u)) != 0;
+    }
     touched_word = __ballot(touched);
   }
   // fused ADD nodes: their other input may be active where the conv is not
@@ -130,7 +145,7 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
 #pragma unroll
   for (int f = 0; f < kMaxFusedAdds; ++f) {
     skip_word[f] = 0;
-    if (f < p.n_fused) skip_word[f] = p.dense ? touched_word : p.fused[f].occ_skip[tile];
+    if (f < p.n_fused) skip_word[f] = p.dense ? touched_word : (p.fused[f].occ_skip[tile] & row_mask);
     site_word |= skip_word[f];
   }
   if (site_word == 0) return;
@@ -142,7 +157,7 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
   float z_old[EP_ITERS];
 #pragma unroll
   for (int it = 0; it < EP_ITERS; ++it) {
-    const int site = it * EP_SITES + (tid >> 5);
+    const int site = r0 * 8 + it * EP_SITES + (tid >> 5);
     z_old[it] = 0.0f;
     if (!p.dense && ((touched_word >> site) & 1ull)) {
       const int oy = tile_y * 8 + (site >> 3), ox = tile_x * 8 + (site & 7);
@@ -152,8 +167,8 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
 
   // ---- patch gather: per thread a fixed list of (LDS offset, byte offset into the input)
   constexpr unsigned kOob = 0x80000000u;
-  const int total_v = P * P * NV;
-  const int p_magic = (65536 + P - 1) / P;  // site / P == (site * p_magic) >> 16 for site < 441
+  const int total_v = PH * PW * NV;
+  const int pw_magic = (65536 + PW - 1) / PW;  // site / PW == (site * pw_magic) >> 16 for site < 441
   int lds_off[MAXV];
   unsigned g_off[MAXV];
 #pragma unroll
@@ -163,7 +178,7 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
     g_off[j] = kOob;
     if (e < total_v) {
       const int site = e / NV, v = e - site * NV;
-      const int py = (site * p_magic) >> 16, px = site - py * P;
+      const int py = (site * pw_magic) >> 16, px = site - py * PW;
       lds_off[j] = BF16 ? site * CS + v * 2 : site * CS + v * 4;
       if ((s_rows[py] >> px) & 1u) g_off[j] = (unsigned)((((iy0 + py) * W + ix0 + px) * Cin + v * 4) * 4);
     }
@@ -199,8 +214,8 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
   const int cop = p.c_out_pad;
   const int n_units = K * K * KG;
   const int cin_rows = BF16 ? Cin >> 3 : Cin >> 2;  // 16-byte weight rows per tap: 8 bf16 or 4 floats
-  const int a_lane_off = (mly * s * P + mlx * s) * CS + half * 4;
-  const int a_blk1 = 4 * s * P * CS;
+  const int a_lane_off = (mly * s * PW + mlx * s) * CS + half * 4;
+  const int a_blk1 = 4 * s * PW * CS;
   const float4* __restrict__ wlane = (const float4*)p.w + (size_t)half * cop + co0 + m;
   // units of this wave: u_j = wave + j * NW, j < n_mine
   const int n_mine = (n_units - wave + NW - 1) / NW;
@@ -220,26 +235,27 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
     const int u = wave + j * NW;
     const int tap = u / KG, kg = u % KG;
     const int ky = (tap * k_magic) >> 16, kx = tap - ky * K;
-    return a_lane_off + (ky * P + kx) * CS + kg * 8;  // 8 words = 8 floats or 16 bf16
+    return a_lane_off + (ky * PW + kx) * CS + kg * 8;  // 8 words = 8 floats or 16 bf16
   };
   auto unit = [&](int j, const float4& b) {
     const float* ap = &s_mem[a_off(j)];
     const float4 a0 = *(const float4*)ap;
-    const float4 a1 = *(const float4*)(ap + a_blk1);
+    float4 a1 = a0;
+    if (MB == 2) a1 = *(const float4*)(ap + a_blk1);
     if (BF16) {
       const bf16x8 bb = __builtin_bit_cast(bf16x8, b);
       acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a0), bb, acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a1), bb, acc1, 0, 0, 0);
+      if (MB == 2) acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a1), bb, acc1, 0, 0, 0);
       return;
     }
     acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.x, b.x, acc0, 0, 0, 0);
-    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.x, b.x, acc1, 0, 0, 0);
+    if (MB == 2) acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.x, b.x, acc1, 0, 0, 0);
     acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.y, b.y, acc0, 0, 0, 0);
-    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.y, b.y, acc1, 0, 0, 0);
+    if (MB == 2) acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.y, b.y, acc1, 0, 0, 0);
     acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.z, b.z, acc0, 0, 0, 0);
-    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.z, b.z, acc1, 0, 0, 0);
+    if (MB == 2) acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.z, b.z, acc1, 0, 0, 0);
     acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.w, b.w, acc0, 0, 0, 0);
-    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.w, b.w, acc1, 0, 0, 0);
+    if (MB == 2) acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.w, b.w, acc1, 0, 0, 0);
   };
 
   // Ring of three weight fragments, two units of look-ahead, no register copies: vector loads
@@ -278,53 +294,47 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
   }
 
   // ---- reduce the NW partial sums through LDS: slots [4][block*16 + reg][lane]
-  __syncthreads();
-  if (NW == 8) {
-    if (wave >= 4) {
-      float* part = s_mem + (wave - 4) * (32 * 64);
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        part[i * 64 + lane] = acc0[i];
-        part[(16 + i) * 64 + lane] = acc1[i];
-      }
-    }
-    __syncthreads();
-    if (wave < 4) {
-      const float* part = s_mem + wave * (32 * 64);
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        acc0[i] += part[i * 64 + lane];
-        acc1[i] += part[(16 + i) * 64 + lane];
-      }
-    }
-  }
-  if (wave < 4) {
-    float* part = s_mem + wave * (32 * 64);
+  auto spill = [&](float* part) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       part[i * 64 + lane] = acc0[i];
-      part[(16 + i) * 64 + lane] = acc1[i];
+      if (MB == 2) part[(16 + i) * 64 + lane] = acc1[i];
+    }
+  };
+  __syncthreads();
+  if (NW == 8) {
+    if (wave >= 4) spill(s_mem + (wave - 4) * SLOT);
+    __syncthreads();
+    if (wave < 4) {
+      const float* part = s_mem + wave * SLOT;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        acc0[i] += part[i * 64 + lane];
+        if (MB == 2) acc1[i] += part[(16 + i) * 64 + lane];
+      }
     }
   }
+  if (wave < 4) spill(s_mem + wave * SLOT);
   __syncthreads();
 
   // epilogue: thread -> (output channel = tid % 32, EP_ITERS sites); accumulator element
-  // (block b, register i, lane l) is site b*32 + 8*(i/4) + 4*(l/32) + i%4, channel l%32
+  // (block b, register i, lane l) is local site b*32 + 8*(i/4) + 4*(l/32) + i%4, channel l%32
   uint64_t nz_sites = 0;
   uint64_t nz_fused[kMaxFusedAdds] = {0, 0};
 #pragma unroll
   for (int it = 0; it < EP_ITERS; ++it) {
-    const int site = it * EP_SITES + (tid >> 5);
+    const int ls = it * EP_SITES + (tid >> 5);  // site inside this workgroup's rows
+    const int site = r0 * 8 + ls;               // site inside the tile
     if (!((site_word >> site) & 1ull)) continue;
     const int oy = tile_y * 8 + (site >> 3), ox = tile_x * 8 + (site & 7);
     const size_t q = ((size_t)oy * p.go.w + ox) * Cout + co0 + co;
     float o = 0.0f;
     if ((touched_word >> site) & 1ull) {
-      const int b = site >> 5, r = site & 31;
+      const int b = ls >> 5, r = ls & 31;
       const int reg = (r >> 3) * 4 + (r & 3);
       const int l = ((r >> 2) & 1) * 32 + co;
       const int off = (b * 16 + reg) * 64 + l;
-      const float v = (s_mem[off] + s_mem[off + 2048]) + (s_mem[off + 4096] + s_mem[off + 6144]);
+      const float v = (s_mem[off] + s_mem[off + SLOT]) + (s_mem[off + 2 * SLOT] + s_mem[off + 3 * SLOT]);
       if (p.dense) {
         const float z = v + (p.bias ? p.bias[co0 + co] : 0.0f);
         p.z[q] = z;
@@ -374,11 +384,11 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
     auto glob_or = [](uint64_t* dst, uint64_t bits) {
       if (bits) atomicOr((unsigned long long*)dst, (unsigned long long)bits);
     };
-    // S of the producer as seen by this workgroup's channels; all words are pre-zeroed and the
-    // workgroups of the other channel blocks OR their share in
+    // S of the producer as seen by this workgroup's rows and channels; all words are pre-zeroed
+    // and the other workgroups of the tile OR their share in
     uint64_t s_prev = p.dense ? touched_word : ((uint64_t)s_nz[0] | ((uint64_t)s_nz[1] << 32));
     glob_or(&p.occ_out[tile], s_prev);
-    if (blockIdx.y == 0) p.occ_touched[tile] = touched_word;
+    if (blockIdx.y == 0) glob_or(&p.occ_touched[tile], touched_word);
     for (int f = 0; f < p.n_fused; ++f) {
       const FusedAdd& fa = p.fused[f];
       const uint64_t t_f = s_prev | skip_word[f];  // Eq.11b
@@ -391,26 +401,43 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
   }
 }
 
-int chunk_for(const ConvParams& p) { return (p.gi.c % 32 == 0 && p.stride == 1) ? 32 : 16; }
+int chunk_for(const ConvParams& p) {
+  if (p.stride == 1 && p.k <= 3 && p.gi.c % 64 == 0) return 64;
+  return (p.gi.c % 32 == 0 && p.stride == 1) ? 32 : 16;
+}
 
-template <int CHUNK, int NW, bool BF16>
+template <int CHUNK, int NW, bool BF16, int MB>
 void launch_variant(const ConvParams& p, hipStream_t s) {
-  const int P = 7 * p.stride + p.k;
-  size_t lds = (size_t)P * P * (BF16 ? CHUNK / 2 + 4 : CHUNK + 4) * sizeof(float);
-  if (lds < 4 * 32 * 64 * sizeof(float)) lds = 4 * 32 * 64 * sizeof(float);  // partial sums reuse it
-  dim3 grid(p.go.tiles(), p.go.c / 32);
-  hipLaunchKernelGGL((conv_mfma_kernel<CHUNK, NW, BF16>), grid, dim3(NW * 64), lds, s, p);
+  const int PH = (4 * MB - 1) * p.stride + p.k, PW = 7 * p.stride + p.k;
+  size_t lds = (size_t)PH * PW * (BF16 ? CHUNK / 2 + 4 : CHUNK + 4) * sizeof(float);
+  const size_t part = (size_t)4 * MB * 16 * 64 * sizeof(float);  // partial sums reuse the patch
+  if (lds < part) lds = part;
+  dim3 grid(p.go.tiles() * (2 / MB), p.go.c / 32);
+  hipLaunchKernelGGL((conv_mfma_kernel<CHUNK, NW, BF16, MB>), grid, dim3(NW * 64), lds, s, p);
+}
+
+// share of the chip's 256 CUs kept busy when n equally long workgroups run at once
+double fill(long long n) { return (double)n / 256.0 / (double)((n + 255) / 256); }
+
+template <int CHUNK, bool BF16>
+void launch_shape(const ConvParams& p, hipStream_t s) {
+  const long long n2 = (long long)p.go.tiles() * (p.go.c / 32);  // workgroups with whole tiles
+  const bool halves = fill(2 * n2) > fill(n2) + 0.05;            // half tiles balance better
+  const long long n = halves ? 2 * n2 : n2;
+  const bool eight = n < 512;  // few workgroups: 8 waves each split K further
+  if (halves) {
+    if (eight) launch_variant<CHUNK, 8, BF16, 1>(p, s); else launch_variant<CHUNK, 4, BF16, 1>(p, s);
+  } else {
+    if (eight) launch_variant<CHUNK, 8, BF16, 2>(p, s); else launch_variant<CHUNK, 4, BF16, 2>(p, s);
+  }
 }
 
 template <bool BF16>
 void launch_any(const ConvParams& p, hipStream_t s) {
-  const int chunk = chunk_for(p);
-  // low-resolution layers have few workgroups: give each one 8 waves to split K further
-  const bool wide = (long long)p.go.tiles() * (p.go.c / 32) < 512;
-  if (chunk == 32) {
-    if (wide) launch_variant<32, 8, BF16>(p, s); else launch_variant<32, 4, BF16>(p, s);
-  } else {
-    if (wide) launch_variant<16, 8, BF16>(p, s); else launch_variant<16, 4, BF16>(p, s);
+  switch (chunk_for(p)) {
+    case 64: launch_shape<64, BF16>(p, s); break;
+    case 32: launch_shape<32, BF16>(p, s); break;
+    default: launch_shape<16, BF16>(p, s); break;
   }
 }
 
@@ -420,7 +447,6 @@ bool conv_mfma_f32_supported(const ConvParams& p) {
   return p.gi.c % 16 == 0 && p.go.c % 32 == 0 && p.c_out_pad == p.go.c &&
          (long long)p.gi.h * p.gi.w * p.gi.c * 4 < (1ll << 31);  // byte offsets of the gather fit 31 bits
 }
-
 void launch_conv_mfma_f32(const ConvParams& p, hipStream_t s) { launch_any<false>(p, s); }
 
 // bf16 operands, fp32 accumulation; weights are [tap][c_in/8][c_out][8] bf16
