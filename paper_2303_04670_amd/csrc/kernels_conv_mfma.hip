@@ -31,6 +31,8 @@
 // Epilogue: lane = output channel, so every z / increment access is a 128-byte row segment; the
 // old z values are requested before the contraction starts.  ADD nodes that consume the conv
 // output (residual add + activation, skip adds) run here as well, writing their own buffers.
+#include <cstdlib>
+
 #include "evconv_kernels.h"
 
 namespace evk {
@@ -422,9 +424,13 @@ double fill(long long n) { return (double)n / 256.0 / (double)((n + 255) / 256);
 template <int CHUNK, bool BF16>
 void launch_shape(const ConvParams& p, hipStream_t s) {
   const long long n2 = (long long)p.go.tiles() * (p.go.c / 32);  // workgroups with whole tiles
-  const bool halves = fill(2 * n2) > fill(n2) + 0.05;            // half tiles balance better
+  bool halves = fill(2 * n2) > fill(n2) + 0.05;                  // half tiles balance better
   const long long n = halves ? 2 * n2 : n2;
-  const bool eight = n < 512;  // few workgroups: 8 waves each split K further
+  bool eight = n < 512;  // few workgroups: 8 waves each split K further
+#ifdef EVK_TUNE  // timing sweeps of the launch shape from a stand-alone harness
+  if (const char* e = getenv("EVK_MB")) halves = atoi(e) == 1;
+  if (const char* e = getenv("EVK_NW")) eight = atoi(e) == 8;
+#endif
   if (halves) {
     if (eight) launch_variant<CHUNK, 8, BF16, 1>(p, s); else launch_variant<CHUNK, 4, BF16, 1>(p, s);
   } else {
