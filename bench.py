@@ -40,23 +40,30 @@ def run_variant(args, np, torch, ev, wl, variant, frames, dframes, with_dense, w
     net = wl.net_unet_depth(1003, h=H, w=W, bf16=(variant == "bf16"))
     n_frames = args.warmup + args.steps
 
-    def timed_run(mode):
+    def timed_run(mode, profile):
         g = ev.EvConvNet(net, device="cuda:0")
         g.set_mode(mode)
         g.reset(dframes[0])
         for i in range(1, args.warmup + 1):
             g.step_frame(dframes[i])
         torch.cuda.synchronize()
-        g.profile_begin(args.steps * len(net.nodes))
+        if profile:
+            g.profile_begin(args.steps * len(net.nodes))
         t0 = time.perf_counter()
         for i in range(args.warmup + 1, n_frames + 1):
             g.step_frame(dframes[i])
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        g.profile_end()
+        if profile:
+            g.profile_end()
         return g, dt
 
-    g, dt = timed_run(ev.MODE_INCREMENTAL)
+    # pass 1: the K timed steps with nothing but the library's own launches on the stream -> value
+    g, dt = timed_run(ev.MODE_INCREMENTAL, False)
+    g.destroy()
+    # pass 2: the same K steps with a HIP event pair around every node's launches -> per-kernel
+    # durations for the roofline (the events themselves cost ~1 us each and stretch this pass)
+    g, dt_prof = timed_run(ev.MODE_INCREMENTAL, True)
     # per kernel family: accumulated event time, launches, algorithmic flops of the timed launches
     fam, layers = {}, []
     for i, nd in enumerate(net.nodes):
@@ -77,11 +84,14 @@ def run_variant(args, np, torch, ev, wl, variant, frames, dframes, with_dense, w
     achieved = fam[dom]["flops"] / (fam[dom]["ms"] * 1e-3) / 1e12 if fam[dom]["ms"] > 0 else 0.0
     roofline = dict(kernel=dom, bound=bound, achieved=achieved, peak=peak, unit=unit, frac=achieved / peak,
                     traffic=TRAFFIC_FROM_PROFILE.get(dom), avg_launch_ms=fam[dom]["ms"] / max(fam[dom]["launches"], 1),
-                    launches=fam[dom]["launches"], share_of_step=fam[dom]["ms"] / (dt * 1e3))
+                    launches=fam[dom]["launches"], share_of_step=fam[dom]["ms"] / (dt_prof * 1e3),
+                    event_pass_ms_per_step=dt_prof / args.steps * 1e3)
     g.destroy()
     res = dict(value=args.steps / dt, ms_per_step=dt / args.steps * 1e3, roofline=roofline)
     if with_dense:
-        g2, dt2 = timed_run(ev.MODE_DENSE_RECOMPUTE)
+        g2, dt2 = timed_run(ev.MODE_DENSE_RECOMPUTE, False)
+        g2.destroy()
+        g2, _ = timed_run(ev.MODE_DENSE_RECOMPUTE, True)
         for i, l in enumerate(layers):
             ms, n = g2.node_time(i)
             l["dense_ms_avg"] = ms / max(n, 1)
