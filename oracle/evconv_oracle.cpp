@@ -31,6 +31,15 @@
 //     with clamped borders (weights 0.25 / 0.75).
 //   * a linear op without activation emits y_inc = theta_L(x_inc) itself (Eq.10), not the
 //     difference of the accumulated sums.
+//   * sparsification layer (Eq.3-8; the printed Eq.4 and Eq.8 disagree in sign and Eq.8 counts
+//     the old residual twice): delta(-1) = 0; x_corr = delta(n-1) + x_inc(n);
+//     y_inc = k * floor(0.5 + x_corr / k); delta(n) = x_corr - y_inc.  This keeps
+//     sum(y_inc) + delta == sum(x_inc) and -k/2 <= delta < k/2, which is what the text asks of
+//     the residual.  A refresh is a regular forward pass (the layer is the identity) and clears
+//     delta.  k = t_p * RMS(layer input at the last refresh), rounded to 8 significant bits so
+//     that both sides of a comparison use the identical step (the paper says "t_p times the L2
+//     norm of a rolling average of the input" without giving window or normalisation);
+//     k == 0 makes the layer the identity.
 //
 // Parity pins live in tests/ (CPU, "not gpu"): dense ops against PyTorch CPU fp64 routines,
 // Eq.2 invariant against the dense pass, linearity, zero increment, tile independence,
@@ -46,7 +55,7 @@
 
 namespace {
 
-enum Op { OP_CONV = 0, OP_ADD, OP_CONCAT, OP_UP2X, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_ACT };
+enum Op { OP_CONV = 0, OP_ADD, OP_CONCAT, OP_UP2X, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_ACT, OP_SPARSIFY };
 enum Act { ACT_NONE = 0, ACT_RELU, ACT_SIGMOID };
 
 struct NodeDesc {
@@ -86,6 +95,8 @@ struct NodeState {
   std::vector<uint8_t> touched;  // structural touched set T
   std::vector<T> y;              // output nodes: running sum of increments (Eq.2)
   std::vector<T> dz, da;         // dense pass: pre-activation and value of this node
+  float k = 0.f;                 // sparsification layer: rounding step (z holds the residual delta)
+  float k_fixed = -1.f;          // >= 0: step given by the description instead of t_p * RMS
   bool keeps_z = false, structural = false;
   double macs_site = 0, macs_dense = 0;
 };
@@ -101,6 +112,7 @@ struct Net {
   std::vector<T> x_dense;             // HWC copy of the frame for the dense pass
   std::vector<NodeState<T>> st;
   bool has_state = false;
+  double sparsify_tp = 0.0;
 
   const Shape& shape_of(int i) const { return i < 0 ? in : st[i].shp; }
   const std::vector<T>& dy_of(int i) const { return i < 0 ? dx : st[i].dy; }
@@ -149,6 +161,14 @@ struct Net {
           break;
         }
         case OP_ACT: o = a; break;
+        case OP_SPARSIFY:
+          if (nd.act != ACT_NONE) return 3;
+          o = a;
+          if (nd.w_off >= 0) {
+            if (nd.w_off >= n_w) return 9;
+            st[i].k_fixed = float(weights[nd.w_off]);
+          }
+          break;
         case OP_CONCAT: {
           Shape b = shape_of(nd.in1);
           if (b.h != a.h || b.w != a.w) return 5;
@@ -167,7 +187,7 @@ struct Net {
       NodeState<T>& s = st[i];
       s.shp = o;
       s.keeps_z = (nd.op == OP_CONV || nd.op == OP_LINEAR || nd.op == OP_GAP || nd.op == OP_ACT ||
-                   nd.act != ACT_NONE) && nd.op != OP_MAXPOOL;
+                   nd.op == OP_SPARSIFY || nd.act != ACT_NONE) && nd.op != OP_MAXPOOL;
       s.structural = (nd.op == OP_ADD || nd.op == OP_CONCAT || nd.op == OP_UP2X || nd.op == OP_GAP) &&
                      nd.act == ACT_NONE;
       s.dy.assign(o.elems(), T(0));
@@ -242,6 +262,7 @@ struct Net {
         break;
       }
       case OP_ACT: s.dz = xa; break;
+      case OP_SPARSIFY: s.dz = xa; break;  // a regular forward pass does not sparsify
       case OP_CONCAT: {
         const Shape b = shape_of(nd.in1);
         const std::vector<T>& xb = dense_of(nd.in1);
@@ -306,6 +327,16 @@ struct Net {
     for (size_t i = 0; i < nodes.size(); ++i) {
       NodeState<T>& s = st[i];
       if (s.keeps_z) s.z = s.dz;
+      if (nodes[i].op == OP_SPARSIFY) {
+        std::fill(s.z.begin(), s.z.end(), T(0));  // residual delta
+        if (s.k_fixed >= 0.f) {
+          s.k = s.k_fixed;
+        } else {
+          double sum = 0;
+          for (size_t e = 0; e < s.dz.size(); ++e) sum += double(s.dz[e]) * double(s.dz[e]);
+          s.k = quantise_step(float(sparsify_tp * std::sqrt(sum / double(s.dz.size()))));
+        }
+      }
       if (nodes[i].op == OP_MAXPOOL) s.pool_in = dense_of(nodes[i].in0);
       if (nodes[i].is_output) s.y = s.da;
       std::fill(s.dy.begin(), s.dy.end(), T(0));
@@ -353,6 +384,15 @@ struct Net {
     for (size_t i = 0; i < nodes.size(); ++i) incr_node(int(i));
   }
 
+  // rounding step kept to 8 significant bits (round to nearest on the 16th mantissa bit)
+  static float quantise_step(float k) {
+    uint32_t u;
+    std::memcpy(&u, &k, 4);
+    u = (u + 0x4000u) & 0xffff8000u;
+    std::memcpy(&k, &u, 4);
+    return k;
+  }
+
   // touched set of a windowed op (conv / max-pool): mark every output that reads an active,
   // in-bounds input site through some tap
   static void touched_windowed(const std::vector<uint8_t>& s_in, const Shape& a, const Shape& o,
@@ -386,6 +426,32 @@ struct Net {
     // clear last step's increment on its old support
     for (size_t q = 0; q < o.sites(); ++q)
       if (s.touched[q]) std::fill(&s.dy[q * o.c], &s.dy[q * o.c] + o.c, T(0));
+    if (nd.op == OP_SPARSIFY) {  // Eq.3-8 under the reading in the header
+      const T k = T(s.k);
+      for (size_t q = 0; q < o.sites(); ++q) {
+        s.touched[q] = sa[q];
+        s.active[q] = 0;
+        if (!sa[q]) continue;
+        uint8_t nz = 0;
+        for (int c = 0; c < o.c; ++c) {
+          const size_t e = q * o.c + c;
+          T y = da[e];
+          if (k > T(0)) {
+            const T x_corr = s.z[e] + da[e];
+            y = k * std::floor(T(0.5) + x_corr / k);
+            s.z[e] = x_corr - y;
+          }
+          s.dy[e] = y;
+          nz |= (float(y) != 0.0f);
+        }
+        s.active[q] = nz;
+        if (!nz) std::fill(&s.dy[q * o.c], &s.dy[q * o.c] + o.c, T(0));
+        if (nz && nd.is_output)  // Eq.2
+          for (int c = 0; c < o.c; ++c) s.y[q * o.c + c] += s.dy[q * o.c + c];
+      }
+      s.macs_site = 0;
+      return;
+    }
     std::vector<T> v;  // linear-part increment at touched sites, HWC dense-addressed
     v.assign(o.elems(), T(0));
     std::vector<float> v32;  // max-pool only: the increment formed from binary32-rounded maxima
@@ -593,9 +659,11 @@ extern "C" {
 
 // desc: n_nodes x 12 int32 {op, act, in0, in1, c_in, c_out, k, stride, pad, w_off, b_off, is_output}
 void* evo_create(int n_nodes, const int* desc, const double* weights, long long n_weights,
-                 int in_c, int in_h, int in_w, int fp32_state) {
+                 int in_c, int in_h, int in_w, int fp32_state, double sparsify_tp) {
   Handle* h = new Handle();
   h->fp32 = fp32_state;
+  h->d.sparsify_tp = sparsify_tp;
+  h->f.sparsify_tp = sparsify_tp;
   int rc = fp32_state ? h->f.init(n_nodes, desc, weights, n_weights, in_c, in_h, in_w)
                       : h->d.init(n_nodes, desc, weights, n_weights, in_c, in_h, in_w);
   if (rc) { delete h; return nullptr; }
@@ -635,6 +703,11 @@ void evo_get_x_prev(void* h, float* dst) {
   Handle* p = (Handle*)h;
   const std::vector<float>& v = p->fp32 ? p->f.x_prev : p->d.x_prev;
   std::copy(v.begin(), v.end(), dst);
+}
+// rounding step of a sparsification node (0 for other nodes)
+float evo_get_step(void* h, int node) {
+  Handle* p = (Handle*)h;
+  return p->fp32 ? p->f.st[node].k : p->d.st[node].k;
 }
 // executed multiply-accumulates of the last step at site granularity, and of a dense pass
 void evo_get_macs(void* h, int node, double* site, double* dense) {

@@ -43,7 +43,9 @@ def _load():
         L = ctypes.CDLL(_SO)
         L.evo_create.restype = ctypes.c_void_p
         L.evo_create.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_longlong,
-                                 ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+                                 ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double]
+        L.evo_get_step.restype = ctypes.c_float
+        L.evo_get_step.argtypes = [ctypes.c_void_p, ctypes.c_int]
         L.evo_destroy.argtypes = [ctypes.c_void_p]
         for f in (L.evo_dense_forward, L.evo_reset, L.evo_step_frame, L.evo_step_increment):
             f.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
@@ -78,7 +80,8 @@ class Oracle:
         w = np.ascontiguousarray(net.weights, dtype=np.float64)
         self._h = L.evo_create(len(net.nodes), desc.ctypes.data_as(ctypes.c_void_p),
                                w.ctypes.data_as(ctypes.c_void_p), w.size,
-                               net.in_c, net.in_h, net.in_w, int(fp32_state))
+                               net.in_c, net.in_h, net.in_w, int(fp32_state),
+                               float(getattr(net, "sparsify_tp", 0.0)))
         if not self._h:
             raise ValueError("oracle rejected the network description")
         self.n_nodes = len(net.nodes)
@@ -148,6 +151,10 @@ class Oracle:
     def site_list(self, node, kind=SET_ACTIVE) -> np.ndarray:
         """Strictly ascending int32 linear indices y*W + x of the set."""
         return np.flatnonzero(self.mask(node, kind).ravel()).astype(np.int32)
+
+    def step_size(self, node) -> float:
+        """Rounding step k of a sparsification node after the last refresh."""
+        return float(_load().evo_get_step(self._h, node))
 
     def macs(self, node):
         a, b = ctypes.c_double(), ctypes.c_double()

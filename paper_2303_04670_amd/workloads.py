@@ -23,7 +23,7 @@ from typing import Iterator, List, Optional, Tuple
 import numpy as np
 
 # op / activation codes: plain data shared by both marshalling layers
-OP_CONV2D, OP_ADD, OP_CONCAT, OP_UPSAMPLE2X, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_ACT = range(8)
+OP_CONV2D, OP_ADD, OP_CONCAT, OP_UPSAMPLE2X, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_ACT, OP_SPARSIFY = range(9)
 ACT_NONE, ACT_RELU, ACT_SIGMOID = range(3)
 WD_F32, WD_BF16 = 0, 1
 
@@ -53,6 +53,7 @@ class Net:
     in_w: int
     nodes: List[Node]
     weights: np.ndarray      # flat float32
+    sparsify_tp: float = 0.0  # threshold parameter t_p of the sparsification layers (0: none)
 
     def node_shapes(self) -> List[Tuple[int, int, int]]:
         """(C, H, W) of every node's output (pure shape bookkeeping)."""
@@ -65,7 +66,7 @@ class Net:
                 ho = (h + 2 * nd.pad - nd.k) // nd.stride + 1
                 wo = (w + 2 * nd.pad - nd.k) // nd.stride + 1
                 out.append((nd.c_out if nd.op == OP_CONV2D else c, ho, wo))
-            elif nd.op in (OP_ADD, OP_ACT):
+            elif nd.op in (OP_ADD, OP_ACT, OP_SPARSIFY):
                 out.append((c, h, w))
             elif nd.op == OP_CONCAT:
                 c2, _, _ = shp(nd.in1)
@@ -84,7 +85,11 @@ class Net:
 class _NetBuilder:
     """Appends nodes and draws He-initialised weights N(0, 2/(k*k*c_in))."""
 
-    def __init__(self, name, in_c, in_h, in_w, seed, bf16=False, bias=False):
+    def __init__(self, name, in_c, in_h, in_w, seed, bf16=False, bias=False, sparsify=False, sparsify_k=None):
+        """sparsify: put a sparsification layer ahead of every convolution whose input is not the
+        network input; sparsify_k: fixed rounding step for all of them (None: the library derives
+        it from the net's threshold parameter and the layer input at refresh time)."""
+        self.sparsify, self.sparsify_k = sparsify, sparsify_k
         self.name, self.in_c, self.in_h, self.in_w = name, in_c, in_h, in_w
         self.rng = np.random.Generator(np.random.PCG64(seed))
         self.nodes: List[Node] = []
@@ -99,6 +104,8 @@ class _NetBuilder:
         nd = self.nodes[i]
         if nd.op in (OP_CONV2D, OP_LINEAR):
             return nd.c_out
+        if nd.op == OP_SPARSIFY:
+            return self._chan(nd.in0)
         if nd.op == OP_CONCAT:
             return self._chan(nd.in0) + self._chan(nd.in1)
         return self._chan(nd.in0)
@@ -111,6 +118,12 @@ class _NetBuilder:
 
     def conv(self, src, c_out, k, stride=1, pad=None, act=ACT_RELU, out=0, op=OP_CONV2D):
         c_in = self._chan(src)
+        if self.sparsify and src >= 0 and op == OP_CONV2D:
+            k_off = -1
+            if self.sparsify_k is not None:
+                k_off = self._push(np.asarray([self.sparsify_k], np.float32))
+            self.nodes.append(Node(OP_SPARSIFY, ACT_NONE, src, -2, c_in, c_in, 1, 1, 0, k_off, -1, 0))
+            src = len(self.nodes) - 1
         pad = k // 2 if pad is None else pad
         std = math.sqrt(2.0 / (k * k * c_in))
         w = self.rng.standard_normal((c_out, c_in, k, k)) * std
@@ -155,9 +168,10 @@ def net_single_conv(seed=1001, c=16, h=64, w=64) -> Net:
     return b.finish()
 
 
-def net_conv_stack(seed=1002, h=180, w=240) -> Net:
+def net_conv_stack(seed=1002, h=180, w=240, sparsify=False, sparsify_k=None) -> Net:
     """Workload 2: 4 conv3x3 layers 5->32 s1, 32->32 s2, 32->64 s2, 64->64 s1, ReLU each."""
-    b = _NetBuilder("conv_stack4", 5, h, w, seed)
+    b = _NetBuilder("conv_stack4" + ("_sp" if sparsify else ""), 5, h, w, seed, sparsify=sparsify,
+                    sparsify_k=sparsify_k)
     x = b.conv(-1, 32, 3, 1)
     x = b.conv(x, 32, 3, 2)
     x = b.conv(x, 64, 3, 2)
@@ -165,10 +179,11 @@ def net_conv_stack(seed=1002, h=180, w=240) -> Net:
     return b.finish()
 
 
-def net_unet_depth(seed=1003, h=256, w=352, bf16=False, width=32) -> Net:
+def net_unet_depth(seed=1003, h=256, w=352, bf16=False, width=32, sparsify=False, sparsify_k=None) -> Net:
     """Workload 3: UNet depth net.  head 5x5 -> 3 strided 5x5 encoders -> 2 residual blocks
     -> 3 x (skip-add, bilinear x2, conv5x5) -> skip-add with head -> 1x1 conv + sigmoid."""
-    b = _NetBuilder("unet_depth" + ("_bf16" if bf16 else ""), 5, h, w, seed, bf16=bf16)
+    b = _NetBuilder("unet_depth" + ("_bf16" if bf16 else "") + ("_sp" if sparsify else ""), 5, h, w, seed,
+                    bf16=bf16, sparsify=sparsify, sparsify_k=sparsify_k)
     head = b.conv(-1, width, 5)
     e1 = b.conv(head, 2 * width, 5, 2)
     e2 = b.conv(e1, 4 * width, 5, 2)
