@@ -23,6 +23,13 @@
  *                    with an active source site.  Linear, so Eq.10 applies.
  *   ACT              y_lin = x_inc, T = S_in (the activation increment layer, Eq.12-14).
  *   GLOBAL_AVGPOOL   y_lin = mean over sites of x_inc (1 x 1 x C), T = {0} if S_in nonempty.
+ *   SPARSIFY         the sparsification layer with error feedback (Eq.3-8): residual delta (kept
+ *                    as this node's accumulated tensor, zero after reset), x_corr = delta + x_inc,
+ *                    y_inc = k * floor(0.5 + x_corr / k), delta = x_corr - y_inc, at S_in; S_out =
+ *                    sites with a nonzero y_inc.  k = sparsify_tp * RMS(node input at the last
+ *                    reset), kept to 8 significant bits, or the fp32 value at weight_off when
+ *                    weight_off >= 0; k == 0 is the identity.  In reset and in dense-recompute
+ *                    mode the node is the identity.  Lossy: y no longer equals the forward pass.
  *   MAXPOOL          state a += x_inc; y_inc = max(window of a_new) - max(window of a_old) at
  *                    windows containing an active site; padding value -inf; act must be NONE.
  * A node keeps an accumulated tensor z (+= y_lin at T) if it is CONV2D, LINEAR,
@@ -65,7 +72,8 @@ typedef enum {
   EVCONV_OP_MAXPOOL = 4,
   EVCONV_OP_GLOBAL_AVGPOOL = 5,
   EVCONV_OP_LINEAR = 6,
-  EVCONV_OP_ACT = 7
+  EVCONV_OP_ACT = 7,
+  EVCONV_OP_SPARSIFY = 8
 } evconv_op;
 
 typedef enum { EVCONV_ACT_NONE = 0, EVCONV_ACT_RELU = 1, EVCONV_ACT_SIGMOID = 2 } evconv_act;
@@ -102,7 +110,7 @@ typedef struct {
   const evconv_node_desc* nodes; /* HOST, n_nodes entries, topological order */
   int32_t in_c, in_h, in_w;
   int32_t tile_h, tile_w; /* mask tile; 0 = default 8 x 8 (the only size this build accepts) */
-  float sparsify_tp;      /* lossy sparsification threshold; must be 0 (lossless) */
+  float sparsify_tp;      /* threshold parameter t_p of the SPARSIFY nodes (>= 0; 0 = lossless) */
   int32_t n_streams;      /* independent streams sharing the weights; must be 1 */
 } evconv_net_desc;
 
@@ -133,7 +141,8 @@ typedef enum {
   EVCONV_STATE_BITMAP = 4,      /* uint64 words, bit t%64 of word t/64 = tile t non-empty */
   EVCONV_STATE_OCC = 5,         /* uint64 per tile: S_out, bit (y%8)*8 + x%8, tiles row-major */
   EVCONV_STATE_OCC_TOUCHED = 6, /* uint64 per tile: T */
-  EVCONV_STATE_X_PREV = 7       /* node -1 only: fp32 C x H x W cached previous frame */
+  EVCONV_STATE_X_PREV = 7,      /* node -1 only: fp32 C x H x W cached previous frame */
+  EVCONV_STATE_STEP = 8         /* SPARSIFY nodes: one fp32, the rounding step k */
 } evconv_state_kind;
 
 /* Bytes of device workspace a net of this description needs.  No GPU work. */

@@ -40,6 +40,9 @@ struct NodePlan {
   int n_fused = 0;          // conv node: ADD nodes it executes, in order
   int fused_nodes[kMaxFusedAdds] = {-1, -1};
   // workspace offsets (bytes); resolved to pointers at create
+  size_t off_step = 0;      // SPARSIFY: device scalar k
+  float* step = nullptr;
+  float step_fixed = -1.0f; // >= 0: k supplied by the description
   size_t off_z = 0, off_out = 0, off_pool = 0, off_occ = 0, off_touched = 0, off_idx = 0, off_count = 0,
          off_bitmap = 0, off_w = 0, off_bias = 0, off_y = 0, off_dy = 0;
   float *z = nullptr, *out = nullptr, *pool_in = nullptr, *bias = nullptr, *y = nullptr, *dy = nullptr;
@@ -53,7 +56,7 @@ struct Layout {
   Geo gin;
   size_t off_x_prev = 0, off_dx = 0, off_occ_in = 0, off_idx_in = 0, off_count_in = 0, off_bitmap_in = 0;
   size_t off_occ_nodes = 0, n_occ_words = 0;  // contiguous occupancy region of all nodes
-  size_t off_sets = 0;
+  size_t off_sets = 0, off_rms = 0;
   size_t total = 0;
   int max_ty = 0;
 };
@@ -83,7 +86,7 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
   if (desc->in_c <= 0 || desc->in_h <= 0 || desc->in_w <= 0) return fail(err, EVCONV_ERR_SHAPE, "bad input shape");
   if ((desc->tile_h != 0 && desc->tile_h != kTile) || (desc->tile_w != 0 && desc->tile_w != kTile))
     return fail(err, EVCONV_ERR_UNSUPPORTED, "only 8 x 8 mask tiles are built");
-  if (desc->sparsify_tp != 0.0f) return fail(err, EVCONV_ERR_UNSUPPORTED, "lossy sparsification is not built");
+  if (!(desc->sparsify_tp >= 0.0f)) return fail(err, EVCONV_ERR_INVALID_ARG, "sparsify_tp must be >= 0");
   if (desc->n_streams != 0 && desc->n_streams != 1) return fail(err, EVCONV_ERR_UNSUPPORTED, "n_streams must be 1");
   if ((long long)desc->in_h * desc->in_w > (1ll << 30)) return fail(err, EVCONV_ERR_SHAPE, "input too large");
 
@@ -101,7 +104,7 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
     n.d = d;
     char where[64];
     snprintf(where, sizeof where, "node %d: ", i);
-    if (d.op < 0 || d.op > EVCONV_OP_ACT) return fail(err, EVCONV_ERR_INVALID_ARG, std::string(where) + "bad op");
+    if (d.op < 0 || d.op > EVCONV_OP_SPARSIFY) return fail(err, EVCONV_ERR_INVALID_ARG, std::string(where) + "bad op");
     if (d.act < 0 || d.act > EVCONV_ACT_SIGMOID) return fail(err, EVCONV_ERR_INVALID_ARG, std::string(where) + "bad act");
     if (d.in0 < -1 || d.in0 >= i) return fail(err, EVCONV_ERR_BAD_DESC, std::string(where) + "in0 is not an earlier node");
     const bool two = d.op == EVCONV_OP_ADD || d.op == EVCONV_OP_CONCAT;
@@ -151,12 +154,18 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
       case EVCONV_OP_UPSAMPLE_BILINEAR2X: h *= 2; w *= 2; break;
       case EVCONV_OP_GLOBAL_AVGPOOL: h = 1; w = 1; break;
       case EVCONV_OP_ACT: break;
+      case EVCONV_OP_SPARSIFY:
+        if (d.act != EVCONV_ACT_NONE) return fail(err, EVCONV_ERR_UNSUPPORTED, std::string(where) + "SPARSIFY takes no activation");
+        if (d.weight_off >= 0 && ((d.weight_off & 3) || (check_weights && (size_t)d.weight_off + 4 > weight_bytes)))
+          return fail(err, EVCONV_ERR_BAD_DESC, std::string(where) + "step value out of range");
+        break;
     }
     if ((long long)h * w > (1ll << 30)) return fail(err, EVCONV_ERR_SHAPE, std::string(where) + "output too large");
     n.go = make_geo(c, h, w);
     if (n.go.ty > L->max_ty) L->max_ty = n.go.ty;
     const bool lin = d.op == EVCONV_OP_CONV2D || d.op == EVCONV_OP_LINEAR;
-    n.keeps_z = (lin || d.op == EVCONV_OP_GLOBAL_AVGPOOL || d.op == EVCONV_OP_ACT || d.act != EVCONV_ACT_NONE) &&
+    n.keeps_z = (lin || d.op == EVCONV_OP_GLOBAL_AVGPOOL || d.op == EVCONV_OP_ACT ||
+                 d.op == EVCONV_OP_SPARSIFY || d.act != EVCONV_ACT_NONE) &&
                 d.op != EVCONV_OP_MAXPOOL;
     n.structural = (d.op == EVCONV_OP_ADD || d.op == EVCONV_OP_CONCAT || d.op == EVCONV_OP_UPSAMPLE_BILINEAR2X ||
                     d.op == EVCONV_OP_GLOBAL_AVGPOOL) && d.act == EVCONV_ACT_NONE;
@@ -188,6 +197,7 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
     NodePlan& n = L->nodes[i];
     const size_t elems = (size_t)n.go.c * n.go.sites();
     if (n.keeps_z || n.d.op == EVCONV_OP_MAXPOOL) n.off_z = b.take(elems * 4);
+    if (n.d.op == EVCONV_OP_SPARSIFY) n.off_step = b.take(4);
     if (n.d.op == EVCONV_OP_MAXPOOL) n.off_pool = b.take((size_t)n.ga.c * n.ga.sites() * 4);
     n.off_out = b.take(elems * 4);
     n.off_idx = b.take((size_t)n.go.sites() * 4);
@@ -203,6 +213,7 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
       n.off_dy = b.take(elems * 4);
     }
   }
+  L->off_rms = b.take(sizeof(float) * kRmsBlocks);
   L->off_sets = b.take(sizeof(SetDesc) * (size_t)(desc->n_nodes + 1));
   L->total = b.cur;
   return EVCONV_OK;
@@ -212,6 +223,8 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
 
 struct evconv_net {
   Layout L;
+  float sparsify_tp = 0.0f;
+  float* rms_partial = nullptr;
   std::vector<evconv_node_desc> desc_nodes;
   char* ws = nullptr;
   hipStream_t stream = nullptr;
@@ -297,7 +310,11 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
       case kKernElementwise: {
         EwParams p;
         p.op = d.op == EVCONV_OP_ADD ? kEwAdd : d.op == EVCONV_OP_CONCAT ? kEwConcat :
-               d.op == EVCONV_OP_UPSAMPLE_BILINEAR2X ? kEwUp2x : kEwAct;
+               d.op == EVCONV_OP_UPSAMPLE_BILINEAR2X ? kEwUp2x : d.op == EVCONV_OP_SPARSIFY ? kEwSparsify : kEwAct;
+        p.step = n.step;
+        if (d.op == EVCONV_OP_SPARSIFY && pass == kPassReset && n.step_fixed < 0.0f)
+          // refresh: k = t_p * RMS of the layer input, which the producer has just written in full
+          launch_rms_step(a, (size_t)n.ga.c * n.ga.sites(), net->sparsify_tp, net->rms_partial, n.step, s);
         p.act = d.act; p.dense = dense; p.keeps_z = n.keeps_z; p.structural = n.structural;
         p.ga = n.ga; p.gb = n.gb; p.go = n.go; p.a = a; p.occ_a = occ_a; p.b = bptr; p.occ_b = occ_b;
         p.z = n.z; p.out = n.out; p.occ_out = n.occ; p.occ_touched = n.touched;
@@ -394,6 +411,8 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
   net->bitmap_in = (uint64_t*)(ws + L.off_bitmap_in);
   net->occ_nodes = (uint64_t*)(ws + L.off_occ_nodes);
   net->sets_dev = (SetDesc*)(ws + L.off_sets);
+  net->rms_partial = (float*)(ws + L.off_rms);
+  net->sparsify_tp = desc->sparsify_tp;
 
   hipError_t e = hipMemsetAsync(ws, 0, L.total, net->stream);
   if (e != hipSuccess) { g_create_error = std::string("hipMemsetAsync: ") + hipGetErrorString(e); delete net; return EVCONV_ERR_HIP; }
@@ -406,6 +425,15 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
     const size_t elems = (size_t)n.go.c * n.go.sites();
     (void)elems;
     n.z = (n.keeps_z || n.d.op == EVCONV_OP_MAXPOOL) ? (float*)(ws + n.off_z) : nullptr;
+    if (n.d.op == EVCONV_OP_SPARSIFY) {
+      n.step = (float*)(ws + n.off_step);
+      if (n.d.weight_off >= 0) {
+        memcpy(&n.step_fixed, (const char*)weights + n.d.weight_off, 4);
+        if (!(n.step_fixed >= 0.0f)) { g_create_error = "negative sparsification step"; delete net; return EVCONV_ERR_BAD_DESC; }
+        e = hipMemcpy(n.step, &n.step_fixed, 4, hipMemcpyHostToDevice);
+        if (e != hipSuccess) { g_create_error = std::string("upload: ") + hipGetErrorString(e); delete net; return EVCONV_ERR_HIP; }
+      }
+    }
     n.pool_in = n.d.op == EVCONV_OP_MAXPOOL ? (float*)(ws + n.off_pool) : nullptr;
     n.out = (float*)(ws + n.off_out);
     n.occ = (uint64_t*)(ws + n.off_occ);
@@ -566,6 +594,7 @@ evconv_status evconv_get_state(evconv_net* net, int32_t node, int32_t kind, void
     case EVCONV_STATE_OCC: src = n ? n->occ : net->occ_in; need = (size_t)g.tiles() * 8; break;
     case EVCONV_STATE_OCC_TOUCHED: src = n ? n->touched : net->occ_in; need = (size_t)g.tiles() * 8; break;
     case EVCONV_STATE_X_PREV: src = n ? nullptr : net->x_prev; need = elems * 4; break;
+    case EVCONV_STATE_STEP: src = n ? n->step : nullptr; need = 4; break;
     default: net->err = "bad state kind"; return EVCONV_ERR_INVALID_ARG;
   }
   if (!src) { net->err = "this node keeps no such state"; return EVCONV_ERR_INVALID_ARG; }

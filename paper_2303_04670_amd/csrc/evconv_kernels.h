@@ -81,7 +81,7 @@ bool conv_mfma_bf16_supported(const ConvParams& p);
 void launch_conv_mfma_bf16(const ConvParams& p, hipStream_t s);
 
 // ---- elementwise / structural increment operators ---------------------------------------
-enum EwOp { kEwAdd = 0, kEwAct, kEwConcat, kEwUp2x, kEwPoolAcc, kEwPoolMax };
+enum EwOp { kEwAdd = 0, kEwAct, kEwConcat, kEwUp2x, kEwPoolAcc, kEwPoolMax, kEwSparsify };
 struct EwParams {
   int op, act, dense, keeps_z, structural;
   Geo ga, gb, go;
@@ -91,8 +91,14 @@ struct EwParams {
   float* out;
   uint64_t* occ_out; uint64_t* occ_touched;
   int k, stride, pad;       // pooling window
+  const float* step;        // sparsification layer: device scalar, the rounding step k
 };
 void launch_elementwise(const EwParams& p, hipStream_t s);
+
+// ---- rounding step of a sparsification layer: k = tp * RMS(x), 8 significant bits ---------------
+// Two fixed-order reduction stages (no floating-point atomics): `partial` holds kRmsBlocks floats.
+constexpr int kRmsBlocks = 256;
+void launch_rms_step(const float* x, size_t n, float tp, float* partial, float* step_out, hipStream_t s);
 
 // ---- global average pool -----------------------------------------------------------------
 struct GapParams {

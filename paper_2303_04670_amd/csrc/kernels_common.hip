@@ -152,7 +152,7 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
       wa = p.occ_a[tile];
       wb = p.occ_b[tile];
       t = ((wa | wb) >> tid) & 1ull;
-    } else if (p.op == kEwAct || p.op == kEwPoolAcc) {
+    } else if (p.op == kEwAct || p.op == kEwPoolAcc || p.op == kEwSparsify) {
       wa = p.occ_a[tile];
       t = (wa >> tid) & 1ull;
     } else if (p.op == kEwUp2x) {
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
       const VecT<VEC> vb = on_b ? ldv<VEC>(&p.b[q * C + c]) : zerov<VEC>();
 #pragma unroll
       for (int i = 0; i < VEC; ++i) lin.v[i] = va.v[i] + vb.v[i];
-    } else if (p.op == kEwAct || p.op == kEwPoolAcc) {
+    } else if (p.op == kEwAct || p.op == kEwPoolAcc || p.op == kEwSparsify) {
       lin = ldv<VEC>(&p.a[q * C + c]);
     } else if (p.op == kEwConcat) {
       const bool on_a = (wa >> site) & 1ull, on_b = (wb >> site) & 1ull;
@@ -266,7 +266,22 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
     }
     VecT<VEC> o;
     bool nz = false;
-    if (p.op == kEwPoolMax) {
+    if (p.op == kEwSparsify) {
+      // Eq.3-8: x_corr = delta + x_inc; y_inc = k floor(0.5 + x_corr / k); delta = x_corr - y_inc
+      const float k = p.dense ? 0.0f : *p.step;
+      VecT<VEC> d_new = zerov<VEC>();
+      o = lin;
+      if (k > 0.0f) {
+        const VecT<VEC> d_old = ldv<VEC>(zq);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+          const float x_corr = d_old.v[i] + lin.v[i];
+          o.v[i] = k * floorf(0.5f + x_corr / k);
+          d_new.v[i] = x_corr - o.v[i];
+        }
+      }
+      if (p.dense || k > 0.0f) stv<VEC>(zq, d_new);  // a refresh clears the residual
+    } else if (p.op == kEwPoolMax) {
       const VecT<VEC> m_old = ldv<VEC>(zq);
       stv<VEC>(zq, lin);
 #pragma unroll
@@ -465,6 +480,45 @@ __global__ __launch_bounds__(512) void build_lists_kernel(const SetDesc* sets) {
 
 void launch_build_lists(const SetDesc* sets_dev, int n_sets, int max_ty, hipStream_t s) {
   hipLaunchKernelGGL(build_lists_kernel, dim3(max_ty, n_sets), dim3(512), 0, s, sets_dev);
+}
+
+// =============================================================================== rounding step
+// stage 1: block b sums the squares of its contiguous slice in a fixed order (thread-strided
+// partials, then a shared-memory tree); stage 2: one block adds the kRmsBlocks partials the same
+// way and writes k = tp * sqrt(sum / n) kept to 8 significant bits.
+__global__ __launch_bounds__(256) void rms_stage1_kernel(const float* x, size_t n, float* partial) {
+  __shared__ float s_sum[256];
+  const size_t per = (n + kRmsBlocks - 1) / kRmsBlocks;
+  const size_t lo = blockIdx.x * per, hi = min(n, lo + per);
+  float acc = 0.0f;
+  for (size_t i = lo + threadIdx.x; i < hi; i += 256) acc += x[i] * x[i];
+  s_sum[threadIdx.x] = acc;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) s_sum[threadIdx.x] += s_sum[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) partial[blockIdx.x] = s_sum[0];
+}
+__global__ __launch_bounds__(256) void rms_stage2_kernel(const float* partial, size_t n, float tp, float* step_out) {
+  __shared__ float s_sum[256];
+  s_sum[threadIdx.x] = threadIdx.x < kRmsBlocks ? partial[threadIdx.x] : 0.0f;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) s_sum[threadIdx.x] += s_sum[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const float k = tp * sqrtf(s_sum[0] / (float)n);
+    unsigned u = __float_as_uint(k);
+    u = (u + 0x4000u) & 0xffff8000u;
+    *step_out = __uint_as_float(u);
+  }
+}
+void launch_rms_step(const float* x, size_t n, float tp, float* partial, float* step_out, hipStream_t s) {
+  static_assert(kRmsBlocks == 256, "stage 2 adds one partial per thread");
+  hipLaunchKernelGGL(rms_stage1_kernel, dim3(kRmsBlocks), dim3(256), 0, s, x, n, partial);
+  hipLaunchKernelGGL(rms_stage2_kernel, dim3(1), dim3(256), 0, s, partial, n, tp, step_out);
 }
 
 __global__ void fill_u64_kernel(uint64_t* p, size_t n, uint64_t v) {

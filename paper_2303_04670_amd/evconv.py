@@ -22,7 +22,7 @@ STATUS_NAMES = ["OK", "ERR_INVALID_ARG", "ERR_BAD_DESC", "ERR_SHAPE", "ERR_STATE
 (ERR_INVALID_ARG, ERR_BAD_DESC, ERR_SHAPE, ERR_STATE, ERR_WORKSPACE, ERR_HIP, ERR_UNSUPPORTED) = range(1, 8)
 MODE_INCREMENTAL, MODE_DENSE_RECOMPUTE = 0, 1
 (STATE_Z, STATE_DY, STATE_IDX, STATE_COUNT, STATE_BITMAP, STATE_OCC, STATE_OCC_TOUCHED,
- STATE_X_PREV) = range(8)
+ STATE_X_PREV, STATE_STEP) = range(9)
 
 EXPORTS = ["evconv_query_workspace", "evconv_create", "evconv_num_outputs", "evconv_reset", "evconv_step",
            "evconv_step_frame", "evconv_destroy", "evconv_set_mode", "evconv_node_shape", "evconv_get_state",
@@ -97,7 +97,7 @@ class EvConvError(RuntimeError):
         self.status = status
 
 
-def marshal_desc(net, tile=(0, 0), sparsify_tp=0.0, n_streams=1):
+def marshal_desc(net, tile=(0, 0), sparsify_tp=None, n_streams=1):
     """workloads.Net -> (NetDesc, keep-alive node array).  Element offsets become byte offsets."""
     nodes = (NodeDesc * len(net.nodes))()
     for i, nd in enumerate(net.nodes):
@@ -107,6 +107,8 @@ def marshal_desc(net, tile=(0, 0), sparsify_tp=0.0, n_streams=1):
         n.wdtype, n.is_output = nd.wdtype, nd.is_output
         n.weight_off = nd.w_off * 4 if nd.w_off >= 0 else -1
         n.bias_off = nd.b_off * 4 if nd.b_off >= 0 else -1
+    if sparsify_tp is None:
+        sparsify_tp = float(getattr(net, "sparsify_tp", 0.0))
     d = NetDesc(ABI_VERSION, len(net.nodes), nodes, net.in_c, net.in_h, net.in_w, tile[0], tile[1],
                 sparsify_tp, n_streams)
     return d, nodes
@@ -199,6 +201,8 @@ class EvConvNet:
             a = np.empty(h * w, np.int32)
         elif kind == STATE_COUNT:
             a = np.empty(1, np.int32)
+        elif kind == STATE_STEP:
+            a = np.empty(1, np.float32)
         elif kind == STATE_BITMAP:
             a = np.empty(-(-tiles // 64), np.uint64)
         else:

@@ -58,8 +58,8 @@ def test_bad_descriptions_are_rejected():
     nodes[0].op = 42
     assert _status(desc) == ev.ERR_INVALID_ARG
     nodes[0].op = wl.OP_CONV2D
-    desc.sparsify_tp = 0.1                 # lossy sparsification is a later row
-    assert _status(desc) == ev.ERR_UNSUPPORTED
+    desc.sparsify_tp = -0.1
+    assert _status(desc) == ev.ERR_INVALID_ARG
     desc.sparsify_tp = 0.0
     desc.tile_h, desc.tile_w = 6, 6
     assert _status(desc) == ev.ERR_UNSUPPORTED

@@ -340,3 +340,112 @@ def test_workload3_unet_full_size_100_steps():
     rep = run_stream(net, x0, gen, "frame", check_nodes_at={1, 2, 50, 100}, label="w3",
                      max_flips=4 * int(0.005 * 256 * 352))
     assert set(rep.flips_by_node) <= {"node 20 active"}, rep.flips_by_node
+
+
+# --------------------------------------------------------------------------- sparsification layer
+
+def _sp_only_net(c, h, w, k=None, tp=0.0):
+    w_arr = np.zeros(0, np.float32)
+    k_off = -1
+    if k is not None:
+        w_arr, k_off = np.asarray([k], np.float32), 0
+    nodes = [wl.Node(wl.OP_SPARSIFY, wl.ACT_NONE, -1, -2, c, c, 1, 1, 0, k_off, -1, 1)]
+    return wl.Net("sp_only", c, h, w, nodes, w_arr, sparsify_tp=tp)
+
+
+@pytest.mark.parametrize("k,tp", [(0.3, 0.0), (None, 0.25)])
+def test_sparsification_layer_bit_exact_against_fp32_oracle(k, tp):
+    """Eq.3-8 are single-rounded fp32 operations on an input both sides see bit-identically, so
+    the residual, the emitted increments and the lists must match the binary32 oracle exactly;
+    with k = t_p * RMS both sides must also arrive at the identical 8-bit step."""
+    _say(f"sparsification layer alone, k={k} tp={tp}: bit-exact vs the binary32 oracle")
+    net = _sp_only_net(8, 21, 27, k=k, tp=tp)
+    rng = np.random.default_rng(3)
+    x0 = rng.standard_normal((8, 21, 27)).astype(np.float32)
+    frames, x = [], x0
+    for t in range(12):
+        m = rng.random((21, 27)) < 0.3
+        x = (x + 0.2 * rng.standard_normal(x.shape).astype(np.float32) * m[None]).astype(np.float32)
+        frames.append(x)
+    g, o = ev.EvConvNet(net), Oracle(net, fp32_state=True)
+    g.reset(_dev(x0))
+    o.reset(x0)
+    assert float(g.state(0, ev.STATE_STEP)[0]) == o.step_size(0) > 0
+    g.destroy()
+    run_stream(net, x0, frames, "frame", tol=0.0, exact_sets=True, fp32_oracle=True, label="sp-bits")
+
+
+def test_sparsified_conv_net_exact_arithmetic():
+    """Two convolutions with a sparsification layer between them, on values chosen so that every
+    sum is exact in binary32 (dyadic weights and inputs, k = 0.5): the rounding decisions cannot
+    differ, so the GPU must equal the fp64 oracle on every tensor and every list."""
+    _say("conv -> sparsify -> conv with exact arithmetic")
+    b = wl._NetBuilder("sp_exact", 4, 19, 23, 5, sparsify=True, sparsify_k=0.5)
+    x = b.conv(-1, 32, 3, 1)
+    b.conv(x, 32, 3, 1, out=1)
+    net = b.finish()
+    rng = np.random.default_rng(6)
+    wts = net.weights.copy()
+    for nd in net.nodes:
+        if nd.op == wl.OP_CONV2D:
+            n = nd.c_out * nd.c_in * 9
+            wts[nd.w_off:nd.w_off + n] = rng.integers(-2, 3, n) / 4.0
+    net.weights = wts
+    x0 = (rng.integers(-8, 9, (4, 19, 23)) / 4.0).astype(np.float32)
+    incs = [((rng.integers(-4, 5, x0.shape) / 4.0) * (rng.random((1, 19, 23)) < 0.1)).astype(np.float32)
+            for _ in range(8)]
+    g = ev.EvConvNet(net)
+    assert g.kernel_name(2) == "conv_mfma_f32"
+    g.destroy()
+    rep = run_stream(net, x0, incs, "increment", tol=1e-7, exact_sets=True, label="sp-exact")
+    assert rep.flips == 0
+
+
+def test_sparsified_unet_properties_and_speed_of_convergence():
+    """Lossy path on a reduced UNet with t_p = 0.3: what must hold whatever the rounding
+    decisions were - residual bounded by k/2, emitted increments multiples of k, fewer active
+    sites than the lossless run, output a bounded approximation of the regular forward pass,
+    and a refresh returns to the regular forward pass."""
+    _say("sparsified UNet (t_p = 0.3): residual bound, quantised increments, sparsity, refresh")
+    base = wl.net_unet_depth(1003, h=64, w=96)
+    sp = wl.net_unet_depth(1003, h=64, w=96, sparsify=True)
+    sp.sparsify_tp = 0.3
+    # small-valued increments (what the layer is for): a dense frame plus faint changes at 2 % of
+    # the pixels per step
+    rng = np.random.default_rng(11)
+    frames = [rng.standard_normal((5, 64, 96)).astype(np.float32)]
+    for _ in range(12):
+        m = rng.random((1, 64, 96)) < 0.02
+        frames.append((frames[-1] + 0.05 * rng.standard_normal(frames[0].shape).astype(np.float32) * m).astype(np.float32))
+    ga, gs = ev.EvConvNet(base), ev.EvConvNet(sp)
+    ga.reset(_dev(frames[0]))
+    gs.reset(_dev(frames[0]))
+    act_a = act_s = 0
+    for f in frames[1:]:
+        ga.step_frame(_dev(f))
+        gs.step_frame(_dev(f))
+        act_a += sum(ga.stats(i).n_active for i, nd in enumerate(base.nodes) if nd.op == wl.OP_CONV2D)
+        act_s += sum(gs.stats(i).n_active for i, nd in enumerate(sp.nodes) if nd.op == wl.OP_CONV2D)
+        for i, nd in enumerate(sp.nodes):
+            if nd.op != wl.OP_SPARSIFY:
+                continue
+            k = float(gs.state(i, ev.STATE_STEP)[0])
+            assert k > 0
+            d = gs.state(i, ev.STATE_Z)
+            assert d.min() >= -0.5 * k * (1 + 1e-5) and d.max() <= 0.5 * k * (1 + 1e-5), f"node {i}"
+            m = cmp.words_to_mask(gs.state(i, ev.STATE_OCC), *gs.shape(i)[1:]).astype(bool)
+            y = gs.state(i, ev.STATE_DY)[m]
+            if y.size:
+                assert np.abs(y / k - np.rint(y / k)).max() < 1e-3, f"node {i}: increments not multiples of k"
+    assert act_s < 0.8 * act_a, (act_s, act_a)
+    import torch
+    torch.cuda.synchronize()
+    ya = ga.outputs()[0]["y"].cpu().numpy()
+    ys = gs.outputs()[0]["y"].cpu().numpy()
+    assert 0 < np.abs(ya - ys).max() < 0.2          # sigmoid output in (0, 1)
+    gs.reset(_dev(frames[-1]))
+    ga.reset(_dev(frames[-1]))
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(ga.outputs()[0]["y"].cpu().numpy(), gs.outputs()[0]["y"].cpu().numpy())
+    ga.destroy()
+    gs.destroy()
