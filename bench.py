@@ -32,7 +32,7 @@ PEAKS = {  # MI355X published dense peaks
 
 # HBM bytes per launch of the dominant kernel family, from the committed rocprofv3 counter runs
 # (profiles/unet_depth_f32_incremental_kernels.md: FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00)
-TRAFFIC_FROM_PROFILE = {"conv_mfma_f32": 33.9e6}
+TRAFFIC_FROM_PROFILE = {"conv_mfma_f32": 38.3e6}
 
 
 def run_variant(args, np, torch, ev, wl, variant, frames, dframes, with_dense, with_layers):
@@ -114,6 +114,8 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=20)
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-second-variant", action="store_true")
+    ap.add_argument("--no-sparsified", action="store_true")
+    ap.add_argument("--sparsify-tp", type=float, default=0.1)
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run plain device-to-device copies of this size (for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings against a kernel of known traffic)")
@@ -167,6 +169,8 @@ def main():
         r2["weights"] = other
         r2["parity_bar"] = "2e-2 relative (Frobenius)" if other == "bf16" else "1e-4 max-abs"
         out[f"{other}_variant"] = r2
+    if not args.no_sparsified:
+        out["sparsified_variant"] = sparsified_leg(args, np, torch, ev, wl, dframes)
     if not args.no_cpu_baseline:
         from oracle.oracle import Oracle
         ora = Oracle(net)
@@ -181,6 +185,45 @@ def main():
                                "sample": f"first {k} frames of the same stream, fp64, OpenMP"}
     out["layers"] = res["layers"]
     print(json.dumps(out), flush=True)
+
+
+def sparsified_leg(args, np, torch, ev, wl, dframes):
+    """The same frames through the UNet with a sparsification layer ahead of every convolution
+    that reads a layer output (Eq.3-8; threshold parameter t_p, default 0.1, the paper's quoted
+    operating point).  Lossy: reports how far the output moved from the lossless run, and how
+    many convolution output sites were touched compared with it."""
+    H, W = 256, 352
+    n_frames = args.warmup + args.steps
+    res = {}
+    ys = {}
+    for tp in (0.0, args.sparsify_tp):
+        net = wl.net_unet_depth(1003, h=H, w=W, sparsify=True)
+        net.sparsify_tp = tp
+        g = ev.EvConvNet(net, device="cuda:0")
+        g.reset(dframes[0])
+        for i in range(1, args.warmup + 1):
+            g.step_frame(dframes[i])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.warmup + 1, n_frames + 1):
+            g.step_frame(dframes[i])
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        conv = [i for i, nd in enumerate(net.nodes) if nd.op == wl.OP_CONV2D]
+        touched = sum(g.stats(i).n_touched for i in conv)
+        sites = sum(g.stats(i).n_sites for i in conv)
+        ex = sum(g.stats(i).flops_executed for i in conv)
+        de = sum(g.stats(i).flops_dense for i in conv)
+        ys[tp] = g.outputs()[0]["y"].clone()
+        g.destroy()
+        res[tp] = dict(value=args.steps / dt, ms_per_step=dt / args.steps * 1e3, touched_site_fraction=touched / sites,
+                       tile_flop_fraction=ex / de)
+    a, b = res[0.0], res[args.sparsify_tp]
+    dev_out = float((ys[0.0] - ys[args.sparsify_tp]).abs().max())
+    return {"t_p": args.sparsify_tp, "value": b["value"], "unit": "steps/s", "ms_per_step": b["ms_per_step"],
+            "touched_site_fraction": b["touched_site_fraction"], "tile_flop_fraction": b["tile_flop_fraction"],
+            "with_t_p_0": a, "max_abs_output_deviation_from_lossless": dev_out,
+            "note": "random weights and unit-size input increments: few elements fall under k, see the text"}
 
 
 def density_sweep(args, np, torch, ev, wl, dev):

@@ -295,6 +295,25 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
     }
   }
 
+  // operands of the fused ADD stages, requested together now so that one memory latency covers
+  // all of them and the reduction below hides part of it
+  float f_skip[kMaxFusedAdds][EP_ITERS], f_zold[kMaxFusedAdds][EP_ITERS];
+#pragma unroll
+  for (int f = 0; f < kMaxFusedAdds; ++f) {
+#pragma unroll
+    for (int it = 0; it < EP_ITERS; ++it) {
+      f_skip[f][it] = 0.0f;
+      f_zold[f][it] = 0.0f;
+      if (f >= p.n_fused) continue;
+      const int site = r0 * 8 + it * EP_SITES + (tid >> 5);
+      if (!((site_word >> site) & 1ull)) continue;
+      const int oy = tile_y * 8 + (site >> 3), ox = tile_x * 8 + (site & 7);
+      const size_t q = ((size_t)oy * p.go.w + ox) * Cout + co0 + co;
+      if ((skip_word[f] >> site) & 1ull) f_skip[f][it] = p.fused[f].skip[q];
+      if (p.fused[f].keeps_z && !p.dense) f_zold[f][it] = p.fused[f].z[q];
+    }
+  }
+
   // ---- reduce the NW partial sums through LDS: slots [4][block*16 + reg][lane]
   auto spill = [&](float* part) {
 #pragma unroll
@@ -354,14 +373,13 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
     for (int f = 0; f < kMaxFusedAdds; ++f) {
       if (f >= p.n_fused) break;
       const FusedAdd& fa = p.fused[f];
-      const float vb = ((skip_word[f] >> site) & 1ull) ? fa.skip[q] : 0.0f;
-      const float lin = o + vb;
+      const float lin = o + f_skip[f][it];
       if (fa.keeps_z) {
         if (p.dense) {
           fa.z[q] = lin;
           o = act_m(fa.act, lin);
         } else {
-          const float z2_old = fa.z[q];
+          const float z2_old = f_zold[f][it];
           const float z2_new = z2_old + lin;
           fa.z[q] = z2_new;
           o = (fa.act == kActNone) ? lin : act_m(fa.act, z2_new) - act_m(fa.act, z2_old);
