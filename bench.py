@@ -229,7 +229,15 @@ def sparsified_leg(args, np, torch, ev, wl, dframes):
 def density_sweep(args, np, torch, ev, wl, dev):
     """Workload 5: where does incremental inference beat a dense recompute built from the same
     kernels?  One stream per density so that every timed step runs at that density."""
-    net = wl.net_flow(1005)
+    out = {"metric": "density sweep: incremental vs dense recompute (flow encoder-decoder 4x256x256 and its "
+                     "delayed-integration variant)",
+           "unit": "ms/step", "n_gpus": 1, "steps_per_density": args.sweep_steps, "dtype": "f32", "data": "synthetic"}
+    for key, net in (("rows", wl.net_flow(1005)), ("rows_delayed_integration", wl.net_flow_delayed(1006))):
+        out[key] = sweep_one(args, np, torch, ev, wl, dev, net)
+    print(json.dumps(out), flush=True)
+
+
+def sweep_one(args, np, torch, ev, wl, dev, net):
     rows = []
     for dens in np.geomspace(0.001, 0.2, 10):
         n = 5 + args.sweep_steps
@@ -256,9 +264,7 @@ def density_sweep(args, np, torch, ev, wl, dev):
         rows.append(dict(density=real, incremental_ms=t[ev.MODE_INCREMENTAL], dense_ms=t[ev.MODE_DENSE_RECOMPUTE],
                          speedup=t[ev.MODE_DENSE_RECOMPUTE] / t[ev.MODE_INCREMENTAL],
                          tile_flop_fraction=ex / de))
-    print(json.dumps({"metric": "density sweep: incremental vs dense recompute (flow encoder-decoder 4x256x256)",
-                      "unit": "ms/step", "n_gpus": 1, "steps_per_density": args.sweep_steps, "dtype": "f32",
-                      "data": "synthetic", "rows": rows}), flush=True)
+    return rows
 
 
 if __name__ == "__main__":

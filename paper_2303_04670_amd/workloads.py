@@ -245,6 +245,51 @@ def net_flow(seed=1005, h=256, w=256, width=64) -> Net:
     return b.finish()
 
 
+def net_flow_delayed(seed=1006, h=256, w=256, width=64, d_width=32) -> Net:
+    """Delayed-integration variant of the optical-flow encoder-decoder ("Mitigating Reduced
+    Sparsity on Upsampling"): same encoders and residual blocks as `net_flow`; a decoder no
+    longer receives the previous decoder's output, only its skip (the first one still gets the
+    bottleneck); every decoder output D and its 2-channel prediction P is upsampled to full
+    resolution, all are concatenated, and two convolutions produce the final prediction.
+
+    Own choices (the figures are not available): every decoder emits `d_width` channels so that
+    the full-resolution tensors stay small; the first of the two final convolutions (3x3 over
+    the concatenation of all D' and all P') is applied as two partial convolutions, over the D'
+    channels and over the P' channels, whose outputs are added before the ReLU - the same
+    function by linearity (Eq.9), and it keeps the wide part a multiple of 32 channels.
+    """
+    b = _NetBuilder("flow_delayed", 4, h, w, seed)
+    enc = []
+    x = -1
+    for i in range(4):
+        x = b.conv(x, width << i, 3, 2)
+        enc.append(x)
+    for _ in range(2):
+        r = b.conv(x, width << 3, 3)
+        r = b.conv(r, width << 3, 3, act=ACT_NONE)
+        x = b.simple(OP_ADD, x, r, act=ACT_RELU)
+    u = b.simple(OP_UPSAMPLE2X, x)
+    dec_in = [b.simple(OP_CONCAT, u, enc[2]), enc[1], enc[0], -1]   # resolutions 1/8, 1/4, 1/2, 1
+    d_full, p_full = [], []
+    for level, src in enumerate(dec_in):
+        d = b.conv(src, d_width, 3)
+        p = b.conv(d, 2, 1, 1, 0, ACT_NONE, out=1)
+        for _ in range(3 - level):
+            d = b.simple(OP_UPSAMPLE2X, d)
+            p = b.simple(OP_UPSAMPLE2X, p)
+        d_full.append(d)
+        p_full.append(p)
+    dc, pc = d_full[0], p_full[0]
+    for d, p in zip(d_full[1:], p_full[1:]):
+        dc = b.simple(OP_CONCAT, dc, d)
+        pc = b.simple(OP_CONCAT, pc, p)
+    fd = b.conv(dc, d_width, 3, act=ACT_NONE)
+    fp = b.conv(pc, d_width, 3, act=ACT_NONE)
+    f = b.simple(OP_ADD, fd, fp, act=ACT_RELU)
+    b.conv(f, 2, 1, 1, 0, ACT_NONE, out=1)
+    return b.finish()
+
+
 def net_random_small(seed, in_c=3, h=13, w=11, bias=True) -> Net:
     """A tiny graph touching every op, odd sizes, K in {1,3,5,7}, strides 1 and 2 (tests only)."""
     b = _NetBuilder("random_small", in_c, h, w, seed, bias=bias)

@@ -181,6 +181,15 @@ def test_flow_net_reduced_concat_upsample():
     run_stream(net, frames[0], frames[1:], "frame", label="flow-small", max_flips=8)
 
 
+def test_delayed_flow_net_reduced():
+    """Delayed-integration encoder-decoder: decoders fed by skips only, upsampled decoder outputs
+    and predictions concatenated at full resolution, two final convolutions."""
+    _say("delayed-integration flow net, reduced 4x64x96 width 8, all nodes every step")
+    net = wl.net_flow_delayed(1006, h=64, w=96, width=8, d_width=32)
+    frames = list(wl.stream_count_timestamp(1006, 64, 96, densities=[0.001, 0.01, 0.05, 0.2], steps_per=4))
+    run_stream(net, frames[0], frames[1:], "frame", label="delayed-small", max_flips=8)
+
+
 def test_resnet_reduced_pool_gap_linear():
     _say("ResNet-18-style classifier, reduced 2x64x64 width 8")
     net = wl.net_resnet18(1004, h=64, w=64, n_classes=11, width=8)
@@ -312,6 +321,15 @@ def test_workload5_flow_net_full_size_density_sweep():
     gen = wl.stream_count_timestamp(1005, 256, 256, densities=[0.001, 0.01, 0.05, 0.2], steps_per=4)
     x0 = next(gen)
     run_stream(net, x0, gen, "frame", check_nodes_at={1, 6, 11, 16}, label="w5", max_flips=64)
+
+
+@pytest.mark.timeout(600)
+def test_delayed_flow_net_full_size():
+    _say("delayed-integration flow net 4x256x256, densities 0.1 / 1 / 5 %, 4 steps each")
+    net = wl.net_flow_delayed()
+    gen = wl.stream_count_timestamp(1006, 256, 256, densities=[0.001, 0.01, 0.05], steps_per=4)
+    x0 = next(gen)
+    run_stream(net, x0, gen, "frame", check_nodes_at={1, 6, 11}, label="delayed-full", max_flips=64)
 
 
 @pytest.mark.timeout(900)

@@ -21,6 +21,7 @@ def small_nets():
         wl.net_unet_depth(13, h=16, w=24, width=4),
         wl.net_resnet18(14, h=40, w=40, n_classes=7, width=4),
         wl.net_flow(15, h=32, w=32, width=4),
+        wl.net_flow_delayed(16, h=32, w=48, width=4, d_width=4),
     ]
 
 
