@@ -40,6 +40,9 @@
 //     that both sides of a comparison use the identical step (the paper says "t_p times the L2
 //     norm of a rolling average of the input" without giving window or normalisation);
 //     k == 0 makes the layer the identity.
+//   * elementwise multiply (Eq.15-17) keeps the accumulated values of both inputs; the output
+//     increment uses the accumulators as they were before this step, then both are advanced;
+//     its mask is the OR of the input masks (Eq.16, structural, like addition).
 //
 // Parity pins live in tests/ (CPU, "not gpu"): dense ops against PyTorch CPU fp64 routines,
 // Eq.2 invariant against the dense pass, linearity, zero increment, tile independence,
@@ -55,8 +58,8 @@
 
 namespace {
 
-enum Op { OP_CONV = 0, OP_ADD, OP_CONCAT, OP_UP2X, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_ACT, OP_SPARSIFY };
-enum Act { ACT_NONE = 0, ACT_RELU, ACT_SIGMOID };
+enum Op { OP_CONV = 0, OP_ADD, OP_CONCAT, OP_UP2X, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_ACT, OP_SPARSIFY, OP_MUL };
+enum Act { ACT_NONE = 0, ACT_RELU, ACT_SIGMOID, ACT_TANH };
 
 struct NodeDesc {
   int op, act, in0, in1, c_in, c_out, k, stride, pad;
@@ -69,6 +72,7 @@ template <class T>
 T activate(int act, T v) {
   if (act == ACT_RELU) return v > T(0) ? v : T(0);
   if (act == ACT_SIGMOID) return T(1) / (T(1) + std::exp(-v));
+  if (act == ACT_TANH) return std::tanh(v);
   return v;
 }
 
@@ -89,6 +93,7 @@ template <class T>
 struct NodeState {
   Shape shp;                     // output shape
   std::vector<T> z;              // accumulated pre-activation / accumulated linear result
+  std::vector<T> z2;             // elementwise multiply: accumulated second input (z: the first)
   std::vector<T> pool_in;        // max-pool: accumulated input (input shape)
   std::vector<T> dy;             // this step's output increment, HWC, zero off the active set
   std::vector<uint8_t> active;   // value-pruned (or structural) active set S
@@ -160,6 +165,13 @@ struct Net {
           o = a;
           break;
         }
+        case OP_MUL: {
+          Shape b = shape_of(nd.in1);
+          if (b.c != a.c || b.h != a.h || b.w != a.w) return 4;
+          if (nd.act != ACT_NONE) return 3;
+          o = a;
+          break;
+        }
         case OP_ACT: o = a; break;
         case OP_SPARSIFY:
           if (nd.act != ACT_NONE) return 3;
@@ -188,12 +200,13 @@ struct Net {
       s.shp = o;
       s.keeps_z = (nd.op == OP_CONV || nd.op == OP_LINEAR || nd.op == OP_GAP || nd.op == OP_ACT ||
                    nd.op == OP_SPARSIFY || nd.act != ACT_NONE) && nd.op != OP_MAXPOOL;
-      s.structural = (nd.op == OP_ADD || nd.op == OP_CONCAT || nd.op == OP_UP2X || nd.op == OP_GAP) &&
-                     nd.act == ACT_NONE;
+      s.structural = (nd.op == OP_ADD || nd.op == OP_CONCAT || nd.op == OP_UP2X || nd.op == OP_GAP ||
+                      nd.op == OP_MUL) && nd.act == ACT_NONE;
       s.dy.assign(o.elems(), T(0));
       s.active.assign(o.sites(), 0);
       s.touched.assign(o.sites(), 0);
       if (s.keeps_z) s.z.assign(o.elems(), T(0));
+      if (nd.op == OP_MUL) { s.z.assign(o.elems(), T(0)); s.z2.assign(o.elems(), T(0)); }
       if (nd.op == OP_MAXPOOL) s.pool_in.assign(a.elems(), T(0));
       if (nd.is_output) s.y.assign(o.elems(), T(0));
       if (nd.op == OP_CONV || nd.op == OP_LINEAR) {
@@ -259,6 +272,11 @@ struct Net {
       case OP_ADD: {
         const std::vector<T>& xb = dense_of(nd.in1);
         for (size_t e = 0; e < o.elems(); ++e) s.dz[e] = xa[e] + xb[e];
+        break;
+      }
+      case OP_MUL: {
+        const std::vector<T>& xb = dense_of(nd.in1);
+        for (size_t e = 0; e < o.elems(); ++e) s.dz[e] = xa[e] * xb[e];
         break;
       }
       case OP_ACT: s.dz = xa; break;
@@ -337,6 +355,7 @@ struct Net {
           s.k = quantise_step(float(sparsify_tp * std::sqrt(sum / double(s.dz.size()))));
         }
       }
+      if (nodes[i].op == OP_MUL) { s.z = dense_of(nodes[i].in0); s.z2 = dense_of(nodes[i].in1); }
       if (nodes[i].op == OP_MAXPOOL) s.pool_in = dense_of(nodes[i].in0);
       if (nodes[i].is_output) s.y = s.da;
       std::fill(s.dy.begin(), s.dy.end(), T(0));
@@ -499,6 +518,22 @@ struct Net {
         }
         break;
       }
+      case OP_MUL: {  // Eq.15-17
+        const std::vector<T>& db = dy_of(nd.in1);
+        const std::vector<uint8_t>& sb = set_of(nd.in1);
+        for (size_t q = 0; q < o.sites(); ++q) {
+          s.touched[q] = sa[q] | sb[q];  // Eq.16
+          if (!s.touched[q]) continue;
+          for (int c = 0; c < o.c; ++c) {
+            const size_t e = q * o.c + c;
+            const T x1 = sa[q] ? da[e] : T(0), x2 = sb[q] ? db[e] : T(0);
+            v[e] = (s.z[e] + x1) * x2 + s.z2[e] * x1;  // Eq.15, accumulators of the previous step
+            s.z[e] += x1;                              // Eq.17
+            s.z2[e] += x2;
+          }
+        }
+        break;
+      }
       case OP_ACT:
         for (size_t q = 0; q < o.sites(); ++q) {
           s.touched[q] = sa[q];
@@ -624,7 +659,7 @@ void copy_out(const std::vector<T>& v, double* dst) {
 
 template <class T>
 long long get_tensor(Net<T>& n, int node, int kind, double* dst) {
-  // kind: 0 z, 1 dy, 2 y (outputs), 3 dense pre-activation, 4 dense value, 5 pool_in
+  // kind: 0 z, 1 dy, 2 y (outputs), 3 dense pre-activation, 4 dense value, 5 pool_in, 6 z2
   if (node < 0) {
     if (kind != 1) return -1;
     if (dst) copy_out(n.dx, dst);
@@ -639,6 +674,7 @@ long long get_tensor(Net<T>& n, int node, int kind, double* dst) {
     case 3: v = &s.dz; break;
     case 4: v = &s.da; break;
     case 5: v = &s.pool_in; break;
+    case 6: v = &s.z2; break;
     default: return -1;
   }
   if (dst) copy_out(*v, dst);

@@ -129,6 +129,7 @@ class Oracle:
         return out.reshape(h, w, c) if n else out
 
     def z(self, node): return self.tensor(node, KIND_Z)
+    def z2(self, node): return self.tensor(node, 6)   # elementwise multiply: accumulated second input
     def dy(self, node): return self.tensor(node, KIND_DY)
     def y(self, node): return self.tensor(node, KIND_Y)
     def dense_z(self, node): return self.tensor(node, KIND_DENSE_Z)

@@ -23,8 +23,9 @@ from typing import Iterator, List, Optional, Tuple
 import numpy as np
 
 # op / activation codes: plain data shared by both marshalling layers
-OP_CONV2D, OP_ADD, OP_CONCAT, OP_UPSAMPLE2X, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_ACT, OP_SPARSIFY = range(9)
-ACT_NONE, ACT_RELU, ACT_SIGMOID = range(3)
+(OP_CONV2D, OP_ADD, OP_CONCAT, OP_UPSAMPLE2X, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_ACT, OP_SPARSIFY,
+ OP_MUL) = range(10)
+ACT_NONE, ACT_RELU, ACT_SIGMOID, ACT_TANH = range(4)
 WD_F32, WD_BF16 = 0, 1
 
 
@@ -66,7 +67,7 @@ class Net:
                 ho = (h + 2 * nd.pad - nd.k) // nd.stride + 1
                 wo = (w + 2 * nd.pad - nd.k) // nd.stride + 1
                 out.append((nd.c_out if nd.op == OP_CONV2D else c, ho, wo))
-            elif nd.op in (OP_ADD, OP_ACT, OP_SPARSIFY):
+            elif nd.op in (OP_ADD, OP_ACT, OP_SPARSIFY, OP_MUL):
                 out.append((c, h, w))
             elif nd.op == OP_CONCAT:
                 c2, _, _ = shp(nd.in1)
@@ -287,6 +288,25 @@ def net_flow_delayed(seed=1006, h=256, w=256, width=64, d_width=32) -> Net:
     fp = b.conv(pc, d_width, 3, act=ACT_NONE)
     f = b.simple(OP_ADD, fd, fp, act=ACT_RELU)
     b.conv(f, 2, 1, 1, 0, ACT_NONE, out=1)
+    return b.finish()
+
+
+def net_gated(seed=1007, in_c=5, h=64, w=96, width=32, bias=False) -> Net:
+    """Gated convolution blocks: the gate structure of ConvLSTM / ConvGRU cells (a sigmoid gate
+    times a tanh candidate, an update gate blending the block input with the candidate), without
+    the recurrence.  Exercises the elementwise-multiply increment (Eq.15-17) with both operands
+    changing, one operand constant over a step, and a product of products."""
+    b = _NetBuilder("gated", in_c, h, w, seed, bias=bias)
+    x = b.conv(-1, width, 3)
+    for _ in range(2):
+        g = b.conv(x, width, 3, act=ACT_SIGMOID)          # gate in (0, 1)
+        c = b.conv(x, width, 3, act=ACT_TANH)             # candidate in (-1, 1)
+        gc = b.simple(OP_MUL, g, c)                       # g * c
+        u = b.conv(x, width, 1, 1, 0, act=ACT_SIGMOID)    # update gate
+        ux = b.simple(OP_MUL, u, x)                       # u * x
+        x = b.simple(OP_ADD, gc, ux, act=ACT_RELU)
+    sq = b.simple(OP_MUL, x, x)                           # both operands the same node
+    b.conv(sq, 2, 1, 1, 0, ACT_NONE, out=1)
     return b.finish()
 
 

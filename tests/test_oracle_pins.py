@@ -22,6 +22,7 @@ def small_nets():
         wl.net_resnet18(14, h=40, w=40, n_classes=7, width=4),
         wl.net_flow(15, h=32, w=32, width=4),
         wl.net_flow_delayed(16, h=32, w=48, width=4, d_width=4),
+        wl.net_gated(17, in_c=3, h=11, w=13, width=4, bias=True),
     ]
 
 

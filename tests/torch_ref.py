@@ -24,7 +24,9 @@ def torch_forward(net, x_chw, upto=None):
             z = F.conv2d(a, wt, b, stride=nd.stride, padding=nd.pad)
         elif nd.op == wl.OP_ADD:
             z = a + src(nd.in1)
-        elif nd.op == wl.OP_ACT:
+        elif nd.op == wl.OP_MUL:
+            z = a * src(nd.in1)
+        elif nd.op in (wl.OP_ACT, wl.OP_SPARSIFY):
             z = a
         elif nd.op == wl.OP_CONCAT:
             z = torch.cat([a, src(nd.in1)], dim=1)
@@ -41,6 +43,8 @@ def torch_forward(net, x_chw, upto=None):
             v = F.relu(z)
         elif nd.act == wl.ACT_SIGMOID:
             v = torch.sigmoid(z)
+        elif nd.act == wl.ACT_TANH:
+            v = torch.tanh(z)
         vals.append(v)
         outs.append((z[0].permute(1, 2, 0).numpy(), v[0].permute(1, 2, 0).numpy()))
     return outs
