@@ -30,12 +30,17 @@
  *                    reset), kept to 8 significant bits, or the fp32 value at weight_off when
  *                    weight_off >= 0; k == 0 is the identity.  In reset and in dense-recompute
  *                    mode the node is the identity.  Lossy: y no longer equals the forward pass.
+ *   MUL              elementwise product of two nodes of equal shape (Eq.15-17): keeps the
+ *                    accumulated values of both factors (states Z and Z2); y_inc = (x1acc + x1_inc)
+ *                    * x2_inc + x2acc * x1_inc with the accumulators of the previous step, each
+ *                    operation rounded once (no fused multiply-add); then both accumulators
+ *                    advance (Eq.17).  T = S_out = S_a | S_b (Eq.16).  act must be NONE.
  *   MAXPOOL          state a += x_inc; y_inc = max(window of a_new) - max(window of a_old) at
  *                    windows containing an active site; padding value -inf; act must be NONE.
  * A node keeps an accumulated tensor z (+= y_lin at T) if it is CONV2D, LINEAR,
  * GLOBAL_AVGPOOL, ACT, or has an activation.  With an activation theta_a the output is
  * y_inc = theta_a(z_new) - theta_a(z_old) (Eq.12), else y_inc = y_lin.
- * S_out is T for ADD / CONCAT / UPSAMPLE / GLOBAL_AVGPOOL without activation (Eq.11b), otherwise
+ * S_out is T for ADD / CONCAT / UPSAMPLE / GLOBAL_AVGPOOL / MUL without activation (Eq.11b), otherwise
  * the sites of T where some channel of y_inc is != 0 (-0 counts as zero, NaN as nonzero).
  * Output nodes additionally keep y += y_inc on S_out (Eq.2).
  */
@@ -73,10 +78,11 @@ typedef enum {
   EVCONV_OP_GLOBAL_AVGPOOL = 5,
   EVCONV_OP_LINEAR = 6,
   EVCONV_OP_ACT = 7,
-  EVCONV_OP_SPARSIFY = 8
+  EVCONV_OP_SPARSIFY = 8,
+  EVCONV_OP_MUL = 9
 } evconv_op;
 
-typedef enum { EVCONV_ACT_NONE = 0, EVCONV_ACT_RELU = 1, EVCONV_ACT_SIGMOID = 2 } evconv_act;
+typedef enum { EVCONV_ACT_NONE = 0, EVCONV_ACT_RELU = 1, EVCONV_ACT_SIGMOID = 2, EVCONV_ACT_TANH = 3 } evconv_act;
 
 /* dtype of the weights and of the increments inside the channel contraction; accumulation and
  * every cached tensor are always fp32 */
@@ -142,7 +148,8 @@ typedef enum {
   EVCONV_STATE_OCC = 5,         /* uint64 per tile: S_out, bit (y%8)*8 + x%8, tiles row-major */
   EVCONV_STATE_OCC_TOUCHED = 6, /* uint64 per tile: T */
   EVCONV_STATE_X_PREV = 7,      /* node -1 only: fp32 C x H x W cached previous frame */
-  EVCONV_STATE_STEP = 8         /* SPARSIFY nodes: one fp32, the rounding step k */
+  EVCONV_STATE_STEP = 8,        /* SPARSIFY nodes: one fp32, the rounding step k */
+  EVCONV_STATE_Z2 = 9           /* MUL nodes: fp32 H x W x C accumulated second factor (Z: the first) */
 } evconv_state_kind;
 
 /* Bytes of device workspace a net of this description needs.  No GPU work. */

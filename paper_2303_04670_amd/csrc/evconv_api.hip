@@ -41,6 +41,8 @@ struct NodePlan {
   int fused_nodes[kMaxFusedAdds] = {-1, -1};
   // workspace offsets (bytes); resolved to pointers at create
   size_t off_step = 0;      // SPARSIFY: device scalar k
+  size_t off_z2 = 0;        // MUL: accumulated second factor
+  float* z2 = nullptr;
   float* step = nullptr;
   float step_fixed = -1.0f; // >= 0: k supplied by the description
   size_t off_z = 0, off_out = 0, off_pool = 0, off_occ = 0, off_touched = 0, off_idx = 0, off_count = 0,
@@ -104,10 +106,10 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
     n.d = d;
     char where[64];
     snprintf(where, sizeof where, "node %d: ", i);
-    if (d.op < 0 || d.op > EVCONV_OP_SPARSIFY) return fail(err, EVCONV_ERR_INVALID_ARG, std::string(where) + "bad op");
-    if (d.act < 0 || d.act > EVCONV_ACT_SIGMOID) return fail(err, EVCONV_ERR_INVALID_ARG, std::string(where) + "bad act");
+    if (d.op < 0 || d.op > EVCONV_OP_MUL) return fail(err, EVCONV_ERR_INVALID_ARG, std::string(where) + "bad op");
+    if (d.act < 0 || d.act > EVCONV_ACT_TANH) return fail(err, EVCONV_ERR_INVALID_ARG, std::string(where) + "bad act");
     if (d.in0 < -1 || d.in0 >= i) return fail(err, EVCONV_ERR_BAD_DESC, std::string(where) + "in0 is not an earlier node");
-    const bool two = d.op == EVCONV_OP_ADD || d.op == EVCONV_OP_CONCAT;
+    const bool two = d.op == EVCONV_OP_ADD || d.op == EVCONV_OP_CONCAT || d.op == EVCONV_OP_MUL;
     if (two && (d.in1 < -1 || d.in1 >= i)) return fail(err, EVCONV_ERR_BAD_DESC, std::string(where) + "in1 is not an earlier node");
     n.ga = d.in0 < 0 ? L->gin : L->nodes[d.in0].go;
     n.gb = two ? (d.in1 < 0 ? L->gin : L->nodes[d.in1].go) : n.ga;
@@ -147,6 +149,10 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
       case EVCONV_OP_ADD:
         if (n.gb.c != c || n.gb.h != h || n.gb.w != w) return fail(err, EVCONV_ERR_SHAPE, std::string(where) + "ADD inputs differ in shape");
         break;
+      case EVCONV_OP_MUL:
+        if (n.gb.c != c || n.gb.h != h || n.gb.w != w) return fail(err, EVCONV_ERR_SHAPE, std::string(where) + "MUL inputs differ in shape");
+        if (d.act != EVCONV_ACT_NONE) return fail(err, EVCONV_ERR_UNSUPPORTED, std::string(where) + "MUL takes no activation");
+        break;
       case EVCONV_OP_CONCAT:
         if (n.gb.h != h || n.gb.w != w) return fail(err, EVCONV_ERR_SHAPE, std::string(where) + "CONCAT inputs differ in size");
         c += n.gb.c;
@@ -165,10 +171,10 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
     if (n.go.ty > L->max_ty) L->max_ty = n.go.ty;
     const bool lin = d.op == EVCONV_OP_CONV2D || d.op == EVCONV_OP_LINEAR;
     n.keeps_z = (lin || d.op == EVCONV_OP_GLOBAL_AVGPOOL || d.op == EVCONV_OP_ACT ||
-                 d.op == EVCONV_OP_SPARSIFY || d.act != EVCONV_ACT_NONE) &&
+                 d.op == EVCONV_OP_SPARSIFY || d.op == EVCONV_OP_MUL || d.act != EVCONV_ACT_NONE) &&
                 d.op != EVCONV_OP_MAXPOOL;
     n.structural = (d.op == EVCONV_OP_ADD || d.op == EVCONV_OP_CONCAT || d.op == EVCONV_OP_UPSAMPLE_BILINEAR2X ||
-                    d.op == EVCONV_OP_GLOBAL_AVGPOOL) && d.act == EVCONV_ACT_NONE;
+                    d.op == EVCONV_OP_GLOBAL_AVGPOOL || d.op == EVCONV_OP_MUL) && d.act == EVCONV_ACT_NONE;
     if (lin) {
       n.kernel = kKernConvValu;
       n.c_out_pad = (d.c_out + 31) / 32 * 32;
@@ -198,6 +204,7 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
     const size_t elems = (size_t)n.go.c * n.go.sites();
     if (n.keeps_z || n.d.op == EVCONV_OP_MAXPOOL) n.off_z = b.take(elems * 4);
     if (n.d.op == EVCONV_OP_SPARSIFY) n.off_step = b.take(4);
+    if (n.d.op == EVCONV_OP_MUL) n.off_z2 = b.take(elems * 4);
     if (n.d.op == EVCONV_OP_MAXPOOL) n.off_pool = b.take((size_t)n.ga.c * n.ga.sites() * 4);
     n.off_out = b.take(elems * 4);
     n.off_idx = b.take((size_t)n.go.sites() * 4);
@@ -268,7 +275,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
     const evconv_node_desc& d = n.d;
     const float* a = d.in0 < 0 ? net->dx : net->L.nodes[d.in0].out;
     const uint64_t* occ_a = d.in0 < 0 ? net->occ_in : net->L.nodes[d.in0].occ;
-    const bool two = d.op == EVCONV_OP_ADD || d.op == EVCONV_OP_CONCAT;
+    const bool two = d.op == EVCONV_OP_ADD || d.op == EVCONV_OP_CONCAT || d.op == EVCONV_OP_MUL;
     const float* bptr = two ? (d.in1 < 0 ? net->dx : net->L.nodes[d.in1].out) : nullptr;
     const uint64_t* occ_b = two ? (d.in1 < 0 ? net->occ_in : net->L.nodes[d.in1].occ) : nullptr;
     if (n.fused_into >= 0) {  // computed by the producing conv's epilogue
@@ -309,7 +316,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
       }
       case kKernElementwise: {
         EwParams p;
-        p.op = d.op == EVCONV_OP_ADD ? kEwAdd : d.op == EVCONV_OP_CONCAT ? kEwConcat :
+        p.op = d.op == EVCONV_OP_ADD ? kEwAdd : d.op == EVCONV_OP_CONCAT ? kEwConcat : d.op == EVCONV_OP_MUL ? kEwMul :
                d.op == EVCONV_OP_UPSAMPLE_BILINEAR2X ? kEwUp2x : d.op == EVCONV_OP_SPARSIFY ? kEwSparsify : kEwAct;
         p.step = n.step;
         if (d.op == EVCONV_OP_SPARSIFY && pass == kPassReset && n.step_fixed < 0.0f)
@@ -317,7 +324,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
           launch_rms_step(a, (size_t)n.ga.c * n.ga.sites(), net->sparsify_tp, net->rms_partial, n.step, s);
         p.act = d.act; p.dense = dense; p.keeps_z = n.keeps_z; p.structural = n.structural;
         p.ga = n.ga; p.gb = n.gb; p.go = n.go; p.a = a; p.occ_a = occ_a; p.b = bptr; p.occ_b = occ_b;
-        p.z = n.z; p.out = n.out; p.occ_out = n.occ; p.occ_touched = n.touched;
+        p.z = n.z; p.z2 = n.z2; p.out = n.out; p.occ_out = n.occ; p.occ_touched = n.touched;
         p.k = 1; p.stride = 1; p.pad = 0;
         launch_elementwise(p, s);
         break;
@@ -435,6 +442,7 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
       }
     }
     n.pool_in = n.d.op == EVCONV_OP_MAXPOOL ? (float*)(ws + n.off_pool) : nullptr;
+    n.z2 = n.d.op == EVCONV_OP_MUL ? (float*)(ws + n.off_z2) : nullptr;
     n.out = (float*)(ws + n.off_out);
     n.occ = (uint64_t*)(ws + n.off_occ);
     n.touched = (uint64_t*)(ws + n.off_touched);
@@ -595,6 +603,7 @@ evconv_status evconv_get_state(evconv_net* net, int32_t node, int32_t kind, void
     case EVCONV_STATE_OCC_TOUCHED: src = n ? n->touched : net->occ_in; need = (size_t)g.tiles() * 8; break;
     case EVCONV_STATE_X_PREV: src = n ? nullptr : net->x_prev; need = elems * 4; break;
     case EVCONV_STATE_STEP: src = n ? n->step : nullptr; need = 4; break;
+    case EVCONV_STATE_Z2: src = n ? n->z2 : nullptr; need = elems * 4; break;
     default: net->err = "bad state kind"; return EVCONV_ERR_INVALID_ARG;
   }
   if (!src) { net->err = "this node keeps no such state"; return EVCONV_ERR_INVALID_ARG; }

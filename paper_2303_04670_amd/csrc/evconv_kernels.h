@@ -25,7 +25,7 @@ inline Geo make_geo(int c, int h, int w) {
   return g;
 }
 
-enum Act { kActNone = 0, kActRelu = 1, kActSigmoid = 2 };
+enum Act { kActNone = 0, kActRelu = 1, kActSigmoid = 2, kActTanh = 3 };
 
 // ---- increment builder (Eq.1 + mask) ---------------------------------------------------
 enum BuilderMode { kBuildFrame = 0, kBuildIncrement = 1, kBuildReset = 2, kBuildIncrementDense = 3 };
@@ -81,13 +81,14 @@ bool conv_mfma_bf16_supported(const ConvParams& p);
 void launch_conv_mfma_bf16(const ConvParams& p, hipStream_t s);
 
 // ---- elementwise / structural increment operators ---------------------------------------
-enum EwOp { kEwAdd = 0, kEwAct, kEwConcat, kEwUp2x, kEwPoolAcc, kEwPoolMax, kEwSparsify };
+enum EwOp { kEwAdd = 0, kEwAct, kEwConcat, kEwUp2x, kEwPoolAcc, kEwPoolMax, kEwSparsify, kEwMul };
 struct EwParams {
   int op, act, dense, keeps_z, structural;
   Geo ga, gb, go;
   const float* a; const uint64_t* occ_a;
   const float* b; const uint64_t* occ_b;
   float* z;                 // accumulated tensor (pool: cached window max; pool-acc: pooled input)
+  float* z2;                // elementwise multiply: accumulated second factor (z: the first)
   float* out;
   uint64_t* occ_out; uint64_t* occ_touched;
   int k, stride, pad;       // pooling window

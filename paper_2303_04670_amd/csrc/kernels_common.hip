@@ -19,6 +19,7 @@ __device__ __forceinline__ bool occ_bit(const uint64_t* __restrict__ occ, int tx
 __device__ __forceinline__ float apply_act(int act, float v) {
   if (act == kActRelu) return fmaxf(v, 0.0f);
   if (act == kActSigmoid) return 1.0f / (1.0f + expf(-v));
+  if (act == kActTanh) return tanhf(v);
   return v;
 }
 
@@ -148,7 +149,7 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
     if (p.dense) {
       t = inb;
       wa = wb = ~0ull;
-    } else if (p.op == kEwAdd || p.op == kEwConcat) {
+    } else if (p.op == kEwAdd || p.op == kEwConcat || p.op == kEwMul) {
       wa = p.occ_a[tile];
       wb = p.occ_b[tile];
       t = ((wa | wb) >> tid) & 1ull;
@@ -201,8 +202,12 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
     const int oy = tile_y * 8 + (site >> 3), ox = tile_x * 8 + (site & 7);
     const size_t q = (size_t)oy * p.go.w + ox;
     const int c = v * VEC;
-    VecT<VEC> lin;
-    if (p.op == kEwAdd) {
+    VecT<VEC> lin, lin_b;
+    if (p.op == kEwMul) {  // the two factors' increments (full values in a regular forward pass)
+      const bool on_a = (wa >> site) & 1ull, on_b = (wb >> site) & 1ull;
+      lin = on_a ? ldv<VEC>(&p.a[q * C + c]) : zerov<VEC>();
+      lin_b = on_b ? ldv<VEC>(&p.b[q * C + c]) : zerov<VEC>();
+    } else if (p.op == kEwAdd) {
       const bool on_a = (wa >> site) & 1ull, on_b = (wb >> site) & 1ull;
       const VecT<VEC> va = on_a ? ldv<VEC>(&p.a[q * C + c]) : zerov<VEC>();
       const VecT<VEC> vb = on_b ? ldv<VEC>(&p.b[q * C + c]) : zerov<VEC>();
@@ -266,12 +271,37 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
     }
     VecT<VEC> o;
     bool nz = false;
-    if (p.op == kEwSparsify) {
+    if (p.op == kEwMul) {
+      // Eq.15-17: y_inc = (x1acc + x1_inc) * x2_inc + x2acc * x1_inc, then both accumulators
+      // advance.  Explicitly rounded operations: no fused multiply-add, so the result is the
+      // same single-rounded sequence on any implementation.
+      float* z2q = &p.z2[q * C + c];
+      if (p.dense) {
+        stv<VEC>(zq, lin);
+        stv<VEC>(z2q, lin_b);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) o.v[i] = lin.v[i] * lin_b.v[i];
+      } else {
+#pragma clang fp contract(off)
+        const VecT<VEC> a1 = ldv<VEC>(zq), a2 = ldv<VEC>(z2q);
+        VecT<VEC> n1, n2;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+          n1.v[i] = a1.v[i] + lin.v[i];
+          n2.v[i] = a2.v[i] + lin_b.v[i];
+          const float t1 = n1.v[i] * lin_b.v[i], t2 = a2.v[i] * lin.v[i];
+          o.v[i] = t1 + t2;
+        }
+        stv<VEC>(zq, n1);
+        stv<VEC>(z2q, n2);
+      }
+    } else if (p.op == kEwSparsify) {
       // Eq.3-8: x_corr = delta + x_inc; y_inc = k floor(0.5 + x_corr / k); delta = x_corr - y_inc
       const float k = p.dense ? 0.0f : *p.step;
       VecT<VEC> d_new = zerov<VEC>();
       o = lin;
       if (k > 0.0f) {
+#pragma clang fp contract(off)  // the residual is x_corr minus the rounded product, not a fused form
         const VecT<VEC> d_old = ldv<VEC>(zq);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) {

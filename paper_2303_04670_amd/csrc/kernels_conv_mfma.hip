@@ -45,6 +45,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 __device__ __forceinline__ float act_m(int act, float v) {
   if (act == kActRelu) return fmaxf(v, 0.0f);
   if (act == kActSigmoid) return 1.0f / (1.0f + expf(-v));
+  if (act == kActTanh) return tanhf(v);
   return v;
 }
 

@@ -22,7 +22,7 @@ STATUS_NAMES = ["OK", "ERR_INVALID_ARG", "ERR_BAD_DESC", "ERR_SHAPE", "ERR_STATE
 (ERR_INVALID_ARG, ERR_BAD_DESC, ERR_SHAPE, ERR_STATE, ERR_WORKSPACE, ERR_HIP, ERR_UNSUPPORTED) = range(1, 8)
 MODE_INCREMENTAL, MODE_DENSE_RECOMPUTE = 0, 1
 (STATE_Z, STATE_DY, STATE_IDX, STATE_COUNT, STATE_BITMAP, STATE_OCC, STATE_OCC_TOUCHED,
- STATE_X_PREV, STATE_STEP) = range(9)
+ STATE_X_PREV, STATE_STEP, STATE_Z2) = range(10)
 
 EXPORTS = ["evconv_query_workspace", "evconv_create", "evconv_num_outputs", "evconv_reset", "evconv_step",
            "evconv_step_frame", "evconv_destroy", "evconv_set_mode", "evconv_node_shape", "evconv_get_state",
@@ -193,7 +193,7 @@ class EvConvNet:
     def state(self, node, kind) -> np.ndarray:
         c, h, w = self.shape(node)
         tiles = (-(-h // 8)) * (-(-w // 8))
-        if kind in (STATE_Z, STATE_DY):
+        if kind in (STATE_Z, STATE_DY, STATE_Z2):
             a = np.empty((h, w, c), np.float32)
         elif kind == STATE_X_PREV:
             a = np.empty((c, h, w), np.float32)

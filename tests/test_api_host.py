@@ -58,6 +58,14 @@ def test_bad_descriptions_are_rejected():
     nodes[0].op = 42
     assert _status(desc) == ev.ERR_INVALID_ARG
     nodes[0].op = wl.OP_CONV2D
+    nodes[0].act = 4                       # one past tanh
+    assert _status(desc) == ev.ERR_INVALID_ARG
+    nodes[0].act = wl.ACT_TANH
+    assert _status(desc) == ev.OK
+    nodes[0].act = wl.ACT_RELU
+    nodes[3].op, nodes[3].in1 = wl.OP_MUL, 1       # 64 x 4 x 4 times 32 x 8 x 8
+    assert _status(desc) == ev.ERR_SHAPE
+    nodes[3].op, nodes[3].in1 = wl.OP_CONV2D, -2
     desc.sparsify_tp = -0.1
     assert _status(desc) == ev.ERR_INVALID_ARG
     desc.sparsify_tp = 0.0

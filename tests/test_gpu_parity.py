@@ -467,3 +467,46 @@ def test_sparsified_unet_properties_and_speed_of_convergence():
     np.testing.assert_array_equal(ga.outputs()[0]["y"].cpu().numpy(), gs.outputs()[0]["y"].cpu().numpy())
     ga.destroy()
     gs.destroy()
+
+
+# --------------------------------------------------------------------------- elementwise multiply
+
+def test_multiply_increment_bit_exact_against_fp32_oracle():
+    """Eq.15-17 as single-rounded binary32 operations: two 1x1 selector convolutions (exact: weights
+    1, 0 and 0, 3) feed the product, so its inputs are bit-identical on both sides and the product
+    increments, both accumulators and the OR-ed sets must match bit for bit."""
+    _say("bit-exact elementwise multiply against the binary32 oracle")
+    w = np.asarray([1.0, 0.0, 0.0, 3.0], np.float32)
+    nodes = [wl.Node(wl.OP_CONV2D, wl.ACT_NONE, -1, -2, 2, 1, 1, 1, 0, 0, -1, 0),
+             wl.Node(wl.OP_CONV2D, wl.ACT_NONE, -1, -2, 2, 1, 1, 1, 0, 2, -1, 0),
+             wl.Node(wl.OP_MUL, wl.ACT_NONE, 0, 1, 1, 1, 1, 1, 0, -1, -1, 1),
+             wl.Node(wl.OP_MUL, wl.ACT_NONE, 2, 2, 1, 1, 1, 1, 0, -1, -1, 1)]
+    net = wl.Net("mul_bits", 2, 21, 27, nodes, w)
+    rng = np.random.default_rng(8)
+    x0 = rng.standard_normal((2, 21, 27)).astype(np.float32)
+    frames, x = [], x0
+    for t in range(10):
+        m = rng.random((2, 21, 27)) < 0.2          # channels change independently
+        x = (x + rng.standard_normal(x.shape).astype(np.float32) * m).astype(np.float32)
+        frames.append(x)
+    run_stream(net, x0, frames, "frame", tol=0.0, exact_sets=True, fp32_oracle=True, label="mul-bits")
+    g, o = ev.EvConvNet(net), Oracle(net, fp32_state=True)
+    g.reset(_dev(x0))
+    o.reset(x0)
+    for f in frames[:4]:
+        g.step_frame(_dev(f))
+        o.step_frame(f)
+    for i in (2, 3):
+        np.testing.assert_array_equal(g.state(i, ev.STATE_Z2), o.z2(i).astype(np.float32))
+        np.testing.assert_array_equal(g.state(i, ev.STATE_Z), o.z(i).astype(np.float32))
+    g.destroy()
+
+
+@pytest.mark.parametrize("width,h,w", [(8, 37, 45), (32, 64, 96)])
+def test_gated_network_sigmoid_tanh_products(width, h, w):
+    """Gate structure of ConvLSTM / ConvGRU cells (sigmoid gate x tanh candidate, update gate x
+    block input, a square) against the fp64 oracle; width 32 runs the matrix-core convolutions."""
+    _say(f"gated network width {width} on 5x{h}x{w}: multiply increments, tanh, all nodes every step")
+    net = wl.net_gated(1007, in_c=5, h=h, w=w, width=width)
+    frames = list(wl.stream_voxel(1007, h, w, 12, 0.03, n_prim=6))
+    run_stream(net, frames[0], frames[1:], "frame", label=f"gated-{width}", max_flips=16)
