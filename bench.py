@@ -123,6 +123,12 @@ def main():
                     help="instead of the headline run: optical-flow encoder-decoder (4x256x256), incremental "
                          "vs dense recompute at 10 increment densities 0.1 % .. 20 %; prints one JSON line")
     ap.add_argument("--sweep-steps", type=int, default=30)
+    ap.add_argument("--drift", action="store_true",
+                    help="instead of the headline run: drift of the fp32 running sums over --drift-steps steps of "
+                         "the UNet stream, without refresh and with a refresh every --refresh-period steps, measured "
+                         "against a regular forward pass of the same frame; prints one JSON line")
+    ap.add_argument("--drift-steps", type=int, default=1000)
+    ap.add_argument("--refresh-period", type=int, default=100)
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (one event stream per device, no collectives); "
@@ -137,6 +143,8 @@ def main():
     dev = torch.device("cuda:0")
     if args.sweep:
         return density_sweep(args, np, torch, ev, wl, dev)
+    if args.drift:
+        return drift_study(args, np, torch, ev, wl, dev)
     H, W = 256, 352
     n_frames = args.warmup + args.steps
     frames = list(wl.stream_voxel(1003, H, W, n_frames, args.density))
@@ -224,6 +232,48 @@ def sparsified_leg(args, np, torch, ev, wl, dframes):
             "touched_site_fraction": b["touched_site_fraction"], "tile_flop_fraction": b["tile_flop_fraction"],
             "with_t_p_0": a, "max_abs_output_deviation_from_lossless": dev_out,
             "note": "random weights and unit-size input increments: few elements fall under k, see the text"}
+
+
+def drift_study(args, np, torch, ev, wl, dev):
+    """"Drift Errors": the accumulated tensors are fp32 running sums, so their difference from a
+    regular forward pass of the current frame grows with the number of steps since the last
+    refresh.  Three nets see the same frames: no refresh, a refresh every N steps, and a reference
+    that is reset (regular forward pass) at every checkpoint."""
+    H, W = 256, 352
+    net = wl.net_unet_depth(1003, h=H, w=W)
+    deep = max(i for i, nd in enumerate(net.nodes) if nd.op == wl.OP_CONV2D and nd.c_out > 1)
+    free, pol, ref = (ev.EvConvNet(net, device="cuda:0") for _ in range(3))
+    pol.set_refresh_period(args.refresh_period)
+    gen = wl.stream_voxel(1003, H, W, args.drift_steps, args.density)
+    x0 = torch.from_numpy(next(gen)).to(dev)
+    for g in (free, pol):
+        g.reset(x0)
+    checks = sorted({c for c in (1, 3, 10, 30, 99, 100, 101, 199, 300, 500, 999, 1000, 2000, 5000, 10000)
+                     if c <= args.drift_steps} | {args.drift_steps})
+    rows = []
+    t0 = time.perf_counter()
+    for t, f in enumerate(gen, 1):
+        x = torch.from_numpy(f).to(dev)
+        free.step_frame(x)
+        pol.step_frame(x)
+        if t in checks:
+            ref.reset(x)
+            torch.cuda.synchronize()
+            zr = ref.state(deep, ev.STATE_Z).astype(np.float64)
+            yr = ref.outputs()[0]["y"].double()
+            row = {"step": t}
+            for name, g in (("no_refresh", free), ("refresh_every_%d" % args.refresh_period, pol)):
+                z = g.state(deep, ev.STATE_Z).astype(np.float64)
+                row[name] = {"max_abs_z_error_rel": float(np.abs(z - zr).max() / np.abs(zr).max()),
+                             "max_abs_output_error": float((g.outputs()[0]["y"].double() - yr).abs().max())}
+            rows.append(row)
+            print(f"# step {t} ({time.perf_counter() - t0:.0f} s)", file=sys.stderr, flush=True)
+    for g in (free, pol, ref):
+        g.destroy()
+    print(json.dumps({"metric": "drift of the fp32 incremental state against a regular forward pass (UNet depth net)",
+                      "unit": "max-abs error (deepest wide conv's accumulated tensor relative to its max; output absolute)",
+                      "n_gpus": 1, "steps": args.drift_steps, "dtype": "f32", "data": "synthetic",
+                      "node": deep, "rows": rows}), flush=True)
 
 
 def density_sweep(args, np, torch, ev, wl, dev):

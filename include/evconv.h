@@ -186,6 +186,15 @@ evconv_status evconv_destroy(evconv_net* net);
 
 evconv_status evconv_set_mode(evconv_net* net, int32_t mode /* evconv_mode */);
 
+/* Refresh policy of "Drift Errors": with period N > 0 every N-th call of evconv_step /
+ * evconv_step_frame after a reset runs as a regular forward pass of x(n) that re-initialises
+ * every accumulated tensor (for a supplied increment, x(n) = cached frame + increment), which
+ * removes the rounding drift of the fp32 running sums (and the sparsification residuals).  The
+ * increments and lists of such a step are empty; y and dy are the forward pass values.  0 (the
+ * default) never refreshes; the count restarts at every reset and at every call of this
+ * function.  EVCONV_ERR_INVALID_ARG for a negative period. */
+evconv_status evconv_set_refresh_period(evconv_net* net, int32_t period);
+
 /* Shape (c, h, w) of a node's output; node -1 is the network input. */
 evconv_status evconv_node_shape(const evconv_net* net, int32_t node, int32_t* chw /* HOST[3] */);
 

@@ -236,6 +236,7 @@ struct evconv_net {
   char* ws = nullptr;
   hipStream_t stream = nullptr;
   int mode = EVCONV_MODE_INCREMENTAL;
+  int refresh_period = 0, since_refresh = 0;
   bool has_state = false;
   std::string err;
   std::vector<int> outputs;
@@ -531,6 +532,7 @@ evconv_status evconv_reset(evconv_net* net, const float* x0, evconv_out* out) {
   evconv_status st = run_pass(net, x0, kBuildReset, kPassReset);
   if (st != EVCONV_OK) return st;
   net->has_state = true;
+  net->since_refresh = 0;
   fill_outputs(net, out);
   return EVCONV_OK;
 }
@@ -540,12 +542,19 @@ static evconv_status step_common(evconv_net* net, const float* in, int builder_m
   if (!in) { net->err = "null input"; return EVCONV_ERR_INVALID_ARG; }
   if (!net->has_state) { net->err = "step before reset"; return EVCONV_ERR_STATE; }
   evconv_status st;
-  if (net->mode == EVCONV_MODE_DENSE_RECOMPUTE) {
+  const bool refresh = net->refresh_period > 0 && net->since_refresh + 1 >= net->refresh_period;
+  if (refresh) {
+    // "Drift Errors": every N-th step is a regular forward pass of x(n) that re-initialises every
+    // accumulated tensor (and the sparsification residuals and step sizes)
+    st = run_pass(net, in, builder_mode == kBuildFrame ? kBuildReset : kBuildIncrementDense, kPassReset);
+    net->since_refresh = 0;
+  } else if (net->mode == EVCONV_MODE_DENSE_RECOMPUTE) {
     // regular forward pass of x(n): the builder first folds the input into x_prev (and, for a
     // supplied increment, adds it), then the dense pass reads the updated frame
     st = run_pass(net, in, builder_mode == kBuildFrame ? kBuildReset : kBuildIncrementDense, kPassRecompute);
   } else {
     st = run_pass(net, in, builder_mode, kPassStep);
+    ++net->since_refresh;
   }
   if (st != EVCONV_OK) return st;
   fill_outputs(net, out);
@@ -575,6 +584,14 @@ evconv_status evconv_set_mode(evconv_net* net, int32_t mode) {
     return EVCONV_ERR_INVALID_ARG;
   }
   net->mode = mode;
+  return EVCONV_OK;
+}
+
+evconv_status evconv_set_refresh_period(evconv_net* net, int32_t period) {
+  if (!net) return EVCONV_ERR_INVALID_ARG;
+  if (period < 0) { net->err = "refresh period must be >= 0"; return EVCONV_ERR_INVALID_ARG; }
+  net->refresh_period = period;
+  net->since_refresh = 0;
   return EVCONV_OK;
 }
 

@@ -27,7 +27,7 @@ MODE_INCREMENTAL, MODE_DENSE_RECOMPUTE = 0, 1
 EXPORTS = ["evconv_query_workspace", "evconv_create", "evconv_num_outputs", "evconv_reset", "evconv_step",
            "evconv_step_frame", "evconv_destroy", "evconv_set_mode", "evconv_node_shape", "evconv_get_state",
            "evconv_get_stats", "evconv_node_kernel", "evconv_last_error", "evconv_profile_begin",
-           "evconv_profile_end", "evconv_get_node_time"]
+           "evconv_profile_end", "evconv_get_node_time", "evconv_set_refresh_period"]
 
 
 class NodeDesc(ctypes.Structure):
@@ -76,6 +76,7 @@ def lib() -> ctypes.CDLL:
         L.evconv_step_frame.argtypes = [vp, vp, ctypes.POINTER(Out)]
         L.evconv_destroy.argtypes = [vp]
         L.evconv_set_mode.argtypes = [vp, i32]
+        L.evconv_set_refresh_period.argtypes = [vp, i32]
         L.evconv_node_shape.argtypes = [vp, i32, ctypes.POINTER(i32)]
         L.evconv_get_state.argtypes = [vp, i32, i32, vp, ctypes.c_size_t]
         L.evconv_get_stats.argtypes = [vp, i32, ctypes.POINTER(LayerStats)]
@@ -183,6 +184,9 @@ class EvConvNet:
 
     def set_mode(self, mode):
         self._check(lib().evconv_set_mode(self._h, mode))
+
+    def set_refresh_period(self, period):
+        self._check(lib().evconv_set_refresh_period(self._h, int(period)))
 
     # ---- observability
     def shape(self, node):

@@ -510,3 +510,44 @@ def test_gated_network_sigmoid_tanh_products(width, h, w):
     net = wl.net_gated(1007, in_c=5, h=h, w=w, width=width)
     frames = list(wl.stream_voxel(1007, h, w, 12, 0.03, n_prim=6))
     run_stream(net, frames[0], frames[1:], "frame", label=f"gated-{width}", max_flips=16)
+
+
+# --------------------------------------------------------------------------- refresh policy
+
+@pytest.mark.parametrize("kind", ["frame", "increment"])
+def test_refresh_period_runs_a_regular_forward_pass_every_nth_step(kind):
+    """"Drift Errors": with period 3 the 3rd and 6th step are regular forward passes.  The net
+    with the policy must be bit-identical to one that is reset by hand at those steps, and equal
+    to the oracle's forward pass of the same frame."""
+    _say(f"refresh period 3, {kind} input")
+    net = wl.net_unet_depth(1003, h=32, w=48, width=8)
+    frames = list(wl.stream_voxel(5, 32, 48, 7, 0.05, n_prim=4))
+    a, b = ev.EvConvNet(net), ev.EvConvNet(net)
+    a.set_refresh_period(3)
+    a.reset(_dev(frames[0]))
+    b.reset(_dev(frames[0]))
+    ora = Oracle(net)
+    out = ora.outputs[0]
+    for t in range(1, 8):
+        inp = frames[t] if kind == "frame" else (frames[t] - frames[t - 1]).astype(np.float32)
+        (a.step_frame if kind == "frame" else a.step)(_dev(inp))
+        if t % 3 == 0:
+            cur = b.state(-1, ev.STATE_X_PREV) + inp if kind == "increment" else frames[t]
+            b.reset(_dev(cur.astype(np.float32)))
+        else:
+            (b.step_frame if kind == "frame" else b.step)(_dev(inp))
+        import torch
+        torch.cuda.synchronize()
+        ya, yb = a.outputs()[0]["y"].cpu().numpy(), b.outputs()[0]["y"].cpu().numpy()
+        np.testing.assert_array_equal(ya, yb, err_msg=f"step {t}")
+        for i in (3, 12, 18):
+            np.testing.assert_array_equal(a.state(i, ev.STATE_Z), b.state(i, ev.STATE_Z), err_msg=f"step {t} node {i}")
+        if t % 3 == 0:
+            assert a.site_list(-1).size == 0 and a.site_list(out).size == 0
+            ora.reset(a.state(-1, ev.STATE_X_PREV))
+            ref = np.transpose(ora.y(out), (2, 0, 1))
+            assert np.abs(ya - ref).max() <= TOL * np.abs(ref).max()
+    with pytest.raises(ev.EvConvError):
+        a.set_refresh_period(-1)
+    a.destroy()
+    b.destroy()
