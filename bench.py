@@ -28,6 +28,7 @@ PEAKS = {  # MI355X published dense peaks
     "conv_mfma_bf16": ("mfma", 2500.0, "TFLOP/s"),
     # vector ALU fp32: 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2 (packed) x 2.4 GHz
     "conv_valu_f32": ("alu", 157.3, "TFLOP/s"),
+    "conv_narrow_mfma_f32": ("mfma", 157.3, "TFLOP/s"),
 }
 
 # HBM bytes per launch of the dominant kernel family, from the committed rocprofv3 counter runs

@@ -18,9 +18,10 @@ namespace {
 
 thread_local std::string g_create_error;
 
-enum KernelKind { kKernConvValu = 0, kKernConvMfmaF32, kKernElementwise, kKernGap, kKernPool, kKernConvMfmaBf16 };
+enum KernelKind { kKernConvValu = 0, kKernConvMfmaF32, kKernElementwise, kKernGap, kKernPool, kKernConvMfmaBf16,
+                  kKernConvNarrow };
 const char* const kKernelNames[] = {"conv_valu_f32", "conv_mfma_f32", "elementwise", "global_avgpool",
-                                    "maxpool", "conv_mfma_bf16"};
+                                    "maxpool", "conv_mfma_bf16", "conv_narrow_mfma_f32"};
 
 // fp32 -> bf16 bits, round to nearest even
 uint16_t to_bf16(float x) {
@@ -212,7 +213,7 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
     n.off_bitmap = b.take(((size_t)n.go.tiles() + 63) / 64 * 8);
     if (n.d.op == EVCONV_OP_CONV2D || n.d.op == EVCONV_OP_LINEAR) {
       const int k = n.d.kh;
-      n.off_w = b.take((size_t)k * k * n.d.c_in * n.c_out_pad * 4);
+      n.off_w = b.take(((size_t)k * k * n.d.c_in + 16) * n.c_out_pad * 4);  // room for a padded contraction
       if (n.d.bias_off >= 0) n.off_bias = b.take((size_t)n.d.c_out * 4);
     }
     if (n.d.is_output) {
@@ -292,6 +293,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
     if (timed) (void)hipEventRecord(net->prof_ev[2 * net->prof_node.size()], s);
     switch (n.kernel) {
       case kKernConvValu:
+      case kKernConvNarrow:
       case kKernConvMfmaBf16:
       case kKernConvMfmaF32: {
         ConvParams p;
@@ -312,6 +314,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
         }
         if (n.kernel == kKernConvMfmaF32) launch_conv_mfma_f32(p, s);
         else if (n.kernel == kKernConvMfmaBf16) launch_conv_mfma_bf16(p, s);
+        else if (n.kernel == kKernConvNarrow) launch_conv_narrow(p, s);
         else launch_conv_valu(p, s);
         break;
       }
@@ -460,12 +463,29 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
       const int k = n.d.kh, ci_n = n.d.c_in, co_n = n.d.c_out, cop = n.c_out_pad;
       ConvParams probe;
       probe.gi = n.ga; probe.go = n.go; probe.k = k; probe.stride = n.d.stride; probe.c_out_pad = cop;
+      probe.n_fused = 0;
       const bool force_valu = getenv("EVCONV_FORCE_VALU") != nullptr;
       if (!force_valu && n.d.wdtype == EVCONV_F32 && conv_mfma_f32_supported(probe)) n.kernel = kKernConvMfmaF32;
       if (!force_valu && n.d.wdtype == EVCONV_BF16 && conv_mfma_bf16_supported(probe)) n.kernel = kKernConvMfmaBf16;
+      if (!force_valu && n.kernel == kKernConvValu && conv_narrow_supported(probe)) n.kernel = kKernConvNarrow;
       const float* src = (const float*)((const char*)weights + n.d.weight_off);
-      staging.assign((size_t)k * k * ci_n * cop, 0.0f);
-      if (n.kernel == kKernConvMfmaBf16) {
+      staging.assign(((size_t)k * k * ci_n + 16) * cop, 0.0f);
+      if (n.kernel == kKernConvNarrow) {
+        // flattened contraction [KP][c_out], k = tap * c_in + ci, zero rows beyond taps * c_in;
+        // bf16-declared weights are rounded to bf16 and widened again
+        const int kp = conv_narrow_padded_k(k * k * ci_n);
+        staging.resize((size_t)kp * co_n);
+        for (int co = 0; co < co_n; ++co)
+          for (int ci = 0; ci < ci_n; ++ci)
+            for (int t = 0; t < k * k; ++t) {
+              float w = src[((size_t)co * ci_n + ci) * k * k + t];
+              if (n.d.wdtype == EVCONV_BF16) {
+                const uint32_t u = (uint32_t)to_bf16(w) << 16;
+                memcpy(&w, &u, 4);
+              }
+              staging[((size_t)t * ci_n + ci) * co_n + co] = w;
+            }
+      } else if (n.kernel == kKernConvMfmaBf16) {
         // bf16 matrix-core layout [tap][c_in/8][c_out][8]: a lane's 8 input channels are 16 bytes
         uint16_t* h16 = (uint16_t*)staging.data();
         for (int co = 0; co < co_n; ++co)

@@ -103,7 +103,7 @@ def test_unet_full_width_reduced_size_matrix_core_layers():
     g = ev.EvConvNet(net)
     names = [g.kernel_name(i) for i in range(len(net.nodes))]
     g.destroy()
-    assert names.count("conv_mfma_f32") == 10 and names[0] == "conv_valu_f32", names
+    assert names.count("conv_mfma_f32") == 10 and names[0] == "conv_narrow_mfma_f32" and names[-1] == "conv_valu_f32", names
     assert names.count("fused_into_conv_epilogue") == 6, names   # 2 residual adds + 4 skip adds
     frames = list(wl.stream_voxel(1003, 64, 96, 20, 0.02, n_prim=6))
     run_stream(net, frames[0], frames[1:], "frame", label="unet-wide", max_flips=40)
