@@ -26,6 +26,8 @@ if ROOT not in sys.path:
 PEAKS = {  # MI355X published dense peaks
     "conv_mfma_f32": ("mfma", 157.3, "TFLOP/s"),
     "conv_mfma_bf16": ("mfma", 2500.0, "TFLOP/s"),
+    # three bf16 MFMAs per fp32 product: executed flops = 3 x algorithmic, priced against the bf16 peak
+    "conv_mfma_f32_split_bf16x3": ("mfma", 2500.0, "TFLOP/s"),
     # vector ALU fp32: 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2 (packed) x 2.4 GHz
     "conv_valu_f32": ("alu", 157.3, "TFLOP/s"),
     "conv_narrow_mfma_f32": ("mfma", 157.3, "TFLOP/s"),
@@ -39,6 +41,8 @@ TRAFFIC_FROM_PROFILE = {"conv_mfma_f32": 38.3e6}
 def run_variant(args, np, torch, ev, wl, variant, frames, dframes, with_dense, with_layers):
     H, W = 256, 352
     net = wl.net_unet_depth(1003, h=H, w=W, bf16=(variant == "bf16"))
+    if variant == "f32_split":
+        net = wl.with_weight_dtype(net, wl.WD_F32_SPLIT)
     n_frames = args.warmup + args.steps
 
     def timed_run(mode, profile):
@@ -110,7 +114,8 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--density", type=float, default=0.02)
-    ap.add_argument("--variant", choices=["f32", "bf16"], default="f32", help="weights of the headline run")
+    ap.add_argument("--variant", choices=["f32", "bf16", "f32_split"], default="f32",
+                    help="contraction of the headline run: fp32 MFMA, bf16 weights, or fp32 through bf16 high/low parts")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=20)
     ap.add_argument("--no-dense", action="store_true")
@@ -172,12 +177,14 @@ def main():
     if "dense_recompute" in res:
         out["dense_recompute"] = res["dense_recompute"]
     if not args.no_second_variant:
-        other = "bf16" if args.variant == "f32" else "f32"
-        _, r2 = run_variant(args, np, torch, ev, wl, other, frames, dframes, not args.no_dense, False)
-        r2["unit"] = "steps/s"
-        r2["weights"] = other
-        r2["parity_bar"] = "2e-2 relative (Frobenius)" if other == "bf16" else "1e-4 max-abs"
-        out[f"{other}_variant"] = r2
+        for other in ("f32", "f32_split", "bf16"):
+            if other == args.variant:
+                continue
+            _, r2 = run_variant(args, np, torch, ev, wl, other, frames, dframes, not args.no_dense, False)
+            r2["unit"] = "steps/s"
+            r2["weights"] = other
+            r2["parity_bar"] = "2e-2 relative (Frobenius)" if other == "bf16" else "1e-4 max-abs"
+            out[f"{other}_variant"] = r2
     if not args.no_sparsified:
         out["sparsified_variant"] = sparsified_leg(args, np, torch, ev, wl, dframes)
     if not args.no_cpu_baseline:

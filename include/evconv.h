@@ -85,8 +85,16 @@ typedef enum {
 typedef enum { EVCONV_ACT_NONE = 0, EVCONV_ACT_RELU = 1, EVCONV_ACT_SIGMOID = 2, EVCONV_ACT_TANH = 3 } evconv_act;
 
 /* dtype of the weights and of the increments inside the channel contraction; accumulation and
- * every cached tensor are always fp32 */
-typedef enum { EVCONV_F32 = 0, EVCONV_BF16 = 1 } evconv_dtype;
+ * every cached tensor are always fp32.
+ *   EVCONV_F32        fp32 operands on the fp32 matrix-core (or vector) path.
+ *   EVCONV_BF16       weights rounded to bf16 at create, increments rounded to bf16 inside the
+ *                     contraction: relative error of a product about 2^-8.
+ *   EVCONV_F32_SPLIT  fp32 weights and increments, each written as bf16 high part + bf16 low part
+ *                     (16 significant bits together); a product is lo*hi + hi*lo + hi*hi on the bf16
+ *                     matrix cores with fp32 accumulation: relative error of a product about 2^-16.
+ *                     Meets the fp32 parity bar of this library's tests at several times the speed
+ *                     of EVCONV_F32; layers the matrix-core kernel does not take run as EVCONV_F32. */
+typedef enum { EVCONV_F32 = 0, EVCONV_BF16 = 1, EVCONV_F32_SPLIT = 2 } evconv_dtype;
 
 typedef enum {
   EVCONV_MODE_INCREMENTAL = 0,    /* the paper's method */

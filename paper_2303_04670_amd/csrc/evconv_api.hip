@@ -19,9 +19,9 @@ namespace {
 thread_local std::string g_create_error;
 
 enum KernelKind { kKernConvValu = 0, kKernConvMfmaF32, kKernElementwise, kKernGap, kKernPool, kKernConvMfmaBf16,
-                  kKernConvNarrow };
+                  kKernConvNarrow, kKernConvMfmaSplit };
 const char* const kKernelNames[] = {"conv_valu_f32", "conv_mfma_f32", "elementwise", "global_avgpool",
-                                    "maxpool", "conv_mfma_bf16", "conv_narrow_mfma_f32"};
+                                    "maxpool", "conv_mfma_bf16", "conv_narrow_mfma_f32", "conv_mfma_f32_split_bf16x3"};
 
 // fp32 -> bf16 bits, round to nearest even
 uint16_t to_bf16(float x) {
@@ -134,7 +134,7 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
         } else {
           if (d.c_in != c) return fail(err, EVCONV_ERR_SHAPE, std::string(where) + "c_in does not match the input node");
           if (d.c_out <= 0) return fail(err, EVCONV_ERR_SHAPE, std::string(where) + "c_out must be positive");
-          if (d.wdtype != EVCONV_F32 && d.wdtype != EVCONV_BF16) return fail(err, EVCONV_ERR_INVALID_ARG, std::string(where) + "bad wdtype");
+          if (d.wdtype != EVCONV_F32 && d.wdtype != EVCONV_BF16 && d.wdtype != EVCONV_F32_SPLIT) return fail(err, EVCONV_ERR_INVALID_ARG, std::string(where) + "bad wdtype");
           const size_t wb = (size_t)d.c_out * d.c_in * k * k * sizeof(float);
           if (d.weight_off < 0 || (d.weight_off & 3)) return fail(err, EVCONV_ERR_BAD_DESC, std::string(where) + "bad weight_off");
           if (check_weights && (size_t)d.weight_off + wb > weight_bytes) return fail(err, EVCONV_ERR_BAD_DESC, std::string(where) + "weights out of range");
@@ -294,6 +294,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
     switch (n.kernel) {
       case kKernConvValu:
       case kKernConvNarrow:
+      case kKernConvMfmaSplit:
       case kKernConvMfmaBf16:
       case kKernConvMfmaF32: {
         ConvParams p;
@@ -315,6 +316,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
         if (n.kernel == kKernConvMfmaF32) launch_conv_mfma_f32(p, s);
         else if (n.kernel == kKernConvMfmaBf16) launch_conv_mfma_bf16(p, s);
         else if (n.kernel == kKernConvNarrow) launch_conv_narrow(p, s);
+        else if (n.kernel == kKernConvMfmaSplit) launch_conv_mfma_split(p, s);
         else launch_conv_valu(p, s);
         break;
       }
@@ -467,6 +469,7 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
       const bool force_valu = getenv("EVCONV_FORCE_VALU") != nullptr;
       if (!force_valu && n.d.wdtype == EVCONV_F32 && conv_mfma_f32_supported(probe)) n.kernel = kKernConvMfmaF32;
       if (!force_valu && n.d.wdtype == EVCONV_BF16 && conv_mfma_bf16_supported(probe)) n.kernel = kKernConvMfmaBf16;
+      if (!force_valu && n.d.wdtype == EVCONV_F32_SPLIT && conv_mfma_split_supported(probe)) n.kernel = kKernConvMfmaSplit;
       if (!force_valu && n.kernel == kKernConvValu && conv_narrow_supported(probe)) n.kernel = kKernConvNarrow;
       const float* src = (const float*)((const char*)weights + n.d.weight_off);
       staging.assign(((size_t)k * k * ci_n + 16) * cop, 0.0f);
@@ -484,6 +487,22 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
                 memcpy(&w, &u, 4);
               }
               staging[((size_t)t * ci_n + ci) * co_n + co] = w;
+            }
+      } else if (n.kernel == kKernConvMfmaSplit) {
+        // two bf16 planes [tap][c_in/8][c_out][8]: hi = bf16(w), then lo = bf16(w - hi)
+        uint16_t* h16 = (uint16_t*)staging.data();
+        const size_t plane = (size_t)k * k * ci_n * cop;
+        for (int co = 0; co < co_n; ++co)
+          for (int ci = 0; ci < ci_n; ++ci)
+            for (int t = 0; t < k * k; ++t) {
+              const float w = src[((size_t)co * ci_n + ci) * k * k + t];
+              const uint16_t hi = to_bf16(w);
+              float hf;
+              const uint32_t hu = (uint32_t)hi << 16;
+              memcpy(&hf, &hu, 4);
+              const size_t at = (((size_t)t * (ci_n / 8) + ci / 8) * cop + co) * 8 + (ci & 7);
+              h16[at] = hi;
+              h16[plane + at] = to_bf16(w - hf);
             }
       } else if (n.kernel == kKernConvMfmaBf16) {
         // bf16 matrix-core layout [tap][c_in/8][c_out][8]: a lane's 8 input channels are 16 bytes
@@ -532,7 +551,8 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
       if (later < 0 || later == other) continue;
       const int host = L.nodes[later].fused_into >= 0 ? L.nodes[later].fused_into : later;
       NodePlan& c_node = L.nodes[host];
-      if ((c_node.kernel != kKernConvMfmaF32 && c_node.kernel != kKernConvMfmaBf16) ||
+      if ((c_node.kernel != kKernConvMfmaF32 && c_node.kernel != kKernConvMfmaBf16 &&
+           c_node.kernel != kKernConvMfmaSplit) ||
           c_node.n_fused >= kMaxFusedAdds) continue;
       if (host != later && c_node.fused_nodes[c_node.n_fused - 1] != later) continue;  // chain must be contiguous
       if (other >= host) continue;  // the other input must exist before the conv runs

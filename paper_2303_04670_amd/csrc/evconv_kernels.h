@@ -79,6 +79,9 @@ void launch_conv_mfma_f32(const ConvParams& p, hipStream_t s);
 // bf16 MFMA variant (increments rounded to bf16 in the gather, bf16 weights, fp32 accumulation)
 bool conv_mfma_bf16_supported(const ConvParams& p);
 void launch_conv_mfma_bf16(const ConvParams& p, hipStream_t s);
+// fp32 operands contracted as bf16 high/low parts (three bf16 MFMAs per product)
+bool conv_mfma_split_supported(const ConvParams& p);
+void launch_conv_mfma_split(const ConvParams& p, hipStream_t s);
 // narrow-input variant: taps * c_in <= 128, c_out % 32 == 0; weights [padded k][c_out] fp32
 bool conv_narrow_supported(const ConvParams& p);
 int conv_narrow_padded_k(int k_tot);

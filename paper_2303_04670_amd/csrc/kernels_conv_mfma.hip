@@ -5,12 +5,18 @@
 // tile as two 32-row MFMA blocks, rows 0-3 and 4-7; MB = 1: one workgroup per half tile),
 // N = 32 output channels per workgroup, K = taps x c_in.
 //
-//   BF16 = false: fp32 operands, v_mfma_f32_32x32x2_f32; a unit = one tap x 8 channels (4 MFMA
-//                 steps per block); MFMA j of a unit contracts channels {j, 4+j}: lanes 0-31 hold
-//                 channel j, lanes 32-63 channel 4+j, for both operands.
-//   BF16 = true : the gather rounds increments to bf16 on their way into LDS, weights are bf16,
-//                 v_mfma_f32_32x32x16_bf16 with fp32 accumulation; a unit = one tap x 16 channels
-//                 (one MFMA per block); lanes 0-31 hold channels 0-7, lanes 32-63 channels 8-15.
+//   fp32 mode : fp32 operands, v_mfma_f32_32x32x2_f32; a unit = one tap x 8 channels (4 MFMA
+//               steps per block); MFMA j of a unit contracts channels {j, 4+j}: lanes 0-31 hold
+//               channel j, lanes 32-63 channel 4+j, for both operands.
+//   bf16 mode : the gather rounds increments to bf16 on their way into LDS, weights are bf16,
+//               v_mfma_f32_32x32x16_bf16 with fp32 accumulation; a unit = one tap x 16 channels
+//               (one MFMA per block); lanes 0-31 hold channels 0-7, lanes 32-63 channels 8-15.
+//   split mode: fp32 accuracy from the bf16 matrix cores.  Each fp32 operand is written as
+//               hi + lo with hi = bf16(x), lo = bf16(x - hi) (16 significant bits together); the
+//               gather does that for the increments, the host for the weights; a product is
+//               lo*hi + hi*lo + hi*hi, three bf16 MFMAs with fp32 accumulation (relative error of
+//               a product about 2^-16, against 2^-8 in bf16 mode).  16 times the fp32 MFMA rate
+//               at 3 MFMAs per product.
 //
 // Workgroup = NW (4 or 8) wavefronts that split K: the units of every channel chunk are dealt
 // round-robin to the waves; each wave keeps the MB accumulators and the partial sums are added
@@ -42,6 +48,14 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
+// operand modes of the contraction
+constexpr int kOpF32 = 0;    // fp32 operands, v_mfma_f32_32x32x2_f32
+constexpr int kOpBf16 = 1;   // bf16 operands (increments rounded in the gather), v_mfma_f32_32x32x16_bf16
+constexpr int kOpSplit = 2;  // fp32 operands split into bf16 high + low parts, three bf16 MFMAs per product
+
+// one weight fragment of a lane; .l is the low-part plane in split mode, unused otherwise
+struct BFrag { float4 h, l; };
+
 __device__ __forceinline__ float act_m(int act, float v) {
   if (act == kActRelu) return fmaxf(v, 0.0f);
   if (act == kActSigmoid) return 1.0f / (1.0f + expf(-v));
@@ -64,11 +78,15 @@ constexpr int max_patch_sites(int chunk, int mb) {
   return chunk == 64 ? (rows + 3) * 10 : chunk == 32 ? (rows + 7) * 14 : (rows * 2 + 7) * 21;
 }
 
-template <int CHUNK, int NW, bool BF16, int MB>
+template <int CHUNK, int NW, int OPM, int MB>
 __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
+  constexpr bool BF16 = OPM != kOpF32;     // bf16 MFMA, 16 channels per unit
+  constexpr bool SPLIT = OPM == kOpSplit;  // operands as bf16 high + low parts, three products
   constexpr int NT = NW * 64;
-  // LDS site stride in 4-byte words; stride / 4 is odd => conflict-free ds_read_b128
-  constexpr int CS = BF16 ? CHUNK / 2 + 4 : CHUNK + 4;
+  // LDS site stride in 4-byte words; stride / 4 is odd => conflict-free ds_read_b128.  Split
+  // mode keeps a high plane and a low plane of CHUNK bf16 each per site.
+  constexpr int CS = (BF16 && !SPLIT) ? CHUNK / 2 + 4 : CHUNK + 4;
+  constexpr int LO = CHUNK / 2;  // word offset of the low plane inside a site (split mode)
   constexpr int UCH = BF16 ? 16 : 8;  // channels per unit
   constexpr int KG = CHUNK / UCH;     // units per tap and chunk
   constexpr int NV = CHUNK / 4;       // float4 per patch site
@@ -198,7 +216,17 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
 #pragma unroll
     for (int j = 0; j < MAXV; ++j)
       if (lds_off[j] >= 0) {
-        if (BF16) {
+        if (SPLIT) {
+          // x = hi + lo + O(2^-17 |x|): hi = bf16(x), lo = bf16(x - hi)
+          const float4 x = pre[j];
+          uint2 h, l;
+          h.x = pack_bf16x2(x.x, x.y);
+          h.y = pack_bf16x2(x.z, x.w);
+          l.x = pack_bf16x2(x.x - __uint_as_float(h.x << 16), x.y - __uint_as_float(h.x & 0xffff0000u));
+          l.y = pack_bf16x2(x.z - __uint_as_float(h.y << 16), x.w - __uint_as_float(h.y & 0xffff0000u));
+          *(uint2*)&s_mem[lds_off[j]] = h;
+          *(uint2*)&s_mem[lds_off[j] + LO] = l;
+        } else if (BF16) {
           uint2 w;
           w.x = pack_bf16x2(pre[j].x, pre[j].y);
           w.y = pack_bf16x2(pre[j].z, pre[j].w);
@@ -240,11 +268,38 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
     const int ky = (tap * k_magic) >> 16, kx = tap - ky * K;
     return a_lane_off + (ky * PW + kx) * CS + kg * 8;  // 8 words = 8 floats or 16 bf16
   };
-  auto unit = [&](int j, const float4& b) {
+  // split mode: the low-part weight plane follows the high-part plane
+  const size_t w_plane = SPLIT ? (size_t)K * K * cin_rows * cop : 0;
+  auto b_load = [&](int c0, int j) {
+    BFrag f;
+    const float4* q = b_ptr(c0, j);
+    f.h = *q;
+    f.l = SPLIT ? q[w_plane] : f.h;
+    return f;
+  };
+  auto unit = [&](int j, const BFrag& bf) {
+    const float4& b = bf.h;
     const float* ap = &s_mem[a_off(j)];
     const float4 a0 = *(const float4*)ap;
     float4 a1 = a0;
     if (MB == 2) a1 = *(const float4*)(ap + a_blk1);
+    if (SPLIT) {
+      // a * b ~ a_lo * b_hi + a_hi * b_lo + a_hi * b_hi (the low x low term, 2^-16 smaller, is dropped)
+      const bf16x8 bh = __builtin_bit_cast(bf16x8, bf.h), bl = __builtin_bit_cast(bf16x8, bf.l);
+      const bf16x8 a0h = __builtin_bit_cast(bf16x8, a0);
+      const bf16x8 a0l = __builtin_bit_cast(bf16x8, *(const float4*)(ap + LO));
+      acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0l, bh, acc0, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, bl, acc0, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, bh, acc0, 0, 0, 0);
+      if (MB == 2) {
+        const bf16x8 a1h = __builtin_bit_cast(bf16x8, a1);
+        const bf16x8 a1l = __builtin_bit_cast(bf16x8, *(const float4*)(ap + a_blk1 + LO));
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1l, bh, acc1, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, bl, acc1, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, bh, acc1, 0, 0, 0);
+      }
+      return;
+    }
     if (BF16) {
       const bf16x8 bb = __builtin_bit_cast(bf16x8, b);
       acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a0), bb, acc0, 0, 0, 0);
@@ -264,12 +319,15 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
   // Ring of three weight fragments, two units of look-ahead, no register copies: vector loads
   // complete in order, so each wait only covers loads issued two units earlier.  The first two
   // fragments of a chunk are requested before the barriers that precede it.
-  float4 bq0 = make_float4(0.f, 0.f, 0.f, 0.f), bq1 = bq0, bq2 = bq0;
+  BFrag bq0, bq1, bq2;
+  bq0.h = bq0.l = make_float4(0.f, 0.f, 0.f, 0.f);
+  bq1 = bq0;
+  bq2 = bq0;
   if (conv_on) {
     fetch(0);
     if (n_mine > 0) {
-      bq0 = *b_ptr(0, 0);
-      bq1 = *b_ptr(0, 1);
+      bq0 = b_load(0, 0);
+      bq1 = b_load(0, 1);
     }
   }
   for (int c0 = 0; conv_on && c0 < Cin; c0 += CHUNK) {
@@ -281,18 +339,18 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
     if (n_mine <= 0) continue;    // more waves than units (1 x 1 taps): only help with the gather
     int j = 0;
     for (; j + 3 <= n_mine; j += 3) {
-      bq2 = *b_ptr(c0, j + 2);
+      bq2 = b_load(c0, j + 2);
       unit(j, bq0);
-      bq0 = *b_ptr(c0, j + 3);
+      bq0 = b_load(c0, j + 3);
       unit(j + 1, bq1);
-      bq1 = *b_ptr(c0, j + 4);
+      bq1 = b_load(c0, j + 4);
       unit(j + 2, bq2);
     }
     if (j < n_mine) unit(j, bq0);
     if (j + 1 < n_mine) unit(j + 1, bq1);
     if (more) {
-      bq0 = *b_ptr(c0 + CHUNK, 0);
-      bq1 = *b_ptr(c0 + CHUNK, 1);
+      bq0 = b_load(c0 + CHUNK, 0);
+      bq1 = b_load(c0 + CHUNK, 1);
     }
   }
 
@@ -427,20 +485,20 @@ int chunk_for(const ConvParams& p) {
   return (p.gi.c % 32 == 0 && p.stride == 1) ? 32 : 16;
 }
 
-template <int CHUNK, int NW, bool BF16, int MB>
+template <int CHUNK, int NW, int OPM, int MB>
 void launch_variant(const ConvParams& p, hipStream_t s) {
   const int PH = (4 * MB - 1) * p.stride + p.k, PW = 7 * p.stride + p.k;
-  size_t lds = (size_t)PH * PW * (BF16 ? CHUNK / 2 + 4 : CHUNK + 4) * sizeof(float);
+  size_t lds = (size_t)PH * PW * (OPM == kOpBf16 ? CHUNK / 2 + 4 : CHUNK + 4) * sizeof(float);
   const size_t part = (size_t)4 * MB * 16 * 64 * sizeof(float);  // partial sums reuse the patch
   if (lds < part) lds = part;
   dim3 grid(p.go.tiles() * (2 / MB), p.go.c / 32);
-  hipLaunchKernelGGL((conv_mfma_kernel<CHUNK, NW, BF16, MB>), grid, dim3(NW * 64), lds, s, p);
+  hipLaunchKernelGGL((conv_mfma_kernel<CHUNK, NW, OPM, MB>), grid, dim3(NW * 64), lds, s, p);
 }
 
 // share of the chip's 256 CUs kept busy when n equally long workgroups run at once
 double fill(long long n) { return (double)n / 256.0 / (double)((n + 255) / 256); }
 
-template <int CHUNK, bool BF16>
+template <int CHUNK, int OPM>
 void launch_shape(const ConvParams& p, hipStream_t s) {
   const long long n2 = (long long)p.go.tiles() * (p.go.c / 32);  // workgroups with whole tiles
   bool halves = fill(2 * n2) > fill(n2) + 0.05;                  // half tiles balance better
@@ -451,18 +509,18 @@ void launch_shape(const ConvParams& p, hipStream_t s) {
   if (const char* e = getenv("EVK_NW")) eight = atoi(e) == 8;
 #endif
   if (halves) {
-    if (eight) launch_variant<CHUNK, 8, BF16, 1>(p, s); else launch_variant<CHUNK, 4, BF16, 1>(p, s);
+    if (eight) launch_variant<CHUNK, 8, OPM, 1>(p, s); else launch_variant<CHUNK, 4, OPM, 1>(p, s);
   } else {
-    if (eight) launch_variant<CHUNK, 8, BF16, 2>(p, s); else launch_variant<CHUNK, 4, BF16, 2>(p, s);
+    if (eight) launch_variant<CHUNK, 8, OPM, 2>(p, s); else launch_variant<CHUNK, 4, OPM, 2>(p, s);
   }
 }
 
-template <bool BF16>
+template <int OPM>
 void launch_any(const ConvParams& p, hipStream_t s) {
   switch (chunk_for(p)) {
-    case 64: launch_shape<64, BF16>(p, s); break;
-    case 32: launch_shape<32, BF16>(p, s); break;
-    default: launch_shape<16, BF16>(p, s); break;
+    case 64: launch_shape<64, OPM>(p, s); break;
+    case 32: launch_shape<32, OPM>(p, s); break;
+    default: launch_shape<16, OPM>(p, s); break;
   }
 }
 
@@ -472,10 +530,15 @@ bool conv_mfma_f32_supported(const ConvParams& p) {
   return p.gi.c % 16 == 0 && p.go.c % 32 == 0 && p.c_out_pad == p.go.c &&
          (long long)p.gi.h * p.gi.w * p.gi.c * 4 < (1ll << 31);  // byte offsets of the gather fit 31 bits
 }
-void launch_conv_mfma_f32(const ConvParams& p, hipStream_t s) { launch_any<false>(p, s); }
+void launch_conv_mfma_f32(const ConvParams& p, hipStream_t s) { launch_any<kOpF32>(p, s); }
 
 // bf16 operands, fp32 accumulation; weights are [tap][c_in/8][c_out][8] bf16
 bool conv_mfma_bf16_supported(const ConvParams& p) { return conv_mfma_f32_supported(p); }
-void launch_conv_mfma_bf16(const ConvParams& p, hipStream_t s) { launch_any<true>(p, s); }
+void launch_conv_mfma_bf16(const ConvParams& p, hipStream_t s) { launch_any<kOpBf16>(p, s); }
+
+// fp32 weights and increments, each split into bf16 high + low parts: three bf16 MFMAs per
+// product with fp32 accumulation; weights are [2 planes][tap][c_in/8][c_out][8] bf16
+bool conv_mfma_split_supported(const ConvParams& p) { return conv_mfma_f32_supported(p); }
+void launch_conv_mfma_split(const ConvParams& p, hipStream_t s) { launch_any<kOpSplit>(p, s); }
 
 }  // namespace evk

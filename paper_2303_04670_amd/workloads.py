@@ -26,7 +26,7 @@ import numpy as np
 (OP_CONV2D, OP_ADD, OP_CONCAT, OP_UPSAMPLE2X, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_ACT, OP_SPARSIFY,
  OP_MUL) = range(10)
 ACT_NONE, ACT_RELU, ACT_SIGMOID, ACT_TANH = range(4)
-WD_F32, WD_BF16 = 0, 1
+WD_F32, WD_BF16, WD_F32_SPLIT = 0, 1, 2   # WD_F32_SPLIT: fp32 weights, contraction through bf16 high/low parts
 
 
 @dataclasses.dataclass
@@ -151,6 +151,13 @@ class _NetBuilder:
     def finish(self) -> Net:
         w = np.concatenate(self.chunks) if self.chunks else np.zeros(0, np.float32)
         return Net(self.name, self.in_c, self.in_h, self.in_w, self.nodes, w)
+
+
+def with_weight_dtype(net: Net, wdtype: int) -> Net:
+    """The same network and fp32 weight values with another declared contraction dtype on every
+    conv / linear node (plain data; WD_BF16 here does not round the values)."""
+    nodes = [dataclasses.replace(nd, wdtype=wdtype) if nd.op in (OP_CONV2D, OP_LINEAR) else nd for nd in net.nodes]
+    return dataclasses.replace(net, nodes=nodes, name=net.name + f"_wd{wdtype}")
 
 
 def round_to_bf16(a: np.ndarray) -> np.ndarray:

@@ -551,3 +551,55 @@ def test_refresh_period_runs_a_regular_forward_pass_every_nth_step(kind):
         a.set_refresh_period(-1)
     a.destroy()
     b.destroy()
+
+
+# --------------------------------------------------------------------------- fp32 through bf16 high/low parts
+
+def test_split_bf16_conv_shapes_meet_the_fp32_bar():
+    """EVCONV_F32_SPLIT: fp32 weights and increments contracted as three bf16 products.  Every
+    kernel variant on ragged sizes, against the fp64 oracle with the unrounded fp32 weights, at
+    the fp32 tolerance."""
+    _say("split-bf16 matrix-core conv variants at the fp32 tolerance")
+    worst = 0.0
+    for k, s, ci, co in [(3, 1, 32, 32), (3, 2, 16, 64), (5, 1, 64, 32), (5, 2, 48, 96), (7, 2, 16, 32), (1, 1, 32, 64),
+                         (3, 1, 128, 64)]:
+        b = wl._NetBuilder(f"conv{k}s{s}", ci, 21, 27, 100 + k * 10 + s, bias=True)
+        b.conv(-1, co, k, s, act=wl.ACT_RELU, out=1)
+        net = wl.with_weight_dtype(b.finish(), wl.WD_F32_SPLIT)
+        rng = np.random.default_rng(k + s)
+        x0 = rng.standard_normal((ci, 21, 27)).astype(np.float32)
+        incs = []
+        for t in range(4):
+            m = rng.random((21, 27)) < (0.03 if t < 3 else 1.0)
+            incs.append(rng.standard_normal(x0.shape).astype(np.float32) * m[None])
+        g = ev.EvConvNet(net)
+        assert g.kernel_name(0) == "conv_mfma_f32_split_bf16x3"
+        g.destroy()
+        rep = run_stream(net, x0, incs, "increment", label=f"split k{k}s{s}", max_flips=2)
+        worst = max(worst, rep.max_rel_z, rep.max_rel_y)
+    _say(f"split-bf16: worst relative error {worst:.2e} (bar {TOL:.0e})")
+
+
+def test_split_bf16_unet_reduced():
+    _say("UNet depth net, full width on 5x64x96, split-bf16 contraction, fp32 tolerance")
+    net = wl.with_weight_dtype(wl.net_unet_depth(1003, h=64, w=96), wl.WD_F32_SPLIT)
+    g = ev.EvConvNet(net)
+    names = [g.kernel_name(i) for i in range(len(net.nodes))]
+    g.destroy()
+    assert names.count("conv_mfma_f32_split_bf16x3") == 10, names
+    frames = list(wl.stream_voxel(1003, 64, 96, 20, 0.02, n_prim=6))
+    rep = run_stream(net, frames[0], frames[1:], "frame", label="unet-split", max_flips=40)
+    _say(f"split-bf16 UNet: max rel z err {rep.max_rel_z:.2e}, y err {rep.max_rel_y:.2e}")
+
+
+@pytest.mark.timeout(900)
+def test_workload3_unet_split_bf16_full_size_100_steps():
+    """The bench configuration with the split-bf16 contraction: 100 frames, fp32 tolerance."""
+    _say("workload 3, split-bf16 contraction: UNet depth net 5x256x352, 100 frames at 2 %")
+    net = wl.with_weight_dtype(wl.net_unet_depth(), wl.WD_F32_SPLIT)
+    gen = wl.stream_voxel(1003, 256, 352, 100, 0.02)
+    x0 = next(gen)
+    rep = run_stream(net, x0, gen, "frame", check_nodes_at={1, 2, 50, 100}, label="w3-split",
+                     max_flips=4 * int(0.005 * 256 * 352))
+    assert set(rep.flips_by_node) <= {"node 20 active"}, rep.flips_by_node
+    _say(f"split-bf16 w3: max rel z err {rep.max_rel_z:.2e}, y err {rep.max_rel_y:.2e}")
