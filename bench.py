@@ -121,6 +121,8 @@ def main():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-second-variant", action="store_true")
     ap.add_argument("--no-sparsified", action="store_true")
+    ap.add_argument("--streams", type=int, default=16,
+                    help="independent event streams per net in the multi_stream leg (0: skip the leg)")
     ap.add_argument("--sparsify-tp", type=float, default=0.1)
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run plain device-to-device copies of this size (for scaling rocprofv3 "
@@ -185,6 +187,8 @@ def main():
             r2["weights"] = other
             r2["parity_bar"] = "2e-2 relative (Frobenius)" if other == "bf16" else "1e-4 max-abs"
             out[f"{other}_variant"] = r2
+    if args.streams > 1:
+        out["multi_stream"] = multi_stream_leg(args, np, torch, ev, wl, dev)
     if not args.no_sparsified:
         out["sparsified_variant"] = sparsified_leg(args, np, torch, ev, wl, dframes)
     if not args.no_cpu_baseline:
@@ -201,6 +205,40 @@ def main():
                                "sample": f"first {k} frames of the same stream, fp64, OpenMP"}
     out["layers"] = res["layers"]
     print(json.dumps(out), flush=True)
+
+
+def multi_stream_leg(args, np, torch, ev, wl, dev):
+    """The chip-filling shape: n independent event streams (cameras) in one net, sharing the
+    weights and stepped by one call.  Reported as stream-steps per second; not the headline (the
+    headline is one stream, batch 1)."""
+    H, W, n = 256, 352, args.streams
+    steps = max(10, args.steps // 4)
+    n_frames = 3 + steps
+    gens = [wl.stream_voxel(2000 + s, H, W, n_frames, args.density) for s in range(n)]
+    frames = []
+    for t in range(n_frames + 1):
+        frames.append(torch.from_numpy(np.stack([next(g) for g in gens])).to(dev))
+    res = {"streams": n, "unit": "stream-steps/s", "steps": steps}
+    for variant in ("f32", "f32_split", "bf16"):
+        net = wl.net_unet_depth(1003, h=H, w=W, bf16=(variant == "bf16"))
+        if variant == "f32_split":
+            net = wl.with_weight_dtype(net, wl.WD_F32_SPLIT)
+        g = ev.EvConvNet(net, device="cuda:0", n_streams=n)
+        g.reset(frames[0])
+        for t in range(1, 4):
+            g.step_frame(frames[t])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(4, n_frames + 1):
+            g.step_frame(frames[t])
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        conv = [i for i, nd in enumerate(net.nodes) if nd.op == wl.OP_CONV2D]
+        flops = sum(2.0 * net.nodes[i].k ** 2 * net.nodes[i].c_in * net.nodes[i].c_out * g.stats(i).n_touched for i in conv)
+        g.destroy()
+        res[variant] = {"value": n * steps / dt, "ms_per_call": dt / steps * 1e3,
+                        "conv_tflops_alg": flops * n * steps / dt / 1e12}
+    return res
 
 
 def sparsified_leg(args, np, torch, ev, wl, dframes):

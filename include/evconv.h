@@ -125,7 +125,10 @@ typedef struct {
   int32_t in_c, in_h, in_w;
   int32_t tile_h, tile_w; /* mask tile; 0 = default 8 x 8 (the only size this build accepts) */
   float sparsify_tp;      /* threshold parameter t_p of the SPARSIFY nodes (>= 0; 0 = lossless) */
-  int32_t n_streams;      /* independent streams sharing the weights; must be 1 */
+  int32_t n_streams;      /* independent event streams (cameras) stepped together and sharing the
+                           * weights, 1..256 (0 = 1).  Every stream owns a copy of the whole state;
+                           * inputs are contiguous [n_streams][C][H][W]; the pointers in evconv_out
+                           * are stream 0's, stream s lies s * evconv_stream_stride bytes further. */
 } evconv_net_desc;
 
 /* Result of one output node.  All pointers are DEVICE memory inside the workspace, valid until
@@ -209,6 +212,15 @@ evconv_status evconv_node_shape(const evconv_net* net, int32_t node, int32_t* ch
 /* Synchronous copy of internal state to HOST memory (parity checks, checkpoints).  `bytes`
  * must be the exact size; node -1 addresses the input increment stage. */
 evconv_status evconv_get_state(evconv_net* net, int32_t node, int32_t kind, void* dst, size_t bytes);
+
+/* The same for stream `stream` of a net created with n_streams > 1 (evconv_get_state reads
+ * stream 0).  EVCONV_ERR_INVALID_ARG for a stream outside [0, n_streams). */
+evconv_status evconv_get_state_stream(evconv_net* net, int32_t stream, int32_t node, int32_t kind, void* dst,
+                                      size_t bytes);
+
+/* Bytes between the copies of any state or output pointer of consecutive streams, and the number
+ * of streams (n_streams may be NULL).  The workspace holds n_streams such copies back to back. */
+evconv_status evconv_stream_stride(const evconv_net* net, size_t* bytes /* HOST */, int32_t* n_streams /* HOST */);
 
 /* Synchronous; counts come from the occupancy words of the last step. */
 evconv_status evconv_get_stats(evconv_net* net, int32_t node, evconv_layer_stats* out);

@@ -60,6 +60,8 @@ struct Layout {
   size_t off_x_prev = 0, off_dx = 0, off_occ_in = 0, off_idx_in = 0, off_count_in = 0, off_bitmap_in = 0;
   size_t off_occ_nodes = 0, n_occ_words = 0;  // contiguous occupancy region of all nodes
   size_t off_sets = 0, off_rms = 0;
+  size_t stride = 0;   // bytes of one stream's state (the weights live in stream 0's copy)
+  int n_streams = 1;
   size_t total = 0;
   int max_ty = 0;
 };
@@ -90,7 +92,7 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
   if ((desc->tile_h != 0 && desc->tile_h != kTile) || (desc->tile_w != 0 && desc->tile_w != kTile))
     return fail(err, EVCONV_ERR_UNSUPPORTED, "only 8 x 8 mask tiles are built");
   if (!(desc->sparsify_tp >= 0.0f)) return fail(err, EVCONV_ERR_INVALID_ARG, "sparsify_tp must be >= 0");
-  if (desc->n_streams != 0 && desc->n_streams != 1) return fail(err, EVCONV_ERR_UNSUPPORTED, "n_streams must be 1");
+  if (desc->n_streams < 0 || desc->n_streams > 256) return fail(err, EVCONV_ERR_INVALID_ARG, "n_streams must be in [0, 256]");
   if ((long long)desc->in_h * desc->in_w > (1ll << 30)) return fail(err, EVCONV_ERR_SHAPE, "input too large");
 
   L->gin = make_geo(desc->in_c, desc->in_h, desc->in_w);
@@ -223,7 +225,9 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
   }
   L->off_rms = b.take(sizeof(float) * kRmsBlocks);
   L->off_sets = b.take(sizeof(SetDesc) * (size_t)(desc->n_nodes + 1));
-  L->total = b.cur;
+  L->stride = (b.cur + 255) / 256 * 256;  // one stream's copy of everything
+  L->n_streams = desc->n_streams > 0 ? desc->n_streams : 1;
+  L->total = L->stride * (size_t)L->n_streams;
   return EVCONV_OK;
 }
 
@@ -239,6 +243,8 @@ struct evconv_net {
   int mode = EVCONV_MODE_INCREMENTAL;
   int refresh_period = 0, since_refresh = 0;
   bool has_state = false;
+  Streams st{0, 1};
+  size_t in_stride = 0;
   std::string err;
   std::vector<int> outputs;
   float *x_prev = nullptr, *dx = nullptr;
@@ -270,6 +276,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
   bp.in = input; bp.x_prev = net->x_prev; bp.dx = net->dx; bp.occ = net->occ_in;
   bp.clear = net->occ_nodes; bp.n_clear = (int)net->L.n_occ_words;
   bp.g = net->L.gin; bp.mode = builder_mode;
+  bp.st = net->st; bp.in_stride = net->in_stride;
   launch_builder(bp, s);
 
   for (size_t i = 0; i < net->L.nodes.size(); ++i) {
@@ -285,6 +292,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
         IntegrateParams ip;
         ip.delta = n.out; ip.occ = n.occ; ip.y = n.y; ip.dy = n.dy; ip.g = n.go;
         ip.mode = pass == kPassStep ? kIntStep : pass == kPassReset ? kIntReset : kIntRecompute;
+        ip.st = net->st;
         launch_integrate(ip, s);
       }
       continue;
@@ -302,6 +310,8 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
         p.occ_out = n.occ; p.occ_touched = n.touched; p.gi = n.ga; p.go = n.go; p.c_out_pad = n.c_out_pad;
         p.k = d.kh; p.stride = d.stride; p.pad = d.pad; p.act = d.act; p.dense = dense;
         p.n_fused = n.n_fused;
+        p.st = net->st;
+        for (int f = 0; f < kMaxFusedAdds; ++f) p.fused[f] = FusedAdd{};
         for (int f = 0; f < n.n_fused; ++f) {
           const NodePlan& a_node = net->L.nodes[n.fused_nodes[f]];
           // the ADD's other input: the one that is not the previous stage
@@ -325,9 +335,10 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
         p.op = d.op == EVCONV_OP_ADD ? kEwAdd : d.op == EVCONV_OP_CONCAT ? kEwConcat : d.op == EVCONV_OP_MUL ? kEwMul :
                d.op == EVCONV_OP_UPSAMPLE_BILINEAR2X ? kEwUp2x : d.op == EVCONV_OP_SPARSIFY ? kEwSparsify : kEwAct;
         p.step = n.step;
+        p.st = net->st;
         if (d.op == EVCONV_OP_SPARSIFY && pass == kPassReset && n.step_fixed < 0.0f)
           // refresh: k = t_p * RMS of the layer input, which the producer has just written in full
-          launch_rms_step(a, (size_t)n.ga.c * n.ga.sites(), net->sparsify_tp, net->rms_partial, n.step, s);
+          launch_rms_step(a, (size_t)n.ga.c * n.ga.sites(), net->sparsify_tp, net->rms_partial, n.step, net->st, s);
         p.act = d.act; p.dense = dense; p.keeps_z = n.keeps_z; p.structural = n.structural;
         p.ga = n.ga; p.gb = n.gb; p.go = n.go; p.a = a; p.occ_a = occ_a; p.b = bptr; p.occ_b = occ_b;
         p.z = n.z; p.z2 = n.z2; p.out = n.out; p.occ_out = n.occ; p.occ_touched = n.touched;
@@ -337,6 +348,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
       }
       case kKernPool: {
         EwParams p;
+        p.st = net->st; p.z2 = nullptr; p.step = nullptr;
         p.act = kActNone; p.dense = dense; p.keeps_z = 0; p.structural = 0;
         p.ga = n.ga; p.gb = n.ga; p.a = a; p.occ_a = occ_a; p.b = nullptr; p.occ_b = nullptr;
         p.out = nullptr; p.occ_out = nullptr; p.occ_touched = nullptr;
@@ -352,6 +364,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
         GapParams p;
         p.a = a; p.occ_a = occ_a; p.ga = n.ga; p.z = n.z; p.out = n.out; p.occ_out = n.occ;
         p.occ_touched = n.touched; p.act = d.act; p.dense = dense;
+        p.st = net->st;
         launch_gap(p, s);
         break;
       }
@@ -364,11 +377,12 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
       IntegrateParams ip;
       ip.delta = n.out; ip.occ = n.occ; ip.y = n.y; ip.dy = n.dy; ip.g = n.go;
       ip.mode = pass == kPassStep ? kIntStep : pass == kPassReset ? kIntReset : kIntRecompute;
+      ip.st = net->st;
       launch_integrate(ip, s);
     }
   }
-  if (pass == kPassReset) launch_fill_u64(net->occ_nodes, net->L.n_occ_words, 0, s);
-  launch_build_lists(net->sets_dev, (int)net->L.nodes.size() + 1, net->L.max_ty, s);
+  if (pass == kPassReset) launch_fill_u64(net->occ_nodes, net->L.n_occ_words, 0, net->st, s);
+  launch_build_lists(net->sets_dev, (int)net->L.nodes.size() + 1, net->L.max_ty, net->st, s);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(net, e, "kernel launch");
   return EVCONV_OK;
@@ -426,6 +440,8 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
   net->sets_dev = (SetDesc*)(ws + L.off_sets);
   net->rms_partial = (float*)(ws + L.off_rms);
   net->sparsify_tp = desc->sparsify_tp;
+  net->st = Streams{L.stride, L.n_streams};
+  net->in_stride = (size_t)L.gin.c * L.gin.sites() * sizeof(float);
 
   hipError_t e = hipMemsetAsync(ws, 0, L.total, net->stream);
   if (e != hipSuccess) { g_create_error = std::string("hipMemsetAsync: ") + hipGetErrorString(e); delete net; return EVCONV_ERR_HIP; }
@@ -443,7 +459,8 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
       if (n.d.weight_off >= 0) {
         memcpy(&n.step_fixed, (const char*)weights + n.d.weight_off, 4);
         if (!(n.step_fixed >= 0.0f)) { g_create_error = "negative sparsification step"; delete net; return EVCONV_ERR_BAD_DESC; }
-        e = hipMemcpy(n.step, &n.step_fixed, 4, hipMemcpyHostToDevice);
+        for (int sidx = 0; sidx < L.n_streams && e == hipSuccess; ++sidx)
+          e = hipMemcpy((char*)n.step + (size_t)sidx * L.stride, &n.step_fixed, 4, hipMemcpyHostToDevice);
         if (e != hipSuccess) { g_create_error = std::string("upload: ") + hipGetErrorString(e); delete net; return EVCONV_ERR_HIP; }
       }
     }
@@ -643,7 +660,20 @@ evconv_status evconv_node_shape(const evconv_net* net, int32_t node, int32_t* ch
 }
 
 evconv_status evconv_get_state(evconv_net* net, int32_t node, int32_t kind, void* dst, size_t bytes) {
+  return evconv_get_state_stream(net, 0, node, kind, dst, bytes);
+}
+
+evconv_status evconv_stream_stride(const evconv_net* net, size_t* bytes, int32_t* n_streams) {
+  if (!net || !bytes) return EVCONV_ERR_INVALID_ARG;
+  *bytes = net->L.stride;
+  if (n_streams) *n_streams = net->L.n_streams;
+  return EVCONV_OK;
+}
+
+evconv_status evconv_get_state_stream(evconv_net* net, int32_t stream, int32_t node, int32_t kind, void* dst,
+                                      size_t bytes) {
   if (!net) return EVCONV_ERR_INVALID_ARG;
+  if (stream < 0 || stream >= net->L.n_streams) { net->err = "no such stream"; return EVCONV_ERR_INVALID_ARG; }
   if (!dst || node < -1 || node >= (int)net->L.nodes.size()) { net->err = "bad node or null dst"; return EVCONV_ERR_INVALID_ARG; }
   const Geo& g = node < 0 ? net->L.gin : net->L.nodes[node].go;
   const NodePlan* n = node < 0 ? nullptr : &net->L.nodes[node];
@@ -666,7 +696,8 @@ evconv_status evconv_get_state(evconv_net* net, int32_t node, int32_t kind, void
   if (!src) { net->err = "this node keeps no such state"; return EVCONV_ERR_INVALID_ARG; }
   if (bytes != need) { net->err = "size mismatch: expected " + std::to_string(need) + " bytes"; return EVCONV_ERR_INVALID_ARG; }
   hipError_t e = hipStreamSynchronize(net->stream);
-  if (e == hipSuccess) e = hipMemcpy(dst, src, need, hipMemcpyDeviceToHost);
+  if (e == hipSuccess)
+    e = hipMemcpy(dst, (const char*)src + (size_t)stream * net->L.stride, need, hipMemcpyDeviceToHost);
   if (e != hipSuccess) return hip_fail(net, e, "get_state");
   return EVCONV_OK;
 }

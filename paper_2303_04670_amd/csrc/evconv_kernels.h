@@ -27,6 +27,18 @@ inline Geo make_geo(int c, int h, int w) {
 
 enum Act { kActNone = 0, kActRelu = 1, kActSigmoid = 2, kActTanh = 3 };
 
+// Independent streams (cameras) that share the weights: every stream owns a copy of the whole
+// state region; copy number blockIdx.z of any state pointer lies blockIdx.z * stride bytes
+// further on.  Launchers put the number of streams into the grid's z dimension.
+struct Streams {
+  size_t stride;  // bytes between the copies of one state pointer
+  int n;          // number of streams (grid z)
+};
+template <class T>
+__device__ __forceinline__ T* at_stream(T* q, size_t off) {
+  return q ? (T*)((uintptr_t)q + off) : nullptr;
+}
+
 // ---- increment builder (Eq.1 + mask) ---------------------------------------------------
 enum BuilderMode { kBuildFrame = 0, kBuildIncrement = 1, kBuildReset = 2, kBuildIncrementDense = 3 };
 struct BuilderParams {
@@ -38,6 +50,8 @@ struct BuilderParams {
   int n_clear;
   Geo g;
   int mode;
+  Streams st;
+  size_t in_stride;   // bytes between the streams' inputs (contiguous [n][C][H][W])
 };
 void launch_builder(const BuilderParams& p, hipStream_t s);
 
@@ -71,6 +85,7 @@ struct ConvParams {
   int dense;                // 1: regular forward pass (all sites, z overwritten with bias)
   int n_fused;              // matrix-core kernel only: ADD nodes applied in the epilogue, in order
   FusedAdd fused[kMaxFusedAdds];
+  Streams st;               // w and bias are shared by all streams
 };
 void launch_conv_valu(const ConvParams& p, hipStream_t s);
 // fp32 MFMA variant; requires c_in % 16 == 0 and c_out % 32 == 0
@@ -100,19 +115,21 @@ struct EwParams {
   uint64_t* occ_out; uint64_t* occ_touched;
   int k, stride, pad;       // pooling window
   const float* step;        // sparsification layer: device scalar, the rounding step k
+  Streams st;
 };
 void launch_elementwise(const EwParams& p, hipStream_t s);
 
 // ---- rounding step of a sparsification layer: k = tp * RMS(x), 8 significant bits ---------------
 // Two fixed-order reduction stages (no floating-point atomics): `partial` holds kRmsBlocks floats.
 constexpr int kRmsBlocks = 256;
-void launch_rms_step(const float* x, size_t n, float tp, float* partial, float* step_out, hipStream_t s);
+void launch_rms_step(const float* x, size_t n, float tp, float* partial, float* step_out, Streams st, hipStream_t s);
 
 // ---- global average pool -----------------------------------------------------------------
 struct GapParams {
   const float* a; const uint64_t* occ_a; Geo ga;
   float* z; float* out; uint64_t* occ_out; uint64_t* occ_touched;
   int act, dense;
+  Streams st;
 };
 void launch_gap(const GapParams& p, hipStream_t s);
 
@@ -123,6 +140,7 @@ struct IntegrateParams {
   const uint64_t* occ;      // S_out words
   float* y; float* dy;      // C x H x W
   Geo g; int mode;
+  Streams st;
 };
 void launch_integrate(const IntegrateParams& p, hipStream_t s);
 
@@ -131,8 +149,8 @@ struct SetDesc {
   const uint64_t* occ; int32_t* idx; int32_t* count; uint64_t* bitmap;
   int h, w, tx, ty;
 };
-void launch_build_lists(const SetDesc* sets_dev, int n_sets, int max_ty, hipStream_t s);
+void launch_build_lists(const SetDesc* sets_dev, int n_sets, int max_ty, Streams st, hipStream_t s);
 
-void launch_fill_u64(uint64_t* p, size_t n, uint64_t v, hipStream_t s);
+void launch_fill_u64(uint64_t* p, size_t n, uint64_t v, Streams st, hipStream_t s);
 
 }  // namespace evk

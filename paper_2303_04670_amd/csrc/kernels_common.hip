@@ -39,6 +39,12 @@ __device__ __forceinline__ uint64_t inbounds_word(int h, int w, int tile_y, int 
 // 256-byte coalesced loads per channel; its ballot is the 64-column activity of that row.  The
 // eight ballots are transposed through LDS into eight tile occupancy words.
 __global__ __launch_bounds__(512) void builder_kernel(BuilderParams p) {
+  {
+    const size_t so = (size_t)blockIdx.z * p.st.stride;
+    p.in = at_stream(p.in, (size_t)blockIdx.z * p.in_stride);
+    p.x_prev = at_stream(p.x_prev, so); p.dx = at_stream(p.dx, so);
+    p.occ = at_stream(p.occ, so); p.clear = at_stream(p.clear, so);
+  }
   __shared__ uint64_t s_rows[8];
   const int lane = threadIdx.x & 63;
   const int r = threadIdx.x >> 6;
@@ -92,7 +98,7 @@ __global__ __launch_bounds__(512) void builder_kernel(BuilderParams p) {
 }
 
 void launch_builder(const BuilderParams& p, hipStream_t s) {
-  dim3 grid((p.g.w + 63) / 64, (p.g.h + 7) / 8);
+  dim3 grid((p.g.w + 63) / 64, (p.g.h + 7) / 8, p.st.n);
   hipLaunchKernelGGL(builder_kernel, grid, dim3(512), 0, s, p);
 }
 
@@ -131,6 +137,14 @@ template <int VEC> __device__ __forceinline__ VecT<VEC> zerov() {
 
 template <int VEC>
 __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
+  {
+    const size_t so = (size_t)blockIdx.z * p.st.stride;
+    p.a = at_stream(p.a, so); p.occ_a = at_stream(p.occ_a, so);
+    p.b = at_stream(p.b, so); p.occ_b = at_stream(p.occ_b, so);
+    p.z = at_stream(p.z, so); p.z2 = at_stream(p.z2, so); p.out = at_stream(p.out, so);
+    p.occ_out = at_stream(p.occ_out, so); p.occ_touched = at_stream(p.occ_touched, so);
+    p.step = at_stream(p.step, so);
+  }
   __shared__ int s_sites[64];
   __shared__ unsigned char s_src[64];  // upsample: which of the four source sites are active
   __shared__ unsigned s_flags[2];
@@ -356,7 +370,7 @@ void launch_elementwise(const EwParams& p, hipStream_t s) {
   bool vec4 = (p.go.c % 4) == 0;
   if (p.op == kEwConcat) vec4 = vec4 && (p.ga.c % 4) == 0;
   const int cv_all = p.go.c / (vec4 ? 4 : 1);
-  dim3 grid(p.go.tiles(), (cv_all + kEwVecPerBlock - 1) / kEwVecPerBlock);
+  dim3 grid(p.go.tiles(), (cv_all + kEwVecPerBlock - 1) / kEwVecPerBlock, p.st.n);
   if (vec4) hipLaunchKernelGGL(elementwise_kernel<4>, grid, dim3(256), 0, s, p);
   else hipLaunchKernelGGL(elementwise_kernel<1>, grid, dim3(256), 0, s, p);
 }
@@ -365,6 +379,11 @@ void launch_elementwise(const EwParams& p, hipStream_t s) {
 // One thread per channel; active sites are visited in tile order (ascending tiles, ascending
 // bits), a fixed order, so the fp32 sum is reproducible.
 __global__ __launch_bounds__(256) void gap_kernel(GapParams p) {
+  {
+    const size_t so = (size_t)blockIdx.z * p.st.stride;
+    p.a = at_stream(p.a, so); p.occ_a = at_stream(p.occ_a, so); p.z = at_stream(p.z, so);
+    p.out = at_stream(p.out, so); p.occ_out = at_stream(p.occ_out, so); p.occ_touched = at_stream(p.occ_touched, so);
+  }
   const int c = blockIdx.x * 256 + threadIdx.x;
   const int C = p.ga.c;
   bool any = false;
@@ -406,11 +425,16 @@ __global__ __launch_bounds__(256) void gap_kernel(GapParams p) {
 }
 
 void launch_gap(const GapParams& p, hipStream_t s) {
-  hipLaunchKernelGGL(gap_kernel, dim3((p.ga.c + 255) / 256), dim3(256), 0, s, p);
+  hipLaunchKernelGGL(gap_kernel, dim3((p.ga.c + 255) / 256, 1, p.st.n), dim3(256), 0, s, p);
 }
 
 // =============================================================================== Eq.2
 __global__ __launch_bounds__(256) void integrate_kernel(IntegrateParams p) {
+  {
+    const size_t so = (size_t)blockIdx.z * p.st.stride;
+    p.delta = at_stream(p.delta, so); p.occ = at_stream(p.occ, so);
+    p.y = at_stream(p.y, so); p.dy = at_stream(p.dy, so);
+  }
   const int site = blockIdx.x * 256 + threadIdx.x;
   const int hw = p.g.h * p.g.w;
   if (site >= hw) return;
@@ -433,7 +457,7 @@ __global__ __launch_bounds__(256) void integrate_kernel(IntegrateParams p) {
 }
 
 void launch_integrate(const IntegrateParams& p, hipStream_t s) {
-  hipLaunchKernelGGL(integrate_kernel, dim3((p.g.sites() + 255) / 256), dim3(256), 0, s, p);
+  hipLaunchKernelGGL(integrate_kernel, dim3((p.g.sites() + 255) / 256, 1, p.st.n), dim3(256), 0, s, p);
 }
 
 // =============================================================================== ordered lists
@@ -441,10 +465,15 @@ void launch_integrate(const IntegrateParams& p, hipStream_t s) {
 // the number of active sites in all earlier strips (a reduction over their occupancy words);
 // inside the strip wave r owns image row r and scans the per-tile byte popcounts with a
 // wave-wide prefix sum, so indices come out strictly ascending in y*W + x.
-__global__ __launch_bounds__(512) void build_lists_kernel(const SetDesc* sets) {
+__global__ __launch_bounds__(512) void build_lists_kernel(const SetDesc* sets, size_t stream_stride) {
   __shared__ int s_part[8];
   __shared__ int s_rowcnt[8];
-  const SetDesc d = sets[blockIdx.y];
+  SetDesc d = sets[blockIdx.y];  // the descriptors hold stream 0's pointers
+  {
+    const size_t so = (size_t)blockIdx.z * stream_stride;
+    d.occ = at_stream(d.occ, so); d.idx = at_stream(d.idx, so);
+    d.count = at_stream(d.count, so); d.bitmap = at_stream(d.bitmap, so);
+  }
   const int strip = blockIdx.x;
   if (strip >= d.ty) return;
   const int tid = threadIdx.x, lane = tid & 63, r = tid >> 6;
@@ -508,15 +537,17 @@ __global__ __launch_bounds__(512) void build_lists_kernel(const SetDesc* sets) {
   }
 }
 
-void launch_build_lists(const SetDesc* sets_dev, int n_sets, int max_ty, hipStream_t s) {
-  hipLaunchKernelGGL(build_lists_kernel, dim3(max_ty, n_sets), dim3(512), 0, s, sets_dev);
+void launch_build_lists(const SetDesc* sets_dev, int n_sets, int max_ty, Streams st, hipStream_t s) {
+  hipLaunchKernelGGL(build_lists_kernel, dim3(max_ty, n_sets, st.n), dim3(512), 0, s, sets_dev, st.stride);
 }
 
 // =============================================================================== rounding step
 // stage 1: block b sums the squares of its contiguous slice in a fixed order (thread-strided
 // partials, then a shared-memory tree); stage 2: one block adds the kRmsBlocks partials the same
 // way and writes k = tp * sqrt(sum / n) kept to 8 significant bits.
-__global__ __launch_bounds__(256) void rms_stage1_kernel(const float* x, size_t n, float* partial) {
+__global__ __launch_bounds__(256) void rms_stage1_kernel(const float* x, size_t n, float* partial, size_t stream_stride) {
+  x = at_stream(x, (size_t)blockIdx.y * stream_stride);
+  partial = at_stream(partial, (size_t)blockIdx.y * stream_stride);
   __shared__ float s_sum[256];
   const size_t per = (n + kRmsBlocks - 1) / kRmsBlocks;
   const size_t lo = blockIdx.x * per, hi = min(n, lo + per);
@@ -530,7 +561,10 @@ __global__ __launch_bounds__(256) void rms_stage1_kernel(const float* x, size_t 
   }
   if (threadIdx.x == 0) partial[blockIdx.x] = s_sum[0];
 }
-__global__ __launch_bounds__(256) void rms_stage2_kernel(const float* partial, size_t n, float tp, float* step_out) {
+__global__ __launch_bounds__(256) void rms_stage2_kernel(const float* partial, size_t n, float tp, float* step_out,
+                                                        size_t stream_stride) {
+  partial = at_stream(partial, (size_t)blockIdx.y * stream_stride);
+  step_out = at_stream(step_out, (size_t)blockIdx.y * stream_stride);
   __shared__ float s_sum[256];
   s_sum[threadIdx.x] = threadIdx.x < kRmsBlocks ? partial[threadIdx.x] : 0.0f;
   __syncthreads();
@@ -545,20 +579,21 @@ __global__ __launch_bounds__(256) void rms_stage2_kernel(const float* partial, s
     *step_out = __uint_as_float(u);
   }
 }
-void launch_rms_step(const float* x, size_t n, float tp, float* partial, float* step_out, hipStream_t s) {
+void launch_rms_step(const float* x, size_t n, float tp, float* partial, float* step_out, Streams st, hipStream_t s) {
   static_assert(kRmsBlocks == 256, "stage 2 adds one partial per thread");
-  hipLaunchKernelGGL(rms_stage1_kernel, dim3(kRmsBlocks), dim3(256), 0, s, x, n, partial);
-  hipLaunchKernelGGL(rms_stage2_kernel, dim3(1), dim3(256), 0, s, partial, n, tp, step_out);
+  hipLaunchKernelGGL(rms_stage1_kernel, dim3(kRmsBlocks, st.n), dim3(256), 0, s, x, n, partial, st.stride);
+  hipLaunchKernelGGL(rms_stage2_kernel, dim3(1, st.n), dim3(256), 0, s, partial, n, tp, step_out, st.stride);
 }
 
-__global__ void fill_u64_kernel(uint64_t* p, size_t n, uint64_t v) {
+__global__ void fill_u64_kernel(uint64_t* p, size_t n, uint64_t v, size_t stream_stride) {
+  p = at_stream(p, (size_t)blockIdx.y * stream_stride);
   for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
-void launch_fill_u64(uint64_t* p, size_t n, uint64_t v, hipStream_t s) {
+void launch_fill_u64(uint64_t* p, size_t n, uint64_t v, Streams st, hipStream_t s) {
   if (!n) return;
   int blocks = (int)((n + 255) / 256);
   if (blocks > 1024) blocks = 1024;
-  hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks), dim3(256), 0, s, p, n, v);
+  hipLaunchKernelGGL(fill_u64_kernel, dim3(blocks, st.n), dim3(256), 0, s, p, n, v, st.stride);
 }
 
 }  // namespace evk

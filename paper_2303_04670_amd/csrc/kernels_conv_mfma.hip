@@ -80,6 +80,9 @@ constexpr int max_patch_sites(int chunk, int mb) {
 
 template <int CHUNK, int NW, int OPM, int MB>
 __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
+  // this workgroup's stream: every state pointer of p is used through at_stream(.., so); p itself
+  // stays untouched so that it remains in the kernel-argument segment
+  const size_t so = (size_t)blockIdx.z * p.st.stride;
   constexpr bool BF16 = OPM != kOpF32;     // bf16 MFMA, 16 channels per unit
   constexpr bool SPLIT = OPM == kOpSplit;  // operands as bf16 high + low parts, three products
   constexpr int NT = NW * 64;
@@ -119,7 +122,7 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
     const int ty = rty0 + ry, tx = rtx0 + rx;
     uint64_t w = 0;
     if (ry < rny && rx < rnx && ty >= 0 && ty < p.gi.ty && tx >= 0 && tx < p.gi.tx)
-      w = p.dense ? ~0ull : p.occ_in[ty * p.gi.tx + tx];
+      w = p.dense ? ~0ull : at_stream(p.occ_in, so)[ty * p.gi.tx + tx];
     s_occ[tid] = w;
   }
   if (tid < 2 * (1 + kMaxFusedAdds)) s_nz[tid] = 0;
@@ -166,7 +169,7 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
 #pragma unroll
   for (int f = 0; f < kMaxFusedAdds; ++f) {
     skip_word[f] = 0;
-    if (f < p.n_fused) skip_word[f] = p.dense ? touched_word : (p.fused[f].occ_skip[tile] & row_mask);
+    if (f < p.n_fused) skip_word[f] = p.dense ? touched_word : (at_stream(p.fused[f].occ_skip, so)[tile] & row_mask);
     site_word |= skip_word[f];
   }
   if (site_word == 0) return;
@@ -182,7 +185,7 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
     z_old[it] = 0.0f;
     if (!p.dense && ((touched_word >> site) & 1ull)) {
       const int oy = tile_y * 8 + (site >> 3), ox = tile_x * 8 + (site & 7);
-      z_old[it] = p.z[((size_t)oy * p.go.w + ox) * Cout + co0 + co];
+      z_old[it] = at_stream(p.z, so)[((size_t)oy * p.go.w + ox) * Cout + co0 + co];
     }
   }
 
@@ -205,7 +208,7 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
     }
   }
   const __amdgpu_buffer_rsrc_t in_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc((void*)p.in, 0, H * W * Cin * 4, 0x00020000);
+      __builtin_amdgcn_make_buffer_rsrc((void*)at_stream(p.in, so), 0, H * W * Cin * 4, 0x00020000);
   float4 pre[MAXV];
   auto fetch = [&](int c0) {
 #pragma unroll
@@ -368,8 +371,8 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
       if (!((site_word >> site) & 1ull)) continue;
       const int oy = tile_y * 8 + (site >> 3), ox = tile_x * 8 + (site & 7);
       const size_t q = ((size_t)oy * p.go.w + ox) * Cout + co0 + co;
-      if ((skip_word[f] >> site) & 1ull) f_skip[f][it] = p.fused[f].skip[q];
-      if (p.fused[f].keeps_z && !p.dense) f_zold[f][it] = p.fused[f].z[q];
+      if ((skip_word[f] >> site) & 1ull) f_skip[f][it] = at_stream(p.fused[f].skip, so)[q];
+      if (p.fused[f].keeps_z && !p.dense) f_zold[f][it] = at_stream(p.fused[f].z, so)[q];
     }
   }
 
@@ -417,14 +420,14 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
       const float v = (s_mem[off] + s_mem[off + SLOT]) + (s_mem[off + 2 * SLOT] + s_mem[off + 3 * SLOT]);
       if (p.dense) {
         const float z = v + (p.bias ? p.bias[co0 + co] : 0.0f);
-        p.z[q] = z;
+        at_stream(p.z, so)[q] = z;
         o = act_m(p.act, z);
       } else {
         const float z_new = z_old[it] + v;
-        p.z[q] = z_new;
+        at_stream(p.z, so)[q] = z_new;
         o = (p.act == kActNone) ? v : act_m(p.act, z_new) - act_m(p.act, z_old[it]);
       }
-      p.out[q] = o;
+      at_stream(p.out, so)[q] = o;
       if (o != 0.0f) nz_sites |= 1ull << site;
     }
     // fused ADD nodes (Eq.11 followed by Eq.12-14): a = the value just produced, b = skip input
@@ -435,18 +438,18 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
       const float lin = o + f_skip[f][it];
       if (fa.keeps_z) {
         if (p.dense) {
-          fa.z[q] = lin;
+          at_stream(fa.z, so)[q] = lin;
           o = act_m(fa.act, lin);
         } else {
           const float z2_old = f_zold[f][it];
           const float z2_new = z2_old + lin;
-          fa.z[q] = z2_new;
+          at_stream(fa.z, so)[q] = z2_new;
           o = (fa.act == kActNone) ? lin : act_m(fa.act, z2_new) - act_m(fa.act, z2_old);
         }
       } else {
         o = lin;
       }
-      fa.out[q] = o;
+      at_stream(fa.out, so)[q] = o;
       if (o != 0.0f) nz_fused[f] |= 1ull << site;
     }
   }
@@ -466,15 +469,15 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
     // S of the producer as seen by this workgroup's rows and channels; all words are pre-zeroed
     // and the other workgroups of the tile OR their share in
     uint64_t s_prev = p.dense ? touched_word : ((uint64_t)s_nz[0] | ((uint64_t)s_nz[1] << 32));
-    glob_or(&p.occ_out[tile], s_prev);
-    if (blockIdx.y == 0) glob_or(&p.occ_touched[tile], touched_word);
+    glob_or(&at_stream(p.occ_out, so)[tile], s_prev);
+    if (blockIdx.y == 0) glob_or(&at_stream(p.occ_touched, so)[tile], touched_word);
     for (int f = 0; f < p.n_fused; ++f) {
       const FusedAdd& fa = p.fused[f];
       const uint64_t t_f = s_prev | skip_word[f];  // Eq.11b
       const uint64_t nz_f = (uint64_t)s_nz[2 + 2 * f] | ((uint64_t)s_nz[3 + 2 * f] << 32);
       const uint64_t s_f = (fa.structural || p.dense) ? t_f : nz_f;
-      glob_or(&fa.occ_touched[tile], t_f);
-      glob_or(&fa.occ_out[tile], s_f);
+      glob_or(&at_stream(fa.occ_touched, so)[tile], t_f);
+      glob_or(&at_stream(fa.occ_out, so)[tile], s_f);
       s_prev = s_f;
     }
   }
@@ -491,7 +494,7 @@ void launch_variant(const ConvParams& p, hipStream_t s) {
   size_t lds = (size_t)PH * PW * (OPM == kOpBf16 ? CHUNK / 2 + 4 : CHUNK + 4) * sizeof(float);
   const size_t part = (size_t)4 * MB * 16 * 64 * sizeof(float);  // partial sums reuse the patch
   if (lds < part) lds = part;
-  dim3 grid(p.go.tiles() * (2 / MB), p.go.c / 32);
+  dim3 grid(p.go.tiles() * (2 / MB), p.go.c / 32, p.st.n);
   hipLaunchKernelGGL((conv_mfma_kernel<CHUNK, NW, OPM, MB>), grid, dim3(NW * 64), lds, s, p);
 }
 
@@ -500,7 +503,7 @@ double fill(long long n) { return (double)n / 256.0 / (double)((n + 255) / 256);
 
 template <int CHUNK, int OPM>
 void launch_shape(const ConvParams& p, hipStream_t s) {
-  const long long n2 = (long long)p.go.tiles() * (p.go.c / 32);  // workgroups with whole tiles
+  const long long n2 = (long long)p.go.tiles() * (p.go.c / 32) * p.st.n;  // workgroups with whole tiles
   bool halves = fill(2 * n2) > fill(n2) + 0.05;                  // half tiles balance better
   const long long n = halves ? 2 * n2 : n2;
   bool eight = n < 512;  // few workgroups: 8 waves each split K further

@@ -38,6 +38,7 @@ __device__ __forceinline__ float act_n(int act, float v) {
 
 template <int NB>
 __global__ __launch_bounds__(128 * NB) void conv_narrow_kernel(ConvParams p) {
+  const size_t so = (size_t)blockIdx.z * p.st.stride;  // this workgroup's stream
   constexpr int NT = 128 * NB;
   constexpr int NC = 32 * NB;  // output channels per workgroup
   extern __shared__ __align__(16) float s_dyn[];  // [KP][NC] weights, then the patch
@@ -89,7 +90,7 @@ __global__ __launch_bounds__(128 * NB) void conv_narrow_kernel(ConvParams p) {
     const int ty = rty0 + ry, tx = rtx0 + rx;
     uint64_t w = 0;
     if (ry < rny && rx < rnx && ty >= 0 && ty < p.gi.ty && tx >= 0 && tx < p.gi.tx)
-      w = p.dense ? ~0ull : p.occ_in[ty * p.gi.tx + tx];
+      w = p.dense ? ~0ull : at_stream(p.occ_in, so)[ty * p.gi.tx + tx];
     s_occ[tid] = w;
   }
   __syncthreads();
@@ -137,14 +138,14 @@ __global__ __launch_bounds__(128 * NB) void conv_narrow_kernel(ConvParams p) {
     if (!p.dense && ((my_touched >> ls) & 1u)) {
       const int site = half * 32 + ls;
       const int oy = tile_y * 8 + (site >> 3), ox = tile_x * 8 + (site & 7);
-      z_old[i] = p.z[((size_t)oy * p.go.w + ox) * Cout + co];
+      z_old[i] = at_stream(p.z, so)[((size_t)oy * p.go.w + ox) * Cout + co];
     }
   }
 
   // patch: conditioned fetch, inactive and out-of-image sites become zeros without a memory access
   {
     const __amdgpu_buffer_rsrc_t in_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void*)p.in, 0, H * W * Cin * 4, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc((void*)at_stream(p.in, so), 0, H * W * Cin * 4, 0x00020000);
     const int total = P * P * Cin;
 #pragma unroll 4
     for (int e = tid; e < total; e += NT) {
@@ -196,14 +197,14 @@ __global__ __launch_bounds__(128 * NB) void conv_narrow_kernel(ConvParams p) {
       const float v = acc[i];
       if (p.dense) {
         const float z = v + (p.bias ? p.bias[co] : 0.0f);
-        p.z[q] = z;
+        at_stream(p.z, so)[q] = z;
         o = act_n(p.act, z);
       } else {
         const float z_new = z_old[i] + v;
-        p.z[q] = z_new;
+        at_stream(p.z, so)[q] = z_new;
         o = (p.act == kActNone) ? v : act_n(p.act, z_new) - act_n(p.act, z_old[i]);
       }
-      p.out[q] = o;
+      at_stream(p.out, so)[q] = o;
     }
     const uint64_t b = __ballot(on && o != 0.0f);
     const int ls_lo = 8 * (i >> 2) + (i & 3);
@@ -212,10 +213,10 @@ __global__ __launch_bounds__(128 * NB) void conv_narrow_kernel(ConvParams p) {
   }
   if (lane == 0) {
     const uint64_t mine = (uint64_t)(p.dense ? my_touched : nz) << (32 * half);
-    if (mine) atomicOr((unsigned long long*)&p.occ_out[tile], (unsigned long long)mine);  // pre-zeroed word
+    if (mine) atomicOr((unsigned long long*)&at_stream(p.occ_out, so)[tile], (unsigned long long)mine);  // pre-zeroed word
     if (blockIdx.y == 0 && nsub == 0) {
       const uint64_t t = (uint64_t)my_touched << (32 * half);
-      if (t) atomicOr((unsigned long long*)&p.occ_touched[tile], (unsigned long long)t);
+      if (t) atomicOr((unsigned long long*)&at_stream(p.occ_touched, so)[tile], (unsigned long long)t);
     }
   }
   }  // tiles
@@ -236,7 +237,7 @@ void launch_conv_narrow(const ConvParams& p, hipStream_t s) {
   const int KP = conv_narrow_padded_k(p.k * p.k * p.gi.c);
   const int nb = (p.go.c % 64 == 0) ? 2 : 1;
   const size_t lds = ((size_t)KP * 32 * nb + (size_t)P * P * (p.gi.c | 1)) * sizeof(float);
-  dim3 grid(std::min(p.go.tiles(), 1024), p.go.c / (32 * nb));
+  dim3 grid(std::min(p.go.tiles(), std::max(1024 / p.st.n, 64)), p.go.c / (32 * nb), p.st.n);
   if (nb == 2) hipLaunchKernelGGL(conv_narrow_kernel<2>, grid, dim3(256), lds, s, p);
   else hipLaunchKernelGGL(conv_narrow_kernel<1>, grid, dim3(128), lds, s, p);
 }

@@ -31,6 +31,10 @@ __device__ __forceinline__ float act_f(int act, float v) {
 }
 
 __global__ __launch_bounds__(256) void conv_valu_kernel(ConvParams p) {
+  const size_t so = (size_t)blockIdx.z * p.st.stride;  // this workgroup's stream
+  const float* const in_s = at_stream(p.in, so);
+  float* const z_s = at_stream(p.z, so);
+  float* const out_s = at_stream(p.out, so);
   extern __shared__ __align__(16) float s_patch[];
   __shared__ uint64_t s_occ[16];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -52,7 +56,7 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(ConvParams p) {
     const int ty = rty0 + ry, tx = rtx0 + rx;
     uint64_t w = 0;
     if (ry < rny && rx < rnx && ty >= 0 && ty < p.gi.ty && tx >= 0 && tx < p.gi.tx)
-      w = p.dense ? ~0ull : p.occ_in[ty * p.gi.tx + tx];
+      w = p.dense ? ~0ull : at_stream(p.occ_in, so)[ty * p.gi.tx + tx];
     s_occ[tid] = w;
   }
   __syncthreads();
@@ -99,7 +103,7 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(ConvParams p) {
         if ((unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W) {
           const uint64_t w = s_occ[((iy >> 3) - rty0) * 4 + ((ix >> 3) - rtx0)];
           if ((w >> (((iy & 7) << 3) | (ix & 7))) & 1ull)
-            val = *(const float4*)&p.in[((size_t)iy * W + ix) * Cin + c0 + v * 4];
+            val = *(const float4*)&in_s[((size_t)iy * W + ix) * Cin + c0 + v * 4];
         }
         *(float4*)&s_patch[site * kChunkPad + v * 4] = val;
       }
@@ -112,7 +116,7 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(ConvParams p) {
         float val = 0.0f;
         if ((unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W) {
           const uint64_t w = s_occ[((iy >> 3) - rty0) * 4 + ((ix >> 3) - rtx0)];
-          if ((w >> (((iy & 7) << 3) | (ix & 7))) & 1ull) val = p.in[((size_t)iy * W + ix) * Cin + c0 + c];
+          if ((w >> (((iy & 7) << 3) | (ix & 7))) & 1ull) val = in_s[((size_t)iy * W + ix) * Cin + c0 + c];
         }
         s_patch[site * kChunkPad + c] = val;
       }
@@ -155,23 +159,23 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(ConvParams p) {
         float o;
         if (p.dense) {
           const float z = acc[j] + (p.bias ? p.bias[co] : 0.0f);
-          p.z[qoff + co] = z;
+          z_s[qoff + co] = z;
           o = act_f(p.act, z);
         } else {
-          const float z_old = p.z[qoff + co];
+          const float z_old = z_s[qoff + co];
           const float z_new = z_old + acc[j];
-          p.z[qoff + co] = z_new;
+          z_s[qoff + co] = z_new;
           o = (p.act == kActNone) ? acc[j] : act_f(p.act, z_new) - act_f(p.act, z_old);
         }
-        p.out[qoff + co] = o;
+        out_s[qoff + co] = o;
         nz |= (o != 0.0f);
       }
     }
   }
   const uint64_t nz_word = p.dense ? touched_word : __ballot(touched && nz);
   if (lane == 0) {
-    if (nz_word) atomicOr((unsigned long long*)&p.occ_out[tile], (unsigned long long)nz_word);
-    if (wave == 0 && blockIdx.y == 0) p.occ_touched[tile] = touched_word;
+    if (nz_word) atomicOr((unsigned long long*)&at_stream(p.occ_out, so)[tile], (unsigned long long)nz_word);
+    if (wave == 0 && blockIdx.y == 0) at_stream(p.occ_touched, so)[tile] = touched_word;
   }
 }
 
@@ -180,7 +184,7 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(ConvParams p) {
 void launch_conv_valu(const ConvParams& p, hipStream_t s) {
   const int P = 7 * p.stride + p.k;
   const size_t lds = ((size_t)P * P * kChunkPad + (size_t)p.k * kChunk * 32) * sizeof(float);
-  dim3 grid(p.go.tiles(), (p.go.c + 4 * kCpt - 1) / (4 * kCpt));
+  dim3 grid(p.go.tiles(), (p.go.c + 4 * kCpt - 1) / (4 * kCpt), p.st.n);
   hipLaunchKernelGGL(conv_valu_kernel, grid, dim3(256), lds, s, p);
 }
 

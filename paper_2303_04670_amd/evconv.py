@@ -27,7 +27,8 @@ MODE_INCREMENTAL, MODE_DENSE_RECOMPUTE = 0, 1
 EXPORTS = ["evconv_query_workspace", "evconv_create", "evconv_num_outputs", "evconv_reset", "evconv_step",
            "evconv_step_frame", "evconv_destroy", "evconv_set_mode", "evconv_node_shape", "evconv_get_state",
            "evconv_get_stats", "evconv_node_kernel", "evconv_last_error", "evconv_profile_begin",
-           "evconv_profile_end", "evconv_get_node_time", "evconv_set_refresh_period"]
+           "evconv_profile_end", "evconv_get_node_time", "evconv_set_refresh_period", "evconv_get_state_stream",
+           "evconv_stream_stride"]
 
 
 class NodeDesc(ctypes.Structure):
@@ -79,6 +80,8 @@ def lib() -> ctypes.CDLL:
         L.evconv_set_refresh_period.argtypes = [vp, i32]
         L.evconv_node_shape.argtypes = [vp, i32, ctypes.POINTER(i32)]
         L.evconv_get_state.argtypes = [vp, i32, i32, vp, ctypes.c_size_t]
+        L.evconv_get_state_stream.argtypes = [vp, i32, i32, i32, vp, ctypes.c_size_t]
+        L.evconv_stream_stride.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(i32)]
         L.evconv_get_stats.argtypes = [vp, i32, ctypes.POINTER(LayerStats)]
         L.evconv_node_kernel.argtypes = [vp, i32]
         L.evconv_node_kernel.restype = ctypes.c_char_p
@@ -150,6 +153,9 @@ class EvConvNet:
         self._h = h
         self.n_outputs = lib().evconv_num_outputs(self._h)
         self._outs = (Out * self.n_outputs)()
+        stride, n = ctypes.c_size_t(0), ctypes.c_int32(0)
+        self._check(lib().evconv_stream_stride(self._h, ctypes.byref(stride), ctypes.byref(n)))
+        self.stream_stride, self.n_streams = stride.value, n.value
 
     # ---- the four calls
     def _check(self, st):
@@ -159,7 +165,8 @@ class EvConvNet:
     def _dev_ptr(self, t):
         torch = self.torch
         assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()
-        assert tuple(t.shape) == (self.net.in_c, self.net.in_h, self.net.in_w)
+        want = (self.net.in_c, self.net.in_h, self.net.in_w)
+        assert tuple(t.shape) == (want if self.n_streams == 1 else (self.n_streams,) + want)
         return ctypes.c_void_p(t.data_ptr())
 
     def reset(self, x0):
@@ -194,7 +201,7 @@ class EvConvNet:
         self._check(lib().evconv_node_shape(self._h, node, s))
         return int(s[0]), int(s[1]), int(s[2])
 
-    def state(self, node, kind) -> np.ndarray:
+    def state(self, node, kind, stream=0) -> np.ndarray:
         c, h, w = self.shape(node)
         tiles = (-(-h // 8)) * (-(-w // 8))
         if kind in (STATE_Z, STATE_DY, STATE_Z2):
@@ -211,12 +218,13 @@ class EvConvNet:
             a = np.empty(-(-tiles // 64), np.uint64)
         else:
             a = np.empty(tiles, np.uint64)
-        self._check(lib().evconv_get_state(self._h, node, kind, a.ctypes.data_as(ctypes.c_void_p), a.nbytes))
+        self._check(lib().evconv_get_state_stream(self._h, stream, node, kind, a.ctypes.data_as(ctypes.c_void_p),
+                                                  a.nbytes))
         return a
 
-    def site_list(self, node) -> np.ndarray:
-        n = int(self.state(node, STATE_COUNT)[0])
-        return self.state(node, STATE_IDX)[:n].copy()
+    def site_list(self, node, stream=0) -> np.ndarray:
+        n = int(self.state(node, STATE_COUNT, stream)[0])
+        return self.state(node, STATE_IDX, stream)[:n].copy()
 
     def stats(self, node) -> LayerStats:
         s = LayerStats()
@@ -238,9 +246,9 @@ class EvConvNet:
     def kernel_name(self, node) -> str:
         return lib().evconv_node_kernel(self._h, node).decode()
 
-    def outputs(self):
-        """Per output node: dict of torch views (y, dy as C x H x W; idx; count), valid until the
-        next call on this net.  The caller synchronises the stream before reading."""
+    def outputs(self, stream=0):
+        """Per output node: dict of torch views (y, dy as C x H x W; idx; count) of one stream, valid
+        until the next call on this net.  The caller synchronises the stream before reading."""
         torch = self.torch
         res = []
         base = self._ws_ptr
@@ -248,7 +256,7 @@ class EvConvNet:
         off0 = base - raw.data_ptr()
 
         def view(ptr, nbytes, dtype, shape):
-            o = ptr - base + off0
+            o = ptr - base + off0 + stream * self.stream_stride
             return raw[o:o + nbytes].view(dtype).view(*shape)
         for j in range(self.n_outputs):
             o = self._outs[j]

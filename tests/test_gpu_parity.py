@@ -603,3 +603,79 @@ def test_workload3_unet_split_bf16_full_size_100_steps():
                      max_flips=4 * int(0.005 * 256 * 352))
     assert set(rep.flips_by_node) <= {"node 20 active"}, rep.flips_by_node
     _say(f"split-bf16 w3: max rel z err {rep.max_rel_z:.2e}, y err {rep.max_rel_y:.2e}")
+
+
+# --------------------------------------------------------------------------- several streams per net
+
+@pytest.mark.parametrize("which", ["unet", "mixed_ops", "sparsified"])
+def test_streams_stepped_together_equal_single_stream_nets(which):
+    """n_streams = 3: three independent event streams share the weights and are stepped by one
+    call.  Every stream must equal a single-stream net fed the same frames, and stream 1 is also
+    checked against the oracle."""
+    _say(f"three streams in one net ({which}) against three single-stream nets")
+    import torch
+    if which == "unet":
+        net = wl.net_unet_depth(1003, h=64, w=96)
+        gens = [list(wl.stream_voxel(40 + s, 64, 96, 6, 0.01 * (s + 1), n_prim=5)) for s in range(3)]
+    elif which == "mixed_ops":
+        net = wl.net_random_small(7)
+        rng = np.random.default_rng(3)
+        gens = []
+        for s in range(3):
+            x = rng.standard_normal((3, 13, 11)).astype(np.float32)
+            fr = [x]
+            for _ in range(6):
+                x = (x + rng.standard_normal(x.shape).astype(np.float32) * (rng.random((1, 13, 11)) < 0.2)).astype(np.float32)
+                fr.append(x)
+            gens.append(fr)
+    else:
+        net = wl.net_conv_stack(1002, h=40, w=56, sparsify=True)
+        net.sparsify_tp = 0.2
+        gens = [list(wl.stream_voxel(50 + s, 40, 56, 6, 0.03, n_prim=4)) for s in range(3)]
+    multi = ev.EvConvNet(net, n_streams=3)
+    singles = [ev.EvConvNet(net) for _ in range(3)]
+    assert multi.n_streams == 3 and multi.stream_stride % 256 == 0
+    ora = Oracle(net)
+    keeps = [i for i in range(len(net.nodes)) if multi.kernel_name(i) != "fused_into_conv_epilogue"]
+    for t in range(7):
+        batch = _dev(np.stack([gens[s][t] for s in range(3)]))
+        if t == 0:
+            multi.reset(batch)
+            ora.reset(gens[1][0])
+        else:
+            multi.step_frame(batch)
+            ora.step_frame(gens[1][t])
+        for s in range(3):
+            (singles[s].reset if t == 0 else singles[s].step_frame)(_dev(gens[s][t]))
+        torch.cuda.synchronize()
+        # The matrix-core convolutions pick their launch shape (and with it the order of the partial
+        # sums) from the number of workgroups, which grows with the number of streams: those nets
+        # agree to rounding, the net without matrix-core layers bit for bit.
+        exact = which == "mixed_ops"
+        for s in range(3):
+            for a, b in zip(multi.outputs(s), singles[s].outputs()):
+                if exact:
+                    assert torch.equal(a["y"], b["y"]) and torch.equal(a["dy"], b["dy"]), f"step {t} stream {s}"
+                    assert int(a["count"]) == int(b["count"])
+                else:
+                    scale = float(b["y"].abs().max())
+                    assert float((a["y"] - b["y"]).abs().max()) <= 1e-5 * scale, f"step {t} stream {s}"
+            for i in keeps[:: max(1, len(keeps) // 6)]:
+                if exact:
+                    np.testing.assert_array_equal(multi.state(i, ev.STATE_OCC, s), singles[s].state(i, ev.STATE_OCC))
+                    np.testing.assert_array_equal(multi.site_list(i, s), singles[s].site_list(i))
+                    np.testing.assert_array_equal(multi.state(i, ev.STATE_DY, s), singles[s].state(i, ev.STATE_DY))
+                else:
+                    np.testing.assert_array_equal(multi.state(i, ev.STATE_OCC_TOUCHED, s),
+                                                  singles[s].state(i, ev.STATE_OCC_TOUCHED))
+            np.testing.assert_array_equal(multi.state(-1, ev.STATE_X_PREV, s), gens[s][t])
+        if which != "sparsified":
+            out = ora.outputs[0]
+            y1 = multi.outputs(1)[[o["node"] for o in multi.outputs(1)].index(out)]["y"].cpu().numpy()
+            ref = np.transpose(ora.y(out), (2, 0, 1))
+            assert np.abs(y1 - ref).max() <= TOL * max(np.abs(ref).max(), 1e-30)
+    with pytest.raises(ev.EvConvError):
+        multi.state(0, ev.STATE_DY, stream=3)
+    multi.destroy()
+    for g in singles:
+        g.destroy()
