@@ -178,7 +178,10 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
 /* Number of output nodes (entries written to the `out` arrays below). */
 int32_t evconv_num_outputs(const evconv_net* net);
 
-/* Refresh ("Drift Errors"): regular forward pass of x0 (DEVICE, C x H x W fp32) that fills the
+/* In the three calls below the input tensor holds one C x H x W fp32 frame (or increment) per
+ * stream, contiguous [n_streams][C][H][W]; all streams advance together.
+ *
+ * Refresh ("Drift Errors"): regular forward pass of x0 (DEVICE, C x H x W fp32) that fills the
  * previous-frame cache, every accumulated tensor and y(0).  `out` (HOST array of
  * evconv_num_outputs entries, may be NULL) receives the pointers; dy is zero, count 0.
  * Asynchronous on the net's stream. */
@@ -222,7 +225,7 @@ evconv_status evconv_get_state_stream(evconv_net* net, int32_t stream, int32_t n
  * of streams (n_streams may be NULL).  The workspace holds n_streams such copies back to back. */
 evconv_status evconv_stream_stride(const evconv_net* net, size_t* bytes /* HOST */, int32_t* n_streams /* HOST */);
 
-/* Synchronous; counts come from the occupancy words of the last step. */
+/* Synchronous; counts come from the occupancy words of the last step (stream 0). */
 evconv_status evconv_get_stats(evconv_net* net, int32_t node, evconv_layer_stats* out);
 
 /* Per-node kernel timing with HIP events recorded on the net's stream around each node's
