@@ -31,6 +31,7 @@ PEAKS = {  # MI355X published dense peaks
     # vector ALU fp32: 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2 (packed) x 2.4 GHz
     "conv_valu_f32": ("alu", 157.3, "TFLOP/s"),
     "conv_narrow_mfma_f32": ("mfma", 157.3, "TFLOP/s"),
+    "conv_pointwise_f32": ("hbm", 8000.0, "GB/s"),
 }
 
 # HBM bytes per launch of the dominant kernel family, from the committed rocprofv3 counter runs

@@ -19,9 +19,9 @@ namespace {
 thread_local std::string g_create_error;
 
 enum KernelKind { kKernConvValu = 0, kKernConvMfmaF32, kKernElementwise, kKernGap, kKernPool, kKernConvMfmaBf16,
-                  kKernConvNarrow, kKernConvMfmaSplit };
+                  kKernConvNarrow, kKernConvMfmaSplit, kKernConvPointwise };
 const char* const kKernelNames[] = {"conv_valu_f32", "conv_mfma_f32", "elementwise", "global_avgpool",
-                                    "maxpool", "conv_mfma_bf16", "conv_narrow_mfma_f32", "conv_mfma_f32_split_bf16x3"};
+                                    "maxpool", "conv_mfma_bf16", "conv_narrow_mfma_f32", "conv_mfma_f32_split_bf16x3", "conv_pointwise_f32"};
 
 // fp32 -> bf16 bits, round to nearest even
 uint16_t to_bf16(float x) {
@@ -215,7 +215,8 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
     n.off_bitmap = b.take(((size_t)n.go.tiles() + 63) / 64 * 8);
     if (n.d.op == EVCONV_OP_CONV2D || n.d.op == EVCONV_OP_LINEAR) {
       const int k = n.d.kh;
-      n.off_w = b.take(((size_t)k * k * n.d.c_in + 16) * n.c_out_pad * 4);  // room for a padded contraction
+      // room for input channels padded to whole chunks (at most 64) or a padded flattened contraction
+      n.off_w = b.take(((size_t)k * k * ((n.d.c_in + 63) / 64 * 64) + 16) * n.c_out_pad * 4);
       if (n.d.bias_off >= 0) n.off_bias = b.take((size_t)n.d.c_out * 4);
     }
     if (n.d.is_output) {
@@ -302,6 +303,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
     switch (n.kernel) {
       case kKernConvValu:
       case kKernConvNarrow:
+      case kKernConvPointwise:
       case kKernConvMfmaSplit:
       case kKernConvMfmaBf16:
       case kKernConvMfmaF32: {
@@ -326,6 +328,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
         if (n.kernel == kKernConvMfmaF32) launch_conv_mfma_f32(p, s);
         else if (n.kernel == kKernConvMfmaBf16) launch_conv_mfma_bf16(p, s);
         else if (n.kernel == kKernConvNarrow) launch_conv_narrow(p, s);
+        else if (n.kernel == kKernConvPointwise) launch_conv_pointwise(p, s);
         else if (n.kernel == kKernConvMfmaSplit) launch_conv_mfma_split(p, s);
         else launch_conv_valu(p, s);
         break;
@@ -482,15 +485,28 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
       const int k = n.d.kh, ci_n = n.d.c_in, co_n = n.d.c_out, cop = n.c_out_pad;
       ConvParams probe;
       probe.gi = n.ga; probe.go = n.go; probe.k = k; probe.stride = n.d.stride; probe.c_out_pad = cop;
-      probe.n_fused = 0;
+      probe.n_fused = 0; probe.pad = n.d.pad;
       const bool force_valu = getenv("EVCONV_FORCE_VALU") != nullptr;
       if (!force_valu && n.d.wdtype == EVCONV_F32 && conv_mfma_f32_supported(probe)) n.kernel = kKernConvMfmaF32;
       if (!force_valu && n.d.wdtype == EVCONV_BF16 && conv_mfma_bf16_supported(probe)) n.kernel = kKernConvMfmaBf16;
       if (!force_valu && n.d.wdtype == EVCONV_F32_SPLIT && conv_mfma_split_supported(probe)) n.kernel = kKernConvMfmaSplit;
       if (!force_valu && n.kernel == kKernConvValu && conv_narrow_supported(probe)) n.kernel = kKernConvNarrow;
+      if (!force_valu && conv_pointwise_supported(probe)) n.kernel = kKernConvPointwise;
       const float* src = (const float*)((const char*)weights + n.d.weight_off);
-      staging.assign(((size_t)k * k * ci_n + 16) * cop, 0.0f);
-      if (n.kernel == kKernConvNarrow) {
+      staging.assign(((size_t)k * k * ((ci_n + 63) / 64 * 64) + 16) * cop, 0.0f);
+      const int ci_p = conv_mfma_padded_cin(probe);  // matrix-core kinds: channels padded with zero rows
+      if (n.kernel == kKernConvPointwise) {
+        // 1 x 1 taps: [c_out][c_in] as supplied; bf16-declared weights are rounded and widened again
+        staging.resize((size_t)co_n * ci_n);
+        for (size_t e = 0; e < staging.size(); ++e) {
+          float w = src[e];
+          if (n.d.wdtype == EVCONV_BF16) {
+            const uint32_t u = (uint32_t)to_bf16(w) << 16;
+            memcpy(&w, &u, 4);
+          }
+          staging[e] = w;
+        }
+      } else if (n.kernel == kKernConvNarrow) {
         // flattened contraction [KP][c_out], k = tap * c_in + ci, zero rows beyond taps * c_in;
         // bf16-declared weights are rounded to bf16 and widened again
         const int kp = conv_narrow_padded_k(k * k * ci_n);
@@ -508,7 +524,7 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
       } else if (n.kernel == kKernConvMfmaSplit) {
         // two bf16 planes [tap][c_in/8][c_out][8]: hi = bf16(w), then lo = bf16(w - hi)
         uint16_t* h16 = (uint16_t*)staging.data();
-        const size_t plane = (size_t)k * k * ci_n * cop;
+        const size_t plane = (size_t)k * k * ci_p * cop;
         for (int co = 0; co < co_n; ++co)
           for (int ci = 0; ci < ci_n; ++ci)
             for (int t = 0; t < k * k; ++t) {
@@ -517,7 +533,7 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
               float hf;
               const uint32_t hu = (uint32_t)hi << 16;
               memcpy(&hf, &hu, 4);
-              const size_t at = (((size_t)t * (ci_n / 8) + ci / 8) * cop + co) * 8 + (ci & 7);
+              const size_t at = (((size_t)t * (ci_p / 8) + ci / 8) * cop + co) * 8 + (ci & 7);
               h16[at] = hi;
               h16[plane + at] = to_bf16(w - hf);
             }
@@ -527,14 +543,14 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
         for (int co = 0; co < co_n; ++co)
           for (int ci = 0; ci < ci_n; ++ci)
             for (int t = 0; t < k * k; ++t)
-              h16[(((size_t)t * (ci_n / 8) + ci / 8) * cop + co) * 8 + (ci & 7)] =
+              h16[(((size_t)t * (ci_p / 8) + ci / 8) * cop + co) * 8 + (ci & 7)] =
                   to_bf16(src[((size_t)co * ci_n + ci) * k * k + t]);
       } else if (n.kernel == kKernConvMfmaF32) {
         // matrix-core layout [tap][c_in/4][c_out][4]: a lane's 4 input channels are 16 bytes
         for (int co = 0; co < co_n; ++co)
           for (int ci = 0; ci < ci_n; ++ci)
             for (int t = 0; t < k * k; ++t)
-              staging[(((size_t)t * (ci_n / 4) + ci / 4) * cop + co) * 4 + (ci & 3)] =
+              staging[(((size_t)t * (ci_p / 4) + ci / 4) * cop + co) * 4 + (ci & 3)] =
                   src[((size_t)co * ci_n + ci) * k * k + t];
       } else {
         // vector-ALU layout [tap][c_in][c_out_pad] (zero padded output channels)

@@ -88,8 +88,10 @@ struct ConvParams {
   Streams st;               // w and bias are shared by all streams
 };
 void launch_conv_valu(const ConvParams& p, hipStream_t s);
-// fp32 MFMA variant; requires c_in % 16 == 0 and c_out % 32 == 0
+// fp32 MFMA variant; requires c_in % 4 == 0, c_in >= 16 and c_out % 32 == 0.  The re-laid weights
+// of all matrix-core variants carry conv_mfma_padded_cin input channels (zero rows beyond c_in).
 bool conv_mfma_f32_supported(const ConvParams& p);
+int conv_mfma_padded_cin(const ConvParams& p);
 void launch_conv_mfma_f32(const ConvParams& p, hipStream_t s);
 // bf16 MFMA variant (increments rounded to bf16 in the gather, bf16 weights, fp32 accumulation)
 bool conv_mfma_bf16_supported(const ConvParams& p);
@@ -97,6 +99,9 @@ void launch_conv_mfma_bf16(const ConvParams& p, hipStream_t s);
 // fp32 operands contracted as bf16 high/low parts (three bf16 MFMAs per product)
 bool conv_mfma_split_supported(const ConvParams& p);
 void launch_conv_mfma_split(const ConvParams& p, hipStream_t s);
+// 1 x 1 taps with at most 8 output channels, or LINEAR on a 1 x 1 grid; weights [c_out][c_in] fp32
+bool conv_pointwise_supported(const ConvParams& p);
+void launch_conv_pointwise(const ConvParams& p, hipStream_t s);
 // narrow-input variant: taps * c_in <= 128, c_out % 32 == 0; weights [padded k][c_out] fp32
 bool conv_narrow_supported(const ConvParams& p);
 int conv_narrow_padded_k(int k_tot);

@@ -1,6 +1,7 @@
 // Sparse incremental convolution on the matrix cores.
 //
-// Used where the per-tile channel contraction is a dense GEMM: c_in % 16 == 0, c_out % 32 == 0.
+// Used where the per-tile channel contraction is a dense GEMM: c_in >= 16 and a multiple of 4
+// (the last channel chunk is zero-padded), c_out % 32 == 0.
 // Implicit GEMM per touched output tile (8 x 8 sites): M = 32 * MB sites (MB = 2: the whole
 // tile as two 32-row MFMA blocks, rows 0-3 and 4-7; MB = 1: one workgroup per half tile),
 // N = 32 output channels per workgroup, K = taps x c_in.
@@ -210,10 +211,16 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
   const __amdgpu_buffer_rsrc_t in_rsrc =
       __builtin_amdgcn_make_buffer_rsrc((void*)at_stream(p.in, so), 0, H * W * Cin * 4, 0x00020000);
   float4 pre[MAXV];
+  // c_in need not be a multiple of the chunk: channel groups beyond c_in read as zeros (their
+  // weight rows are zero padding as well)
+  const bool ragged = (Cin % CHUNK) != 0;
   auto fetch = [&](int c0) {
 #pragma unroll
-    for (int j = 0; j < MAXV; ++j)
-      pre[j] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(in_rsrc, g_off[j], c0 * 4, 0));
+    for (int j = 0; j < MAXV; ++j) {
+      unsigned off = g_off[j];
+      if (ragged && c0 + ((tid + j * NT) % NV) * 4 >= Cin) off = kOob;
+      pre[j] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(in_rsrc, off, c0 * 4, 0));
+    }
   };
   auto stash = [&]() {
 #pragma unroll
@@ -247,7 +254,8 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
   const int mly = m >> 3, mlx = m & 7;  // site of this lane inside a 32-row block
   const int cop = p.c_out_pad;
   const int n_units = K * K * KG;
-  const int cin_rows = BF16 ? Cin >> 3 : Cin >> 2;  // 16-byte weight rows per tap: 8 bf16 or 4 floats
+  const int cin_pad = (Cin + CHUNK - 1) / CHUNK * CHUNK;    // the weights are zero-padded to whole chunks
+  const int cin_rows = BF16 ? cin_pad >> 3 : cin_pad >> 2;  // 16-byte weight rows per tap: 8 bf16 or 4 floats
   const int a_lane_off = (mly * s * PW + mlx * s) * CS + half * 4;
   const int a_blk1 = 4 * s * PW * CS;
   const float4* __restrict__ wlane = (const float4*)p.w + (size_t)half * cop + co0 + m;
@@ -485,7 +493,8 @@ __global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
 
 int chunk_for(const ConvParams& p) {
   if (p.stride == 1 && p.k <= 3 && p.gi.c % 64 == 0) return 64;
-  return (p.gi.c % 32 == 0 && p.stride == 1) ? 32 : 16;
+  if (p.stride == 1 && (p.gi.c % 32 == 0 || (p.gi.c % 16 != 0 && p.gi.c > 32))) return 32;  // ragged: fewer, padded chunks
+  return 16;
 }
 
 template <int CHUNK, int NW, int OPM, int MB>
@@ -530,8 +539,13 @@ void launch_any(const ConvParams& p, hipStream_t s) {
 }  // namespace
 
 bool conv_mfma_f32_supported(const ConvParams& p) {
-  return p.gi.c % 16 == 0 && p.go.c % 32 == 0 && p.c_out_pad == p.go.c &&
+  return p.gi.c % 4 == 0 && p.gi.c >= 16 && p.go.c % 32 == 0 && p.c_out_pad == p.go.c &&
          (long long)p.gi.h * p.gi.w * p.gi.c * 4 < (1ll << 31);  // byte offsets of the gather fit 31 bits
+}
+// input channels of the re-laid weights: c_in rounded up to whole chunks of the variant that runs
+int conv_mfma_padded_cin(const ConvParams& p) {
+  const int chunk = chunk_for(p);
+  return (p.gi.c + chunk - 1) / chunk * chunk;
 }
 void launch_conv_mfma_f32(const ConvParams& p, hipStream_t s) { launch_any<kOpF32>(p, s); }
 

@@ -103,7 +103,7 @@ def test_unet_full_width_reduced_size_matrix_core_layers():
     g = ev.EvConvNet(net)
     names = [g.kernel_name(i) for i in range(len(net.nodes))]
     g.destroy()
-    assert names.count("conv_mfma_f32") == 10 and names[0] == "conv_narrow_mfma_f32" and names[-1] == "conv_valu_f32", names
+    assert names.count("conv_mfma_f32") == 10 and names[0] == "conv_narrow_mfma_f32" and names[-1] == "conv_pointwise_f32", names
     assert names.count("fused_into_conv_epilogue") == 6, names   # 2 residual adds + 4 skip adds
     frames = list(wl.stream_voxel(1003, 64, 96, 20, 0.02, n_prim=6))
     run_stream(net, frames[0], frames[1:], "frame", label="unet-wide", max_flips=40)
@@ -138,7 +138,7 @@ def test_unet_bf16_matrix_core_variant_reduced():
 
 def test_matrix_core_conv_shapes_bf16():
     _say("bf16 matrix-core conv variants")
-    for k, s, ci, co in [(3, 1, 32, 32), (3, 2, 16, 64), (5, 1, 64, 32), (5, 2, 48, 96), (7, 2, 16, 32), (1, 1, 32, 64)]:
+    for k, s, ci, co in [(3, 1, 32, 32), (3, 2, 16, 64), (5, 1, 64, 32), (5, 2, 48, 96), (7, 2, 16, 32), (1, 1, 32, 64), (3, 1, 68, 32), (5, 2, 20, 32)]:
         b = wl._NetBuilder(f"conv{k}s{s}", ci, 21, 27, 100 + k * 10 + s, bf16=True, bias=True)
         b.conv(-1, co, k, s, act=wl.ACT_RELU, out=1)
         net = b.finish()
@@ -158,7 +158,8 @@ def test_matrix_core_conv_shapes():
     """Every (kernel, stride, channel-chunk) variant of the matrix-core conv on ragged sizes, with
     bias, dense and sparse increments."""
     _say("matrix-core conv variants: k in {1,3,5,7}, stride {1,2}, c_in in {16,32,48,64}")
-    for k, s, ci, co in [(3, 1, 32, 32), (3, 2, 16, 64), (5, 1, 64, 32), (5, 2, 48, 96), (7, 2, 16, 32), (1, 1, 32, 64)]:
+    for k, s, ci, co in [(3, 1, 32, 32), (3, 2, 16, 64), (5, 1, 64, 32), (5, 2, 48, 96), (7, 2, 16, 32), (1, 1, 32, 64),
+                         (3, 1, 68, 32), (5, 1, 20, 32), (3, 2, 36, 64)]:   # the last three: ragged channel chunks
         b = wl._NetBuilder(f"conv{k}s{s}", ci, 21, 27, 100 + k * 10 + s, bias=True)
         b.conv(-1, co, k, s, act=wl.ACT_RELU, out=1)
         net = b.finish()
@@ -562,7 +563,7 @@ def test_split_bf16_conv_shapes_meet_the_fp32_bar():
     _say("split-bf16 matrix-core conv variants at the fp32 tolerance")
     worst = 0.0
     for k, s, ci, co in [(3, 1, 32, 32), (3, 2, 16, 64), (5, 1, 64, 32), (5, 2, 48, 96), (7, 2, 16, 32), (1, 1, 32, 64),
-                         (3, 1, 128, 64)]:
+                         (3, 1, 128, 64), (3, 1, 68, 32), (5, 2, 20, 32)]:
         b = wl._NetBuilder(f"conv{k}s{s}", ci, 21, 27, 100 + k * 10 + s, bias=True)
         b.conv(-1, co, k, s, act=wl.ACT_RELU, out=1)
         net = wl.with_weight_dtype(b.finish(), wl.WD_F32_SPLIT)
