@@ -79,8 +79,12 @@ constexpr int max_patch_sites(int chunk, int mb) {
   return chunk == 64 ? (rows + 3) * 10 : chunk == 32 ? (rows + 7) * 14 : (rows * 2 + 7) * 21;
 }
 
+// The register budget is held to 4 (half tiles) or 3 (whole tiles) waves per SIMD: the bf16 and
+// split modes are bound by latencies, not by the matrix cores, and lose a third of their speed
+// when one workgroup fewer fits on a CU.
 template <int CHUNK, int NW, int OPM, int MB>
-__global__ __launch_bounds__(NW * 64) void conv_mfma_kernel(ConvParams p) {
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(MB == 1 ? 4 : 3)))
+void conv_mfma_kernel(ConvParams p) {
   // this workgroup's stream: every state pointer of p is used through at_stream(.., so); p itself
   // stays untouched so that it remains in the kernel-argument segment
   const size_t so = (size_t)blockIdx.z * p.st.stride;
