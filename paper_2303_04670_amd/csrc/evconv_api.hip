@@ -40,6 +40,9 @@ struct NodePlan {
   int fused_into = -1;      // ADD node executed in the epilogue of that conv node
   int n_fused = 0;          // conv node: ADD nodes it executes, in order
   int fused_nodes[kMaxFusedAdds] = {-1, -1};
+  int gather_fused_into = -1;  // UPSAMPLE node computed inside the gather of that conv node, never stored
+  int upsampled_from = -2;     // conv node: the node (-1: network input) whose x2 up-sampling it reads through
+                               // its gather, its in0 being the folded UPSAMPLE node; -2: none
   // workspace offsets (bytes); resolved to pointers at create
   size_t off_step = 0;      // SPARSIFY: device scalar k
   size_t off_z2 = 0;        // MUL: accumulated second factor
@@ -288,6 +291,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
     const bool two = d.op == EVCONV_OP_ADD || d.op == EVCONV_OP_CONCAT || d.op == EVCONV_OP_MUL;
     const float* bptr = two ? (d.in1 < 0 ? net->dx : net->L.nodes[d.in1].out) : nullptr;
     const uint64_t* occ_b = two ? (d.in1 < 0 ? net->occ_in : net->L.nodes[d.in1].occ) : nullptr;
+    if (n.gather_fused_into >= 0) continue;  // exists only inside the consuming conv's gather
     if (n.fused_into >= 0) {  // computed by the producing conv's epilogue
       if (d.is_output) {
         IntegrateParams ip;
@@ -313,6 +317,15 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
         p.k = d.kh; p.stride = d.stride; p.pad = d.pad; p.act = d.act; p.dense = dense;
         p.n_fused = n.n_fused;
         p.st = net->st;
+        p.upsample = 0; p.lo_h = 0; p.lo_w = 0;
+        if (n.upsampled_from != -2) {
+          // read the stored low-resolution tensor; p.gi stays the up-sampled geometry
+          const int src = n.upsampled_from;
+          p.in = src < 0 ? net->dx : net->L.nodes[src].out;
+          p.occ_in = src < 0 ? net->occ_in : net->L.nodes[src].occ;
+          const Geo& gl = src < 0 ? net->L.gin : net->L.nodes[src].go;
+          p.upsample = 1; p.lo_h = gl.h; p.lo_w = gl.w;
+        }
         for (int f = 0; f < kMaxFusedAdds; ++f) p.fused[f] = FusedAdd{};
         for (int f = 0; f < n.n_fused; ++f) {
           const NodePlan& a_node = net->L.nodes[n.fused_nodes[f]];
@@ -593,6 +606,32 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
       a_node.fused_into = host;
     }
   }
+  // Fold a bilinear x2 up-sampling into the gather of the matrix-core conv that is its only
+  // consumer: the up-sampled tensor is then never written (its node keeps no state).
+  if (!getenv("EVCONV_NO_FUSION")) {
+    std::vector<int> n_consumers(L.nodes.size(), 0);
+    for (size_t i = 0; i < L.nodes.size(); ++i) {
+      const evconv_node_desc& d = L.nodes[i].d;
+      if (d.in0 >= 0) ++n_consumers[d.in0];
+      const bool two = d.op == EVCONV_OP_ADD || d.op == EVCONV_OP_CONCAT || d.op == EVCONV_OP_MUL;
+      if (two && d.in1 >= 0 && d.in1 != d.in0) ++n_consumers[d.in1];
+    }
+    for (size_t i = 0; i < L.nodes.size(); ++i) {
+      NodePlan& c_node = L.nodes[i];
+      if (c_node.d.op != EVCONV_OP_CONV2D || c_node.d.in0 < 0) continue;
+      NodePlan& u_node = L.nodes[c_node.d.in0];
+      if (u_node.d.op != EVCONV_OP_UPSAMPLE_BILINEAR2X || u_node.d.act != EVCONV_ACT_NONE || u_node.d.is_output ||
+          n_consumers[c_node.d.in0] != 1 || u_node.fused_into >= 0) continue;
+      if (c_node.kernel != kKernConvMfmaF32 && c_node.kernel != kKernConvMfmaBf16 && c_node.kernel != kKernConvMfmaSplit)
+        continue;
+      ConvParams probe;
+      probe.gi = c_node.ga; probe.go = c_node.go; probe.k = c_node.d.kh; probe.stride = c_node.d.stride;
+      probe.c_out_pad = c_node.c_out_pad; probe.n_fused = 0; probe.pad = c_node.d.pad;
+      if (!conv_mfma_upsample_supported(probe)) continue;
+      u_node.gather_fused_into = (int)i;
+      c_node.upsampled_from = u_node.d.in0;
+    }
+  }
   *out = net;
   return EVCONV_OK;
 }
@@ -690,6 +729,10 @@ evconv_status evconv_get_state_stream(evconv_net* net, int32_t stream, int32_t n
                                       size_t bytes) {
   if (!net) return EVCONV_ERR_INVALID_ARG;
   if (stream < 0 || stream >= net->L.n_streams) { net->err = "no such stream"; return EVCONV_ERR_INVALID_ARG; }
+  if (node >= 0 && net->L.nodes[node].gather_fused_into >= 0) {
+    net->err = "this node is computed inside its consumer's gather and keeps no state";
+    return EVCONV_ERR_INVALID_ARG;
+  }
   if (!dst || node < -1 || node >= (int)net->L.nodes.size()) { net->err = "bad node or null dst"; return EVCONV_ERR_INVALID_ARG; }
   const Geo& g = node < 0 ? net->L.gin : net->L.nodes[node].go;
   const NodePlan* n = node < 0 ? nullptr : &net->L.nodes[node];
@@ -787,6 +830,7 @@ evconv_status evconv_get_node_time(const evconv_net* net, int32_t node, double* 
 const char* evconv_node_kernel(const evconv_net* net, int32_t node) {
   if (!net || node < 0 || node >= (int)net->L.nodes.size()) return "";
   if (net->L.nodes[node].fused_into >= 0) return "fused_into_conv_epilogue";
+  if (net->L.nodes[node].gather_fused_into >= 0) return "fused_into_conv_gather";
   return kKernelNames[net->L.nodes[node].kernel];
 }
 

@@ -86,12 +86,16 @@ struct ConvParams {
   int n_fused;              // matrix-core kernel only: ADD nodes applied in the epilogue, in order
   FusedAdd fused[kMaxFusedAdds];
   Streams st;               // w and bias are shared by all streams
+  // matrix-core kernel only: the input is the bilinear x2 up-sampling of `in` (lo_h x lo_w stored
+  // sites, occ_in their occupancy words); gi describes the up-sampled tensor
+  int upsample, lo_h, lo_w;
 };
 void launch_conv_valu(const ConvParams& p, hipStream_t s);
 // fp32 MFMA variant; requires c_in % 4 == 0, c_in >= 16 and c_out % 32 == 0.  The re-laid weights
 // of all matrix-core variants carry conv_mfma_padded_cin input channels (zero rows beyond c_in).
 bool conv_mfma_f32_supported(const ConvParams& p);
 int conv_mfma_padded_cin(const ConvParams& p);
+bool conv_mfma_upsample_supported(const ConvParams& p);
 void launch_conv_mfma_f32(const ConvParams& p, hipStream_t s);
 // bf16 MFMA variant (increments rounded to bf16 in the gather, bf16 weights, fp32 accumulation)
 bool conv_mfma_bf16_supported(const ConvParams& p);

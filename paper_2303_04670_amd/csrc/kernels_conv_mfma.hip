@@ -82,7 +82,14 @@ constexpr int max_patch_sites(int chunk, int mb) {
 // The register budget is held to 4 (half tiles) or 3 (whole tiles) waves per SIMD: the bf16 and
 // split modes are bound by latencies, not by the matrix cores, and lose a third of their speed
 // when one workgroup fewer fits on a CU.
-template <int CHUNK, int NW, int OPM, int MB>
+//
+// UPS: the conv's input is the bilinear x2 up-sampling of p.in (half-pixel centres, weights
+// 0.25 / 0.75, clamped borders), which is never written to memory: the low-resolution sites under
+// the halo are gathered into a second LDS buffer and every patch element is interpolated from
+// four of them on its way into the patch buffer.  p.gi describes the up-sampled tensor, p.lo_h x
+// p.lo_w the stored one; p.occ_in are the stored tensor's occupancy words, and an up-sampled
+// site is active where one of its four sources is.
+template <int CHUNK, int NW, int OPM, int MB, bool UPS>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(MB == 1 ? 4 : 3)))
 void conv_mfma_kernel(ConvParams p) {
   // this workgroup's stream: every state pointer of p is used through at_stream(.., so); p itself
@@ -105,9 +112,13 @@ void conv_mfma_kernel(ConvParams p) {
   constexpr int EP_SITES = NT / 32;   // sites per epilogue pass
   constexpr int EP_ITERS = NSITES / EP_SITES;
   constexpr int SLOT = MB * 16 * 64;  // floats per partial-sum slot
+  constexpr int CSL = CHUNK + 4;      // UPS: site stride of the low-resolution fp32 buffer
+  constexpr int LPMAX = 10;           // UPS: a 14-row patch has sources in at most 14 / 2 + 3 rows
+  constexpr int MAXG = UPS ? (LPMAX * LPMAX * NV + NT - 1) / NT : MAXV;  // gathered float4 per thread
   extern __shared__ __align__(16) float s_mem[];
   __shared__ uint64_t s_occ[16];
   __shared__ unsigned s_rows[24];  // bit px of s_rows[py]: patch site (py, px) is active
+  __shared__ unsigned s_lrows[UPS ? LPMAX : 1];  // UPS: the same for the low-resolution source region
   __shared__ unsigned s_nz[2 * (1 + kMaxFusedAdds)];  // nonzero-site bits: conv, then each fused ADD
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -119,39 +130,68 @@ void conv_mfma_kernel(ConvParams p) {
   const int H = p.gi.h, W = p.gi.w, Cin = p.gi.c, Cout = p.go.c;
   const int iy0 = (tile_y * 8 + r0) * s - p.pad, ix0 = tile_x * 8 * s - p.pad;
   const int PH = (NROWS - 1) * s + K, PW = 7 * s + K;
-  const int rty0 = iy0 >> 3, rtx0 = ix0 >> 3;
-  const int rny = ((iy0 + PH - 1) >> 3) - rty0 + 1, rnx = ((ix0 + PW - 1) >> 3) - rtx0 + 1;
+  // The region whose stored occupancy is read: the patch itself, or (UPS) the low-resolution
+  // sources of the patch: rows (iy0 >> 1) - 1 .. and columns likewise, PH / 2 + 3 by PW / 2 + 3
+  // sites (a source index is i/2 - 1, i/2 or i/2 + 1 before clamping to the image).
+  const int SH = UPS ? p.lo_h : H, SW = UPS ? p.lo_w : W;  // stored tensor
+  const int s_ty = (SH + 7) >> 3, s_tx = (SW + 7) >> 3;
+  const int gy0 = UPS ? (iy0 >> 1) - 1 : iy0, gx0 = UPS ? (ix0 >> 1) - 1 : ix0;
+  const int GH = UPS ? PH / 2 + 3 : PH, GW = UPS ? PW / 2 + 3 : PW;
+  const int rty0 = gy0 >> 3, rtx0 = gx0 >> 3;
+  const int rny = ((gy0 + GH - 1) >> 3) - rty0 + 1, rnx = ((gx0 + GW - 1) >> 3) - rtx0 + 1;
 
   if (tid < 16) {
     const int ry = tid >> 2, rx = tid & 3;
     const int ty = rty0 + ry, tx = rtx0 + rx;
     uint64_t w = 0;
-    if (ry < rny && rx < rnx && ty >= 0 && ty < p.gi.ty && tx >= 0 && tx < p.gi.tx)
-      w = p.dense ? ~0ull : at_stream(p.occ_in, so)[ty * p.gi.tx + tx];
+    if (ry < rny && rx < rnx && ty >= 0 && ty < s_ty && tx >= 0 && tx < s_tx)
+      w = p.dense ? ~0ull : at_stream(p.occ_in, so)[ty * s_tx + tx];
     s_occ[tid] = w;
   }
   if (tid < 2 * (1 + kMaxFusedAdds)) s_nz[tid] = 0;
   __syncthreads();
-  if (tid < PH) {  // one bit row per patch row; out-of-image sites are 0
-    const int iy = iy0 + tid;
+  if (tid < GH) {  // one bit row per row of the region; out-of-image sites are 0
+    const int gy = gy0 + tid;
     unsigned bits = 0;
-    if ((unsigned)iy < (unsigned)H) {
-      const int ry = (iy >> 3) - rty0;
+    if ((unsigned)gy < (unsigned)SH) {
+      const int ry = (gy >> 3) - rty0;
       // 32 consecutive columns starting at image column rtx0 * 8
       uint64_t span = 0;
 #pragma unroll
       for (int rx = 0; rx < 4; ++rx)
-        span |= ((s_occ[ry * 4 + rx] >> ((iy & 7) * 8)) & 0xffull) << (8 * rx);
-      bits = (unsigned)(span >> (ix0 - rtx0 * 8));
-      // clear columns outside the image (dense mode sets every bit) and beyond the patch
-      const int lo = max(0, -ix0), hi = min(PW, W - ix0);  // valid px in [lo, hi)
+        span |= ((s_occ[ry * 4 + rx] >> ((gy & 7) * 8)) & 0xffull) << (8 * rx);
+      bits = (unsigned)(span >> (gx0 - rtx0 * 8));
+      // clear columns outside the image (dense mode sets every bit) and beyond the region
+      const int lo = max(0, -gx0), hi = min(GW, SW - gx0);  // valid columns in [lo, hi)
       unsigned m = hi >= 32 ? ~0u : ((1u << max(hi, 0)) - 1u);
       m &= ~((1u << lo) - 1u);
       bits &= m;
     }
-    s_rows[tid] = bits;
+    if (UPS) s_lrows[tid] = bits; else s_rows[tid] = bits;
   }
   __syncthreads();
+  if (UPS) {
+    // an up-sampled site is active where one of its four sources is: OR of two source rows, then
+    // of two source columns; sites outside the up-sampled image stay 0
+    if (tid < PH) {
+      const int iy = iy0 + tid;
+      unsigned bits = 0;
+      if ((unsigned)iy < (unsigned)H) {
+        const int hy = iy >> 1;
+        const int y0 = (iy & 1) ? hy : max(hy - 1, 0), y1 = (iy & 1) ? min(hy + 1, SH - 1) : hy;
+        const unsigned src = s_lrows[y0 - gy0] | s_lrows[y1 - gy0];
+        for (int px = 0; px < PW; ++px) {
+          const int ix = ix0 + px;
+          if ((unsigned)ix >= (unsigned)W) continue;
+          const int hx = ix >> 1;
+          const int x0 = (ix & 1) ? hx : max(hx - 1, 0), x1 = (ix & 1) ? min(hx + 1, SW - 1) : hx;
+          bits |= (((src >> (x0 - gx0)) | (src >> (x1 - gx0))) & 1u) << px;
+        }
+      }
+      s_rows[tid] = bits;
+    }
+    __syncthreads();
+  }
 
   // touched word of this workgroup's rows (identical in all waves): OR of the K bit rows under a
   // site, then any of the K columns
@@ -195,60 +235,95 @@ void conv_mfma_kernel(ConvParams p) {
   }
 
   // ---- patch gather: per thread a fixed list of (LDS offset, byte offset into the input)
+  // The gathered region is the patch itself, or (UPS) its low-resolution source region, which
+  // goes to a second fp32 buffer behind the patch buffer.
   constexpr unsigned kOob = 0x80000000u;
-  const int total_v = PH * PW * NV;
-  const int pw_magic = (65536 + PW - 1) / PW;  // site / PW == (site * pw_magic) >> 16 for site < 441
-  int lds_off[MAXV];
-  unsigned g_off[MAXV];
+  float* const s_low = s_mem + PH * PW * CS;  // UPS only
+  const int total_v = GH * GW * NV;
+  const int gw_magic = (65536 + GW - 1) / GW;  // site / GW == (site * gw_magic) >> 16 for site < 441
+  int lds_off[MAXG];
+  unsigned g_off[MAXG];
 #pragma unroll
-  for (int j = 0; j < MAXV; ++j) {
+  for (int j = 0; j < MAXG; ++j) {
     const int e = tid + j * NT;
     lds_off[j] = -1;
     g_off[j] = kOob;
     if (e < total_v) {
       const int site = e / NV, v = e - site * NV;
-      const int py = (site * pw_magic) >> 16, px = site - py * PW;
-      lds_off[j] = BF16 ? site * CS + v * 2 : site * CS + v * 4;
-      if ((s_rows[py] >> px) & 1u) g_off[j] = (unsigned)((((iy0 + py) * W + ix0 + px) * Cin + v * 4) * 4);
+      const int py = (site * gw_magic) >> 16, px = site - py * GW;
+      lds_off[j] = UPS ? site * CSL + v * 4 : (BF16 ? site * CS + v * 2 : site * CS + v * 4);
+      const unsigned row = UPS ? s_lrows[py] : s_rows[py];
+      if ((row >> px) & 1u) g_off[j] = (unsigned)((((gy0 + py) * SW + gx0 + px) * Cin + v * 4) * 4);
     }
   }
   const __amdgpu_buffer_rsrc_t in_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc((void*)at_stream(p.in, so), 0, H * W * Cin * 4, 0x00020000);
-  float4 pre[MAXV];
+      __builtin_amdgcn_make_buffer_rsrc((void*)at_stream(p.in, so), 0, SH * SW * Cin * 4, 0x00020000);
+  float4 pre[MAXG];
   // c_in need not be a multiple of the chunk: channel groups beyond c_in read as zeros (their
   // weight rows are zero padding as well)
   const bool ragged = (Cin % CHUNK) != 0;
   auto fetch = [&](int c0) {
 #pragma unroll
-    for (int j = 0; j < MAXV; ++j) {
+    for (int j = 0; j < MAXG; ++j) {
       unsigned off = g_off[j];
       if (ragged && c0 + ((tid + j * NT) % NV) * 4 >= Cin) off = kOob;
       pre[j] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(in_rsrc, off, c0 * 4, 0));
     }
   };
+  // one float4 of patch channels into the patch buffer, in the operand mode's format
+  auto put = [&](int off, const float4& x) {
+    if (SPLIT) {
+      // x = hi + lo + O(2^-17 |x|): hi = bf16(x), lo = bf16(x - hi)
+      uint2 h, l;
+      h.x = pack_bf16x2(x.x, x.y);
+      h.y = pack_bf16x2(x.z, x.w);
+      l.x = pack_bf16x2(x.x - __uint_as_float(h.x << 16), x.y - __uint_as_float(h.x & 0xffff0000u));
+      l.y = pack_bf16x2(x.z - __uint_as_float(h.y << 16), x.w - __uint_as_float(h.y & 0xffff0000u));
+      *(uint2*)&s_mem[off] = h;
+      *(uint2*)&s_mem[off + LO] = l;
+    } else if (BF16) {
+      uint2 w;
+      w.x = pack_bf16x2(x.x, x.y);
+      w.y = pack_bf16x2(x.z, x.w);
+      *(uint2*)&s_mem[off] = w;
+    } else {
+      *(float4*)&s_mem[off] = x;
+    }
+  };
   auto stash = [&]() {
 #pragma unroll
-    for (int j = 0; j < MAXV; ++j)
+    for (int j = 0; j < MAXG; ++j)
       if (lds_off[j] >= 0) {
-        if (SPLIT) {
-          // x = hi + lo + O(2^-17 |x|): hi = bf16(x), lo = bf16(x - hi)
-          const float4 x = pre[j];
-          uint2 h, l;
-          h.x = pack_bf16x2(x.x, x.y);
-          h.y = pack_bf16x2(x.z, x.w);
-          l.x = pack_bf16x2(x.x - __uint_as_float(h.x << 16), x.y - __uint_as_float(h.x & 0xffff0000u));
-          l.y = pack_bf16x2(x.z - __uint_as_float(h.y << 16), x.w - __uint_as_float(h.y & 0xffff0000u));
-          *(uint2*)&s_mem[lds_off[j]] = h;
-          *(uint2*)&s_mem[lds_off[j] + LO] = l;
-        } else if (BF16) {
-          uint2 w;
-          w.x = pack_bf16x2(pre[j].x, pre[j].y);
-          w.y = pack_bf16x2(pre[j].z, pre[j].w);
-          *(uint2*)&s_mem[lds_off[j]] = w;
-        } else {
-          *(float4*)&s_mem[lds_off[j]] = pre[j];
-        }
+        if (UPS) *(float4*)&s_low[lds_off[j]] = pre[j];
+        else put(lds_off[j], pre[j]);
       }
+  };
+  // UPS: every patch element from its four sources in the low-resolution buffer, with the
+  // weights and the summation order of the stand-alone up-sampling operator
+  const int pw_magic = (65536 + PW - 1) / PW;
+  auto interpolate = [&]() {
+    for (int e = tid; e < PH * PW * NV; e += NT) {
+      const int site = e / NV, v = e - site * NV;
+      const int py = (site * pw_magic) >> 16, px = site - py * PW;
+      const int iy = iy0 + py, ix = ix0 + px;
+      float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+      if ((unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W && ((s_rows[py] >> px) & 1u)) {
+        const int hy = iy >> 1, hx = ix >> 1;
+        const int y0 = ((iy & 1) ? hy : max(hy - 1, 0)) - gy0, y1 = ((iy & 1) ? min(hy + 1, SH - 1) : hy) - gy0;
+        const int x0 = ((ix & 1) ? hx : max(hx - 1, 0)) - gx0, x1 = ((ix & 1) ? min(hx + 1, SW - 1) : hx) - gx0;
+        const float wy0 = (iy & 1) ? 0.75f : 0.25f, wy1 = 1.0f - wy0;
+        const float wx0 = (ix & 1) ? 0.75f : 0.25f, wx1 = 1.0f - wx0;
+        const float4 v00 = *(const float4*)&s_low[(y0 * GW + x0) * CSL + v * 4];
+        const float4 v01 = *(const float4*)&s_low[(y0 * GW + x1) * CSL + v * 4];
+        const float4 v10 = *(const float4*)&s_low[(y1 * GW + x0) * CSL + v * 4];
+        const float4 v11 = *(const float4*)&s_low[(y1 * GW + x1) * CSL + v * 4];
+        r.x = wy0 * (wx0 * v00.x + wx1 * v01.x) + wy1 * (wx0 * v10.x + wx1 * v11.x);
+        r.y = wy0 * (wx0 * v00.y + wx1 * v01.y) + wy1 * (wx0 * v10.y + wx1 * v11.y);
+        r.z = wy0 * (wx0 * v00.z + wx1 * v01.z) + wy1 * (wx0 * v10.z + wx1 * v11.z);
+        r.w = wy0 * (wx0 * v00.w + wx1 * v01.w) + wy1 * (wx0 * v10.w + wx1 * v11.w);
+      }
+      put(BF16 && !SPLIT ? site * CS + v * 2 : (SPLIT ? site * CS + v * 2 : site * CS + v * 4), r);
+    }
   };
 
   floatx16 acc0, acc1;
@@ -349,6 +424,10 @@ void conv_mfma_kernel(ConvParams p) {
     __syncthreads();  // all waves are done reading the previous chunk
     stash();
     __syncthreads();
+    if (UPS) {
+      interpolate();
+      __syncthreads();
+    }
     const bool more = c0 + CHUNK < Cin;
     if (more) fetch(c0 + CHUNK);  // next chunk's patch, in flight during the contraction
     if (n_mine <= 0) continue;    // more waves than units (1 x 1 taps): only help with the gather
@@ -506,9 +585,16 @@ void launch_variant(const ConvParams& p, hipStream_t s) {
   const int PH = (4 * MB - 1) * p.stride + p.k, PW = 7 * p.stride + p.k;
   size_t lds = (size_t)PH * PW * (OPM == kOpBf16 ? CHUNK / 2 + 4 : CHUNK + 4) * sizeof(float);
   const size_t part = (size_t)4 * MB * 16 * 64 * sizeof(float);  // partial sums reuse the patch
-  if (lds < part) lds = part;
   dim3 grid(p.go.tiles() * (2 / MB), p.go.c / 32, p.st.n);
-  hipLaunchKernelGGL((conv_mfma_kernel<CHUNK, NW, OPM, MB>), grid, dim3(NW * 64), lds, s, p);
+  if (CHUNK == 32 && p.upsample) {
+    // the low-resolution source region behind the patch buffer
+    lds += (size_t)(PH / 2 + 3) * (PW / 2 + 3) * (CHUNK + 4) * sizeof(float);
+    if (lds < part) lds = part;
+    hipLaunchKernelGGL((conv_mfma_kernel<CHUNK, NW, OPM, MB, CHUNK == 32>), grid, dim3(NW * 64), lds, s, p);
+    return;
+  }
+  if (lds < part) lds = part;
+  hipLaunchKernelGGL((conv_mfma_kernel<CHUNK, NW, OPM, MB, false>), grid, dim3(NW * 64), lds, s, p);
 }
 
 // share of the chip's 256 CUs kept busy when n equally long workgroups run at once
@@ -545,6 +631,10 @@ void launch_any(const ConvParams& p, hipStream_t s) {
 bool conv_mfma_f32_supported(const ConvParams& p) {
   return p.gi.c % 4 == 0 && p.gi.c >= 16 && p.go.c % 32 == 0 && p.c_out_pad == p.go.c &&
          (long long)p.gi.h * p.gi.w * p.gi.c * 4 < (1ll << 31);  // byte offsets of the gather fit 31 bits
+}
+// a bilinear x2 up-sampling in front of this conv can be folded into its gather
+bool conv_mfma_upsample_supported(const ConvParams& p) {
+  return conv_mfma_f32_supported(p) && chunk_for(p) == 32 && p.stride == 1 && p.k <= 7;
 }
 // input channels of the re-laid weights: c_in rounded up to whole chunks of the variant that runs
 int conv_mfma_padded_cin(const ConvParams& p) {

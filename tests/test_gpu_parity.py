@@ -105,6 +105,7 @@ def test_unet_full_width_reduced_size_matrix_core_layers():
     g.destroy()
     assert names.count("conv_mfma_f32") == 10 and names[0] == "conv_narrow_mfma_f32" and names[-1] == "conv_pointwise_f32", names
     assert names.count("fused_into_conv_epilogue") == 6, names   # 2 residual adds + 4 skip adds
+    assert names.count("fused_into_conv_gather") == 3, names     # the three x2 up-samplings
     frames = list(wl.stream_voxel(1003, 64, 96, 20, 0.02, n_prim=6))
     run_stream(net, frames[0], frames[1:], "frame", label="unet-wide", max_flips=40)
 
@@ -117,7 +118,7 @@ def test_unet_full_width_without_epilogue_fusion(monkeypatch):
     g = ev.EvConvNet(net)
     names = [g.kernel_name(i) for i in range(len(net.nodes))]
     g.destroy()
-    assert "fused_into_conv_epilogue" not in names
+    assert "fused_into_conv_epilogue" not in names and "fused_into_conv_gather" not in names
     frames = list(wl.stream_voxel(1003, 64, 96, 8, 0.02, n_prim=6))
     run_stream(net, frames[0], frames[1:], "frame", label="unet-wide-unfused", max_flips=40)
 
@@ -286,8 +287,9 @@ def test_run_to_run_bit_reproducible():
             g.step_frame(_dev(f))
         import torch
         torch.cuda.synchronize()
-        res.append([g.state(i, ev.STATE_DY).copy() for i in range(len(net.nodes))] +
-                   [g.outputs()[0]["y"].cpu().numpy()] + [g.site_list(i) for i in range(len(net.nodes))])
+        stored = [i for i in range(len(net.nodes)) if g.kernel_name(i) != "fused_into_conv_gather"]
+        res.append([g.state(i, ev.STATE_DY).copy() for i in stored] +
+                   [g.outputs()[0]["y"].cpu().numpy()] + [g.site_list(i) for i in stored])
         g.destroy()
     for u, v in zip(*res):
         np.testing.assert_array_equal(u, v)
@@ -637,7 +639,7 @@ def test_streams_stepped_together_equal_single_stream_nets(which):
     singles = [ev.EvConvNet(net) for _ in range(3)]
     assert multi.n_streams == 3 and multi.stream_stride % 256 == 0
     ora = Oracle(net)
-    keeps = [i for i in range(len(net.nodes)) if multi.kernel_name(i) != "fused_into_conv_epilogue"]
+    keeps = [i for i in range(len(net.nodes)) if not multi.kernel_name(i).startswith("fused_into_conv")]
     for t in range(7):
         batch = _dev(np.stack([gens[s][t] for s in range(3)]))
         if t == 0:
