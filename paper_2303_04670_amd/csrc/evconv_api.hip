@@ -498,7 +498,7 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
       const int k = n.d.kh, ci_n = n.d.c_in, co_n = n.d.c_out, cop = n.c_out_pad;
       ConvParams probe;
       probe.gi = n.ga; probe.go = n.go; probe.k = k; probe.stride = n.d.stride; probe.c_out_pad = cop;
-      probe.n_fused = 0; probe.pad = n.d.pad;
+      probe.n_fused = 0; probe.pad = n.d.pad; probe.st = Streams{L.stride, L.n_streams};
       const bool force_valu = getenv("EVCONV_FORCE_VALU") != nullptr;
       if (!force_valu && n.d.wdtype == EVCONV_F32 && conv_mfma_f32_supported(probe)) n.kernel = kKernConvMfmaF32;
       if (!force_valu && n.d.wdtype == EVCONV_BF16 && conv_mfma_bf16_supported(probe)) n.kernel = kKernConvMfmaBf16;
@@ -627,6 +627,7 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
       ConvParams probe;
       probe.gi = c_node.ga; probe.go = c_node.go; probe.k = c_node.d.kh; probe.stride = c_node.d.stride;
       probe.c_out_pad = c_node.c_out_pad; probe.n_fused = 0; probe.pad = c_node.d.pad;
+      probe.st = Streams{L.stride, L.n_streams};
       if (!conv_mfma_upsample_supported(probe)) continue;
       u_node.gather_fused_into = (int)i;
       c_node.upsampled_from = u_node.d.in0;

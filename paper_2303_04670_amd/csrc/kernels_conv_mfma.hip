@@ -72,11 +72,11 @@ __device__ __forceinline__ unsigned bf16_bits(float x) {
 }
 __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) { return bf16_bits(lo) | (bf16_bits(hi) << 16); }
 
-// Largest halo patch (sites) a variant can meet: 64-channel chunks are used with stride 1 and
-// taps <= 3, 32-channel chunks with stride 1 (taps <= 7), 16-channel chunks also with stride 2.
+// Largest halo patch (sites) a variant can meet: 64- and 128-channel chunks are used with stride 1
+// and taps <= 3, 32-channel chunks with stride 1 (taps <= 7), 16-channel chunks also with stride 2.
 constexpr int max_patch_sites(int chunk, int mb) {
   const int rows = 4 * mb - 1;
-  return chunk == 64 ? (rows + 3) * 10 : chunk == 32 ? (rows + 7) * 14 : (rows * 2 + 7) * 21;
+  return chunk >= 64 ? (rows + 3) * 10 : chunk == 32 ? (rows + 7) * 14 : (rows * 2 + 7) * 21;
 }
 
 // The register budget is held to 4 (half tiles) or 3 (whole tiles) waves per SIMD: the bf16 and
@@ -575,6 +575,10 @@ void conv_mfma_kernel(ConvParams p) {
 }
 
 int chunk_for(const ConvParams& p) {
+  // low-resolution layers (few workgroups, always 8 waves): 128-channel chunks halve the number of
+  // gather round trips, which is what these latency-bound launches consist of
+  if (p.stride == 1 && p.k <= 3 && p.gi.c % 128 == 0 &&
+      (long long)p.go.tiles() * (p.go.c / 32) * p.st.n * 2 < 512) return 128;
   if (p.stride == 1 && p.k <= 3 && p.gi.c % 64 == 0) return 64;
   if (p.stride == 1 && (p.gi.c % 32 == 0 || (p.gi.c % 16 != 0 && p.gi.c > 32))) return 32;  // ragged: fewer, padded chunks
   return 16;
@@ -610,16 +614,22 @@ void launch_shape(const ConvParams& p, hipStream_t s) {
   if (const char* e = getenv("EVK_MB")) halves = atoi(e) == 1;
   if (const char* e = getenv("EVK_NW")) eight = atoi(e) == 8;
 #endif
+  if (CHUNK == 128) {  // chosen only for few workgroups: the 4-wave variants are not built
+    if (halves) launch_variant<CHUNK, 8, OPM, 1>(p, s); else launch_variant<CHUNK, 8, OPM, 2>(p, s);
+    return;
+  }
+  constexpr int NW4 = CHUNK == 128 ? 8 : 4;
   if (halves) {
-    if (eight) launch_variant<CHUNK, 8, OPM, 1>(p, s); else launch_variant<CHUNK, 4, OPM, 1>(p, s);
+    if (eight) launch_variant<CHUNK, 8, OPM, 1>(p, s); else launch_variant<CHUNK, NW4, OPM, 1>(p, s);
   } else {
-    if (eight) launch_variant<CHUNK, 8, OPM, 2>(p, s); else launch_variant<CHUNK, 4, OPM, 2>(p, s);
+    if (eight) launch_variant<CHUNK, 8, OPM, 2>(p, s); else launch_variant<CHUNK, NW4, OPM, 2>(p, s);
   }
 }
 
 template <int OPM>
 void launch_any(const ConvParams& p, hipStream_t s) {
   switch (chunk_for(p)) {
+    case 128: launch_shape<128, OPM>(p, s); break;
     case 64: launch_shape<64, OPM>(p, s); break;
     case 32: launch_shape<32, OPM>(p, s); break;
     default: launch_shape<16, OPM>(p, s); break;
