@@ -566,3 +566,36 @@ def stream_count_timestamp(seed=1005, h=256, w=256, densities=None, steps_per=10
 def changed_fraction(a: np.ndarray, b: np.ndarray) -> float:
     """Fraction of pixels at which two C x H x W frames differ (diagnostic for recipes)."""
     return float(np.any(a != b, axis=0).mean())
+
+
+def net_random_wide(seed, h=24, w=40) -> Net:
+    """A random encoder-decoder-like graph over the ops of the matrix-core paths (tests only):
+    channel counts that are multiples of 4 including ragged ones (20, 36, 68), kernels 1/3/5,
+    strides 1/2, residual and skip adds, x2 up-sampling straight into a convolution, concat,
+    gates (sigmoid x tanh), a prediction head."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    b = _NetBuilder(f"random_wide_{seed}", int(rng.choice([3, 4, 5])), h, w, seed + 1000, bias=bool(rng.integers(0, 2)))
+    chans = [16, 20, 32, 36, 48, 64, 68]
+    c0 = 32 * int(rng.integers(1, 3))
+    x = b.conv(-1, c0, int(rng.choice([3, 5])), 1)                      # narrow-input layer
+    full = [x]
+    c1 = 32 * int(rng.integers(1, 4))
+    y = b.conv(x, c1, int(rng.choice([3, 5])), 2)                       # down
+    for _ in range(int(rng.integers(1, 3))):                            # residual blocks at half resolution
+        r = b.conv(y, c1, 3, 1)
+        r = b.conv(r, c1, int(rng.choice([1, 3])), 1, act=ACT_NONE)
+        y = b.simple(OP_ADD, y, r, act=ACT_RELU)
+    if rng.integers(0, 2):                                              # a gate
+        g = b.conv(y, c1, 1, 1, 0, act=ACT_SIGMOID)
+        t = b.conv(y, c1, 3, 1, act=ACT_TANH)
+        y = b.simple(OP_MUL, g, t)
+    cm = int(rng.choice(chans))
+    if cm % 32:                                                         # ragged channel count into the matrix cores
+        y = b.conv(y, 32, 3, 1)
+        cat = b.simple(OP_CONCAT, y, b.conv(y, cm - 32 if cm > 32 else 4, 1, 1, 0))
+        y = b.conv(cat, c1, 3, 1)
+    u = b.simple(OP_UPSAMPLE2X, y)                                      # straight into a conv: folded into its gather
+    d = b.conv(u, c0, int(rng.choice([3, 5])), 1, act=ACT_NONE)
+    d = b.simple(OP_ADD, d, full[0], act=ACT_RELU)                      # skip add in the conv epilogue
+    b.conv(d, int(rng.choice([1, 2, 3])), 1, 1, 0, int(rng.choice([ACT_NONE, ACT_SIGMOID])), out=1)
+    return b.finish()

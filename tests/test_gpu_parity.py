@@ -1,6 +1,7 @@
 """GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element, on the
 same seeded inputs.  Integer products bit-exact (with counted rounding flips of value-pruned
 sets, see oracle/compare.py); fp32 tensors within 1e-4 * max|tensor| of the fp64 oracle."""
+import dataclasses
 import sys
 
 import numpy as np
@@ -725,3 +726,35 @@ def test_step_captured_in_a_hip_graph_replays_bit_identically():
     del graph
     eager.destroy()
     captured.destroy()
+
+
+# --------------------------------------------------------------------------- random graphs
+
+@pytest.mark.parametrize("seed", range(9))
+def test_random_wide_graphs_all_contraction_modes(seed):
+    """Random graphs over the matrix-core paths (ragged channel counts, fused epilogue adds, fused
+    up-sampling gather, gates, heads), each in one of the three contraction modes, all nodes at
+    every step against the oracle."""
+    rng = np.random.default_rng(100 + seed)
+    mode = ["f32", "split", "bf16"][seed % 3]
+    net = wl.net_random_wide(seed)
+    if mode == "bf16":
+        net = wl.with_weight_dtype(dataclasses.replace(net, weights=wl.round_to_bf16(net.weights)), wl.WD_BF16)
+    elif mode == "split":
+        net = wl.with_weight_dtype(net, wl.WD_F32_SPLIT)
+    _say(f"random wide graph {seed}: {len(net.nodes)} nodes, {mode}")
+    g = ev.EvConvNet(net)
+    names = [g.kernel_name(i) for i in range(len(net.nodes))]
+    g.destroy()
+    want = {"f32": "conv_mfma_f32", "split": "conv_mfma_f32_split_bf16x3", "bf16": "conv_mfma_bf16"}[mode]
+    assert names.count(want) >= 4 and "fused_into_conv_gather" in names and "fused_into_conv_epilogue" in names, names
+    x = rng.standard_normal((net.in_c, net.in_h, net.in_w)).astype(np.float32)
+    frames = [x]
+    for t in range(6):
+        m = rng.random((1, net.in_h, net.in_w)) < (0.04 if t != 3 else 0.6)
+        x = (x + rng.standard_normal(x.shape).astype(np.float32) * m).astype(np.float32)
+        frames.append(x)
+    if mode == "bf16":
+        run_stream(net, frames[0], frames[1:], "frame", tol=2e-2, label=f"wide{seed}", max_flips=10**9, frobenius=True)
+    else:
+        run_stream(net, frames[0], frames[1:], "frame", label=f"wide{seed}", max_flips=40)
