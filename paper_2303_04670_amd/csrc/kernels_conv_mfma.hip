@@ -56,6 +56,9 @@ constexpr int kOpSplit = 2;  // fp32 operands split into bf16 high + low parts, 
 
 // one weight fragment of a lane; .l is the low-part plane in split mode, unused otherwise
 struct BFrag { float4 h, l; };
+// one patch fragment of a lane: both 32-row blocks (h1: second block, two-block workgroups only)
+// and their low parts (split mode only)
+struct AFrag { float4 h0, h1, l0, l1; };
 
 __device__ __forceinline__ float act_m(int act, float v) {
   if (act == kActRelu) return fmaxf(v, 0.0f);
@@ -90,7 +93,7 @@ constexpr int max_patch_sites(int chunk, int mb) {
 // p.lo_w the stored one; p.occ_in are the stored tensor's occupancy words, and an up-sampled
 // site is active where one of its four sources is.
 template <int CHUNK, int NW, int OPM, int MB, bool UPS>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(MB == 1 ? 4 : 3)))
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(MB == 1 && !(UPS && NW == 4) ? 4 : 3)))
 void conv_mfma_kernel(ConvParams p) {
   // this workgroup's stream: every state pointer of p is used through at_stream(.., so); p itself
   // stays untouched so that it remains in the kernel-argument segment
@@ -300,29 +303,72 @@ void conv_mfma_kernel(ConvParams p) {
   };
   // UPS: every patch element from its four sources in the low-resolution buffer, with the
   // weights and the summation order of the stand-alone up-sampling operator
-  const int pw_magic = (65536 + PW - 1) / PW;
-  auto interpolate = [&]() {
-    for (int e = tid; e < PH * PW * NV; e += NT) {
-      const int site = e / NV, v = e - site * NV;
-      const int py = (site * pw_magic) >> 16, px = site - py * PW;
-      const int iy = iy0 + py, ix = ix0 + px;
-      float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
-      if ((unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W && ((s_rows[py] >> px) & 1u)) {
-        const int hy = iy >> 1, hx = ix >> 1;
-        const int y0 = ((iy & 1) ? hy : max(hy - 1, 0)) - gy0, y1 = ((iy & 1) ? min(hy + 1, SH - 1) : hy) - gy0;
-        const int x0 = ((ix & 1) ? hx : max(hx - 1, 0)) - gx0, x1 = ((ix & 1) ? min(hx + 1, SW - 1) : hx) - gx0;
-        const float wy0 = (iy & 1) ? 0.75f : 0.25f, wy1 = 1.0f - wy0;
-        const float wx0 = (ix & 1) ? 0.75f : 0.25f, wx1 = 1.0f - wx0;
-        const float4 v00 = *(const float4*)&s_low[(y0 * GW + x0) * CSL + v * 4];
-        const float4 v01 = *(const float4*)&s_low[(y0 * GW + x1) * CSL + v * 4];
-        const float4 v10 = *(const float4*)&s_low[(y1 * GW + x0) * CSL + v * 4];
-        const float4 v11 = *(const float4*)&s_low[(y1 * GW + x1) * CSL + v * 4];
-        r.x = wy0 * (wx0 * v00.x + wx1 * v01.x) + wy1 * (wx0 * v10.x + wx1 * v11.x);
-        r.y = wy0 * (wx0 * v00.y + wx1 * v01.y) + wy1 * (wx0 * v10.y + wx1 * v11.y);
-        r.z = wy0 * (wx0 * v00.z + wx1 * v01.z) + wy1 * (wx0 * v10.z + wx1 * v11.z);
-        r.w = wy0 * (wx0 * v00.w + wx1 * v01.w) + wy1 * (wx0 * v10.w + wx1 * v11.w);
+  //
+  // Work item = one 2 x 2 block of up-sampled sites (rows 2i+1, 2i+2, columns 2j+1, 2j+2) x four
+  // channels: its four values come from the same four stored sites (rows i, i+1, columns j, j+1,
+  // clamped to the image), so the four reads and the two horizontal sums per stored row are
+  // shared; a site without an active source comes out as zero because inactive sources are
+  // stored as zeros.  The items of a thread are the same for every chunk: offsets and masks are
+  // worked out once (this arithmetic would otherwise take vector-ALU time from the fp32 matrix
+  // instructions, which run on the same pipeline).
+  constexpr int MAXB = UPS ? (8 * (MB == 2 ? 8 : 6) * NV + NT - 1) / NT : 1;  // <= 8 x 8 blocks (K <= 7)
+  // per item two packed words: ib_src = source offset (12 bits) | row step (10) | column step (6);
+  // ib_dst = patch offset + 4096 (16 bits) | write mask (4) | inside-the-image mask (4)
+  int ib_src[MAXB], ib_dst[MAXB];
+  if (UPS) {
+    const int by0 = (iy0 - 1) >> 1, bx0 = (ix0 - 1) >> 1;
+    const int nby = ((iy0 + PH - 2) >> 1) - by0 + 1, nbx = ((ix0 + PW - 2) >> 1) - bx0 + 1;
+    const int nbx_magic = (65536 + nbx - 1) / nbx;  // blk / nbx == (blk * nbx_magic) >> 16 for blk < 64
+#pragma unroll
+    for (int b = 0; b < MAXB; ++b) {
+      const int e = tid + b * NT;
+      const int blk = e / NV, v = e - blk * NV;
+      ib_src[b] = ib_dst[b] = 0;
+      if (blk < nby * nbx) {
+        const int bi = (blk * nbx_magic) >> 16, bj = blk - bi * nbx;
+        const int i = by0 + bi, j = bx0 + bj;
+        const int cy0 = min(max(i, 0), SH - 1), cy1 = min(max(i + 1, 0), SH - 1);
+        const int cx0 = min(max(j, 0), SW - 1), cx1 = min(max(j + 1, 0), SW - 1);
+        ib_src[b] = (((cy0 - gy0) * GW + (cx0 - gx0)) * CSL + v * 4) | (((cy1 - cy0) * GW * CSL) << 12) |
+                    (((cx1 - cx0) * CSL) << 22);
+        const int py = 2 * i + 1 - iy0, px = 2 * j + 1 - ix0;  // patch coordinates of the block, -1 at least
+        const int dst = (py * PW + px) * CS + v * (BF16 ? 2 : 4) + 4096;
+        int mask = 0;
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+          for (int c = 0; c < 2; ++c) {
+            const bool in_patch = py + r >= 0 && py + r < PH && px + c >= 0 && px + c < PW;
+            const bool in_image = (unsigned)(iy0 + py + r) < (unsigned)H && (unsigned)(ix0 + px + c) < (unsigned)W;
+            if (in_patch) mask |= 1 << (r * 2 + c);
+            if (in_patch && in_image) mask |= 16 << (r * 2 + c);
+          }
+        ib_dst[b] = dst | (mask << 16);
       }
-      put(BF16 && !SPLIT ? site * CS + v * 2 : (SPLIT ? site * CS + v * 2 : site * CS + v * 4), r);
+    }
+  }
+  auto interpolate = [&]() {
+#pragma unroll
+    for (int b = 0; b < MAXB; ++b) {
+      const int mask = ib_dst[b] >> 16;
+      if (mask == 0) continue;
+      const float* q = &s_low[ib_src[b] & 0xfff];
+      const int dy = (ib_src[b] >> 12) & 0x3ff, dx = ib_src[b] >> 22;
+      const float4 v00 = *(const float4*)q, v01 = *(const float4*)(q + dx);
+      const float4 v10 = *(const float4*)(q + dy), v11 = *(const float4*)(q + dy + dx);
+      // horizontal sums of the two stored rows for the odd (a) and the even (b) column, then the
+      // vertical ones: the same products and order as wy0 * (wx0 * v00 + wx1 * v01) + wy1 * (...)
+      auto hsum = [](float w0, const float4& l, float w1, const float4& r) {
+        return make_float4(w0 * l.x + w1 * r.x, w0 * l.y + w1 * r.y, w0 * l.z + w1 * r.z, w0 * l.w + w1 * r.w);
+      };
+      const float4 a0 = hsum(0.75f, v00, 0.25f, v01), b0 = hsum(0.25f, v00, 0.75f, v01);
+      const float4 a1 = hsum(0.75f, v10, 0.25f, v11), b1 = hsum(0.25f, v10, 0.75f, v11);
+      const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+      const int dst = (ib_dst[b] & 0xffff) - 4096;
+      if (mask & 1) put(dst, (mask & 16) ? hsum(0.75f, a0, 0.25f, a1) : zero);
+      if (mask & 2) put(dst + CS, (mask & 32) ? hsum(0.75f, b0, 0.25f, b1) : zero);
+      if (mask & 4) put(dst + PW * CS, (mask & 64) ? hsum(0.25f, a0, 0.75f, a1) : zero);
+      if (mask & 8) put(dst + (PW + 1) * CS, (mask & 128) ? hsum(0.25f, b0, 0.75f, b1) : zero);
     }
   };
 
@@ -367,23 +413,31 @@ void conv_mfma_kernel(ConvParams p) {
     f.l = SPLIT ? q[w_plane] : f.h;
     return f;
   };
-  auto unit = [&](int j, const BFrag& bf) {
+  // A fragment of unit j (clamped like the B fragments): the patch values of this lane's site
+  // for both 32-row blocks, and their low parts in split mode; unused members cost nothing
+  auto a_load = [&](int j) {
+    AFrag f;
+    const float* ap = &s_mem[a_off(min(j, last))];
+    f.h0 = *(const float4*)ap;
+    f.h1 = MB == 2 ? *(const float4*)(ap + a_blk1) : f.h0;
+    f.l0 = SPLIT ? *(const float4*)(ap + LO) : f.h0;
+    f.l1 = (SPLIT && MB == 2) ? *(const float4*)(ap + a_blk1 + LO) : f.h0;
+    return f;
+  };
+  auto unit = [&](const AFrag& af, const BFrag& bf) {
     const float4& b = bf.h;
-    const float* ap = &s_mem[a_off(j)];
-    const float4 a0 = *(const float4*)ap;
-    float4 a1 = a0;
-    if (MB == 2) a1 = *(const float4*)(ap + a_blk1);
+    const float4 a0 = af.h0, a1 = af.h1;
     if (SPLIT) {
       // a * b ~ a_lo * b_hi + a_hi * b_lo + a_hi * b_hi (the low x low term, 2^-16 smaller, is dropped)
       const bf16x8 bh = __builtin_bit_cast(bf16x8, bf.h), bl = __builtin_bit_cast(bf16x8, bf.l);
       const bf16x8 a0h = __builtin_bit_cast(bf16x8, a0);
-      const bf16x8 a0l = __builtin_bit_cast(bf16x8, *(const float4*)(ap + LO));
+      const bf16x8 a0l = __builtin_bit_cast(bf16x8, af.l0);
       acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0l, bh, acc0, 0, 0, 0);
       acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, bl, acc0, 0, 0, 0);
       acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0h, bh, acc0, 0, 0, 0);
       if (MB == 2) {
         const bf16x8 a1h = __builtin_bit_cast(bf16x8, a1);
-        const bf16x8 a1l = __builtin_bit_cast(bf16x8, *(const float4*)(ap + a_blk1 + LO));
+        const bf16x8 a1l = __builtin_bit_cast(bf16x8, af.l1);
         acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1l, bh, acc1, 0, 0, 0);
         acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, bl, acc1, 0, 0, 0);
         acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1h, bh, acc1, 0, 0, 0);
@@ -431,17 +485,26 @@ void conv_mfma_kernel(ConvParams p) {
     const bool more = c0 + CHUNK < Cin;
     if (more) fetch(c0 + CHUNK);  // next chunk's patch, in flight during the contraction
     if (n_mine <= 0) continue;    // more waves than units (1 x 1 taps): only help with the gather
+    // fp32 and bf16 modes: the A fragments run one unit ahead of their use (three names, two alive
+    // at a time), so that an LDS read is in flight during the matrix instructions of the unit
+    // before it.  Split mode has no registers to spare for that and reads each fragment at its use.
+    constexpr bool APIPE = !SPLIT;
     int j = 0;
+    AFrag aq0 = a_load(0), aq1 = aq0, aq2 = aq0;
+    auto step = [&](AFrag& cur, AFrag& nxt, int jj, const BFrag& b) {
+      if (APIPE) nxt = a_load(jj + 1); else cur = a_load(jj);
+      unit(cur, b);
+    };
     for (; j + 3 <= n_mine; j += 3) {
       bq2 = b_load(c0, j + 2);
-      unit(j, bq0);
+      step(aq0, aq1, j, bq0);
       bq0 = b_load(c0, j + 3);
-      unit(j + 1, bq1);
+      step(aq1, aq2, j + 1, bq1);
       bq1 = b_load(c0, j + 4);
-      unit(j + 2, bq2);
+      step(aq2, aq0, j + 2, bq2);
     }
-    if (j < n_mine) unit(j, bq0);
-    if (j + 1 < n_mine) unit(j + 1, bq1);
+    if (j < n_mine) step(aq0, aq1, j, bq0);
+    if (j + 1 < n_mine) step(aq1, aq2, j + 1, bq1);
     if (more) {
       bq0 = b_load(c0 + CHUNK, 0);
       bq1 = b_load(c0 + CHUNK, 1);
@@ -607,7 +670,11 @@ double fill(long long n) { return (double)n / 256.0 / (double)((n + 255) / 256);
 template <int CHUNK, int OPM>
 void launch_shape(const ConvParams& p, hipStream_t s) {
   const long long n2 = (long long)p.go.tiles() * (p.go.c / 32) * p.st.n;  // workgroups with whole tiles
-  bool halves = fill(2 * n2) > fill(n2) + 0.05;                  // half tiles balance better
+  // Whole tiles (two accumulators per wave, every weight fragment used twice) pay off only when
+  // the launch fills the chip several times over and a workgroup has a long contraction; measured
+  // on the layers of the evaluation networks, half tiles win everywhere else (more, shorter
+  // workgroups: shorter prologues and patches, better balance)
+  bool halves = !(n2 >= 512 && p.k * p.k * p.gi.c >= 1600) || fill(2 * n2) > fill(n2) + 0.1;
   const long long n = halves ? 2 * n2 : n2;
   bool eight = n < 512;  // few workgroups: 8 waves each split K further
 #ifdef EVK_TUNE  // timing sweeps of the launch shape from a stand-alone harness
