@@ -383,35 +383,38 @@ void conv_mfma_kernel(ConvParams p) {
   const int cin_rows = BF16 ? cin_pad >> 3 : cin_pad >> 2;  // 16-byte weight rows per tap: 8 bf16 or 4 floats
   const int a_lane_off = (mly * s * PW + mlx * s) * CS + half * 4;
   const int a_blk1 = 4 * s * PW * CS;
-  const float4* __restrict__ wlane = (const float4*)p.w + (size_t)half * cop + co0 + m;
   // units of this wave: u_j = wave + j * NW, j < n_mine
   const int n_mine = (n_units - wave + NW - 1) / NW;
   const int last = n_mine - 1;
   const int k_magic = (65536 + K - 1) / K;  // tap / K == (tap * k_magic) >> 16 for tap < 49
 
-  // unit j of the chunk starting at channel c0 -> address of its B fragment (j clamped to the
-  // last unit so that look-ahead loads stay unconditional and in bounds)
-  auto b_ptr = [&](int c0, int j) {
+  // Both fragment addresses are a per-lane constant plus a per-unit part that is the same in all
+  // lanes; the latter is kept in scalar registers (pinned there with readfirstlane), so that a
+  // unit costs one vector add: vector-ALU time is taken from the fp32 matrix instructions.
+  // B: buffer load with the lane part as vector offset and the unit part as scalar offset
+  // (bytes; the launcher checks that the re-laid weights stay below 2 GiB).
+  const unsigned w_plane = (unsigned)(K * K * cin_rows * cop) * 16u;  // split mode: the low-part plane follows
+  const __amdgpu_buffer_rsrc_t w_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc((void*)p.w, 0, (int)(w_plane * (SPLIT ? 2u : 1u)), 0x00020000);
+  const unsigned w_lane = (unsigned)(half * cop + co0 + m) * 16u;
+  // unit j of the chunk starting at channel c0 (j clamped to the last unit so that look-ahead
+  // loads stay unconditional and in bounds)
+  auto b_load = [&](int c0, int j) {
     const int u = wave + min(j, last) * NW;
     const int tap = u / KG, kg = u % KG;
     const int row0 = BF16 ? (c0 >> 3) : (c0 >> 2);
-    return wlane + ((size_t)tap * cin_rows + row0 + kg * 2) * cop;
+    const unsigned soff = (unsigned)__builtin_amdgcn_readfirstlane(((tap * cin_rows + row0 + kg * 2) * cop) << 4);
+    BFrag f;
+    f.h = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, w_lane, soff, 0));
+    f.l = SPLIT ? __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, w_lane, soff + w_plane, 0)) : f.h;
+    return f;
   };
   // ... and LDS offset of its A fragment
   auto a_off = [&](int j) {
     const int u = wave + j * NW;
     const int tap = u / KG, kg = u % KG;
     const int ky = (tap * k_magic) >> 16, kx = tap - ky * K;
-    return a_lane_off + (ky * PW + kx) * CS + kg * 8;  // 8 words = 8 floats or 16 bf16
-  };
-  // split mode: the low-part weight plane follows the high-part plane
-  const size_t w_plane = SPLIT ? (size_t)K * K * cin_rows * cop : 0;
-  auto b_load = [&](int c0, int j) {
-    BFrag f;
-    const float4* q = b_ptr(c0, j);
-    f.h = *q;
-    f.l = SPLIT ? q[w_plane] : f.h;
-    return f;
+    return a_lane_off + __builtin_amdgcn_readfirstlane((ky * PW + kx) * CS + kg * 8);  // 8 words = 8 floats or 16 bf16
   };
   // A fragment of unit j (clamped like the B fragments): the patch values of this lane's site
   // for both 32-row blocks, and their low parts in split mode; unused members cost nothing
@@ -707,7 +710,8 @@ void launch_any(const ConvParams& p, hipStream_t s) {
 
 bool conv_mfma_f32_supported(const ConvParams& p) {
   return p.gi.c % 4 == 0 && p.gi.c >= 16 && p.go.c % 32 == 0 && p.c_out_pad == p.go.c &&
-         (long long)p.gi.h * p.gi.w * p.gi.c * 4 < (1ll << 31);  // byte offsets of the gather fit 31 bits
+         (long long)p.gi.h * p.gi.w * p.gi.c * 4 < (1ll << 31) &&  // byte offsets of the gather fit 31 bits
+         (long long)p.k * p.k * ((p.gi.c + 127) / 128 * 128) * p.go.c * 8 < (1ll << 31);  // and those of both weight planes
 }
 // a bilinear x2 up-sampling in front of this conv can be folded into its gather
 bool conv_mfma_upsample_supported(const ConvParams& p) {
