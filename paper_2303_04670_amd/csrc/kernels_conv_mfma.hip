@@ -223,19 +223,40 @@ void conv_mfma_kernel(ConvParams p) {
   if (site_word == 0) return;
   const bool conv_on = touched_word != 0;
 
-  // old z values of the epilogue, requested now so that they arrive during the contraction
+  // Epilogue addressing.  Thread = output channel co0 + tid % 32 at the EP_ITERS sites
+  // r0 * 8 + it * EP_SITES + tid / 32 (EP_SITES = 8 or 16: consecutive `it` are one or two tile rows
+  // apart).  Every tensor of the output geometry is reached as buffer + the byte offset of the
+  // thread's first site (one vector register for the whole kernel) + a scalar offset per `it`;
+  // an access that must not happen gets an out-of-range vector offset (loads return 0, stores are
+  // dropped).  The bits of a thread's sites are kept where they are in the 64-bit words, EP_SITES
+  // bits apart: no per-site shifts, no 64-bit address arithmetic on the vector ALU.
   const int co = tid & 31;
   const int co0 = blockIdx.y * 32;
+  const int es = tid >> 5;
+  const unsigned ep_voff =
+      (unsigned)((((tile_y * 8 + r0 + (es >> 3)) * p.go.w + tile_x * 8 + (es & 7)) * Cout + co0 + co) * 4);
+  const unsigned ep_step = (unsigned)((EP_SITES / 8) * p.go.w * Cout * 4);
+  const int out_bytes = p.go.h * p.go.w * Cout * 4;
+  constexpr unsigned kSkipAccess = 0x80000000u;
+  constexpr uint64_t kMine = EP_SITES == 8 ? 0x0101010101010101ull : 0x0001000100010001ull;
+  auto mine = [&](uint64_t w) { return (w >> (r0 * 8 + es)) & kMine; };   // bit it * EP_SITES: site `it`
+  auto has = [&](uint64_t sp, int it) { return ((sp >> (it * EP_SITES)) & 1ull) != 0; };
+  auto out_rsrc = [&](const void* ptr) {
+    return __builtin_amdgcn_make_buffer_rsrc((void*)ptr, 0, out_bytes, 0x00020000);
+  };
+  auto ep_load = [&](const __amdgpu_buffer_rsrc_t& r, bool on, int it) {
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, on ? ep_voff : kSkipAccess, it * ep_step, 0));
+  };
+  auto ep_store = [&](const __amdgpu_buffer_rsrc_t& r, int it, float v) {
+    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, ep_voff, it * ep_step, 0);
+  };
+  const uint64_t touched_mine = mine(touched_word), site_mine = mine(site_word);
+  const __amdgpu_buffer_rsrc_t z_rsrc = out_rsrc(at_stream(p.z, so));
+
+  // old z values of the epilogue, requested now so that they arrive during the contraction
   float z_old[EP_ITERS];
 #pragma unroll
-  for (int it = 0; it < EP_ITERS; ++it) {
-    const int site = r0 * 8 + it * EP_SITES + (tid >> 5);
-    z_old[it] = 0.0f;
-    if (!p.dense && ((touched_word >> site) & 1ull)) {
-      const int oy = tile_y * 8 + (site >> 3), ox = tile_x * 8 + (site & 7);
-      z_old[it] = at_stream(p.z, so)[((size_t)oy * p.go.w + ox) * Cout + co0 + co];
-    }
-  }
+  for (int it = 0; it < EP_ITERS; ++it) z_old[it] = ep_load(z_rsrc, !p.dense && has(touched_mine, it), it);
 
   // ---- patch gather: per thread a fixed list of (LDS offset, byte offset into the input)
   // The gathered region is the patch itself, or (UPS) its low-resolution source region, which
@@ -520,16 +541,16 @@ void conv_mfma_kernel(ConvParams p) {
 #pragma unroll
   for (int f = 0; f < kMaxFusedAdds; ++f) {
 #pragma unroll
-    for (int it = 0; it < EP_ITERS; ++it) {
-      f_skip[f][it] = 0.0f;
-      f_zold[f][it] = 0.0f;
-      if (f >= p.n_fused) continue;
-      const int site = r0 * 8 + it * EP_SITES + (tid >> 5);
-      if (!((site_word >> site) & 1ull)) continue;
-      const int oy = tile_y * 8 + (site >> 3), ox = tile_x * 8 + (site & 7);
-      const size_t q = ((size_t)oy * p.go.w + ox) * Cout + co0 + co;
-      if ((skip_word[f] >> site) & 1ull) f_skip[f][it] = at_stream(p.fused[f].skip, so)[q];
-      if (p.fused[f].keeps_z && !p.dense) f_zold[f][it] = at_stream(p.fused[f].z, so)[q];
+    for (int it = 0; it < EP_ITERS; ++it) f_skip[f][it] = f_zold[f][it] = 0.0f;
+    if (f >= p.n_fused) continue;
+    const uint64_t skip_mine = mine(skip_word[f]);
+    const __amdgpu_buffer_rsrc_t skip_rsrc = out_rsrc(at_stream(p.fused[f].skip, so));
+#pragma unroll
+    for (int it = 0; it < EP_ITERS; ++it) f_skip[f][it] = ep_load(skip_rsrc, has(skip_mine, it), it);
+    if (p.fused[f].keeps_z && !p.dense) {
+      const __amdgpu_buffer_rsrc_t fz_rsrc = out_rsrc(at_stream(p.fused[f].z, so));
+#pragma unroll
+      for (int it = 0; it < EP_ITERS; ++it) f_zold[f][it] = ep_load(fz_rsrc, has(site_mine, it), it);
     }
   }
 
@@ -559,33 +580,34 @@ void conv_mfma_kernel(ConvParams p) {
 
   // epilogue: thread -> (output channel = tid % 32, EP_ITERS sites); accumulator element
   // (block b, register i, lane l) is local site b*32 + 8*(i/4) + 4*(l/32) + i%4, channel l%32
-  uint64_t nz_sites = 0;
-  uint64_t nz_fused[kMaxFusedAdds] = {0, 0};
+  // (nonzero bits are collected where the thread's sites are, EP_SITES bits apart, and shifted to
+  // their place in the tile word once)
+  uint64_t nz_mine = 0;
+  uint64_t nz_fused_mine[kMaxFusedAdds] = {0, 0};
+  const __amdgpu_buffer_rsrc_t o_rsrc = out_rsrc(at_stream(p.out, so));
+  // partial sum of local site ls = it * EP_SITES + es: the part of the LDS offset that depends on
+  // the thread (es < 16), the rest is a constant per `it`
+  const int off_mine = ((es >> 3) * 4 + (es & 3)) * 64 + ((es >> 2) & 1) * 32 + co;
+  const float bias = (p.dense && p.bias) ? p.bias[co0 + co] : 0.0f;
 #pragma unroll
   for (int it = 0; it < EP_ITERS; ++it) {
-    const int ls = it * EP_SITES + (tid >> 5);  // site inside this workgroup's rows
-    const int site = r0 * 8 + ls;               // site inside the tile
-    if (!((site_word >> site) & 1ull)) continue;
-    const int oy = tile_y * 8 + (site >> 3), ox = tile_x * 8 + (site & 7);
-    const size_t q = ((size_t)oy * p.go.w + ox) * Cout + co0 + co;
+    if (!has(site_mine, it)) continue;
     float o = 0.0f;
-    if ((touched_word >> site) & 1ull) {
-      const int b = ls >> 5, r = ls & 31;
-      const int reg = (r >> 3) * 4 + (r & 3);
-      const int l = ((r >> 2) & 1) * 32 + co;
-      const int off = (b * 16 + reg) * 64 + l;
+    if (has(touched_mine, it)) {
+      constexpr int kRow = EP_SITES / 8;  // tile rows per `it`
+      const int off = off_mine + (((it * kRow) >> 2) * 16 + ((it * kRow) & 3) * 4) * 64;
       const float v = (s_mem[off] + s_mem[off + SLOT]) + (s_mem[off + 2 * SLOT] + s_mem[off + 3 * SLOT]);
       if (p.dense) {
-        const float z = v + (p.bias ? p.bias[co0 + co] : 0.0f);
-        at_stream(p.z, so)[q] = z;
+        const float z = v + bias;
+        ep_store(z_rsrc, it, z);
         o = act_m(p.act, z);
       } else {
         const float z_new = z_old[it] + v;
-        at_stream(p.z, so)[q] = z_new;
+        ep_store(z_rsrc, it, z_new);
         o = (p.act == kActNone) ? v : act_m(p.act, z_new) - act_m(p.act, z_old[it]);
       }
-      at_stream(p.out, so)[q] = o;
-      if (o != 0.0f) nz_sites |= 1ull << site;
+      ep_store(o_rsrc, it, o);
+      if (o != 0.0f) nz_mine |= 1ull << (it * EP_SITES);
     }
     // fused ADD nodes (Eq.11 followed by Eq.12-14): a = the value just produced, b = skip input
 #pragma unroll
@@ -594,22 +616,27 @@ void conv_mfma_kernel(ConvParams p) {
       const FusedAdd& fa = p.fused[f];
       const float lin = o + f_skip[f][it];
       if (fa.keeps_z) {
+        const __amdgpu_buffer_rsrc_t fz_rsrc = out_rsrc(at_stream(fa.z, so));
         if (p.dense) {
-          at_stream(fa.z, so)[q] = lin;
+          ep_store(fz_rsrc, it, lin);
           o = act_m(fa.act, lin);
         } else {
           const float z2_old = f_zold[f][it];
           const float z2_new = z2_old + lin;
-          at_stream(fa.z, so)[q] = z2_new;
+          ep_store(fz_rsrc, it, z2_new);
           o = (fa.act == kActNone) ? lin : act_m(fa.act, z2_new) - act_m(fa.act, z2_old);
         }
       } else {
         o = lin;
       }
-      at_stream(fa.out, so)[q] = o;
-      if (o != 0.0f) nz_fused[f] |= 1ull << site;
+      ep_store(out_rsrc(at_stream(fa.out, so)), it, o);
+      if (o != 0.0f) nz_fused_mine[f] |= 1ull << (it * EP_SITES);
     }
   }
+  const uint64_t nz_sites = nz_mine << (r0 * 8 + es);
+  uint64_t nz_fused[kMaxFusedAdds];
+#pragma unroll
+  for (int f = 0; f < kMaxFusedAdds; ++f) nz_fused[f] = nz_fused_mine[f] << (r0 * 8 + es);
   auto lds_or = [&](int slot, uint64_t bits) {
     if ((unsigned)bits) atomicOr(&s_nz[2 * slot], (unsigned)bits);
     if ((unsigned)(bits >> 32)) atomicOr(&s_nz[2 * slot + 1], (unsigned)(bits >> 32));
@@ -711,6 +738,7 @@ void launch_any(const ConvParams& p, hipStream_t s) {
 bool conv_mfma_f32_supported(const ConvParams& p) {
   return p.gi.c % 4 == 0 && p.gi.c >= 16 && p.go.c % 32 == 0 && p.c_out_pad == p.go.c &&
          (long long)p.gi.h * p.gi.w * p.gi.c * 4 < (1ll << 31) &&  // byte offsets of the gather fit 31 bits
+         (long long)(p.go.h + 8) * p.go.w * p.go.c * 4 < (1ll << 31) &&  // those of the epilogue too
          (long long)p.k * p.k * ((p.gi.c + 127) / 128 * 128) * p.go.c * 8 < (1ll << 31);  // and those of both weight planes
 }
 // a bilinear x2 up-sampling in front of this conv can be folded into its gather
