@@ -143,6 +143,12 @@ void conv_mfma_kernel(ConvParams p) {
   const int rty0 = gy0 >> 3, rtx0 = gx0 >> 3;
   const int rny = ((gy0 + GH - 1) >> 3) - rty0 + 1, rnx = ((gx0 + GW - 1) >> 3) - rtx0 + 1;
 
+  // occupancy words of the fused ADD nodes' other inputs: requested first, so that their latency
+  // runs alongside that of the input's occupancy words instead of after it
+  uint64_t skip_raw[kMaxFusedAdds];
+#pragma unroll
+  for (int f = 0; f < kMaxFusedAdds; ++f)
+    skip_raw[f] = (f < p.n_fused && !p.dense) ? at_stream(p.fused[f].occ_skip, so)[tile] : 0;
   if (tid < 16) {
     const int ry = tid >> 2, rx = tid & 3;
     const int ty = rty0 + ry, tx = rtx0 + rx;
@@ -217,7 +223,7 @@ void conv_mfma_kernel(ConvParams p) {
 #pragma unroll
   for (int f = 0; f < kMaxFusedAdds; ++f) {
     skip_word[f] = 0;
-    if (f < p.n_fused) skip_word[f] = p.dense ? touched_word : (at_stream(p.fused[f].occ_skip, so)[tile] & row_mask);
+    if (f < p.n_fused) skip_word[f] = p.dense ? touched_word : (skip_raw[f] & row_mask);
     site_word |= skip_word[f];
   }
   if (site_word == 0) return;
