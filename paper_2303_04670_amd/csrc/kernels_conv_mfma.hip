@@ -67,13 +67,15 @@ __device__ __forceinline__ float act_m(int act, float v) {
   return v;
 }
 
-// fp32 -> bf16, round to nearest even (NaN kept quiet); two values packed low/high
-__device__ __forceinline__ unsigned bf16_bits(float x) {
-  unsigned u = __float_as_uint(x);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
-  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+// fp32 -> bf16, round to nearest even, two values packed low/high: one v_cvt_pk_bf16_f32
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
+  floatx2 v;
+  v.x = lo;
+  v.y = hi;
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
 }
-__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) { return bf16_bits(lo) | (bf16_bits(hi) << 16); }
 
 // Largest halo patch (sites) a variant can meet: 64- and 128-channel chunks are used with stride 1
 // and taps <= 3, 32-channel chunks with stride 1 (taps <= 7), 16-channel chunks also with stride 2.
