@@ -266,21 +266,29 @@ def multi_stream_leg(args, np, torch, ev, wl, dev):
         net = wl.net_unet_depth(1003, h=H, w=W, bf16=(variant == "bf16"))
         if variant == "f32_split":
             net = wl.with_weight_dtype(net, wl.WD_F32_SPLIT)
-        g = ev.EvConvNet(net, device="cuda:0", n_streams=n)
-        g.reset(frames[0])
-        for t in range(1, 4):
-            g.step_frame(frames[t])
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for t in range(4, n_frames + 1):
-            g.step_frame(frames[t])
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
+        def run(mode):
+            g = ev.EvConvNet(net, device="cuda:0", n_streams=n)
+            g.set_mode(mode)
+            g.reset(frames[0])
+            for t in range(1, 4):
+                g.step_frame(frames[t])
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for t in range(4, n_frames + 1):
+                g.step_frame(frames[t])
+            torch.cuda.synchronize()
+            return g, time.perf_counter() - t0
+        g, dt = run(ev.MODE_INCREMENTAL)
         conv = [i for i, nd in enumerate(net.nodes) if nd.op == wl.OP_CONV2D]
         flops = sum(2.0 * net.nodes[i].k ** 2 * net.nodes[i].c_in * net.nodes[i].c_out * g.stats(i).n_touched for i in conv)
         g.destroy()
         res[variant] = {"value": n * steps / dt, "ms_per_call": dt / steps * 1e3,
                         "conv_tflops_alg": flops * n * steps / dt / 1e12}
+        if not args.no_dense:   # the same frames as regular forward passes through the same kernels
+            g, dt2 = run(ev.MODE_DENSE_RECOMPUTE)
+            g.destroy()
+            res[variant]["dense_recompute_ms_per_call"] = dt2 / steps * 1e3
+            res[variant]["incremental_speedup"] = dt2 / dt
     return res
 
 

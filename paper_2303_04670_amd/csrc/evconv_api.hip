@@ -304,6 +304,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
     }
     const bool timed = net->prof && 2 * (net->prof_node.size() + 1) <= net->prof_ev.size();
     if (timed) (void)hipEventRecord(net->prof_ev[2 * net->prof_node.size()], s);
+    bool integrated = false;  // an output node whose kernel keeps the public tensors itself
     switch (n.kernel) {
       case kKernConvValu:
       case kKernConvNarrow:
@@ -318,6 +319,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
         p.n_fused = n.n_fused;
         p.st = net->st;
         p.upsample = 0; p.lo_h = 0; p.lo_w = 0;
+        p.y = nullptr; p.dy = nullptr; p.int_mode = 0;
         if (n.upsampled_from != -2) {
           // read the stored low-resolution tensor; p.gi stays the up-sampled geometry
           const int src = n.upsampled_from;
@@ -337,6 +339,11 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
           fa.occ_skip = other < 0 ? net->occ_in : net->L.nodes[other].occ;
           fa.z = a_node.z; fa.out = a_node.out; fa.occ_out = a_node.occ; fa.occ_touched = a_node.touched;
           fa.act = a_node.d.act; fa.keeps_z = a_node.keeps_z; fa.structural = a_node.structural;
+        }
+        if (n.kernel == kKernConvPointwise && d.is_output && conv_pointwise_integrates(p)) {
+          p.y = n.y; p.dy = n.dy;
+          p.int_mode = pass == kPassStep ? kIntStep : pass == kPassReset ? kIntReset : kIntRecompute;
+          integrated = true;
         }
         if (n.kernel == kKernConvMfmaF32) launch_conv_mfma_f32(p, s);
         else if (n.kernel == kKernConvMfmaBf16) launch_conv_mfma_bf16(p, s);
@@ -389,7 +396,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
       (void)hipEventRecord(net->prof_ev[2 * net->prof_node.size() + 1], s);
       net->prof_node.push_back((int)i);
     }
-    if (d.is_output) {
+    if (d.is_output && !integrated) {
       IntegrateParams ip;
       ip.delta = n.out; ip.occ = n.occ; ip.y = n.y; ip.dy = n.dy; ip.g = n.go;
       ip.mode = pass == kPassStep ? kIntStep : pass == kPassReset ? kIntReset : kIntRecompute;

@@ -89,6 +89,10 @@ struct ConvParams {
   // matrix-core kernel only: the input is the bilinear x2 up-sampling of `in` (lo_h x lo_w stored
   // sites, occ_in their occupancy words); gi describes the up-sampled tensor
   int upsample, lo_h, lo_w;
+  // few-channel pointwise kernel only: the node is a network output and the kernel keeps the
+  // public tensors itself (y += increment, dy = increment; C x H x W); null otherwise.
+  // int_mode is one of kIntStep / kIntReset / kIntRecompute.
+  float* y; float* dy; int int_mode;
 };
 void launch_conv_valu(const ConvParams& p, hipStream_t s);
 // fp32 MFMA variant; requires c_in % 4 == 0, c_in >= 16 and c_out % 32 == 0.  The re-laid weights
@@ -105,6 +109,9 @@ bool conv_mfma_split_supported(const ConvParams& p);
 void launch_conv_mfma_split(const ConvParams& p, hipStream_t s);
 // 1 x 1 taps with at most 8 output channels, or LINEAR on a 1 x 1 grid; weights [c_out][c_in] fp32
 bool conv_pointwise_supported(const ConvParams& p);
+// true if launch_conv_pointwise(p) runs the per-tile kernel, which can also keep an output node's
+// public tensors (ConvParams::y, dy)
+bool conv_pointwise_integrates(const ConvParams& p);
 void launch_conv_pointwise(const ConvParams& p, hipStream_t s);
 // narrow-input variant: taps * c_in <= 128, c_out % 32 == 0; weights [padded k][c_out] fp32
 bool conv_narrow_supported(const ConvParams& p);

@@ -66,7 +66,16 @@ __global__ __launch_bounds__(256) void conv_pointwise_few_kernel(ConvParams p) {
     for (int r = 0; r < rows; ++r) m |= rowbits << (8 * r);
     touched_word = word & m;
   }
-  if (touched_word == 0) return;
+  // output node kept by this kernel: public tensors are C x H x W
+  const int hw = p.go.h * p.go.w;
+  float* const pub_y = p.y ? at_stream(p.y, so) : nullptr;
+  float* const pub_dy = p.dy ? at_stream(p.dy, so) : nullptr;
+  if (touched_word == 0) {
+    // nothing changed under this tile: the increment of its sites is zero
+    if (pub_dy && inb && q4 == 0)
+      for (int j = 0; j < Cout; ++j) pub_dy[(size_t)j * hw + oy * p.go.w + ox] = 0.0f;
+    return;
+  }
   __syncthreads();
 
   float acc[kMaxFew];
@@ -106,14 +115,31 @@ __global__ __launch_bounds__(256) void conv_pointwise_few_kernel(ConvParams p) {
     acc[j] += __shfl_xor(acc[j], 2);
   }
   bool nz = false;
-  if (on && q4 == 0) {
+  if (inb && q4 == 0) {
     float* z = at_stream(p.z, so);
     float* out = at_stream(p.out, so);
     const size_t q0 = ((size_t)oy * p.go.w + ox) * Cout;
 #pragma unroll
     for (int j = 0; j < kMaxFew; ++j) {
       if (j >= Cout) break;
-      nz |= finish_element(p, z, out, q0 + j, j, acc[j]) != 0.0f;
+      float o = 0.0f;
+      if (on) {
+        o = finish_element(p, z, out, q0 + j, j, acc[j]);
+        nz |= o != 0.0f;
+      }
+      if (pub_y) {  // the step's output and its increment, as the stand-alone integration writes them
+        const size_t e = (size_t)j * hw + oy * p.go.w + ox;
+        if (p.int_mode == kIntStep) {
+          if (on) pub_y[e] += o;
+          pub_dy[e] = o;
+        } else if (p.int_mode == kIntReset) {
+          pub_y[e] = o;
+          pub_dy[e] = 0.0f;
+        } else {
+          pub_dy[e] = o - pub_y[e];
+          pub_y[e] = o;
+        }
+      }
     }
   }
   if (nz) atomicOr(&s_nz[site >> 5], 1u << (site & 31));
@@ -149,6 +175,8 @@ __global__ __launch_bounds__(256) void linear_site_kernel(ConvParams p) {
 }
 
 }  // namespace
+
+bool conv_pointwise_integrates(const ConvParams& p) { return !(p.go.h == 1 && p.go.w == 1 && p.go.c > kMaxFew); }
 
 bool conv_pointwise_supported(const ConvParams& p) {
   if (p.k != 1 || p.stride != 1 || p.pad != 0 || p.n_fused != 0) return false;
