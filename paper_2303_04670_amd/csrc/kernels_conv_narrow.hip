@@ -237,7 +237,9 @@ void launch_conv_narrow(const ConvParams& p, hipStream_t s) {
   const int KP = conv_narrow_padded_k(p.k * p.k * p.gi.c);
   const int nb = (p.go.c % 64 == 0) ? 2 : 1;
   const size_t lds = ((size_t)KP * 32 * nb + (size_t)P * P * (p.gi.c | 1)) * sizeof(float);
-  dim3 grid(std::min(p.go.tiles(), std::max(1024 / p.st.n, 64)), p.go.c / (32 * nb), p.st.n);
+  // workgroups walk the tiles with the grid's stride; enough of them to fill the chip's resident
+  // slots (a tile is one chain of dependent memory round trips, so few long walks are slow)
+  dim3 grid(std::min(p.go.tiles(), std::max(4096 / p.st.n, 256)), p.go.c / (32 * nb), p.st.n);
   if (nb == 2) hipLaunchKernelGGL(conv_narrow_kernel<2>, grid, dim3(256), lds, s, p);
   else hipLaunchKernelGGL(conv_narrow_kernel<1>, grid, dim3(128), lds, s, p);
 }
