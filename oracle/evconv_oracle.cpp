@@ -40,6 +40,13 @@
 //     that both sides of a comparison use the identical step (the paper says "t_p times the L2
 //     norm of a rolling average of the input" without giving window or normalisation);
 //     k == 0 makes the layer the identity.
+//   * recurrence (the paper's evaluation networks are recurrent, "Experiments"; how a recurrent
+//     state is carried is not said): a DELAY node stands for "the value of a later node X at the
+//     previous step".  Its increment at step n is X's increment of step n-1, its mask X's mask
+//     of step n-1 (the state is one more input whose change is known); the state before the first
+//     frame is zero, so after a reset the first step's increment of the DELAY node is X's whole
+//     value, at every site.  A regular forward pass in mid-stream (refresh) keeps the recurrent
+//     state: the DELAY node then holds X's value of the previous step.
 //   * elementwise multiply (Eq.15-17) keeps the accumulated values of both inputs; the output
 //     increment uses the accumulators as they were before this step, then both are advanced;
 //     its mask is the OR of the input masks (Eq.16, structural, like addition).
@@ -58,7 +65,8 @@
 
 namespace {
 
-enum Op { OP_CONV = 0, OP_ADD, OP_CONCAT, OP_UP2X, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_ACT, OP_SPARSIFY, OP_MUL };
+enum Op { OP_CONV = 0, OP_ADD, OP_CONCAT, OP_UP2X, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_ACT, OP_SPARSIFY, OP_MUL,
+          OP_DELAY };  // OP_DELAY: in0 = the later node X it delays, in1 = an earlier node (or -1) with its height and width
 enum Act { ACT_NONE = 0, ACT_RELU, ACT_SIGMOID, ACT_TANH };
 
 struct NodeDesc {
@@ -117,6 +125,8 @@ struct Net {
   std::vector<T> x_dense;             // HWC copy of the frame for the dense pass
   std::vector<NodeState<T>> st;
   bool has_state = false;
+  bool last_dense = true;   // the previous pass was a regular forward pass (DELAY nodes)
+  bool first_pass = true;   // inside reset(): the recurrent state is zero
   double sparsify_tp = 0.0;
 
   const Shape& shape_of(int i) const { return i < 0 ? in : st[i].shp; }
@@ -144,8 +154,12 @@ struct Net {
       nd.op = d[0]; nd.act = d[1]; nd.in0 = d[2]; nd.in1 = d[3]; nd.c_in = d[4]; nd.c_out = d[5];
       nd.k = d[6]; nd.stride = d[7]; nd.pad = d[8]; nd.w_off = d[9]; nd.b_off = d[10];
       nd.is_output = d[11];
-      if (nd.in0 >= i || nd.in1 >= i || nd.in0 < -1) return 1;
-      Shape a = shape_of(nd.in0), o;
+      if (nd.op == OP_DELAY) {
+        if (nd.in0 <= i || nd.in0 >= n_nodes || nd.in1 >= i || nd.in1 < -1 || nd.act != ACT_NONE) return 1;
+      } else if (nd.in0 >= i || nd.in1 >= i || nd.in0 < -1) {
+        return 1;
+      }
+      Shape a = shape_of(nd.op == OP_DELAY ? nd.in1 : nd.in0), o;
       switch (nd.op) {
         case OP_CONV:
           if (a.c != nd.c_in) return 2;
@@ -189,6 +203,7 @@ struct Net {
         }
         case OP_UP2X: o.c = a.c; o.h = 2 * a.h; o.w = 2 * a.w; break;
         case OP_GAP: o.c = a.c; o.h = 1; o.w = 1; break;
+        case OP_DELAY: o.c = nd.c_out; o.h = a.h; o.w = a.w; break;  // checked against X's shape below
         case OP_LINEAR:
           if (a.h != 1 || a.w != 1 || a.c != nd.c_in) return 6;
           o.c = nd.c_out; o.h = 1; o.w = 1;
@@ -201,12 +216,13 @@ struct Net {
       s.keeps_z = (nd.op == OP_CONV || nd.op == OP_LINEAR || nd.op == OP_GAP || nd.op == OP_ACT ||
                    nd.op == OP_SPARSIFY || nd.act != ACT_NONE) && nd.op != OP_MAXPOOL;
       s.structural = (nd.op == OP_ADD || nd.op == OP_CONCAT || nd.op == OP_UP2X || nd.op == OP_GAP ||
-                      nd.op == OP_MUL) && nd.act == ACT_NONE;
+                      nd.op == OP_MUL || nd.op == OP_DELAY) && nd.act == ACT_NONE;
       s.dy.assign(o.elems(), T(0));
       s.active.assign(o.sites(), 0);
       s.touched.assign(o.sites(), 0);
       if (s.keeps_z) s.z.assign(o.elems(), T(0));
       if (nd.op == OP_MUL) { s.z.assign(o.elems(), T(0)); s.z2.assign(o.elems(), T(0)); }
+      if (nd.op == OP_DELAY) s.z.assign(o.elems(), T(0));  // the value emitted so far
       if (nd.op == OP_MAXPOOL) s.pool_in.assign(a.elems(), T(0));
       if (nd.is_output) s.y.assign(o.elems(), T(0));
       if (nd.op == OP_CONV || nd.op == OP_LINEAR) {
@@ -222,6 +238,12 @@ struct Net {
       if (nd.op == OP_CONV || nd.op == OP_LINEAR)
         s.macs_dense = double(o.sites()) * nd.k * nd.k * nd.c_in * nd.c_out;  // upper bound (no border cut)
     }
+    for (int i = 0; i < n_nodes; ++i)
+      if (nodes[i].op == OP_DELAY) {
+        const Shape &x = st[nodes[i].in0].shp, &o = st[i].shp;
+        if (x.c != o.c || x.h != o.h || x.w != o.w) return 10;
+        st[nodes[i].in0].da.assign(o.elems(), T(0));
+      }
     x_prev.assign(in.elems(), 0.f);
     dx.assign(in.elems(), T(0));
     s0.assign(in.sites(), 0);
@@ -239,7 +261,21 @@ struct Net {
   void dense_node(int i) {
     const NodeDesc& nd = nodes[i];
     NodeState<T>& s = st[i];
-    const Shape a = shape_of(nd.in0), o = s.shp;
+    const Shape a = shape_of(nd.op == OP_DELAY ? nd.in1 : nd.in0), o = s.shp;
+    if (nd.op == OP_DELAY) {
+      // X's value at the previous pass: what that pass left in X (a regular pass), or the value
+      // emitted so far plus X's last increment (an incremental pass); zero before the first frame
+      const NodeState<T>& x = st[nd.in0];
+      s.dz.assign(o.elems(), T(0));
+      if (!first_pass)
+        for (size_t q = 0; q < o.sites(); ++q)
+          for (int c = 0; c < o.c; ++c) {
+            const size_t e = q * o.c + c;
+            s.dz[e] = last_dense ? x.da[e] : s.z[e] + (x.active[q] ? x.dy[e] : T(0));
+          }
+      s.da = s.dz;
+      return;
+    }
     const std::vector<T>& xa = dense_of(nd.in0);
     s.dz.assign(o.elems(), T(0));
     switch (nd.op) {
@@ -336,9 +372,15 @@ struct Net {
     return m;
   }
 
-  // refresh: regular forward pass that re-initialises every accumulated tensor
-  void reset(const float* x0) {
+  // reset: regular forward pass that re-initialises every accumulated tensor, from a zero
+  // recurrent state; refresh: the same pass in mid-stream, which keeps the recurrent state
+  void reset(const float* x0) { regular_pass(x0, true); }
+  void refresh(const float* x) { regular_pass(x, false); }
+  void regular_pass(const float* x0, bool first) {
+    first_pass = first;
     dense_forward(x0);
+    first_pass = false;
+    last_dense = true;
     std::copy(x0, x0 + in.elems(), x_prev.begin());
     std::fill(dx.begin(), dx.end(), T(0));
     std::fill(s0.begin(), s0.end(), 0);
@@ -356,6 +398,7 @@ struct Net {
         }
       }
       if (nodes[i].op == OP_MUL) { s.z = dense_of(nodes[i].in0); s.z2 = dense_of(nodes[i].in1); }
+      if (nodes[i].op == OP_DELAY) s.z = s.da;
       if (nodes[i].op == OP_MAXPOOL) s.pool_in = dense_of(nodes[i].in0);
       if (nodes[i].is_output) s.y = s.da;
       std::fill(s.dy.begin(), s.dy.end(), T(0));
@@ -401,6 +444,7 @@ struct Net {
 
   void propagate() {
     for (size_t i = 0; i < nodes.size(); ++i) incr_node(int(i));
+    last_dense = false;
   }
 
   // rounding step kept to 8 significant bits (round to nearest on the 16th mantissa bit)
@@ -439,6 +483,25 @@ struct Net {
   void incr_node(int i) {
     const NodeDesc& nd = nodes[i];
     NodeState<T>& s = st[i];
+    if (nd.op == OP_DELAY) {
+      // X has not been visited in this pass yet: its increment and mask are those of the
+      // previous step; after a regular pass the increment is X's value minus what was emitted
+      const NodeState<T>& x = st[nd.in0];
+      const Shape o = s.shp;
+      for (size_t q = 0; q < o.sites(); ++q) {
+        const uint8_t on = last_dense ? 1 : x.active[q];
+        for (int c = 0; c < o.c; ++c) {
+          const size_t e = q * o.c + c;
+          const T inc = !on ? T(0) : (last_dense ? x.da[e] - s.z[e] : x.dy[e]);
+          s.dy[e] = inc;
+          s.z[e] += inc;
+          if (nd.is_output) s.y[e] += inc;
+        }
+        s.active[q] = s.touched[q] = on;
+      }
+      s.macs_site = 0;
+      return;
+    }
     const Shape a = shape_of(nd.in0), o = s.shp;
     const std::vector<T>& da = dy_of(nd.in0);
     const std::vector<uint8_t>& sa = set_of(nd.in0);
@@ -713,6 +776,10 @@ void evo_dense_forward(void* h, const float* x) {
 void evo_reset(void* h, const float* x0) {
   Handle* p = (Handle*)h;
   if (p->fp32) p->f.reset(x0); else p->d.reset(x0);
+}
+void evo_refresh(void* h, const float* x) {
+  Handle* p = (Handle*)h;
+  if (p->fp32) p->f.refresh(x); else p->d.refresh(x);
 }
 void evo_step_frame(void* h, const float* xt) {
   Handle* p = (Handle*)h;

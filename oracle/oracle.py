@@ -47,7 +47,7 @@ def _load():
         L.evo_get_step.restype = ctypes.c_float
         L.evo_get_step.argtypes = [ctypes.c_void_p, ctypes.c_int]
         L.evo_destroy.argtypes = [ctypes.c_void_p]
-        for f in (L.evo_dense_forward, L.evo_reset, L.evo_step_frame, L.evo_step_increment):
+        for f in (L.evo_dense_forward, L.evo_reset, L.evo_refresh, L.evo_step_frame, L.evo_step_increment):
             f.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
             f.restype = None
         L.evo_get_tensor.restype = ctypes.c_longlong
@@ -100,6 +100,12 @@ class Oracle:
     def reset(self, x0):
         a, p = _f32(x0)
         _load().evo_reset(self._h, p)
+
+    def refresh(self, x):
+        """A regular forward pass in mid-stream: every accumulated tensor is recomputed, the
+        recurrent state (DELAY nodes) is kept."""
+        p = np.ascontiguousarray(x, dtype=np.float32).ctypes.data_as(ctypes.c_void_p)
+        _load().evo_refresh(self._h, p)
 
     def step_frame(self, xt):
         a, p = _f32(xt)

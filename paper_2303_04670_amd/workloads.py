@@ -24,7 +24,8 @@ import numpy as np
 
 # op / activation codes: plain data shared by both marshalling layers
 (OP_CONV2D, OP_ADD, OP_CONCAT, OP_UPSAMPLE2X, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_ACT, OP_SPARSIFY,
- OP_MUL) = range(10)
+ OP_MUL, OP_DELAY) = range(11)   # OP_DELAY: in0 = the LATER node whose previous-step value it is, in1 = an
+#                                  earlier node (or -1) with its height and width, c_out = its channels
 ACT_NONE, ACT_RELU, ACT_SIGMOID, ACT_TANH = range(4)
 WD_F32, WD_BF16, WD_F32_SPLIT = 0, 1, 2   # WD_F32_SPLIT: fp32 weights, contraction through bf16 high/low parts
 
@@ -62,6 +63,10 @@ class Net:
         for nd in self.nodes:
             def shp(i):
                 return (self.in_c, self.in_h, self.in_w) if i == -1 else out[i]
+            if nd.op == OP_DELAY:
+                _, h, w = shp(nd.in1)
+                out.append((nd.c_out, h, w))
+                continue
             c, h, w = shp(nd.in0)
             if nd.op in (OP_CONV2D, OP_MAXPOOL):
                 ho = (h + 2 * nd.pad - nd.k) // nd.stride + 1
@@ -103,7 +108,7 @@ class _NetBuilder:
         if i == -1:
             return self.in_c
         nd = self.nodes[i]
-        if nd.op in (OP_CONV2D, OP_LINEAR):
+        if nd.op in (OP_CONV2D, OP_LINEAR, OP_DELAY):
             return nd.c_out
         if nd.op == OP_SPARSIFY:
             return self._chan(nd.in0)
@@ -147,6 +152,15 @@ class _NetBuilder:
         c_out = c + (self._chan(b) if op == OP_CONCAT else 0)
         self.nodes.append(Node(op, act, a, b, c, c_out, k, stride, pad, -1, -1, out))
         return len(self.nodes) - 1
+
+    def delay(self, c, like=-1):
+        """A recurrent state of c channels with the height and width of node `like`; the node it
+        delays is set afterwards with close_delay()."""
+        self.nodes.append(Node(OP_DELAY, ACT_NONE, -3, like, c, c, 1, 1, 0, -1, -1, 0))
+        return len(self.nodes) - 1
+
+    def close_delay(self, d, src):
+        self.nodes[d].in0 = src
 
     def finish(self) -> Net:
         w = np.concatenate(self.chunks) if self.chunks else np.zeros(0, np.float32)
@@ -598,4 +612,27 @@ def net_random_wide(seed, h=24, w=40) -> Net:
     d = b.conv(u, c0, int(rng.choice([3, 5])), 1, act=ACT_NONE)
     d = b.simple(OP_ADD, d, full[0], act=ACT_RELU)                      # skip add in the conv epilogue
     b.conv(d, int(rng.choice([1, 2, 3])), 1, 1, 0, int(rng.choice([ACT_NONE, ACT_SIGMOID])), out=1)
+    return b.finish()
+
+
+def net_convlstm(seed=1008, in_c=4, h=64, w=96, hidden=28, out_c=2, k=3, bias=True) -> Net:
+    """A ConvLSTM cell on the event tensor followed by a 1 x 1 prediction head (tests and a
+    benchmark leg; random weights): i, f, o = sigmoid(conv([x, h'])), g = tanh(conv([x, h'])),
+    c = f * c' + i * g, h = o * tanh(c), with h', c' the cell's own h, c of the previous step."""
+    b = _NetBuilder(f"convlstm_{hidden}", in_c, h, w, seed, bias=bias)
+    h_prev = b.delay(hidden)
+    c_prev = b.delay(hidden)
+    xh = b.simple(OP_CONCAT, -1, h_prev)
+    gi = b.conv(xh, hidden, k, 1, act=ACT_SIGMOID)
+    gf = b.conv(xh, hidden, k, 1, act=ACT_SIGMOID)
+    go = b.conv(xh, hidden, k, 1, act=ACT_SIGMOID)
+    gg = b.conv(xh, hidden, k, 1, act=ACT_TANH)
+    fc = b.simple(OP_MUL, gf, c_prev)
+    ig = b.simple(OP_MUL, gi, gg)
+    c_new = b.simple(OP_ADD, fc, ig)
+    tc = b.simple(OP_ACT, c_new, act=ACT_TANH)
+    h_new = b.simple(OP_MUL, go, tc)
+    b.close_delay(h_prev, h_new)
+    b.close_delay(c_prev, c_new)
+    b.conv(h_new, out_c, 1, 1, 0, ACT_NONE, out=1)
     return b.finish()

@@ -7,8 +7,10 @@ import torch.nn.functional as F
 from paper_2303_04670_amd import workloads as wl
 
 
-def torch_forward(net, x_chw, upto=None):
-    """Returns per node (pre_activation, value) as H x W x C float64 numpy arrays."""
+def torch_forward(net, x_chw, upto=None, state=None):
+    """Returns per node (pre_activation, value) as H x W x C float64 numpy arrays.  state: for
+    recurrent nets, {index of a DELAY node: 1 x C x H x W tensor, its value in this pass} (a
+    missing entry is the zero state)."""
     w = torch.from_numpy(np.asarray(net.weights, dtype=np.float64))
     x = torch.from_numpy(np.asarray(x_chw, dtype=np.float64))[None]
     vals, outs = [], []
@@ -16,7 +18,13 @@ def torch_forward(net, x_chw, upto=None):
     def src(i):
         return x if i == -1 else vals[i]
 
-    for nd in net.nodes:
+    shapes = net.node_shapes()
+    for idx, nd in enumerate(net.nodes):
+        if nd.op == wl.OP_DELAY:
+            z = state[idx] if state and idx in state else torch.zeros((1,) + tuple(shapes[idx]), dtype=torch.float64)
+            vals.append(z)
+            outs.append((z[0].permute(1, 2, 0).numpy(), z[0].permute(1, 2, 0).numpy()))
+            continue
         a = src(nd.in0)
         if nd.op in (wl.OP_CONV2D, wl.OP_LINEAR):
             wt = w[nd.w_off: nd.w_off + nd.c_out * nd.c_in * nd.k * nd.k].reshape(nd.c_out, nd.c_in, nd.k, nd.k)
@@ -48,3 +56,15 @@ def torch_forward(net, x_chw, upto=None):
         vals.append(v)
         outs.append((z[0].permute(1, 2, 0).numpy(), v[0].permute(1, 2, 0).numpy()))
     return outs
+
+
+def torch_recurrent(net, frames):
+    """Runs a recurrent net over a list of C x H x W frames from the zero state.  Returns, per
+    frame, torch_forward's per-node list."""
+    delays = [i for i, nd in enumerate(net.nodes) if nd.op == wl.OP_DELAY]
+    state, res = {}, []
+    for x in frames:
+        outs = torch_forward(net, x, state=state)
+        res.append(outs)
+        state = {d: torch.from_numpy(np.ascontiguousarray(outs[net.nodes[d].in0][1].transpose(2, 0, 1)))[None] for d in delays}
+    return res
