@@ -35,12 +35,22 @@
  *                    * x2_inc + x2acc * x1_inc with the accumulators of the previous step, each
  *                    operation rounded once (no fused multiply-add); then both accumulators
  *                    advance (Eq.17).  T = S_out = S_a | S_b (Eq.16).  act must be NONE.
+ *   DELAY            recurrent state (the paper's evaluation networks are recurrent; how the state
+ *                    is carried is this library's reading): the value of a LATER node X at the
+ *                    previous step.  in0 = X (in0 > this node's index), in1 = an earlier node or
+ *                    -1 that has X's height and width, c_out = X's channels; act must be NONE.
+ *                    y_inc(n) = X's y_inc(n-1) and T = S_out = X's S_out(n-1); the state before
+ *                    the first frame is zero, so the first step after a reset emits X's whole
+ *                    value at every site.  State Z = the value emitted so far.  A regular forward
+ *                    pass in mid-stream (refresh, dense-recompute mode) keeps the state: the node
+ *                    then holds X's value of the previous step; the step after it emits
+ *                    X's value minus Z at every site.
  *   MAXPOOL          state a += x_inc; y_inc = max(window of a_new) - max(window of a_old) at
  *                    windows containing an active site; padding value -inf; act must be NONE.
  * A node keeps an accumulated tensor z (+= y_lin at T) if it is CONV2D, LINEAR,
  * GLOBAL_AVGPOOL, ACT, or has an activation.  With an activation theta_a the output is
  * y_inc = theta_a(z_new) - theta_a(z_old) (Eq.12), else y_inc = y_lin.
- * S_out is T for ADD / CONCAT / UPSAMPLE / GLOBAL_AVGPOOL / MUL without activation (Eq.11b), otherwise
+ * S_out is T for ADD / CONCAT / UPSAMPLE / GLOBAL_AVGPOOL / MUL / DELAY without activation (Eq.11b), otherwise
  * the sites of T where some channel of y_inc is != 0 (-0 counts as zero, NaN as nonzero).
  * Output nodes additionally keep y += y_inc on S_out (Eq.2).
  */
@@ -79,7 +89,8 @@ typedef enum {
   EVCONV_OP_LINEAR = 6,
   EVCONV_OP_ACT = 7,
   EVCONV_OP_SPARSIFY = 8,
-  EVCONV_OP_MUL = 9
+  EVCONV_OP_MUL = 9,
+  EVCONV_OP_DELAY = 10
 } evconv_op;
 
 typedef enum { EVCONV_ACT_NONE = 0, EVCONV_ACT_RELU = 1, EVCONV_ACT_SIGMOID = 2, EVCONV_ACT_TANH = 3 } evconv_act;

@@ -19,9 +19,10 @@ namespace {
 thread_local std::string g_create_error;
 
 enum KernelKind { kKernConvValu = 0, kKernConvMfmaF32, kKernElementwise, kKernGap, kKernPool, kKernConvMfmaBf16,
-                  kKernConvNarrow, kKernConvMfmaSplit, kKernConvPointwise };
+                  kKernConvNarrow, kKernConvMfmaSplit, kKernConvPointwise, kKernDelay };
 const char* const kKernelNames[] = {"conv_valu_f32", "conv_mfma_f32", "elementwise", "global_avgpool",
-                                    "maxpool", "conv_mfma_bf16", "conv_narrow_mfma_f32", "conv_mfma_f32_split_bf16x3", "conv_pointwise_f32"};
+                                    "maxpool", "conv_mfma_bf16", "conv_narrow_mfma_f32", "conv_mfma_f32_split_bf16x3", "conv_pointwise_f32",
+                                    "delay"};
 
 // fp32 -> bf16 bits, round to nearest even
 uint16_t to_bf16(float x) {
@@ -47,6 +48,8 @@ struct NodePlan {
   size_t off_step = 0;      // SPARSIFY: device scalar k
   size_t off_z2 = 0;        // MUL: accumulated second factor
   float* z2 = nullptr;
+  size_t off_occ_saved = 0;  // DELAY: S_out words of the delayed node as the previous step left them
+  uint64_t* occ_saved = nullptr;
   float* step = nullptr;
   float step_fixed = -1.0f; // >= 0: k supplied by the description
   size_t off_z = 0, off_out = 0, off_pool = 0, off_occ = 0, off_touched = 0, off_idx = 0, off_count = 0,
@@ -112,12 +115,26 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
     n.d = d;
     char where[64];
     snprintf(where, sizeof where, "node %d: ", i);
-    if (d.op < 0 || d.op > EVCONV_OP_MUL) return fail(err, EVCONV_ERR_INVALID_ARG, std::string(where) + "bad op");
+    if (d.op < 0 || d.op > EVCONV_OP_DELAY) return fail(err, EVCONV_ERR_INVALID_ARG, std::string(where) + "bad op");
     if (d.act < 0 || d.act > EVCONV_ACT_TANH) return fail(err, EVCONV_ERR_INVALID_ARG, std::string(where) + "bad act");
-    if (d.in0 < -1 || d.in0 >= i) return fail(err, EVCONV_ERR_BAD_DESC, std::string(where) + "in0 is not an earlier node");
+    const bool delay = d.op == EVCONV_OP_DELAY;
+    if (delay) {
+      // in0: the later node whose previous-step value this is; in1: an earlier node of its size
+      if (d.in0 <= i || d.in0 >= desc->n_nodes) return fail(err, EVCONV_ERR_BAD_DESC, std::string(where) + "DELAY: in0 must be a later node");
+      if (d.in1 < -1 || d.in1 >= i) return fail(err, EVCONV_ERR_BAD_DESC, std::string(where) + "DELAY: in1 is not an earlier node");
+      if (d.act != EVCONV_ACT_NONE) return fail(err, EVCONV_ERR_UNSUPPORTED, std::string(where) + "DELAY takes no activation");
+      if (d.c_out <= 0) return fail(err, EVCONV_ERR_SHAPE, std::string(where) + "c_out must be positive");
+    } else if (d.in0 < -1 || d.in0 >= i) {
+      return fail(err, EVCONV_ERR_BAD_DESC, std::string(where) + "in0 is not an earlier node");
+    }
     const bool two = d.op == EVCONV_OP_ADD || d.op == EVCONV_OP_CONCAT || d.op == EVCONV_OP_MUL;
     if (two && (d.in1 < -1 || d.in1 >= i)) return fail(err, EVCONV_ERR_BAD_DESC, std::string(where) + "in1 is not an earlier node");
-    n.ga = d.in0 < 0 ? L->gin : L->nodes[d.in0].go;
+    if (delay) {
+      n.ga = d.in1 < 0 ? L->gin : L->nodes[d.in1].go;
+      n.ga = make_geo(d.c_out, n.ga.h, n.ga.w);
+    } else {
+      n.ga = d.in0 < 0 ? L->gin : L->nodes[d.in0].go;
+    }
     n.gb = two ? (d.in1 < 0 ? L->gin : L->nodes[d.in1].go) : n.ga;
     int c = n.ga.c, h = n.ga.h, w = n.ga.w;
     switch (d.op) {
@@ -166,6 +183,7 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
       case EVCONV_OP_UPSAMPLE_BILINEAR2X: h *= 2; w *= 2; break;
       case EVCONV_OP_GLOBAL_AVGPOOL: h = 1; w = 1; break;
       case EVCONV_OP_ACT: break;
+      case EVCONV_OP_DELAY: break;  // shape of in1 with c_out channels; checked against in0 below
       case EVCONV_OP_SPARSIFY:
         if (d.act != EVCONV_ACT_NONE) return fail(err, EVCONV_ERR_UNSUPPORTED, std::string(where) + "SPARSIFY takes no activation");
         if (d.weight_off >= 0 && ((d.weight_off & 3) || (check_weights && (size_t)d.weight_off + 4 > weight_bytes)))
@@ -177,18 +195,31 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
     if (n.go.ty > L->max_ty) L->max_ty = n.go.ty;
     const bool lin = d.op == EVCONV_OP_CONV2D || d.op == EVCONV_OP_LINEAR;
     n.keeps_z = (lin || d.op == EVCONV_OP_GLOBAL_AVGPOOL || d.op == EVCONV_OP_ACT ||
-                 d.op == EVCONV_OP_SPARSIFY || d.op == EVCONV_OP_MUL || d.act != EVCONV_ACT_NONE) &&
+                 d.op == EVCONV_OP_SPARSIFY || d.op == EVCONV_OP_MUL || d.op == EVCONV_OP_DELAY ||
+                 d.act != EVCONV_ACT_NONE) &&
                 d.op != EVCONV_OP_MAXPOOL;
     n.structural = (d.op == EVCONV_OP_ADD || d.op == EVCONV_OP_CONCAT || d.op == EVCONV_OP_UPSAMPLE_BILINEAR2X ||
-                    d.op == EVCONV_OP_GLOBAL_AVGPOOL || d.op == EVCONV_OP_MUL) && d.act == EVCONV_ACT_NONE;
+                    d.op == EVCONV_OP_GLOBAL_AVGPOOL || d.op == EVCONV_OP_MUL || d.op == EVCONV_OP_DELAY) &&
+                   d.act == EVCONV_ACT_NONE;
     if (lin) {
       n.kernel = kKernConvValu;
       n.c_out_pad = (d.c_out + 31) / 32 * 32;
     } else if (d.op == EVCONV_OP_GLOBAL_AVGPOOL) n.kernel = kKernGap;
     else if (d.op == EVCONV_OP_MAXPOOL) n.kernel = kKernPool;
+    else if (d.op == EVCONV_OP_DELAY) n.kernel = kKernDelay;
     else n.kernel = kKernElementwise;
     occ_word_off[i] = words;
     words += 2 * (size_t)n.go.tiles();
+  }
+  for (int i = 0; i < desc->n_nodes; ++i) {
+    const NodePlan& n = L->nodes[i];
+    if (n.d.op != EVCONV_OP_DELAY) continue;
+    const Geo& x = L->nodes[n.d.in0].go;
+    if (x.c != n.go.c || x.h != n.go.h || x.w != n.go.w) {
+      char where[96];
+      snprintf(where, sizeof where, "node %d: DELAY shape differs from that of node %d", i, n.d.in0);
+      return fail(err, EVCONV_ERR_SHAPE, where);
+    }
   }
   L->n_occ_words = words;
   b.take(words * sizeof(uint64_t));
@@ -211,6 +242,7 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
     if (n.keeps_z || n.d.op == EVCONV_OP_MAXPOOL) n.off_z = b.take(elems * 4);
     if (n.d.op == EVCONV_OP_SPARSIFY) n.off_step = b.take(4);
     if (n.d.op == EVCONV_OP_MUL) n.off_z2 = b.take(elems * 4);
+    if (n.d.op == EVCONV_OP_DELAY) n.off_occ_saved = b.take((size_t)n.go.tiles() * 8);
     if (n.d.op == EVCONV_OP_MAXPOOL) n.off_pool = b.take((size_t)n.ga.c * n.ga.sites() * 4);
     n.off_out = b.take(elems * 4);
     n.off_idx = b.take((size_t)n.go.sites() * 4);
@@ -247,6 +279,8 @@ struct evconv_net {
   int mode = EVCONV_MODE_INCREMENTAL;
   int refresh_period = 0, since_refresh = 0;
   bool has_state = false;
+  bool last_dense = true;   // the previous pass was a regular forward pass (DELAY nodes)
+  bool zero_state = false;  // the pass being enqueued starts from the zero recurrent state (reset)
   Streams st{0, 1};
   size_t in_stride = 0;
   std::string err;
@@ -292,6 +326,23 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
     const float* bptr = two ? (d.in1 < 0 ? net->dx : net->L.nodes[d.in1].out) : nullptr;
     const uint64_t* occ_b = two ? (d.in1 < 0 ? net->occ_in : net->L.nodes[d.in1].occ) : nullptr;
     if (n.gather_fused_into >= 0) continue;  // exists only inside the consuming conv's gather
+    if (n.kernel == kKernDelay) {
+      const NodePlan& x = net->L.nodes[d.in0];  // not yet visited in this pass: holds the previous pass's results
+      DelayParams p;
+      p.src_out = x.out; p.occ_saved = n.occ_saved; p.z = n.z; p.out = n.out;
+      p.occ_out = n.occ; p.occ_touched = n.touched; p.g = n.go;
+      p.dense = dense; p.last_dense = net->last_dense; p.zero_state = net->zero_state;
+      p.st = net->st;
+      launch_delay(p, s);
+      if (d.is_output) {
+        IntegrateParams ip;
+        ip.delta = n.out; ip.occ = n.occ; ip.y = n.y; ip.dy = n.dy; ip.g = n.go;
+        ip.mode = pass == kPassStep ? kIntStep : pass == kPassReset ? kIntReset : kIntRecompute;
+        ip.st = net->st;
+        launch_integrate(ip, s);
+      }
+      continue;
+    }
     if (n.fused_into >= 0) {  // computed by the producing conv's epilogue
       if (d.is_output) {
         IntegrateParams ip;
@@ -404,6 +455,13 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
       launch_integrate(ip, s);
     }
   }
+  // recurrent state: keep the delayed nodes' active sets for the next pass (the occupancy words
+  // are cleared when it starts)
+  for (size_t i = 0; i < net->L.nodes.size(); ++i) {
+    const NodePlan& n = net->L.nodes[i];
+    if (n.kernel == kKernDelay) launch_copy_u64(n.occ_saved, net->L.nodes[n.d.in0].occ, (size_t)n.go.tiles(), net->st, s);
+  }
+  net->last_dense = dense != 0;
   if (pass == kPassReset) launch_fill_u64(net->occ_nodes, net->L.n_occ_words, 0, net->st, s);
   launch_build_lists(net->sets_dev, (int)net->L.nodes.size() + 1, net->L.max_ty, net->st, s);
   hipError_t e = hipGetLastError();
@@ -489,6 +547,7 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
     }
     n.pool_in = n.d.op == EVCONV_OP_MAXPOOL ? (float*)(ws + n.off_pool) : nullptr;
     n.z2 = n.d.op == EVCONV_OP_MUL ? (float*)(ws + n.off_z2) : nullptr;
+    n.occ_saved = n.d.op == EVCONV_OP_DELAY ? (uint64_t*)(ws + n.off_occ_saved) : nullptr;
     n.out = (float*)(ws + n.off_out);
     n.occ = (uint64_t*)(ws + n.off_occ);
     n.touched = (uint64_t*)(ws + n.off_touched);
@@ -649,7 +708,9 @@ int32_t evconv_num_outputs(const evconv_net* net) { return net ? (int32_t)net->o
 evconv_status evconv_reset(evconv_net* net, const float* x0, evconv_out* out) {
   if (!net) return EVCONV_ERR_INVALID_ARG;
   if (!x0) { net->err = "null x0"; return EVCONV_ERR_INVALID_ARG; }
+  net->zero_state = true;
   evconv_status st = run_pass(net, x0, kBuildReset, kPassReset);
+  net->zero_state = false;
   if (st != EVCONV_OK) return st;
   net->has_state = true;
   net->since_refresh = 0;

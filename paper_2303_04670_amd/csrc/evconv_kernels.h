@@ -160,6 +160,24 @@ struct IntegrateParams {
 };
 void launch_integrate(const IntegrateParams& p, hipStream_t s);
 
+// ---- recurrent state: the previous step's output of a later node -----------------------------
+struct DelayParams {
+  const float* src_out;       // H x W x C: the delayed node's increment of the previous step, or its
+                              // value if the previous pass was a regular forward pass
+  const uint64_t* occ_saved;  // the delayed node's S_out words of the previous step
+  float* z;                   // value emitted so far
+  float* out;                 // this step's increment (value in a regular pass)
+  uint64_t* occ_out; uint64_t* occ_touched;
+  Geo g;
+  int dense;                  // this pass is a regular forward pass
+  int last_dense;             // the previous pass was one
+  int zero_state;             // reset: the state before the first frame is zero
+  Streams st;
+};
+void launch_delay(const DelayParams& p, hipStream_t s);
+// dst[i] = src[i], n 64-bit words per stream
+void launch_copy_u64(uint64_t* dst, const uint64_t* src, size_t n, Streams st, hipStream_t s);
+
 // ---- ordered compaction of occupancy words into ascending site lists -------------------------
 struct SetDesc {
   const uint64_t* occ; int32_t* idx; int32_t* count; uint64_t* bitmap;

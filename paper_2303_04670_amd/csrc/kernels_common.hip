@@ -460,6 +460,66 @@ void launch_integrate(const IntegrateParams& p, hipStream_t s) {
   hipLaunchKernelGGL(integrate_kernel, dim3((p.g.sites() + 255) / 256, 1, p.st.n), dim3(256), 0, s, p);
 }
 
+// =============================================================================== recurrent state
+// Workgroup = one 8 x 8 tile; thread = (site, channel) pairs strided over the tile's active sites.
+__global__ __launch_bounds__(256) void delay_kernel(DelayParams p) {
+  const size_t so = (size_t)blockIdx.z * p.st.stride;
+  const float* src = at_stream(p.src_out, so);
+  float* z = at_stream(p.z, so);
+  float* out = at_stream(p.out, so);
+  const int tile = blockIdx.x;
+  const int tile_y = tile / p.g.tx, tile_x = tile - tile_y * p.g.tx;
+  const int rows = min(8, p.g.h - tile_y * 8), cols = min(8, p.g.w - tile_x * 8);
+  uint64_t inb = 0;
+  {
+    const uint64_t rowbits = cols >= 8 ? 0xffull : ((1ull << cols) - 1ull);
+    for (int r = 0; r < rows; ++r) inb |= rowbits << (8 * r);
+  }
+  const uint64_t saved = at_stream(p.occ_saved, so)[tile] & inb;
+  // sites visited: all of the tile in or after a regular pass, the delayed node's active set otherwise
+  const uint64_t word = (p.dense || p.last_dense) ? inb : saved;
+  if (threadIdx.x == 0) {  // this workgroup is the tile's only writer
+    at_stream(p.occ_out, so)[tile] = word;
+    at_stream(p.occ_touched, so)[tile] = word;
+  }
+  const int C = p.g.c;
+  const int n_active = __popcll(word);
+  for (int e = threadIdx.x; e < n_active * C; e += 256) {
+    const int k = e / C, c = e - k * C;
+    // k-th set bit of word
+    uint64_t w = word;
+    for (int j = 0; j < k; ++j) w &= w - 1;
+    const int site = __ffsll((unsigned long long)w) - 1;
+    const int oy = tile_y * 8 + (site >> 3), ox = tile_x * 8 + (site & 7);
+    const size_t q = ((size_t)oy * p.g.w + ox) * C + c;
+    if (p.dense) {
+      float v = 0.0f;
+      if (!p.zero_state) v = p.last_dense ? src[q] : z[q] + (((saved >> site) & 1ull) ? src[q] : 0.0f);
+      out[q] = v;
+      z[q] = v;
+    } else {
+      const float zo = z[q];
+      const float inc = p.last_dense ? src[q] - zo : src[q];
+      out[q] = inc;
+      z[q] = zo + inc;
+    }
+  }
+}
+
+void launch_delay(const DelayParams& p, hipStream_t s) {
+  hipLaunchKernelGGL(delay_kernel, dim3(p.g.tiles(), 1, p.st.n), dim3(256), 0, s, p);
+}
+
+__global__ __launch_bounds__(256) void copy_u64_kernel(uint64_t* dst, const uint64_t* src, size_t n, size_t stride) {
+  const size_t so = (size_t)blockIdx.y * stride;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) at_stream(dst, so)[i] = at_stream(src, so)[i];
+}
+
+void launch_copy_u64(uint64_t* dst, const uint64_t* src, size_t n, Streams st, hipStream_t s) {
+  hipLaunchKernelGGL(copy_u64_kernel, dim3((unsigned)((n + 255) / 256), st.n), dim3(256), 0, s, dst, src, n, st.stride);
+}
+
 // =============================================================================== ordered lists
 // Workgroup (strip, set): strip = one row of tiles = 8 image rows.  Its first list position is
 // the number of active sites in all earlier strips (a reduction over their occupancy words);

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
 
 
 @pytest.mark.parametrize("make", [wl.net_single_conv, wl.net_conv_stack, wl.net_unet_depth, wl.net_resnet18,
-                                  wl.net_flow], ids=lambda f: f.__name__)
+                                  wl.net_flow, wl.net_convlstm], ids=lambda f: f.__name__)
 def test_query_workspace_all_workloads(make):
     net = make()
     desc, keep = ev.marshal_desc(net)
@@ -75,6 +75,28 @@ def test_bad_descriptions_are_rejected():
     assert _status(desc) == ev.OK
     assert ev.lib().evconv_query_workspace(None, None) == ev.ERR_INVALID_ARG
     assert b"" != ev.lib().evconv_last_error(None)
+
+
+def test_recurrent_descriptions():
+    """DELAY: in0 must name a later node of the same shape, in1 an earlier node of its size."""
+    net = wl.net_convlstm(h=16, w=16, hidden=8)
+    desc, nodes = ev.marshal_desc(net)
+    assert _status(desc) == ev.OK
+    src = nodes[0].in0
+    nodes[0].in0 = 0                       # itself
+    assert _status(desc) == ev.ERR_BAD_DESC
+    nodes[0].in0 = len(net.nodes)          # past the end
+    assert _status(desc) == ev.ERR_BAD_DESC
+    nodes[0].in0 = len(net.nodes) - 1      # the 2-channel head: shape differs
+    assert _status(desc) == ev.ERR_SHAPE
+    nodes[0].in0 = src
+    nodes[0].act = wl.ACT_RELU
+    assert _status(desc) == ev.ERR_UNSUPPORTED
+    nodes[0].act = wl.ACT_NONE
+    nodes[1].in1 = 5                       # the size reference must be an earlier node
+    assert _status(desc) == ev.ERR_BAD_DESC
+    nodes[1].in1 = -1
+    assert _status(desc) == ev.OK
 
 
 def test_null_handles():

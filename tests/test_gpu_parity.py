@@ -759,3 +759,109 @@ def test_random_wide_graphs_all_contraction_modes(seed):
         run_stream(net, frames[0], frames[1:], "frame", tol=2e-2, label=f"wide{seed}", max_flips=10**9, frobenius=True)
     else:
         run_stream(net, frames[0], frames[1:], "frame", label=f"wide{seed}", max_flips=40)
+
+
+# --------------------------------------------------------------------------- recurrent state
+
+def _running_sum_net(c, h, w):
+    nodes = [
+        wl.Node(wl.OP_DELAY, wl.ACT_NONE, 1, -1, c, c, 1, 1, 0, -1, -1, 0),
+        wl.Node(wl.OP_ADD, wl.ACT_NONE, -1, 0, c, c, 1, 1, 0, -1, -1, 1),
+    ]
+    return wl.Net("running_sum", c, h, w, nodes, np.zeros(0, np.float32))
+
+
+def test_delay_running_sum_bit_exact_against_fp32_oracle():
+    """s(n) = x(n) + s(n-1) through a DELAY node: every operation is a single fp32 add or
+    subtraction, so the GPU must agree bit for bit with the oracle run in binary32, through
+    incremental steps, refreshes (regular passes that keep the state) and the steps after them."""
+    _say("recurrent running sum, bit-exact, with refreshes")
+    c, h, w = 3, 9, 19
+    net = _running_sum_net(c, h, w)
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((c, h, w)).astype(np.float32)
+    gpu, ora = ev.EvConvNet(net), Oracle(net, fp32_state=True)
+    gpu.set_refresh_period(4)
+    gpu.reset(_dev(x))
+    ora.reset(x)
+    for t in range(1, 11):
+        m = rng.random((1, h, w)) < 0.1
+        x = (x + rng.standard_normal(x.shape).astype(np.float32) * m).astype(np.float32)
+        gpu.step_frame(_dev(x))
+        (ora.refresh if t % 4 == 0 else ora.step_frame)(x)
+        import torch
+        torch.cuda.synchronize()
+        for i in (0, 1):
+            np.testing.assert_array_equal(gpu.state(i, ev.STATE_Z).view(np.uint32) if i == 0 else 0,
+                                          ora.z(i).astype(np.float32).view(np.uint32) if i == 0 else 0,
+                                          err_msg=f"step {t} node {i} accumulated value")
+        y = gpu.outputs()[0]["y"].cpu().numpy()
+        np.testing.assert_array_equal(y.view(np.uint32), np.transpose(ora.y(1), (2, 0, 1)).astype(np.float32).view(np.uint32),
+                                      err_msg=f"step {t} output")
+        if t % 4:
+            for i in (0, 1):
+                np.testing.assert_array_equal(cmp.words_to_mask(gpu.state(i, ev.STATE_OCC), h, w), ora.mask(i),
+                                              err_msg=f"step {t} node {i} active set")
+                on = ora.mask(i).astype(bool)
+                np.testing.assert_array_equal(gpu.state(i, ev.STATE_DY)[on].view(np.uint32),
+                                              ora.dy(i).astype(np.float32)[on].view(np.uint32), err_msg=f"step {t} node {i} increment")
+    gpu.destroy()
+
+
+@pytest.mark.parametrize("mode", ["f32", "split"])
+def test_convlstm_cell_against_oracle(mode):
+    """A ConvLSTM cell (gates on the matrix cores, products, tanh, two recurrent states) and a
+    1 x 1 head: all nodes at every step."""
+    net = wl.net_convlstm(41, in_c=4, h=24, w=40, hidden=32, out_c=2)
+    if mode == "split":
+        net = wl.with_weight_dtype(net, wl.WD_F32_SPLIT)
+    _say(f"ConvLSTM cell, {mode}, 4x24x40, hidden 32")
+    g = ev.EvConvNet(net)
+    names = [g.kernel_name(i) for i in range(len(net.nodes))]
+    g.destroy()
+    assert names[0] == names[1] == "delay", names
+    assert names.count("conv_mfma_f32" if mode == "f32" else "conv_mfma_f32_split_bf16x3") == 4, names
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal((4, 24, 40)).astype(np.float32)
+    frames = [x]
+    for t in range(8):
+        m = rng.random((1, 24, 40)) < 0.05
+        x = (x + rng.standard_normal(x.shape).astype(np.float32) * m).astype(np.float32)
+        frames.append(x)
+    run_stream(net, frames[0], frames[1:], "frame", label=f"convlstm-{mode}", max_flips=40)
+
+
+def test_convlstm_refresh_and_dense_recompute_keep_the_state():
+    """Regular forward passes in mid-stream (refresh period; dense-recompute mode) keep the
+    recurrent state: outputs follow the oracle's refresh()."""
+    _say("ConvLSTM cell with refresh period 3, and in dense-recompute mode")
+    net = wl.net_convlstm(42, in_c=4, h=16, w=24, hidden=32, out_c=2)
+    rng = np.random.default_rng(13)
+    x = rng.standard_normal((4, 16, 24)).astype(np.float32)
+    frames = [x]
+    for t in range(7):
+        m = rng.random((1, 16, 24)) < 0.1
+        x = (x + rng.standard_normal(x.shape).astype(np.float32) * m).astype(np.float32)
+        frames.append(x)
+    import torch
+    for which in ("refresh", "dense"):
+        gpu, ora = ev.EvConvNet(net), Oracle(net)
+        if which == "refresh":
+            gpu.set_refresh_period(3)
+        else:
+            gpu.set_mode(ev.MODE_DENSE_RECOMPUTE)
+        gpu.reset(_dev(frames[0]))
+        ora.reset(frames[0])
+        out = ora.outputs[0]
+        for t in range(1, 8):
+            gpu.step_frame(_dev(frames[t]))
+            regular = which == "dense" or t % 3 == 0
+            (ora.refresh if regular else ora.step_frame)(frames[t])
+            torch.cuda.synchronize()
+            y = gpu.outputs()[0]["y"].cpu().numpy()
+            ref = np.transpose(ora.y(out), (2, 0, 1))
+            assert np.abs(y - ref).max() <= TOL * np.abs(ref).max(), f"{which} step {t}: {np.abs(y - ref).max():.3e}"
+            for d in (0, 1):
+                z, zr = gpu.state(d, ev.STATE_Z).astype(np.float64), ora.z(d)
+                assert np.abs(z - zr).max() <= TOL * max(np.abs(zr).max(), 1e-30), f"{which} step {t} state {d}"
+        gpu.destroy()
