@@ -9,7 +9,8 @@ fp32 weights (headline) and the bf16-weight variant (reported beside it).
 Prints ONE JSON line.  Extra keys: `dense_recompute` (the same frames run as regular forward
 passes through the same kernels), `roofline` (dominant kernel family, timed with HIP events on the
 library's stream inside the timed region), `cpu_baseline` (the CPU oracle on a bounded sample of
-the same frames), `bf16_variant`, `layers`.
+the same frames), `f32_split_variant`, `bf16_variant`, `hip_graph_replay`, `multi_stream` (16 streams
+in one net), `sparsified_variant`, `recurrent_variant` (a ConvLSTM cell), `layers`.
 
 `--sweep` runs the density sweep of the optical-flow encoder-decoder instead (one JSON line).
 """
@@ -123,6 +124,7 @@ def main():
     ap.add_argument("--no-second-variant", action="store_true")
     ap.add_argument("--no-sparsified", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--no-recurrent", action="store_true")
     ap.add_argument("--streams", type=int, default=16,
                     help="independent event streams per net in the multi_stream leg (0: skip the leg)")
     ap.add_argument("--sparsify-tp", type=float, default=0.1)
@@ -195,6 +197,8 @@ def main():
         out["multi_stream"] = multi_stream_leg(args, np, torch, ev, wl, dev)
     if not args.no_sparsified:
         out["sparsified_variant"] = sparsified_leg(args, np, torch, ev, wl, dframes)
+    if not args.no_recurrent:
+        out["recurrent_variant"] = recurrent_leg(args, np, torch, ev, wl, dframes)
     if not args.no_cpu_baseline:
         from oracle.oracle import Oracle
         ora = Oracle(net)
@@ -329,6 +333,37 @@ def sparsified_leg(args, np, torch, ev, wl, dframes):
             "touched_site_fraction": b["touched_site_fraction"], "tile_flop_fraction": b["tile_flop_fraction"],
             "with_t_p_0": a, "max_abs_output_deviation_from_lossless": dev_out,
             "note": "random weights and unit-size input increments: few elements fall under k, see the text"}
+
+
+def recurrent_leg(args, np, torch, ev, wl, dframes):
+    """The same frames through a ConvLSTM cell (64 hidden channels at full resolution, two
+    recurrent states as DELAY nodes) with a 1 x 1 head.  A recurrent state moves at every step, so
+    everything behind it is dense; reported beside a dense recompute of the same frames."""
+    # (four of the five time bins: 4 + 64 input channels of the gate convs suit the matrix-core kernel)
+    net = wl.net_convlstm(1008, in_c=4, h=256, w=352, hidden=64, out_c=1)
+    dframes = [f[:4].contiguous() for f in dframes[:5 + max(10, args.steps // 4)]]
+    steps = max(10, args.steps // 4)
+    res = {}
+    for mode, key in ((ev.MODE_INCREMENTAL, "incremental"), (ev.MODE_DENSE_RECOMPUTE, "dense_recompute")):
+        g = ev.EvConvNet(net, device="cuda:0")
+        g.set_mode(mode)
+        g.reset(dframes[0])
+        for i in range(1, 4):
+            g.step_frame(dframes[i])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(4, 4 + steps):
+            g.step_frame(dframes[i])
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        conv = [i for i, nd in enumerate(net.nodes) if nd.op == wl.OP_CONV2D]
+        res[key] = dict(value=steps / dt, ms_per_step=dt / steps * 1e3,
+                        touched_site_fraction=sum(g.stats(i).n_touched for i in conv) / sum(g.stats(i).n_sites for i in conv))
+        g.destroy()
+    return {"net": "ConvLSTM 4->64 hidden, 3x3 gates, 256x352, 1x1 head", "unit": "steps/s", "steps": steps,
+            "value": res["incremental"]["value"], "ms_per_step": res["incremental"]["ms_per_step"],
+            "touched_site_fraction": res["incremental"]["touched_site_fraction"],
+            "dense_recompute_ms_per_step": res["dense_recompute"]["ms_per_step"]}
 
 
 def drift_study(args, np, torch, ev, wl, dev):
