@@ -484,12 +484,13 @@ __global__ __launch_bounds__(256) void delay_kernel(DelayParams p) {
   }
   const int C = p.g.c;
   const int n_active = __popcll(word);
+  __shared__ unsigned char s_site[64];  // the visited sites in ascending order
+  if (threadIdx.x < 64 && ((word >> threadIdx.x) & 1ull))
+    s_site[__popcll(word & ((1ull << threadIdx.x) - 1ull))] = (unsigned char)threadIdx.x;
+  __syncthreads();
   for (int e = threadIdx.x; e < n_active * C; e += 256) {
     const int k = e / C, c = e - k * C;
-    // k-th set bit of word
-    uint64_t w = word;
-    for (int j = 0; j < k; ++j) w &= w - 1;
-    const int site = __ffsll((unsigned long long)w) - 1;
+    const int site = s_site[k];
     const int oy = tile_y * 8 + (site >> 3), ox = tile_x * 8 + (site & 7);
     const size_t q = ((size_t)oy * p.g.w + ox) * C + c;
     if (p.dense) {
