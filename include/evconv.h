@@ -192,14 +192,23 @@ int32_t evconv_num_outputs(const evconv_net* net);
 /* In the three calls below the input tensor holds one C x H x W fp32 frame (or increment) per
  * stream, contiguous [n_streams][C][H][W]; all streams advance together.
  *
- * Refresh ("Drift Errors"): regular forward pass of x0 (DEVICE, C x H x W fp32) that fills the
- * previous-frame cache, every accumulated tensor and y(0).  `out` (HOST array of
- * evconv_num_outputs entries, may be NULL) receives the pointers; dy is zero, count 0.
- * Asynchronous on the net's stream. */
+ * Reset: regular forward pass of x0 (DEVICE, C x H x W fp32) that fills the previous-frame
+ * cache, every accumulated tensor and y(0), from a zero recurrent state (DELAY nodes).  `out`
+ * (HOST array of evconv_num_outputs entries, may be NULL) receives the pointers; dy is zero,
+ * count 0.  Asynchronous on the net's stream.  For a net without DELAY nodes this is also the
+ * refresh of the "Drift Errors" section; a recurrent net is refreshed through
+ * evconv_set_refresh_period, which keeps the state. */
 evconv_status evconv_reset(evconv_net* net, const float* x0, evconv_out* out);
 
 /* One incremental step on a caller-supplied increment tensor (DEVICE, dense C x H x W fp32,
- * zeros where nothing changed).  Asynchronous.  EVCONV_ERR_STATE before the first reset. */
+ * zeros where nothing changed).  Asynchronous.  EVCONV_ERR_STATE before the first reset.
+ *
+ * A step only enqueues kernels (no allocation, no synchronisation, no memset), so the caller may
+ * capture it into a HIP graph and replay that.  What a replay cannot see is host-side state:
+ * the refresh period counts calls, not replays, and a net with DELAY nodes passes "the previous
+ * pass was a regular forward pass" to its kernels as an argument.  Capture such a net's step
+ * after an incremental step (not directly after evconv_reset), and run refreshes outside the
+ * graph, followed by one un-captured step. */
 evconv_status evconv_step(evconv_net* net, const float* increment, evconv_out* out);
 
 /* One incremental step on the next frame x(n) (DEVICE, C x H x W fp32): the increment is
