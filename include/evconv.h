@@ -93,7 +93,11 @@ typedef enum {
   EVCONV_OP_DELAY = 10
 } evconv_op;
 
-typedef enum { EVCONV_ACT_NONE = 0, EVCONV_ACT_RELU = 1, EVCONV_ACT_SIGMOID = 2, EVCONV_ACT_TANH = 3 } evconv_act;
+/* ONE_MINUS: theta(z) = 1 - z (the "1 - update gate" of a gated recurrent unit); as every
+ * activation it acts on the accumulated tensor, so its increment is -x_inc. */
+typedef enum {
+  EVCONV_ACT_NONE = 0, EVCONV_ACT_RELU = 1, EVCONV_ACT_SIGMOID = 2, EVCONV_ACT_TANH = 3, EVCONV_ACT_ONE_MINUS = 4
+} evconv_act;
 
 /* dtype of the weights and of the increments inside the channel contraction; accumulation and
  * every cached tensor are always fp32.

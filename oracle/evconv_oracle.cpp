@@ -67,7 +67,7 @@ namespace {
 
 enum Op { OP_CONV = 0, OP_ADD, OP_CONCAT, OP_UP2X, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_ACT, OP_SPARSIFY, OP_MUL,
           OP_DELAY };  // OP_DELAY: in0 = the later node X it delays, in1 = an earlier node (or -1) with its height and width
-enum Act { ACT_NONE = 0, ACT_RELU, ACT_SIGMOID, ACT_TANH };
+enum Act { ACT_NONE = 0, ACT_RELU, ACT_SIGMOID, ACT_TANH, ACT_ONE_MINUS };  // ONE_MINUS: 1 - z
 
 struct NodeDesc {
   int op, act, in0, in1, c_in, c_out, k, stride, pad;
@@ -81,6 +81,7 @@ T activate(int act, T v) {
   if (act == ACT_RELU) return v > T(0) ? v : T(0);
   if (act == ACT_SIGMOID) return T(1) / (T(1) + std::exp(-v));
   if (act == ACT_TANH) return std::tanh(v);
+  if (act == ACT_ONE_MINUS) return T(1) - v;
   return v;
 }
 

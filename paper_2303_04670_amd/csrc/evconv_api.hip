@@ -116,7 +116,7 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
     char where[64];
     snprintf(where, sizeof where, "node %d: ", i);
     if (d.op < 0 || d.op > EVCONV_OP_DELAY) return fail(err, EVCONV_ERR_INVALID_ARG, std::string(where) + "bad op");
-    if (d.act < 0 || d.act > EVCONV_ACT_TANH) return fail(err, EVCONV_ERR_INVALID_ARG, std::string(where) + "bad act");
+    if (d.act < 0 || d.act > EVCONV_ACT_ONE_MINUS) return fail(err, EVCONV_ERR_INVALID_ARG, std::string(where) + "bad act");
     const bool delay = d.op == EVCONV_OP_DELAY;
     if (delay) {
       // in0: the later node whose previous-step value this is; in1: an earlier node of its size

@@ -25,7 +25,7 @@ inline Geo make_geo(int c, int h, int w) {
   return g;
 }
 
-enum Act { kActNone = 0, kActRelu = 1, kActSigmoid = 2, kActTanh = 3 };
+enum Act { kActNone = 0, kActRelu = 1, kActSigmoid = 2, kActTanh = 3, kActOneMinus = 4 };
 
 // Independent streams (cameras) that share the weights: every stream owns a copy of the whole
 // state region; copy number blockIdx.z of any state pointer lies blockIdx.z * stride bytes

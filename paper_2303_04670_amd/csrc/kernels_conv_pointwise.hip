@@ -22,6 +22,7 @@ __device__ __forceinline__ float act_p(int act, float v) {
   if (act == kActRelu) return fmaxf(v, 0.0f);
   if (act == kActSigmoid) return 1.0f / (1.0f + expf(-v));
   if (act == kActTanh) return tanhf(v);
+  if (act == kActOneMinus) return 1.0f - v;
   return v;
 }
 

@@ -26,7 +26,7 @@ import numpy as np
 (OP_CONV2D, OP_ADD, OP_CONCAT, OP_UPSAMPLE2X, OP_MAXPOOL, OP_GAP, OP_LINEAR, OP_ACT, OP_SPARSIFY,
  OP_MUL, OP_DELAY) = range(11)   # OP_DELAY: in0 = the LATER node whose previous-step value it is, in1 = an
 #                                  earlier node (or -1) with its height and width, c_out = its channels
-ACT_NONE, ACT_RELU, ACT_SIGMOID, ACT_TANH = range(4)
+ACT_NONE, ACT_RELU, ACT_SIGMOID, ACT_TANH, ACT_ONE_MINUS = range(5)   # ONE_MINUS: 1 - z
 WD_F32, WD_BF16, WD_F32_SPLIT = 0, 1, 2   # WD_F32_SPLIT: fp32 weights, contraction through bf16 high/low parts
 
 
@@ -634,5 +634,26 @@ def net_convlstm(seed=1008, in_c=4, h=64, w=96, hidden=28, out_c=2, k=3, bias=Tr
     h_new = b.simple(OP_MUL, go, tc)
     b.close_delay(h_prev, h_new)
     b.close_delay(c_prev, c_new)
+    b.conv(h_new, out_c, 1, 1, 0, ACT_NONE, out=1)
+    return b.finish()
+
+
+def net_convgru(seed=1009, in_c=4, h=64, w=96, hidden=32, out_c=2, k=3, bias=True) -> Net:
+    """A ConvGRU cell and a 1 x 1 head (tests; random weights): z, r = sigmoid(conv([x, h'])),
+    c = tanh(conv([x, r * h'])), h = (1 - z) * h' + z * c, with h' the cell's own h of the previous
+    step."""
+    b = _NetBuilder(f"convgru_{hidden}", in_c, h, w, seed, bias=bias)
+    h_prev = b.delay(hidden)
+    xh = b.simple(OP_CONCAT, -1, h_prev)
+    gz = b.conv(xh, hidden, k, 1, act=ACT_SIGMOID)
+    gr = b.conv(xh, hidden, k, 1, act=ACT_SIGMOID)
+    rh = b.simple(OP_MUL, gr, h_prev)
+    xrh = b.simple(OP_CONCAT, -1, rh)
+    cand = b.conv(xrh, hidden, k, 1, act=ACT_TANH)
+    omz = b.simple(OP_ACT, gz, act=ACT_ONE_MINUS)
+    keep = b.simple(OP_MUL, omz, h_prev)
+    new = b.simple(OP_MUL, gz, cand)
+    h_new = b.simple(OP_ADD, keep, new)
+    b.close_delay(h_prev, h_new)
     b.conv(h_new, out_c, 1, 1, 0, ACT_NONE, out=1)
     return b.finish()

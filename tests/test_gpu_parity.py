@@ -865,3 +865,18 @@ def test_convlstm_refresh_and_dense_recompute_keep_the_state():
                 z, zr = gpu.state(d, ev.STATE_Z).astype(np.float64), ora.z(d)
                 assert np.abs(z - zr).max() <= TOL * max(np.abs(zr).max(), 1e-30), f"{which} step {t} state {d}"
         gpu.destroy()
+
+
+def test_convgru_cell_against_oracle():
+    """A ConvGRU cell: two sigmoid gates, r * h', a tanh candidate on [x, r * h'], 1 - z, two
+    products and an add, one recurrent state; all nodes at every step."""
+    net = wl.net_convgru(43, in_c=4, h=24, w=40, hidden=32, out_c=2)
+    _say("ConvGRU cell, 4x24x40, hidden 32")
+    rng = np.random.default_rng(14)
+    x = rng.standard_normal((4, 24, 40)).astype(np.float32)
+    frames = [x]
+    for t in range(8):
+        m = rng.random((1, 24, 40)) < 0.05
+        x = (x + rng.standard_normal(x.shape).astype(np.float32) * m).astype(np.float32)
+        frames.append(x)
+    run_stream(net, frames[0], frames[1:], "frame", label="convgru", max_flips=40)

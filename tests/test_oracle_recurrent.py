@@ -105,3 +105,21 @@ def test_refresh_in_mid_stream_keeps_the_state():
         np.testing.assert_allclose(b.y(out), ref[n][out][1], atol=1e-11, err_msg=f"frame {n}")
         np.testing.assert_allclose(b.y(out), a.y(out), atol=1e-11)
         np.testing.assert_allclose(b.z(0), a.z(0), atol=1e-11)
+
+
+def test_convgru_equals_regular_forward_passes_frame_after_frame():
+    """The gated recurrent unit needs 1 - z: an activation whose increment is -x_inc."""
+    net = wl.net_convgru(34, in_c=3, h=8, w=10, hidden=5, out_c=2)
+    frames = _frames(np.random.default_rng(4), 3, 8, 10, 6)
+    ref = torch_recurrent(net, frames)
+    o = Oracle(net)
+    out = o.outputs[0]
+    omz = next(i for i, nd in enumerate(net.nodes) if nd.act == wl.ACT_ONE_MINUS)
+    for n, x in enumerate(frames):
+        (o.reset if n == 0 else o.step_frame)(x)
+        np.testing.assert_allclose(o.y(out), ref[n][out][1], atol=1e-11, err_msg=f"frame {n}")
+        want = ref[n - 1][net.nodes[0].in0][1] if n else np.zeros_like(ref[0][0][1])
+        np.testing.assert_allclose(o.z(0), want, atol=1e-11)
+        if n:   # the ONE_MINUS node: accumulated input z, increment -(z's increment)
+            np.testing.assert_allclose(o.z(omz), ref[n][net.nodes[omz].in0][1], atol=1e-11)
+            np.testing.assert_allclose(o.dy(omz), -o.dy(net.nodes[omz].in0), atol=1e-12)

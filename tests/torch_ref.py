@@ -53,6 +53,8 @@ def torch_forward(net, x_chw, upto=None, state=None):
             v = torch.sigmoid(z)
         elif nd.act == wl.ACT_TANH:
             v = torch.tanh(z)
+        elif nd.act == wl.ACT_ONE_MINUS:
+            v = 1.0 - z
         vals.append(v)
         outs.append((z[0].permute(1, 2, 0).numpy(), v[0].permute(1, 2, 0).numpy()))
     return outs
