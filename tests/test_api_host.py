@@ -58,7 +58,7 @@ def test_bad_descriptions_are_rejected():
     nodes[0].op = 42
     assert _status(desc) == ev.ERR_INVALID_ARG
     nodes[0].op = wl.OP_CONV2D
-    nodes[0].act = 4                       # one past tanh
+    nodes[0].act = 5                       # one past the last activation
     assert _status(desc) == ev.ERR_INVALID_ARG
     nodes[0].act = wl.ACT_TANH
     assert _status(desc) == ev.OK
