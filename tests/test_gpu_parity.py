@@ -611,7 +611,7 @@ def test_workload3_unet_split_bf16_full_size_100_steps():
 
 # --------------------------------------------------------------------------- several streams per net
 
-@pytest.mark.parametrize("which", ["unet", "mixed_ops", "sparsified"])
+@pytest.mark.parametrize("which", ["unet", "mixed_ops", "sparsified", "recurrent"])
 def test_streams_stepped_together_equal_single_stream_nets(which):
     """n_streams = 3: three independent event streams share the weights and are stepped by one
     call.  Every stream must equal a single-stream net fed the same frames, and stream 1 is also
@@ -621,6 +621,17 @@ def test_streams_stepped_together_equal_single_stream_nets(which):
     if which == "unet":
         net = wl.net_unet_depth(1003, h=64, w=96)
         gens = [list(wl.stream_voxel(40 + s, 64, 96, 6, 0.01 * (s + 1), n_prim=5)) for s in range(3)]
+    elif which == "recurrent":
+        net = wl.net_convlstm(44, in_c=4, h=16, w=24, hidden=32, out_c=2)
+        rng = np.random.default_rng(4)
+        gens = []
+        for s in range(3):
+            x = rng.standard_normal((4, 16, 24)).astype(np.float32)
+            fr = [x]
+            for _ in range(6):
+                x = (x + rng.standard_normal(x.shape).astype(np.float32) * (rng.random((1, 16, 24)) < 0.1)).astype(np.float32)
+                fr.append(x)
+            gens.append(fr)
     elif which == "mixed_ops":
         net = wl.net_random_small(7)
         rng = np.random.default_rng(3)
