@@ -900,3 +900,13 @@ def test_convgru_cell_against_oracle():
         x = (x + rng.standard_normal(x.shape).astype(np.float32) * m).astype(np.float32)
         frames.append(x)
     run_stream(net, frames[0], frames[1:], "frame", label="convgru", max_flips=40)
+
+
+def test_large_frame_720p():
+    """A 720p sensor (5 x 720 x 1280, 14400 tiles; widths 16..128): launch shapes and offsets far
+    from the benchmark's size, two steps against the oracle."""
+    _say("UNet depth net on a 5x720x1280 frame, width 16, reset + 2 steps")
+    net = wl.net_unet_depth(1003, h=720, w=1280, width=16)
+    frames = list(wl.stream_voxel(1010, 720, 1280, 2, 0.01, n_prim=12))
+    rep = run_stream(net, frames[0], frames[1:], "frame", check_nodes_at={2}, label="720p", max_flips=400)
+    _say(f"720p: max rel z err {rep.max_rel_z:.2e}, y err {rep.max_rel_y:.2e}, flips {rep.flips}")
