@@ -415,6 +415,14 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
           launch_rms_step(a, (size_t)n.ga.c * n.ga.sites(), net->sparsify_tp, net->rms_partial, n.step, net->st, s);
         p.act = d.act; p.dense = dense; p.keeps_z = n.keeps_z; p.structural = n.structural;
         p.ga = n.ga; p.gb = n.gb; p.go = n.go; p.a = a; p.occ_a = occ_a; p.b = bptr; p.occ_b = occ_b;
+        if (d.op == EVCONV_OP_CONCAT && n.upsampled_from != -2) {
+          // the first operand is an up-sampling that is never stored: read its stored source
+          const int src = n.upsampled_from;
+          p.op = kEwConcatUp;
+          p.a = src < 0 ? net->dx : net->L.nodes[src].out;
+          p.occ_a = src < 0 ? net->occ_in : net->L.nodes[src].occ;
+          p.ga = src < 0 ? net->L.gin : net->L.nodes[src].go;
+        }
         p.z = n.z; p.z2 = n.z2; p.out = n.out; p.occ_out = n.occ; p.occ_touched = n.touched;
         p.k = 1; p.stride = 1; p.pad = 0;
         launch_elementwise(p, s);
@@ -698,6 +706,17 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
       u_node.gather_fused_into = (int)i;
       c_node.upsampled_from = u_node.d.in0;
     }
+    // the same for a CONCAT whose first operand is an up-sampling nobody else reads: one kernel
+    // interpolates that operand's channels and copies the other's
+    for (size_t i = 0; i < L.nodes.size(); ++i) {
+      NodePlan& c_node = L.nodes[i];
+      if (c_node.d.op != EVCONV_OP_CONCAT || c_node.d.in0 < 0 || c_node.d.in0 == c_node.d.in1) continue;
+      NodePlan& u_node = L.nodes[c_node.d.in0];
+      if (u_node.d.op != EVCONV_OP_UPSAMPLE_BILINEAR2X || u_node.d.act != EVCONV_ACT_NONE || u_node.d.is_output ||
+          n_consumers[c_node.d.in0] != 1 || u_node.fused_into >= 0 || u_node.gather_fused_into >= 0) continue;
+      u_node.gather_fused_into = (int)i;
+      c_node.upsampled_from = u_node.d.in0;
+    }
   }
   *out = net;
   return EVCONV_OK;
@@ -899,7 +918,9 @@ evconv_status evconv_get_node_time(const evconv_net* net, int32_t node, double* 
 const char* evconv_node_kernel(const evconv_net* net, int32_t node) {
   if (!net || node < 0 || node >= (int)net->L.nodes.size()) return "";
   if (net->L.nodes[node].fused_into >= 0) return "fused_into_conv_epilogue";
-  if (net->L.nodes[node].gather_fused_into >= 0) return "fused_into_conv_gather";
+  if (net->L.nodes[node].gather_fused_into >= 0)
+    return net->L.nodes[net->L.nodes[node].gather_fused_into].d.op == EVCONV_OP_CONCAT ? "fused_into_concat_gather"
+                                                                                        : "fused_into_conv_gather";
   return kKernelNames[net->L.nodes[node].kernel];
 }
 

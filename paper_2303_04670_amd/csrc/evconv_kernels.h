@@ -119,7 +119,9 @@ int conv_narrow_padded_k(int k_tot);
 void launch_conv_narrow(const ConvParams& p, hipStream_t s);
 
 // ---- elementwise / structural increment operators ---------------------------------------
-enum EwOp { kEwAdd = 0, kEwAct, kEwConcat, kEwUp2x, kEwPoolAcc, kEwPoolMax, kEwSparsify, kEwMul };
+// kEwConcatUp: concat whose first operand is the bilinear x2 up-sampling of `a` (never stored):
+// ga is the stored low-resolution geometry of a, gb and go are at the output resolution
+enum EwOp { kEwAdd = 0, kEwAct, kEwConcat, kEwUp2x, kEwPoolAcc, kEwPoolMax, kEwSparsify, kEwMul, kEwConcatUp };
 struct EwParams {
   int op, act, dense, keeps_z, structural;
   Geo ga, gb, go;

@@ -171,15 +171,16 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
     } else if (p.op == kEwAct || p.op == kEwPoolAcc || p.op == kEwSparsify) {
       wa = p.occ_a[tile];
       t = (wa >> tid) & 1ull;
-    } else if (p.op == kEwUp2x) {
+    } else if (p.op == kEwUp2x || p.op == kEwConcatUp) {
       src = 0;
+      if (p.op == kEwConcatUp) wb = p.occ_b[tile];
       if (inb) {
         const int iy = oy >> 1, ix = ox >> 1;
         const int y0 = (oy & 1) ? iy : max(iy - 1, 0), y1 = (oy & 1) ? min(iy + 1, p.ga.h - 1) : iy;
         const int x0 = (ox & 1) ? ix : max(ix - 1, 0), x1 = (ox & 1) ? min(ix + 1, p.ga.w - 1) : ix;
         src = (unsigned)occ_bit(p.occ_a, p.ga.tx, y0, x0) | ((unsigned)occ_bit(p.occ_a, p.ga.tx, y0, x1) << 1) |
               ((unsigned)occ_bit(p.occ_a, p.ga.tx, y1, x0) << 2) | ((unsigned)occ_bit(p.occ_a, p.ga.tx, y1, x1) << 3);
-        t = src != 0;
+        t = src != 0 || (p.op == kEwConcatUp && ((wb >> tid) & 1ull));
       }
     } else {  // kEwPoolMax: windows that contain an active input site
       if (inb) {
@@ -243,20 +244,25 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
           lin.v[i] = cc < ca ? (on_a ? p.a[q * ca + cc] : 0.0f) : (on_b ? p.b[q * cb + cc - ca] : 0.0f);
         }
       }
-    } else if (p.op == kEwUp2x) {
+    } else if (p.op == kEwUp2x || (p.op == kEwConcatUp && c < p.ga.c)) {
+      // (kEwConcatUp runs with whole vectors only: c_a % 4 == 0, so a vector is on one side)
+      const int CA = p.ga.c;  // channels of the stored tensor (== C for a bare up-sampling)
       const int iy = oy >> 1, ix = ox >> 1;
       const int y0 = (oy & 1) ? iy : max(iy - 1, 0), y1 = (oy & 1) ? min(iy + 1, p.ga.h - 1) : iy;
       const int x0 = (ox & 1) ? ix : max(ix - 1, 0), x1 = (ox & 1) ? min(ix + 1, p.ga.w - 1) : ix;
       const float wy0 = (oy & 1) ? 0.75f : 0.25f, wy1 = 1.0f - wy0;
       const float wx0 = (ox & 1) ? 0.75f : 0.25f, wx1 = 1.0f - wx0;
       const unsigned src = s_src[site];
-      const VecT<VEC> v00 = (src & 1) ? ldv<VEC>(&p.a[((size_t)y0 * p.ga.w + x0) * C + c]) : zerov<VEC>();
-      const VecT<VEC> v01 = (src & 2) ? ldv<VEC>(&p.a[((size_t)y0 * p.ga.w + x1) * C + c]) : zerov<VEC>();
-      const VecT<VEC> v10 = (src & 4) ? ldv<VEC>(&p.a[((size_t)y1 * p.ga.w + x0) * C + c]) : zerov<VEC>();
-      const VecT<VEC> v11 = (src & 8) ? ldv<VEC>(&p.a[((size_t)y1 * p.ga.w + x1) * C + c]) : zerov<VEC>();
+      const VecT<VEC> v00 = (src & 1) ? ldv<VEC>(&p.a[((size_t)y0 * p.ga.w + x0) * CA + c]) : zerov<VEC>();
+      const VecT<VEC> v01 = (src & 2) ? ldv<VEC>(&p.a[((size_t)y0 * p.ga.w + x1) * CA + c]) : zerov<VEC>();
+      const VecT<VEC> v10 = (src & 4) ? ldv<VEC>(&p.a[((size_t)y1 * p.ga.w + x0) * CA + c]) : zerov<VEC>();
+      const VecT<VEC> v11 = (src & 8) ? ldv<VEC>(&p.a[((size_t)y1 * p.ga.w + x1) * CA + c]) : zerov<VEC>();
 #pragma unroll
       for (int i = 0; i < VEC; ++i)
         lin.v[i] = wy0 * (wx0 * v00.v[i] + wx1 * v01.v[i]) + wy1 * (wx0 * v10.v[i] + wx1 * v11.v[i]);
+    } else if (p.op == kEwConcatUp) {  // the second operand's channels
+      const bool on_b = (wb >> site) & 1ull;
+      lin = on_b ? ldv<VEC>(&p.b[q * p.gb.c + c - p.ga.c]) : zerov<VEC>();
     } else {  // kEwPoolMax: p.a is the accumulated pool input, p.z the cached window maximum
 #pragma unroll
       for (int i = 0; i < VEC; ++i) lin.v[i] = -INFINITY;
@@ -369,7 +375,7 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
 
 void launch_elementwise(const EwParams& p, hipStream_t s) {
   bool vec4 = (p.go.c % 4) == 0;
-  if (p.op == kEwConcat) vec4 = vec4 && (p.ga.c % 4) == 0;
+  if (p.op == kEwConcat || p.op == kEwConcatUp) vec4 = vec4 && (p.ga.c % 4) == 0;
   const int cv_all = p.go.c / (vec4 ? 4 : 1);
   dim3 grid(p.go.tiles(), (cv_all + kEwVecPerBlock - 1) / kEwVecPerBlock, p.st.n);
   if (vec4) hipLaunchKernelGGL(elementwise_kernel<4>, grid, dim3(256), 0, s, p);

@@ -180,6 +180,12 @@ def test_matrix_core_conv_shapes():
 def test_flow_net_reduced_concat_upsample():
     _say("flow encoder-decoder, reduced 4x64x64 width 8, density sweep, all nodes every step")
     net = wl.net_flow(1005, h=64, w=64, width=8)
+    g = ev.EvConvNet(net)
+    names = [g.kernel_name(i) for i in range(len(net.nodes))]
+    g.destroy()
+    # every decoder's up-sampling is read by its concatenation alone: interpolated there, never stored
+    ups = [i for i, n in enumerate(net.nodes) if n.op == wl.OP_UPSAMPLE2X]
+    assert ups and all(names[i] == "fused_into_concat_gather" for i in ups), names
     frames = list(wl.stream_count_timestamp(1005, 64, 64, densities=[0.001, 0.01, 0.05, 0.2], steps_per=4))
     run_stream(net, frames[0], frames[1:], "frame", label="flow-small", max_flips=8)
 
@@ -288,7 +294,7 @@ def test_run_to_run_bit_reproducible():
             g.step_frame(_dev(f))
         import torch
         torch.cuda.synchronize()
-        stored = [i for i in range(len(net.nodes)) if g.kernel_name(i) != "fused_into_conv_gather"]
+        stored = [i for i in range(len(net.nodes)) if not g.kernel_name(i).endswith("_gather")]
         res.append([g.state(i, ev.STATE_DY).copy() for i in stored] +
                    [g.outputs()[0]["y"].cpu().numpy()] + [g.site_list(i) for i in stored])
         g.destroy()
@@ -651,7 +657,7 @@ def test_streams_stepped_together_equal_single_stream_nets(which):
     singles = [ev.EvConvNet(net) for _ in range(3)]
     assert multi.n_streams == 3 and multi.stream_stride % 256 == 0
     ora = Oracle(net)
-    keeps = [i for i in range(len(net.nodes)) if not multi.kernel_name(i).startswith("fused_into_conv")]
+    keeps = [i for i in range(len(net.nodes)) if not multi.kernel_name(i).startswith("fused_into_")]
     for t in range(7):
         batch = _dev(np.stack([gens[s][t] for s in range(3)]))
         if t == 0:
