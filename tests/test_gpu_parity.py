@@ -1,13 +1,13 @@
 """GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element, on the
 same seeded inputs.  Integer products bit-exact (with counted rounding flips of value-pruned
-sets, see oracle/compare.py); fp32 tensors within 1e-4 * max|tensor| of the fp64 oracle."""
+sets, see compare.py); fp32 tensors within 1e-4 * max|tensor| of the fp64 oracle."""
 import dataclasses
 import sys
 
 import numpy as np
 import pytest
 
-from oracle import compare as cmp
+import compare as cmp
 from oracle.oracle import Oracle
 from paper_2303_04670_amd import evconv as ev
 from paper_2303_04670_amd import workloads as wl
