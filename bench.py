@@ -115,25 +115,25 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--density", type=float, default=0.02)
+    ap.add_argument("--density", type=float, default=0.02, help="changed pixels per step of the synthetic event stream")
     ap.add_argument("--variant", choices=["f32", "bf16", "f32_split"], default="f32",
                     help="contraction of the headline run: fp32 MFMA, bf16 weights, or fp32 through bf16 high/low parts")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-steps", type=int, default=20)
-    ap.add_argument("--no-dense", action="store_true")
-    ap.add_argument("--no-second-variant", action="store_true")
-    ap.add_argument("--no-sparsified", action="store_true")
-    ap.add_argument("--no-graph", action="store_true")
-    ap.add_argument("--no-recurrent", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the timed CPU oracle leg")
+    ap.add_argument("--cpu-steps", type=int, default=20, help="frames of the stream the CPU oracle is timed on")
+    ap.add_argument("--no-dense", action="store_true", help="skip the dense-recompute legs")
+    ap.add_argument("--no-second-variant", action="store_true", help="skip the other contraction modes")
+    ap.add_argument("--no-sparsified", action="store_true", help="skip the sparsification-layer leg")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay leg")
+    ap.add_argument("--no-recurrent", action="store_true", help="skip the ConvLSTM leg")
     ap.add_argument("--streams", type=int, default=16,
                     help="independent event streams per net in the multi_stream leg (0: skip the leg)")
-    ap.add_argument("--sparsify-tp", type=float, default=0.1)
+    ap.add_argument("--sparsify-tp", type=float, default=0.1, help="threshold parameter t_p of the sparsification-layer leg")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="also run plain device-to-device copies of this size (for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings against a kernel of known traffic)")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the headline run: optical-flow encoder-decoder (4x256x256), incremental "
-                         "vs dense recompute at 10 increment densities 0.1 % .. 20 %; prints one JSON line")
+                         "vs dense recompute at 10 increment densities 0.1 %% .. 20 %%; prints one JSON line")
     ap.add_argument("--sweep-steps", type=int, default=30)
     ap.add_argument("--drift", action="store_true",
                     help="instead of the headline run: drift of the fp32 running sums over --drift-steps steps of "
