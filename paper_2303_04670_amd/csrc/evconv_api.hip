@@ -44,6 +44,13 @@ struct NodePlan {
   int gather_fused_into = -1;  // UPSAMPLE node computed inside the gather of that conv node, never stored
   int upsampled_from = -2;     // conv node: the node (-1: network input) whose x2 up-sampling it reads through
                                // its gather, its in0 being the folded UPSAMPLE node; -2: none
+  // conv node reading through an up-sampling: the up-sampling folded into per-phase weights
+  // away from the image border (ConvParams::fold_list); room is reserved whenever in0 is an
+  // up-sampling and the taps are 5 x 5, used if the planner folds that up-sampling into this conv
+  size_t off_w_fold = 0, off_fold_list = 0;
+  void* w_fold = nullptr;
+  int* fold_list = nullptr;
+  int fold_k = 0, fold_base[2] = {0, 0};
   // workspace offsets (bytes); resolved to pointers at create
   size_t off_step = 0;      // SPARSIFY: device scalar k
   size_t off_z2 = 0;        // MUL: accumulated second factor
@@ -253,6 +260,12 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
       // room for input channels padded to whole chunks (at most 64) or a padded flattened contraction
       n.off_w = b.take(((size_t)k * k * ((n.d.c_in + 63) / 64 * 64) + 16) * n.c_out_pad * 4);
       if (n.d.bias_off >= 0) n.off_bias = b.take((size_t)n.d.c_out * 4);
+      if (n.d.op == EVCONV_OP_CONV2D && k == 5 && n.d.stride == 1 && n.d.pad == 2 && n.d.in0 >= 0 &&
+          L->nodes[n.d.in0].d.op == EVCONV_OP_UPSAMPLE_BILINEAR2X) {
+        // four phases x (4 x 4 taps) x input channels padded to 32 (see the planner in evconv_create)
+        n.off_w_fold = b.take((size_t)4 * 16 * ((n.d.c_in + 31) / 32 * 32) * n.c_out_pad * 4);
+        n.off_fold_list = b.take((size_t)n.go.tiles() * 4);
+      }
     }
     if (n.d.is_output) {
       n.off_y = b.take(elems * 4);
@@ -371,6 +384,8 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
         p.st = net->st;
         p.upsample = 0; p.lo_h = 0; p.lo_w = 0;
         p.y = nullptr; p.dy = nullptr; p.int_mode = 0;
+        p.fold_list = n.fold_list; p.w_fold = n.w_fold; p.fold_k = n.fold_k;
+        p.fold_base[0] = n.fold_base[0]; p.fold_base[1] = n.fold_base[1];
         if (n.upsampled_from != -2) {
           // read the stored low-resolution tensor; p.gi stays the up-sampled geometry
           const int src = n.upsampled_from;
@@ -485,6 +500,92 @@ void fill_outputs(evconv_net* net, evconv_out* out) {
     out[j].c = n.go.c; out[j].h = n.go.h; out[j].w = n.go.w;
     out[j].y = n.y; out[j].dy = n.dy; out[j].dy_idx = n.idx; out[j].dy_count = n.count;
   }
+}
+
+// Weight folding for a conv (k x k, pad k/2, stride 1) that reads through a bilinear x2
+// up-sampling (half-pixel centres: row 2q of the up-sampled tensor is 0.75 * stored row q + 0.25 *
+// row q - 1, row 2q + 1 is 0.75 * row q + 0.25 * row q + 1).  Both are linear (Eq.9), so for
+// outputs of one parity the composition is a conv on the stored tensor with kf < k taps per
+// dimension.  That holds where the window meets neither the clamped first / last up-sampled row
+// nor the conv's zero padding: stored sites `edge` or more away from the border.  Tiles of stored
+// sites made of such sites only are computed per phase with the folded weights; the up-sampled
+// tiles over all other stored tiles go through the interpolating gather.  Writes the four weight
+// sets and the tile list into the workspace.  `lo` is the stored tensor's geometry.
+hipError_t prepare_fold(evconv_net* net, NodePlan& n, const void* weights, const Geo& lo) {
+  const int k = n.d.kh, pad = n.d.pad, ci_n = n.d.c_in, co_n = n.d.c_out, cop = n.c_out_pad;
+  int base[2], main_row[2][8], other_row[2][8], kf = 0;
+  for (int par = 0; par < 2; ++par) {
+    int first = 1 << 20, last = -(1 << 20);
+    for (int ky = 0; ky < k; ++ky) {
+      const int r = par + ky - pad;                       // up-sampled row relative to 2 * (stored row)
+      const int q = r >= 0 ? r / 2 : -((1 - r) / 2);      // floor(r / 2)
+      main_row[par][ky] = q;
+      other_row[par][ky] = (r - 2 * q) ? q + 1 : q - 1;
+      first = std::min(first, std::min(main_row[par][ky], other_row[par][ky]));
+      last = std::max(last, std::max(main_row[par][ky], other_row[par][ky]));
+    }
+    base[par] = first;
+    kf = std::max(kf, last - first + 1);
+  }
+  const int edge = (pad + 2) / 2;
+  auto interior = [&](int t, int n_sites) { return 8 * t >= edge && 8 * t + 7 <= n_sites - 1 - edge; };
+  std::vector<int> list;
+  for (int ty = 0; ty < n.go.ty; ++ty)
+    for (int tx = 0; tx < n.go.tx; ++tx)
+      if (!(interior(ty / 2, lo.h) && interior(tx / 2, lo.w))) list.push_back(ty * n.go.tx + tx);
+  if ((int)list.size() == n.go.tiles()) return hipSuccess;  // nothing away from the border: no folding
+  for (int ty = 0; ty < lo.ty; ++ty)
+    for (int tx = 0; tx < lo.tx; ++tx)
+      if (interior(ty, lo.h) && interior(tx, lo.w))
+        for (int ph = 0; ph < 4; ++ph) list.push_back(-(1 + 4 * (ty * lo.tx + tx) + ph));
+  if ((int)list.size() != n.go.tiles() || kf != 4) return hipSuccess;  // (room was reserved for 4 x 4 taps)
+
+  const float* src = (const float*)((const char*)weights + n.d.weight_off);
+  const int taps = kf * kf;
+  std::vector<double> folded((size_t)4 * taps * ci_n * co_n, 0.0);
+  for (int py = 0; py < 2; ++py)
+    for (int px = 0; px < 2; ++px)
+      for (int ky = 0; ky < k; ++ky)
+        for (int kx = 0; kx < k; ++kx)
+          for (int sy = 0; sy < 2; ++sy)
+            for (int sx = 0; sx < 2; ++sx) {
+              const int ty = (sy ? other_row[py][ky] : main_row[py][ky]) - base[py];
+              const int tx = (sx ? other_row[px][kx] : main_row[px][kx]) - base[px];
+              const double coef = (sy ? 0.25 : 0.75) * (sx ? 0.25 : 0.75);
+              double* dst = &folded[((size_t)(py * 2 + px) * taps + ty * kf + tx) * ci_n * co_n];
+              for (int co = 0; co < co_n; ++co)
+                for (int ci = 0; ci < ci_n; ++ci)
+                  dst[(size_t)ci * co_n + co] += coef * (double)src[((size_t)co * ci_n + ci) * k * k + ky * k + kx];
+            }
+  const int ci_p = (ci_n + 31) / 32 * 32;
+  const size_t set = (size_t)taps * ci_p * cop;  // fp32 words per phase (two bf16 planes in split mode)
+  std::vector<float> staging(4 * set, 0.0f);
+  for (int ph = 0; ph < 4; ++ph)
+    for (int t = 0; t < taps; ++t)
+      for (int ci = 0; ci < ci_n; ++ci)
+        for (int co = 0; co < co_n; ++co) {
+          const float w = (float)folded[(((size_t)ph * taps + t) * ci_n + ci) * co_n + co];
+          if (n.kernel == kKernConvMfmaSplit) {
+            uint16_t* h16 = (uint16_t*)(staging.data() + ph * set);
+            const size_t at = (((size_t)t * (ci_p / 8) + ci / 8) * cop + co) * 8 + (ci & 7);
+            const uint16_t hi = to_bf16(w);
+            const uint32_t hu = (uint32_t)hi << 16;
+            float hf;
+            memcpy(&hf, &hu, 4);
+            h16[at] = hi;
+            h16[set + at] = to_bf16(w - hf);  // the low plane follows the high plane: `set` bf16 each
+          } else {
+            staging[ph * set + (((size_t)t * (ci_p / 4) + ci / 4) * cop + co) * 4 + (ci & 3)] = w;
+          }
+        }
+  n.w_fold = net->ws + n.off_w_fold;
+  n.fold_list = (int*)(net->ws + n.off_fold_list);
+  n.fold_k = kf;
+  n.fold_base[0] = base[0];
+  n.fold_base[1] = base[1];
+  hipError_t e = hipMemcpy(n.w_fold, staging.data(), staging.size() * 4, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(n.fold_list, list.data(), list.size() * 4, hipMemcpyHostToDevice);
+  return e;
 }
 
 }  // namespace
@@ -705,6 +806,13 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
       if (!conv_mfma_upsample_supported(probe)) continue;
       u_node.gather_fused_into = (int)i;
       c_node.upsampled_from = u_node.d.in0;
+      // away from the image border the up-sampling goes into the weights instead (fp32 products only:
+      // bf16-declared weights would be rounded a second time)
+      if (c_node.off_fold_list && c_node.kernel != kKernConvMfmaBf16 && !getenv("EVCONV_NO_FOLD")) {
+        const Geo& lo = u_node.d.in0 < 0 ? L.gin : L.nodes[u_node.d.in0].go;
+        e = prepare_fold(net, c_node, weights, lo);
+        if (e != hipSuccess) { g_create_error = std::string("folded weights upload: ") + hipGetErrorString(e); delete net; return EVCONV_ERR_HIP; }
+      }
     }
     // the same for a CONCAT whose first operand is an up-sampling nobody else reads: one kernel
     // interpolates that operand's channels and copies the other's
@@ -918,9 +1026,12 @@ evconv_status evconv_get_node_time(const evconv_net* net, int32_t node, double* 
 const char* evconv_node_kernel(const evconv_net* net, int32_t node) {
   if (!net || node < 0 || node >= (int)net->L.nodes.size()) return "";
   if (net->L.nodes[node].fused_into >= 0) return "fused_into_conv_epilogue";
-  if (net->L.nodes[node].gather_fused_into >= 0)
-    return net->L.nodes[net->L.nodes[node].gather_fused_into].d.op == EVCONV_OP_CONCAT ? "fused_into_concat_gather"
-                                                                                        : "fused_into_conv_gather";
+  if (net->L.nodes[node].gather_fused_into >= 0) {
+    const NodePlan& consumer = net->L.nodes[net->L.nodes[node].gather_fused_into];
+    if (consumer.d.op == EVCONV_OP_CONCAT) return "fused_into_concat_gather";
+    // (folded into the conv's weights away from the image border, into its gather along the border)
+    return consumer.fold_list ? "fused_into_conv_weights" : "fused_into_conv_gather";
+  }
   return kKernelNames[net->L.nodes[node].kernel];
 }
 

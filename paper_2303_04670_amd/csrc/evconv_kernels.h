@@ -89,6 +89,15 @@ struct ConvParams {
   // matrix-core kernel only: the input is the bilinear x2 up-sampling of `in` (lo_h x lo_w stored
   // sites, occ_in their occupancy words); gi describes the up-sampled tensor
   int upsample, lo_h, lo_w;
+  // up-sampling variant, optional (null = off): weight folding.  conv o bilinear x2 is, for each
+  // output phase (row parity, column parity), a fold_k x fold_k stride-1 conv on the stored tensor
+  // wherever the window stays clear of the clamped image border (Eq.9: both are linear).
+  // fold_list has one entry per 8 x 8 tile of the output: v >= 0 = that up-sampled tile, run
+  // through the interpolating gather; v < 0 = -(1 + 4 * stored_tile + 2 * row parity + column
+  // parity): the 64 outputs of one phase over one 8 x 8 tile of stored sites.  w_fold: the four
+  // phases' weight sets, each in the layout of w with fold_k x fold_k taps.  fold_base[parity]:
+  // first row (column) of the window relative to the stored site.
+  const int* fold_list; const void* w_fold; int fold_k; int fold_base[2];
   // few-channel pointwise kernel only: the node is a network output and the kernel keeps the
   // public tensors itself (y += increment, dy = increment; C x H x W); null otherwise.
   // int_mode is one of kIntStep / kIntReset / kIntRecompute.

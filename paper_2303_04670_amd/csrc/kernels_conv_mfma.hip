@@ -39,6 +39,14 @@
 // old z values are requested before the contraction starts.  ADD nodes that consume the conv
 // output (residual add + activation, skip adds) run here as well, writing their own buffers.
 //
+// A bilinear x2 up-sampling in front of the conv (Eq.9-10: both linear) never exists in memory
+// (UPS variants).  Along the image border the patch is interpolated from the stored tensor on
+// its way into LDS.  Away from the border the up-sampling is folded into the weights: the
+// outputs of one phase (row parity, column parity) are a conv of the stored tensor with fewer
+// taps (4 x 4 for 5 x 5), so a workgroup takes one phase of one tile of stored sites, gathers
+// the stored tensor directly and writes its 64 outputs two sites apart.  Which workgroup does
+// which is read from a list made at set-up (ConvParams::fold_list).
+//
 // The fp32 matrix instruction executes on the SIMD's vector pipeline: a vector instruction of any
 // wave of the SIMD takes time from the MFMAs.  Hence the addressing style throughout: per-lane
 // parts of an address are computed once and kept, per-unit / per-row parts live in scalar
@@ -126,6 +134,8 @@ void conv_mfma_kernel(ConvParams p) {
   constexpr int CSL = CHUNK + 4;      // UPS: site stride of the low-resolution fp32 buffer
   constexpr int LPMAX = 10;           // UPS: a 14-row patch has sources in at most 14 / 2 + 3 rows
   constexpr int MAXG = UPS ? (LPMAX * LPMAX * NV + NT - 1) / NT : MAXV;  // gathered float4 per thread
+  // a weight-folded workgroup gathers an (NROWS + 3) x 11 patch (4 x 4 taps) through the same registers
+  static_assert(!UPS || MAXG * NT >= (4 * MB + 3) * 11 * NV, "folded patch does not fit the gather registers");
   extern __shared__ __align__(16) float s_mem[];
   __shared__ uint64_t s_occ[16];
   __shared__ unsigned s_rows[24];  // bit px of s_rows[py]: patch site (py, px) is active
@@ -133,21 +143,41 @@ void conv_mfma_kernel(ConvParams p) {
   __shared__ unsigned s_nz[2 * (1 + kMaxFusedAdds)];  // nonzero-site bits: conv, then each fused ADD
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int tile = blockIdx.x / SUBS, sub = blockIdx.x % SUBS;
+  int tile = blockIdx.x / SUBS;
+  const int sub = blockIdx.x % SUBS;
+  // Weight-folded workgroup (UPS variants with a fold list): its 8 x 8 "tile" is a tile of stored
+  // sites, its outputs are the up-sampled sites of one phase, (2 * row + fpy, 2 * column + fpx);
+  // it gathers the stored tensor directly (no interpolation) under a fold_k x fold_k window that
+  // starts fold_base[parity] rows / columns from the site, and takes that phase's weight set.
+  bool fold = false;
+  int fpy = 0, fpx = 0;
+  if (UPS && OPM != kOpBf16 && p.fold_list) {  // (never used with bf16-declared weights)
+    const int e = p.fold_list[tile];
+    tile = e;
+    if (e < 0) {
+      fold = true;
+      tile = (-1 - e) >> 2;
+      fpy = ((-1 - e) >> 1) & 1;
+      fpx = (-1 - e) & 1;
+    }
+  }
+  const bool ups = UPS && !fold;  // this workgroup interpolates its patch
   const int r0 = sub * NROWS;  // first tile row of this workgroup
   const uint64_t row_mask = MB == 2 ? ~0ull : (0xffffffffull << (32 * sub));
-  const int tile_y = tile / p.go.tx, tile_x = tile - tile_y * p.go.tx;
-  const int s = p.stride, K = p.k;
+  const int n_tx = fold ? (p.lo_w + 7) >> 3 : p.go.tx;
+  const int tile_y = tile / n_tx, tile_x = tile - tile_y * n_tx;
+  const int s = p.stride, K = fold ? p.fold_k : p.k;
   const int H = p.gi.h, W = p.gi.w, Cin = p.gi.c, Cout = p.go.c;
-  const int iy0 = (tile_y * 8 + r0) * s - p.pad, ix0 = tile_x * 8 * s - p.pad;
+  const int iy0 = fold ? tile_y * 8 + r0 + p.fold_base[fpy] : (tile_y * 8 + r0) * s - p.pad;
+  const int ix0 = fold ? tile_x * 8 + p.fold_base[fpx] : tile_x * 8 * s - p.pad;
   const int PH = (NROWS - 1) * s + K, PW = 7 * s + K;
   // The region whose stored occupancy is read: the patch itself, or (UPS) the low-resolution
   // sources of the patch: rows (iy0 >> 1) - 1 .. and columns likewise, PH / 2 + 3 by PW / 2 + 3
   // sites (a source index is i/2 - 1, i/2 or i/2 + 1 before clamping to the image).
   const int SH = UPS ? p.lo_h : H, SW = UPS ? p.lo_w : W;  // stored tensor
   const int s_ty = (SH + 7) >> 3, s_tx = (SW + 7) >> 3;
-  const int gy0 = UPS ? (iy0 >> 1) - 1 : iy0, gx0 = UPS ? (ix0 >> 1) - 1 : ix0;
-  const int GH = UPS ? PH / 2 + 3 : PH, GW = UPS ? PW / 2 + 3 : PW;
+  const int gy0 = ups ? (iy0 >> 1) - 1 : iy0, gx0 = ups ? (ix0 >> 1) - 1 : ix0;
+  const int GH = ups ? PH / 2 + 3 : PH, GW = ups ? PW / 2 + 3 : PW;
   const int rty0 = gy0 >> 3, rtx0 = gx0 >> 3;
   const int rny = ((gy0 + GH - 1) >> 3) - rty0 + 1, rnx = ((gx0 + GW - 1) >> 3) - rtx0 + 1;
 
@@ -155,8 +185,18 @@ void conv_mfma_kernel(ConvParams p) {
   // runs alongside that of the input's occupancy words instead of after it
   uint64_t skip_raw[kMaxFusedAdds];
 #pragma unroll
-  for (int f = 0; f < kMaxFusedAdds; ++f)
-    skip_raw[f] = (f < p.n_fused && !p.dense) ? at_stream(p.fused[f].occ_skip, so)[tile] : 0;
+  for (int f = 0; f < kMaxFusedAdds; ++f) {
+    skip_raw[f] = 0;
+    if (f >= p.n_fused || p.dense) continue;
+    if (fold) {
+      // per lane (= site of the stored tile) the word of the up-sampled tile its output lies in;
+      // turned into this phase's site bits further down
+      const int ly = lane >> 3, lx = lane & 7;
+      skip_raw[f] = at_stream(p.fused[f].occ_skip, so)[(2 * tile_y + (ly >> 2)) * p.go.tx + 2 * tile_x + (lx >> 2)];
+    } else {
+      skip_raw[f] = at_stream(p.fused[f].occ_skip, so)[tile];
+    }
+  }
   if (tid < 16) {
     const int ry = tid >> 2, rx = tid & 3;
     const int ty = rty0 + ry, tx = rtx0 + rx;
@@ -184,10 +224,10 @@ void conv_mfma_kernel(ConvParams p) {
       m &= ~((1u << lo) - 1u);
       bits &= m;
     }
-    if (UPS) s_lrows[tid] = bits; else s_rows[tid] = bits;
+    if (ups) s_lrows[tid] = bits; else s_rows[tid] = bits;
   }
   __syncthreads();
-  if (UPS) {
+  if (ups) {
     // an up-sampled site is active where one of its four sources is: OR of two source rows, then
     // of two source columns; sites outside the up-sampled image stay 0
     if (tid < PH) {
@@ -218,7 +258,8 @@ void conv_mfma_kernel(ConvParams p) {
     const int oy = tile_y * 8 + ly, ox = tile_x * 8 + lx;
     const int lr = ly - r0;
     bool touched = false;
-    if (lr >= 0 && lr < NROWS && oy < p.go.h && ox < p.go.w) {
+    // (a weight-folded workgroup's tile lies inside the stored image, all of its outputs exist)
+    if (lr >= 0 && lr < NROWS && (fold || (oy < p.go.h && ox < p.go.w))) {
       unsigned rows = 0;
       for (int ky = 0; ky < K; ++ky) rows |= s_rows[lr * s + ky];
       touched = p.dense || ((rows >> (lx * s)) & ((1u << K) - 1u)) != 0;
@@ -231,6 +272,8 @@ void conv_mfma_kernel(ConvParams p) {
 #pragma unroll
   for (int f = 0; f < kMaxFusedAdds; ++f) {
     skip_word[f] = 0;
+    if (f < p.n_fused && fold && !p.dense)
+      skip_raw[f] = __ballot(((skip_raw[f] >> ((2 * ((lane >> 3) & 3) + fpy) * 8 + 2 * (lane & 3) + fpx)) & 1ull) != 0);
     if (f < p.n_fused) skip_word[f] = p.dense ? touched_word : (skip_raw[f] & row_mask);
     site_word |= skip_word[f];
   }
@@ -247,9 +290,11 @@ void conv_mfma_kernel(ConvParams p) {
   const int co = tid & 31;
   const int co0 = blockIdx.y * 32;
   const int es = tid >> 5;
+  // (weight-folded: site (y, x) of the stored tile is output site (2y + fpy, 2x + fpx))
+  const int ey = tile_y * 8 + r0 + (es >> 3), ex = tile_x * 8 + (es & 7);
   const unsigned ep_voff =
-      (unsigned)((((tile_y * 8 + r0 + (es >> 3)) * p.go.w + tile_x * 8 + (es & 7)) * Cout + co0 + co) * 4);
-  const unsigned ep_step = (unsigned)((EP_SITES / 8) * p.go.w * Cout * 4);
+      (unsigned)((((fold ? 2 * ey + fpy : ey) * p.go.w + (fold ? 2 * ex + fpx : ex)) * Cout + co0 + co) * 4);
+  const unsigned ep_step = (unsigned)((EP_SITES / 8) * p.go.w * Cout * 4) << (fold ? 1 : 0);
   const int out_bytes = p.go.h * p.go.w * Cout * 4;
   constexpr unsigned kSkipAccess = 0x80000000u;
   constexpr uint64_t kMine = EP_SITES == 8 ? 0x0101010101010101ull : 0x0001000100010001ull;
@@ -289,8 +334,8 @@ void conv_mfma_kernel(ConvParams p) {
     if (e < total_v) {
       const int site = e / NV, v = e - site * NV;
       const int py = (site * gw_magic) >> 16, px = site - py * GW;
-      lds_off[j] = UPS ? site * CSL + v * 4 : (BF16 ? site * CS + v * 2 : site * CS + v * 4);
-      const unsigned row = UPS ? s_lrows[py] : s_rows[py];
+      lds_off[j] = ups ? site * CSL + v * 4 : (BF16 ? site * CS + v * 2 : site * CS + v * 4);
+      const unsigned row = ups ? s_lrows[py] : s_rows[py];
       if ((row >> px) & 1u) g_off[j] = (unsigned)((((gy0 + py) * SW + gx0 + px) * Cin + v * 4) * 4);
     }
   }
@@ -332,7 +377,7 @@ void conv_mfma_kernel(ConvParams p) {
 #pragma unroll
     for (int j = 0; j < MAXG; ++j)
       if (lds_off[j] >= 0) {
-        if (UPS) *(float4*)&s_low[lds_off[j]] = pre[j];
+        if (ups) *(float4*)&s_low[lds_off[j]] = pre[j];
         else put(lds_off[j], pre[j]);
       }
   };
@@ -350,7 +395,9 @@ void conv_mfma_kernel(ConvParams p) {
   // per item two packed words: ib_src = source offset (12 bits) | row step (10) | column step (6);
   // ib_dst = patch offset + 4096 (16 bits) | write mask (4) | inside-the-image mask (4)
   int ib_src[MAXB], ib_dst[MAXB];
-  if (UPS) {
+#pragma unroll
+  for (int b = 0; b < MAXB; ++b) ib_src[b] = ib_dst[b] = 0;
+  if (ups) {
     const int by0 = (iy0 - 1) >> 1, bx0 = (ix0 - 1) >> 1;
     const int nby = ((iy0 + PH - 2) >> 1) - by0 + 1, nbx = ((ix0 + PW - 2) >> 1) - bx0 + 1;
     const int nbx_magic = (65536 + nbx - 1) / nbx;  // blk / nbx == (blk * nbx_magic) >> 16 for blk < 64
@@ -429,8 +476,9 @@ void conv_mfma_kernel(ConvParams p) {
   // B: buffer load with the lane part as vector offset and the unit part as scalar offset
   // (bytes; the launcher checks that the re-laid weights stay below 2 GiB).
   const unsigned w_plane = (unsigned)(K * K * cin_rows * cop) * 16u;  // split mode: the low-part plane follows
-  const __amdgpu_buffer_rsrc_t w_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc((void*)p.w, 0, (int)(w_plane * (SPLIT ? 2u : 1u)), 0x00020000);
+  const unsigned w_set = w_plane * (SPLIT ? 2u : 1u);  // one weight set; a folded workgroup takes its phase's
+  const char* const w_base = fold ? (const char*)p.w_fold + (size_t)(fpy * 2 + fpx) * w_set : (const char*)p.w;
+  const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)w_base, 0, (int)w_set, 0x00020000);
   const unsigned w_lane = (unsigned)(half * cop + co0 + m) * 16u;
   // unit j of the chunk starting at channel c0 (j clamped to the last unit so that look-ahead
   // loads stay unconditional and in bounds)
@@ -516,7 +564,7 @@ void conv_mfma_kernel(ConvParams p) {
     __syncthreads();  // all waves are done reading the previous chunk
     stash();
     __syncthreads();
-    if (UPS) {
+    if (ups) {
       interpolate();
       __syncthreads();
     }
@@ -661,21 +709,39 @@ void conv_mfma_kernel(ConvParams p) {
     if (f < p.n_fused) lds_or(1 + f, nz_fused[f]);
   __syncthreads();
   if (tid == 0) {
-    auto glob_or = [](uint64_t* dst, uint64_t bits) {
-      if (bits) atomicOr((unsigned long long*)dst, (unsigned long long)bits);
+    // site bits of this workgroup into the words of a set: its own tile's word, or (weight-folded)
+    // the words of the four up-sampled tiles over the stored tile, where site (y, x) is bit
+    // (2 * (y % 4) + fpy, 2 * (x % 4) + fpx) of tile (y / 4, x / 4)
+    auto glob_or = [&](uint64_t* words, uint64_t bits) {
+      if (!bits) return;
+      if (!fold) {
+        atomicOr((unsigned long long*)&words[tile], (unsigned long long)bits);
+        return;
+      }
+      for (int a = 0; a < 2; ++a)
+        for (int b = 0; b < 2; ++b) {
+          uint64_t spread = 0;
+          for (int r = 0; r < 4; ++r) {
+            const unsigned nib = (unsigned)(bits >> ((4 * a + r) * 8 + 4 * b)) & 0xfu;
+            const unsigned wide = (nib & 1u) | ((nib & 2u) << 1) | ((nib & 4u) << 2) | ((nib & 8u) << 3);
+            spread |= (uint64_t)wide << ((2 * r + fpy) * 8 + fpx);
+          }
+          if (spread)
+            atomicOr((unsigned long long*)&words[(2 * tile_y + a) * p.go.tx + 2 * tile_x + b], (unsigned long long)spread);
+        }
     };
     // S of the producer as seen by this workgroup's rows and channels; all words are pre-zeroed
     // and the other workgroups of the tile OR their share in
     uint64_t s_prev = p.dense ? touched_word : ((uint64_t)s_nz[0] | ((uint64_t)s_nz[1] << 32));
-    glob_or(&at_stream(p.occ_out, so)[tile], s_prev);
-    if (blockIdx.y == 0) glob_or(&at_stream(p.occ_touched, so)[tile], touched_word);
+    glob_or(at_stream(p.occ_out, so), s_prev);
+    if (blockIdx.y == 0) glob_or(at_stream(p.occ_touched, so), touched_word);
     for (int f = 0; f < p.n_fused; ++f) {
       const FusedAdd& fa = p.fused[f];
       const uint64_t t_f = s_prev | skip_word[f];  // Eq.11b
       const uint64_t nz_f = (uint64_t)s_nz[2 + 2 * f] | ((uint64_t)s_nz[3 + 2 * f] << 32);
       const uint64_t s_f = (fa.structural || p.dense) ? t_f : nz_f;
-      glob_or(&at_stream(fa.occ_touched, so)[tile], t_f);
-      glob_or(&at_stream(fa.occ_out, so)[tile], s_f);
+      glob_or(at_stream(fa.occ_touched, so), t_f);
+      glob_or(at_stream(fa.occ_out, so), s_f);
       s_prev = s_f;
     }
   }

@@ -82,7 +82,7 @@ def compare_node(gpu, ora: Oracle, i: int, rep: Report, tol=1e-4, act_scale=None
     from paper_2303_04670_amd import evconv as ev
     c, h, w = ora.shape(i)
     assert gpu.shape(i) == (c, h, w)
-    if gpu.kernel_name(i) in ("fused_into_conv_gather", "fused_into_concat_gather"):
+    if gpu.kernel_name(i) in ("fused_into_conv_gather", "fused_into_conv_weights", "fused_into_concat_gather"):
         return  # never materialised: the consuming conv, which is compared, reads it through its gather
     s_ref, t_ref = ora.mask(i, SET_ACTIVE), ora.mask(i, SET_TOUCHED)
     occ = gpu.state(i, ev.STATE_OCC)

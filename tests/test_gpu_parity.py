@@ -106,7 +106,8 @@ def test_unet_full_width_reduced_size_matrix_core_layers():
     g.destroy()
     assert names.count("conv_mfma_f32") == 10 and names[0] == "conv_narrow_mfma_f32" and names[-1] == "conv_pointwise_f32", names
     assert names.count("fused_into_conv_epilogue") == 6, names   # 2 residual adds + 4 skip adds
-    assert names.count("fused_into_conv_gather") == 3, names     # the three x2 up-samplings
+    # the three x2 up-samplings: only the last one's stored tensor (32 x 48) has tiles away from the border
+    assert names.count("fused_into_conv_gather") == 2 and names.count("fused_into_conv_weights") == 1, names
     frames = list(wl.stream_voxel(1003, 64, 96, 20, 0.02, n_prim=6))
     run_stream(net, frames[0], frames[1:], "frame", label="unet-wide", max_flips=40)
 
@@ -119,7 +120,7 @@ def test_unet_full_width_without_epilogue_fusion(monkeypatch):
     g = ev.EvConvNet(net)
     names = [g.kernel_name(i) for i in range(len(net.nodes))]
     g.destroy()
-    assert "fused_into_conv_epilogue" not in names and "fused_into_conv_gather" not in names
+    assert not any(nm.startswith("fused_into_") for nm in names), names
     frames = list(wl.stream_voxel(1003, 64, 96, 8, 0.02, n_prim=6))
     run_stream(net, frames[0], frames[1:], "frame", label="unet-wide-unfused", max_flips=40)
 
@@ -294,7 +295,7 @@ def test_run_to_run_bit_reproducible():
             g.step_frame(_dev(f))
         import torch
         torch.cuda.synchronize()
-        stored = [i for i in range(len(net.nodes)) if not g.kernel_name(i).endswith("_gather")]
+        stored = [i for i in range(len(net.nodes)) if not g.kernel_name(i).endswith(("_gather", "_weights"))]
         res.append([g.state(i, ev.STATE_DY).copy() for i in stored] +
                    [g.outputs()[0]["y"].cpu().numpy()] + [g.site_list(i) for i in stored])
         g.destroy()
@@ -474,7 +475,10 @@ def test_sparsified_unet_properties_and_speed_of_convergence():
     gs.reset(_dev(frames[-1]))
     ga.reset(_dev(frames[-1]))
     torch.cuda.synchronize()
-    np.testing.assert_array_equal(ga.outputs()[0]["y"].cpu().numpy(), gs.outputs()[0]["y"].cpu().numpy())
+    # a refresh is a regular forward pass, the layer is the identity there: the same function.  (Not
+    # the same roundings: the plain net's up-sampling convs run with folded weights, this net's
+    # convs read a sparsification layer and do not.)
+    np.testing.assert_allclose(ga.outputs()[0]["y"].cpu().numpy(), gs.outputs()[0]["y"].cpu().numpy(), rtol=0, atol=1e-5)
     ga.destroy()
     gs.destroy()
 
