@@ -533,11 +533,21 @@ hipError_t prepare_fold(evconv_net* net, NodePlan& n, const void* weights, const
   for (int ty = 0; ty < n.go.ty; ++ty)
     for (int tx = 0; tx < n.go.tx; ++tx)
       if (!(interior(ty / 2, lo.h) && interior(tx / 2, lo.w))) list.push_back(ty * n.go.tx + tx);
+  // (the border tiles' workgroups run longest: they come first; interleaving them with the folded
+  // ones measured 3.5 % slower)
   if ((int)list.size() == n.go.tiles()) return hipSuccess;  // nothing away from the border: no folding
+  // Consecutive workgroups go to the chip's 8 XCDs in turn, each with an L2 of its own.  The four
+  // phases of a stored tile gather the same patch: they are placed 8 list entries apart, so that
+  // one XCD runs all four and fetches the patch from memory once.
+  std::vector<int> inner;
   for (int ty = 0; ty < lo.ty; ++ty)
     for (int tx = 0; tx < lo.tx; ++tx)
-      if (interior(ty, lo.h) && interior(tx, lo.w))
-        for (int ph = 0; ph < 4; ++ph) list.push_back(-(1 + 4 * (ty * lo.tx + tx) + ph));
+      if (interior(ty, lo.h) && interior(tx, lo.w)) inner.push_back(ty * lo.tx + tx);
+  for (size_t g = 0; g < inner.size(); g += 8) {
+    const size_t nt = std::min<size_t>(8, inner.size() - g);
+    for (int ph = 0; ph < 4; ++ph)
+      for (size_t t = 0; t < nt; ++t) list.push_back(-(1 + 4 * inner[g + t] + ph));
+  }
   if ((int)list.size() != n.go.tiles() || kf != 4) return hipSuccess;  // (room was reserved for 4 x 4 taps)
 
   const float* src = (const float*)((const char*)weights + n.d.weight_off);
