@@ -262,7 +262,14 @@ evconv_status evconv_profile_end(evconv_net* net);
 evconv_status evconv_get_node_time(const evconv_net* net, int32_t node, double* ms_total /* HOST */,
                                    int64_t* launches /* HOST */);
 
-/* Name of the kernel family that executes a node ("conv_valu_f32", "conv_mfma_f32", ...). */
+/* Name of the kernel family that executes a node ("conv_valu_f32", "conv_mfma_f32", ...).  A node
+ * that another node's kernel computes reports where it went: "fused_into_conv_epilogue" (an ADD
+ * applied by the producing convolution; its buffers are still written), "fused_into_conv_gather",
+ * "fused_into_conv_weights", "fused_into_concat_gather" (an up-sampling that exists only inside
+ * its consumer: such a node keeps no state and evconv_get_state fails for it).  The environment
+ * variables EVCONV_NO_FUSION (no node is computed by another node's kernel), EVCONV_NO_FOLD (an
+ * up-sampling is never folded into the consuming convolution's weights) and EVCONV_FORCE_VALU
+ * (no matrix-core kernels), read by evconv_create, exist for tests and comparisons. */
 const char* evconv_node_kernel(const evconv_net* net, int32_t node);
 
 /* Text of the last error on this net (or of the last failed create when net is NULL). */

@@ -935,11 +935,11 @@ evconv_status evconv_get_state_stream(evconv_net* net, int32_t stream, int32_t n
                                       size_t bytes) {
   if (!net) return EVCONV_ERR_INVALID_ARG;
   if (stream < 0 || stream >= net->L.n_streams) { net->err = "no such stream"; return EVCONV_ERR_INVALID_ARG; }
+  if (!dst || node < -1 || node >= (int)net->L.nodes.size()) { net->err = "bad node or null dst"; return EVCONV_ERR_INVALID_ARG; }
   if (node >= 0 && net->L.nodes[node].gather_fused_into >= 0) {
-    net->err = "this node is computed inside its consumer's gather and keeps no state";
+    net->err = "this node is computed inside its consumer and keeps no state";
     return EVCONV_ERR_INVALID_ARG;
   }
-  if (!dst || node < -1 || node >= (int)net->L.nodes.size()) { net->err = "bad node or null dst"; return EVCONV_ERR_INVALID_ARG; }
   const Geo& g = node < 0 ? net->L.gin : net->L.nodes[node].go;
   const NodePlan* n = node < 0 ? nullptr : &net->L.nodes[node];
   const void* src = nullptr;

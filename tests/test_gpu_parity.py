@@ -309,6 +309,12 @@ def test_step_before_reset_is_an_error():
     with pytest.raises(ev.EvConvError) as e:
         g.step(_dev(np.zeros((4, 8, 8), np.float32)))
     assert e.value.status == ev.ERR_STATE
+    # a node index out of range is refused by the C ABI itself (called directly, past the binding)
+    import ctypes
+    buf = np.zeros(64, np.float32)
+    for node in (1, 7, -2):
+        st = ev.lib().evconv_get_state_stream(g._h, 0, node, ev.STATE_Z, buf.ctypes.data_as(ctypes.c_void_p), buf.nbytes)
+        assert st != 0, node
     g.destroy()
 
 
@@ -789,6 +795,51 @@ def test_random_wide_graphs_all_contraction_modes(seed):
         run_stream(net, frames[0], frames[1:], "frame", tol=2e-2, label=f"wide{seed}", max_flips=10**9, frobenius=True)
     else:
         run_stream(net, frames[0], frames[1:], "frame", label=f"wide{seed}", max_flips=40)
+
+
+@pytest.mark.parametrize("seed,h,w", [(0, 84, 108), (6, 84, 108), (7, 72, 136), (19, 100, 92), (2, 84, 108)])
+def test_upsampling_folded_into_conv_weights(seed, h, w, monkeypatch):
+    """A 5 x 5 conv reading a x2 up-sampling at sizes where the stored tensor has tiles away from
+    the border: those run per output phase with folded 4 x 4 weights, the border tiles through the
+    interpolating gather (ragged tile rows and columns, one or two output-channel blocks, 32-96
+    input channels, fp32 and split products; bf16-declared weights must not fold).  All nodes at
+    every step against the oracle; then the same frames with folding switched off: identical
+    touched sets, values apart by rounding only."""
+    rng = np.random.default_rng(300 + seed)
+    mode = ["f32", "split", "bf16"][seed % 3]
+    net = wl.net_random_wide(seed, h, w)
+    if mode == "bf16":
+        net = wl.with_weight_dtype(dataclasses.replace(net, weights=wl.round_to_bf16(net.weights)), wl.WD_BF16)
+    elif mode == "split":
+        net = wl.with_weight_dtype(net, wl.WD_F32_SPLIT)
+    _say(f"folded up-sampling, random wide graph {seed} at {h}x{w}: {len(net.nodes)} nodes, {mode}")
+    up = [i for i, n in enumerate(net.nodes) if n.op == wl.OP_UPSAMPLE2X][0]
+    g = ev.EvConvNet(net)
+    assert g.kernel_name(up) == ("fused_into_conv_gather" if mode == "bf16" else "fused_into_conv_weights")
+    g.destroy()
+    x = rng.standard_normal((net.in_c, h, w)).astype(np.float32)
+    frames = [x]
+    for t in range(5):
+        m = rng.random((1, h, w)) < (0.03 if t != 2 else 0.5)
+        x = (x + rng.standard_normal(x.shape).astype(np.float32) * m).astype(np.float32)
+        frames.append(x)
+    if mode == "bf16":
+        run_stream(net, frames[0], frames[1:], "frame", tol=2e-2, label=f"fold{seed}", max_flips=10**9, frobenius=True)
+        return
+    run_stream(net, frames[0], frames[1:], "frame", label=f"fold{seed}", max_flips=40)
+    folded = ev.EvConvNet(net)
+    monkeypatch.setenv("EVCONV_NO_FOLD", "1")
+    plain = ev.EvConvNet(net)
+    assert plain.kernel_name(up) == "fused_into_conv_gather"
+    conv = [i for i, n in enumerate(net.nodes) if n.op == wl.OP_CONV2D and n.in0 == up][0]
+    for t, f in enumerate(frames):
+        for net_ in (folded, plain):
+            (net_.reset if t == 0 else net_.step_frame)(_dev(f))
+        np.testing.assert_array_equal(folded.state(conv, ev.STATE_OCC_TOUCHED), plain.state(conv, ev.STATE_OCC_TOUCHED))
+        za, zb = folded.state(conv, ev.STATE_Z), plain.state(conv, ev.STATE_Z)
+        assert np.abs(za - zb).max() <= 2e-5 * np.abs(zb).max(), (t, np.abs(za - zb).max(), np.abs(zb).max())
+    folded.destroy()
+    plain.destroy()
 
 
 # --------------------------------------------------------------------------- recurrent state
