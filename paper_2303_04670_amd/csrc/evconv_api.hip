@@ -384,7 +384,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
         p.st = net->st;
         p.upsample = 0; p.lo_h = 0; p.lo_w = 0;
         p.y = nullptr; p.dy = nullptr; p.int_mode = 0;
-        p.fold_list = n.fold_list; p.w_fold = n.w_fold; p.fold_k = n.fold_k;
+        p.fold_list = n.fold_list; p.w_fold = n.w_fold; p.fold_k = n.fold_k; p.wg_swap = 0;
         p.fold_base[0] = n.fold_base[0]; p.fold_base[1] = n.fold_base[1];
         if (n.upsampled_from != -2) {
           // read the stored low-resolution tensor; p.gi stays the up-sampled geometry
@@ -536,18 +536,14 @@ hipError_t prepare_fold(evconv_net* net, NodePlan& n, const void* weights, const
   // (the border tiles' workgroups run longest: they come first; interleaving them with the folded
   // ones measured 3.5 % slower)
   if ((int)list.size() == n.go.tiles()) return hipSuccess;  // nothing away from the border: no folding
-  // Consecutive workgroups go to the chip's 8 XCDs in turn, each with an L2 of its own.  The four
-  // phases of a stored tile gather the same patch: they are placed 8 list entries apart, so that
-  // one XCD runs all four and fetches the patch from memory once.
-  std::vector<int> inner;
+  // Consecutive workgroups go to the chip's 8 XCDs in turn, each with an L2 of its own.  With the
+  // four phases of a tile next to each other an XCD runs one phase only and so reads one of the
+  // four weight sets (measured: placing a tile's phases on one XCD instead, to share the patch,
+  // raises the HBM fetch of the launches by 12 %: the weights outweigh the patches).
   for (int ty = 0; ty < lo.ty; ++ty)
     for (int tx = 0; tx < lo.tx; ++tx)
-      if (interior(ty, lo.h) && interior(tx, lo.w)) inner.push_back(ty * lo.tx + tx);
-  for (size_t g = 0; g < inner.size(); g += 8) {
-    const size_t nt = std::min<size_t>(8, inner.size() - g);
-    for (int ph = 0; ph < 4; ++ph)
-      for (size_t t = 0; t < nt; ++t) list.push_back(-(1 + 4 * inner[g + t] + ph));
-  }
+      if (interior(ty, lo.h) && interior(tx, lo.w))
+        for (int ph = 0; ph < 4; ++ph) list.push_back(-(1 + 4 * (ty * lo.tx + tx) + ph));
   if ((int)list.size() != n.go.tiles() || kf != 4) return hipSuccess;  // (room was reserved for 4 x 4 taps)
 
   const float* src = (const float*)((const char*)weights + n.d.weight_off);

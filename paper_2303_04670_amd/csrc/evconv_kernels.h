@@ -98,6 +98,9 @@ struct ConvParams {
   // phases' weight sets, each in the layout of w with fold_k x fold_k taps.  fold_base[parity]:
   // first row (column) of the window relative to the stored site.
   const int* fold_list; const void* w_fold; int fold_k; int fold_base[2];
+  // matrix-core kernel only, set by its launcher: the grid's x dimension runs over the blocks of
+  // 32 output channels and y over the tiles, instead of the other way round
+  int wg_swap;
   // few-channel pointwise kernel only: the node is a network output and the kernel keeps the
   // public tensors itself (y += increment, dy = increment; C x H x W); null otherwise.
   // int_mode is one of kIntStep / kIntReset / kIntRecompute.
