@@ -37,7 +37,7 @@ PEAKS = {  # MI355X published dense peaks
 
 # HBM bytes per launch of the dominant kernel family, from the committed rocprofv3 counter runs
 # (profiles/unet_depth_f32_incremental_kernels.md: FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00)
-TRAFFIC_FROM_PROFILE = {"conv_mfma_f32": 32.3e6, "conv_mfma_f32_split_bf16x3": 32.3e6}
+TRAFFIC_FROM_PROFILE = {"conv_mfma_f32": 28.0e6, "conv_mfma_f32_split_bf16x3": 28.0e6}
 
 
 def run_variant(args, np, torch, ev, wl, variant, frames, dframes, with_dense, with_layers):
