@@ -842,6 +842,29 @@ def test_upsampling_folded_into_conv_weights(seed, h, w, monkeypatch):
     plain.destroy()
 
 
+def test_folded_upsampling_ragged_channels_and_output_node():
+    """Folded up-sampling conv with an input channel count that is not a multiple of the chunk
+    (36: the last chunk is zero-padded in the patch and in the folded weight sets), three blocks
+    of output channels, a bias, and the conv being a network output itself."""
+    _say("folded up-sampling conv, 36 -> 96 channels on 40x56 -> 80x112, network output")
+    b = wl._NetBuilder("fold_ragged", 4, 40, 56, 4242, bias=True)
+    x = b.conv(-1, 36, 3)
+    u = b.simple(wl.OP_UPSAMPLE2X, x)
+    b.conv(u, 96, 5, act=wl.ACT_RELU, out=1)
+    net = b.finish()
+    g = ev.EvConvNet(net)
+    assert [g.kernel_name(i) for i in range(3)] == ["conv_valu_f32", "fused_into_conv_weights", "conv_mfma_f32"]
+    g.destroy()
+    rng = np.random.default_rng(4242)
+    x = rng.standard_normal((4, 40, 56)).astype(np.float32)
+    frames = [x]
+    for t in range(5):
+        m = rng.random((1, 40, 56)) < (0.02 if t != 3 else 0.7)
+        x = (x + rng.standard_normal(x.shape).astype(np.float32) * m).astype(np.float32)
+        frames.append(x)
+    run_stream(net, frames[0], frames[1:], "frame", label="fold-ragged", max_flips=10)
+
+
 # --------------------------------------------------------------------------- recurrent state
 
 def _running_sum_net(c, h, w):
