@@ -827,19 +827,24 @@ def test_upsampling_folded_into_conv_weights(seed, h, w, monkeypatch):
         run_stream(net, frames[0], frames[1:], "frame", tol=2e-2, label=f"fold{seed}", max_flips=10**9, frobenius=True)
         return
     run_stream(net, frames[0], frames[1:], "frame", label=f"fold{seed}", max_flips=40)
-    folded = ev.EvConvNet(net)
+    folded, recomputed = ev.EvConvNet(net), ev.EvConvNet(net)
     monkeypatch.setenv("EVCONV_NO_FOLD", "1")
     plain = ev.EvConvNet(net)
     assert plain.kernel_name(up) == "fused_into_conv_gather"
     conv = [i for i, n in enumerate(net.nodes) if n.op == wl.OP_CONV2D and n.in0 == up][0]
     for t, f in enumerate(frames):
-        for net_ in (folded, plain):
+        for net_ in (folded, plain, recomputed):
             (net_.reset if t == 0 else net_.step_frame)(_dev(f))
+        if t == 0:
+            recomputed.set_mode(ev.MODE_DENSE_RECOMPUTE)
         np.testing.assert_array_equal(folded.state(conv, ev.STATE_OCC_TOUCHED), plain.state(conv, ev.STATE_OCC_TOUCHED))
         za, zb = folded.state(conv, ev.STATE_Z), plain.state(conv, ev.STATE_Z)
         assert np.abs(za - zb).max() <= 2e-5 * np.abs(zb).max(), (t, np.abs(za - zb).max(), np.abs(zb).max())
-    folded.destroy()
-    plain.destroy()
+    # a regular forward pass through the folded kernels, as a reset and as a dense-recompute step: same bits
+    folded.reset(_dev(frames[-1]))
+    np.testing.assert_array_equal(folded.state(conv, ev.STATE_Z), recomputed.state(conv, ev.STATE_Z))
+    for net_ in (folded, plain, recomputed):
+        net_.destroy()
 
 
 def test_folded_upsampling_ragged_channels_and_output_node():
