@@ -8,7 +8,9 @@ fp32 weights (headline) and the bf16-weight variant (reported beside it).
 
 Prints ONE JSON line.  Extra keys: `dense_recompute` (the same frames run as regular forward
 passes through the same kernels), `roofline` (dominant kernel family, timed with HIP events on the
-library's stream inside the timed region), `cpu_baseline` (the CPU oracle on a bounded sample of
+library's stream inside the timed region; `achieved` counts the operator's algorithmic FLOPs, `executed`
+the FLOPs of the taps that were run: the library folds a x2 up-sampling into 4 x 4-tap weights on most
+tiles of the 5 x 5 convs that read one), `cpu_baseline` (the CPU oracle on a bounded sample of
 the same frames), `f32_split_variant`, `bf16_variant`, `hip_graph_replay`, `multi_stream` (16 streams
 in one net), `sparsified_variant`, `recurrent_variant` (a ConvLSTM cell), `layers`.
 
@@ -79,17 +81,32 @@ def run_variant(args, np, torch, ev, wl, variant, frames, dframes, with_dense, w
         st = g.stats(i)
         per_site = 2.0 * nd.k * nd.k * nd.c_in * nd.c_out if nd.op in (wl.OP_CONV2D, wl.OP_LINEAR) else 0.0
         flops = per_site * st.n_touched            # algorithmic: touched output sites of the last step
-        f = fam.setdefault(name, dict(ms=0.0, launches=0, flops=0.0))
+        # Executed: a 5 x 5 conv reading a x2 up-sampling that the library folded into its weights
+        # runs 4 x 4 taps on the output tiles over stored tiles whose sites all lie 2 or more from
+        # the border of the stored tensor (the other tiles run all 25 taps)
+        executed = flops
+        if nd.op == wl.OP_CONV2D and nd.in0 >= 0 and g.kernel_name(nd.in0) == "fused_into_conv_weights":
+            c, h, w = g.shape(i)
+            words = g.state(i, ev.STATE_OCC_TOUCHED).reshape(-(-h // 8), -(-w // 8))
+            inner = lambda t, n_sites: (8 * t >= 2) & (8 * t + 7 <= n_sites - 3)
+            ty, tx = np.indices(words.shape)
+            folded_tiles = inner(ty // 2, h // 2) & inner(tx // 2, w // 2)
+            pop = np.array([bin(int(x)).count("1") for x in words.ravel()]).reshape(words.shape)
+            executed = per_site * (pop[~folded_tiles].sum() + pop[folded_tiles].sum() * 16.0 / 25.0)
+        f = fam.setdefault(name, dict(ms=0.0, launches=0, flops=0.0, executed=0.0))
         f["ms"] += ms
         f["launches"] += n
         f["flops"] += flops * n
+        f["executed"] += executed * n
         layers.append(dict(node=i, kernel=name, ms_avg=ms / max(n, 1), touched=st.n_touched, sites=st.n_sites,
                            active=st.n_active, touched_tiles=st.n_touched_tiles, tiles=st.n_tiles,
                            gflop_alg=flops / 1e9))
     dom = max((k for k in fam if k.startswith("conv")), key=lambda k: fam[k]["ms"])
     bound, peak, unit = PEAKS[dom]
     achieved = fam[dom]["flops"] / (fam[dom]["ms"] * 1e-3) / 1e12 if fam[dom]["ms"] > 0 else 0.0
+    executed = fam[dom]["executed"] / (fam[dom]["ms"] * 1e-3) / 1e12 if fam[dom]["ms"] > 0 else 0.0
     roofline = dict(kernel=dom, bound=bound, achieved=achieved, peak=peak, unit=unit, frac=achieved / peak,
+                    executed=executed, executed_frac=executed / peak,
                     traffic=TRAFFIC_FROM_PROFILE.get(dom), avg_launch_ms=fam[dom]["ms"] / max(fam[dom]["launches"], 1),
                     launches=fam[dom]["launches"], share_of_step=fam[dom]["ms"] / (dt_prof * 1e3),
                     event_pass_ms_per_step=dt_prof / args.steps * 1e3)
