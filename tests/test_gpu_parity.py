@@ -870,6 +870,30 @@ def test_folded_upsampling_ragged_channels_and_output_node():
     run_stream(net, frames[0], frames[1:], "frame", label="fold-ragged", max_flips=10)
 
 
+@pytest.mark.parametrize("h,w,ci,co", [(18, 18, 32, 32), (17, 33, 32, 32), (26, 19, 96, 32), (48, 21, 32, 64)])
+def test_folded_upsampling_smallest_interiors(h, w, ci, co):
+    """Stored tensors that have just one tile away from the border (18 rows: sites 8-15 lie 2 or
+    more from both edges), none (17 rows), or a single row / column of them."""
+    _say(f"folded up-sampling conv, stored tensor {h}x{w}, {ci} -> {co} channels")
+    b = wl._NetBuilder("fold_small", 4, h, w, 7 * h + w, bias=True)
+    x = b.conv(-1, ci, 3)
+    u = b.simple(wl.OP_UPSAMPLE2X, x)
+    d = b.conv(u, co, 5)
+    b.conv(d, 2, 1, 1, 0, wl.ACT_NONE, out=1)
+    net = b.finish()
+    g = ev.EvConvNet(net)
+    assert g.kernel_name(u) == ("fused_into_conv_weights" if min(h, w) >= 18 else "fused_into_conv_gather")
+    g.destroy()
+    rng = np.random.default_rng(h * 100 + w)
+    x = rng.standard_normal((4, h, w)).astype(np.float32)
+    frames = [x]
+    for t in range(4):
+        m = rng.random((1, h, w)) < (0.03 if t != 2 else 0.6)
+        x = (x + rng.standard_normal(x.shape).astype(np.float32) * m).astype(np.float32)
+        frames.append(x)
+    run_stream(net, frames[0], frames[1:], "frame", label=f"fold{h}x{w}", max_flips=10)
+
+
 # --------------------------------------------------------------------------- recurrent state
 
 def _running_sum_net(c, h, w):
