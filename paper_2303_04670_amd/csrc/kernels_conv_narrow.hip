@@ -70,14 +70,13 @@ __global__ __launch_bounds__(128 * NB) void conv_narrow_kernel(ConvParams p) {
     }
     s_koff[k] = off;
   }
-  {
-    const float4* __restrict__ wsrc = (const float4*)((const float*)p.w + blockIdx.y * NC);
-    constexpr int NC4 = NC / 4;
-    for (int e = tid; e < KP * NC4; e += NT) {
-      const int k = e / NC4, n4 = e - k * NC4;
-      *(float4*)&s_w[k * NC + n4 * 4] = wsrc[(size_t)k * (Cout / 4) + n4];
-    }
-  }
+  // The weights are fetched when the first touched tile is met (a workgroup without one leaves
+  // without reading them), all of a thread's share at once and between that tile's z and patch
+  // requests, so that one memory latency covers the three.
+  const float4* __restrict__ wsrc = (const float4*)((const float*)p.w + blockIdx.y * NC);
+  constexpr int NC4 = NC / 4;
+  constexpr int WV = kMaxK * NC4 / NT;  // float4 of weights per thread (8)
+  bool staged = false;
 
   // workgroups walk the tiles with the grid's stride; the weights stay in LDS
   for (int tile = blockIdx.x; tile < p.go.tiles(); tile += gridDim.x) {
@@ -143,6 +142,17 @@ __global__ __launch_bounds__(128 * NB) void conv_narrow_kernel(ConvParams p) {
     }
   }
 
+  float4 wreg[WV];
+  if (!staged) {
+#pragma unroll
+    for (int j = 0; j < WV; ++j) {
+      const int e = tid + j * NT;
+      const int k = e / NC4, n4 = e - k * NC4;
+      wreg[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (e < KP * NC4) wreg[j] = wsrc[(size_t)k * (Cout / 4) + n4];
+    }
+  }
+
   // patch: conditioned fetch, inactive and out-of-image sites become zeros without a memory access
   {
     const __amdgpu_buffer_rsrc_t in_rsrc =
@@ -156,6 +166,15 @@ __global__ __launch_bounds__(128 * NB) void conv_narrow_kernel(ConvParams p) {
       if ((s_rows[py] >> px) & 1u) off = (unsigned)((((iy0 + py) * W + ix0 + px) * Cin + c) * 4);
       s_patch[site * CS + c] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(in_rsrc, off, 0, 0));
     }
+  }
+  if (!staged) {
+#pragma unroll
+    for (int j = 0; j < WV; ++j) {
+      const int e = tid + j * NT;
+      const int k = e / NC4, n4 = e - k * NC4;
+      if (e < KP * NC4) *(float4*)&s_w[k * NC + n4 * 4] = wreg[j];
+    }
+    staged = true;
   }
   __syncthreads();
 
