@@ -356,9 +356,9 @@ def recurrent_leg(args, np, torch, ev, wl, dframes):
     """The same frames through a ConvLSTM cell (64 hidden channels at full resolution, two
     recurrent states as DELAY nodes) with a 1 x 1 head.  A recurrent state moves at every step, so
     everything behind it is dense; reported beside a dense recompute of the same frames."""
-    # (four of the five time bins: 4 + 64 input channels of the gate convs suit the matrix-core kernel)
-    net = wl.net_convlstm(1008, in_c=4, h=256, w=352, hidden=64, out_c=1)
-    dframes = [f[:4].contiguous() for f in dframes[:5 + max(10, args.steps // 4)]]
+    # (the gate convs read 5 + 64 = 69 channels)
+    net = wl.net_convlstm(1008, in_c=5, h=256, w=352, hidden=64, out_c=1)
+    dframes = dframes[:5 + max(10, args.steps // 4)]
     steps = max(10, args.steps // 4)
     res = {}
     for mode, key in ((ev.MODE_INCREMENTAL, "incremental"), (ev.MODE_DENSE_RECOMPUTE, "dense_recompute")):
@@ -377,7 +377,7 @@ def recurrent_leg(args, np, torch, ev, wl, dframes):
         res[key] = dict(value=steps / dt, ms_per_step=dt / steps * 1e3,
                         touched_site_fraction=sum(g.stats(i).n_touched for i in conv) / sum(g.stats(i).n_sites for i in conv))
         g.destroy()
-    return {"net": "ConvLSTM 4->64 hidden, 3x3 gates, 256x352, 1x1 head", "unit": "steps/s", "steps": steps,
+    return {"net": "ConvLSTM 5->64 hidden, 3x3 gates, 256x352, 1x1 head", "unit": "steps/s", "steps": steps,
             "value": res["incremental"]["value"], "ms_per_step": res["incremental"]["ms_per_step"],
             "touched_site_fraction": res["incremental"]["touched_site_fraction"],
             "dense_recompute_ms_per_step": res["dense_recompute"]["ms_per_step"]}

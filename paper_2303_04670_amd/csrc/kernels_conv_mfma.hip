@@ -1,7 +1,7 @@
 // Sparse incremental convolution on the matrix cores.
 //
-// Used where the per-tile channel contraction is a dense GEMM: c_in >= 16 and a multiple of 4
-// (the last channel chunk is zero-padded), c_out % 32 == 0.
+// Used where the per-tile channel contraction is a dense GEMM: c_in >= 16 (any count: the last
+// channel chunk is zero-padded), c_out % 32 == 0.
 // Implicit GEMM per touched output tile (8 x 8 sites): M = 32 * MB sites (MB = 2: the whole
 // tile as two 32-row MFMA blocks, rows 0-3 and 4-7; MB = 1: one workgroup per half tile),
 // N = 32 output channels per workgroup, K = taps x c_in.
@@ -344,8 +344,14 @@ void conv_mfma_kernel(ConvParams p) {
       if ((row >> px) & 1u) g_off[j] = (unsigned)((((gy0 + py) * SW + gx0 + px) * Cin + v * 4) * 4);
     }
   }
-  const __amdgpu_buffer_rsrc_t in_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc((void*)at_stream(p.in, so), 0, SH * SW * Cin * 4, 0x00020000);
+  // c_in need not be a multiple of four: the 16-byte load of a site's last channel group then
+  // runs into the next site (buffer loads of dwords need dword alignment only); the foreign
+  // components are zeroed on the way into LDS.  The range is extended by those 12 bytes so that
+  // the last site's group is not rejected as a whole (every tensor of the workspace is followed
+  // by padding or by another buffer of the workspace).
+  const int tail = Cin & 3;
+  const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)at_stream(p.in, so), 0, SH * SW * Cin * 4 + (tail ? 12 : 0), 0x00020000);
   float4 pre[MAXG];
   // c_in need not be a multiple of the chunk: channel groups beyond c_in read as zeros (their
   // weight rows are zero padding as well)
@@ -378,7 +384,18 @@ void conv_mfma_kernel(ConvParams p) {
       *(float4*)&s_mem[off] = x;
     }
   };
-  auto stash = [&]() {
+  auto stash = [&](int c0) {
+    if (tail) {  // (uniform; nets with c_in % 4 == 0 pay nothing)
+#pragma unroll
+      for (int j = 0; j < MAXG; ++j) {
+        const int left = Cin - (c0 + ((tid + j * NT) % NV) * 4);  // channels of this group inside c_in
+        if (left > 0 && left < 4) {
+          if (left < 2) pre[j].y = 0.0f;
+          if (left < 3) pre[j].z = 0.0f;
+          pre[j].w = 0.0f;
+        }
+      }
+    }
 #pragma unroll
     for (int j = 0; j < MAXG; ++j)
       if (lds_off[j] >= 0) {
@@ -567,7 +584,7 @@ void conv_mfma_kernel(ConvParams p) {
   }
   for (int c0 = 0; conv_on && c0 < Cin; c0 += CHUNK) {
     __syncthreads();  // all waves are done reading the previous chunk
-    stash();
+    stash(c0);
     __syncthreads();
     if (ups) {
       interpolate();
@@ -829,7 +846,7 @@ void launch_any(const ConvParams& p, hipStream_t s) {
 }  // namespace
 
 bool conv_mfma_f32_supported(const ConvParams& p) {
-  return p.gi.c % 4 == 0 && p.gi.c >= 16 && p.go.c % 32 == 0 && p.c_out_pad == p.go.c &&
+  return p.gi.c >= 16 && p.go.c % 32 == 0 && p.c_out_pad == p.go.c &&
          (long long)p.gi.h * p.gi.w * p.gi.c * 4 < (1ll << 31) &&  // byte offsets of the gather fit 31 bits
          (long long)(p.go.h + 8) * p.go.w * p.go.c * 4 < (1ll << 31) &&  // those of the epilogue too
          (long long)p.k * p.k * ((p.gi.c + 127) / 128 * 128) * p.go.c * 8 < (1ll << 31);  // and those of both weight planes

@@ -141,7 +141,8 @@ def test_unet_bf16_matrix_core_variant_reduced():
 
 def test_matrix_core_conv_shapes_bf16():
     _say("bf16 matrix-core conv variants")
-    for k, s, ci, co in [(3, 1, 32, 32), (3, 2, 16, 64), (5, 1, 64, 32), (5, 2, 48, 96), (7, 2, 16, 32), (1, 1, 32, 64), (3, 1, 68, 32), (5, 2, 20, 32)]:
+    for k, s, ci, co in [(3, 1, 32, 32), (3, 2, 16, 64), (5, 1, 64, 32), (5, 2, 48, 96), (7, 2, 16, 32), (1, 1, 32, 64), (3, 1, 68, 32), (5, 2, 20, 32),
+                         (3, 1, 69, 32), (5, 2, 21, 32), (3, 1, 18, 64), (5, 1, 35, 64)]:   # c_in % 4 != 0
         b = wl._NetBuilder(f"conv{k}s{s}", ci, 21, 27, 100 + k * 10 + s, bf16=True, bias=True)
         b.conv(-1, co, k, s, act=wl.ACT_RELU, out=1)
         net = b.finish()
@@ -162,7 +163,8 @@ def test_matrix_core_conv_shapes():
     bias, dense and sparse increments."""
     _say("matrix-core conv variants: k in {1,3,5,7}, stride {1,2}, c_in in {16,32,48,64}")
     for k, s, ci, co in [(3, 1, 32, 32), (3, 2, 16, 64), (5, 1, 64, 32), (5, 2, 48, 96), (7, 2, 16, 32), (1, 1, 32, 64),
-                         (3, 1, 68, 32), (5, 1, 20, 32), (3, 2, 36, 64)]:   # the last three: ragged channel chunks
+                         (3, 1, 68, 32), (5, 1, 20, 32), (3, 2, 36, 64),      # ragged channel chunks
+                         (3, 1, 69, 32), (5, 2, 21, 32), (3, 1, 18, 64), (5, 1, 35, 64), (1, 1, 17, 32)]:  # c_in % 4 != 0
         b = wl._NetBuilder(f"conv{k}s{s}", ci, 21, 27, 100 + k * 10 + s, bias=True)
         b.conv(-1, co, k, s, act=wl.ACT_RELU, out=1)
         net = b.finish()
@@ -582,7 +584,8 @@ def test_split_bf16_conv_shapes_meet_the_fp32_bar():
     _say("split-bf16 matrix-core conv variants at the fp32 tolerance")
     worst = 0.0
     for k, s, ci, co in [(3, 1, 32, 32), (3, 2, 16, 64), (5, 1, 64, 32), (5, 2, 48, 96), (7, 2, 16, 32), (1, 1, 32, 64),
-                         (3, 1, 128, 64), (3, 1, 68, 32), (5, 2, 20, 32)]:
+                         (3, 1, 128, 64), (3, 1, 68, 32), (5, 2, 20, 32),
+                         (3, 1, 69, 32), (5, 2, 21, 32), (3, 1, 18, 64), (5, 1, 35, 64)]:   # c_in % 4 != 0
         b = wl._NetBuilder(f"conv{k}s{s}", ci, 21, 27, 100 + k * 10 + s, bias=True)
         b.conv(-1, co, k, s, act=wl.ACT_RELU, out=1)
         net = wl.with_weight_dtype(b.finish(), wl.WD_F32_SPLIT)
@@ -941,21 +944,22 @@ def test_delay_running_sum_bit_exact_against_fp32_oracle():
     gpu.destroy()
 
 
-@pytest.mark.parametrize("mode", ["f32", "split"])
-def test_convlstm_cell_against_oracle(mode):
+@pytest.mark.parametrize("mode,in_c", [("f32", 4), ("split", 4), ("f32", 5), ("split", 5)])
+def test_convlstm_cell_against_oracle(mode, in_c):
     """A ConvLSTM cell (gates on the matrix cores, products, tanh, two recurrent states) and a
-    1 x 1 head: all nodes at every step."""
-    net = wl.net_convlstm(41, in_c=4, h=24, w=40, hidden=32, out_c=2)
+    1 x 1 head: all nodes at every step.  With 5 input channels the gate convs read 37 channels
+    (not a multiple of four)."""
+    net = wl.net_convlstm(41, in_c=in_c, h=24, w=40, hidden=32, out_c=2)
     if mode == "split":
         net = wl.with_weight_dtype(net, wl.WD_F32_SPLIT)
-    _say(f"ConvLSTM cell, {mode}, 4x24x40, hidden 32")
+    _say(f"ConvLSTM cell, {mode}, {in_c}x24x40, hidden 32")
     g = ev.EvConvNet(net)
     names = [g.kernel_name(i) for i in range(len(net.nodes))]
     g.destroy()
     assert names[0] == names[1] == "delay", names
     assert names.count("conv_mfma_f32" if mode == "f32" else "conv_mfma_f32_split_bf16x3") == 4, names
     rng = np.random.default_rng(12)
-    x = rng.standard_normal((4, 24, 40)).astype(np.float32)
+    x = rng.standard_normal((in_c, 24, 40)).astype(np.float32)
     frames = [x]
     for t in range(8):
         m = rng.random((1, 24, 40)) < 0.05
