@@ -1,7 +1,7 @@
 // Sparse incremental convolution on the matrix cores.
 //
 // Used where the per-tile channel contraction is a dense GEMM: c_in >= 16 (any count: the last
-// channel chunk is zero-padded), c_out % 32 == 0.
+// channel chunk is zero-padded), c_out >= 16 (any count: the last block of 32 is zero-padded).
 // Implicit GEMM per touched output tile (8 x 8 sites): M = 32 * MB sites (MB = 2: the whole
 // tile as two 32-row MFMA blocks, rows 0-3 and 4-7; MB = 1: one workgroup per half tile),
 // N = 32 output channels per workgroup, K = taps x c_in.
@@ -303,7 +303,10 @@ void conv_mfma_kernel(ConvParams p) {
   const int out_bytes = p.go.h * p.go.w * Cout * 4;
   constexpr unsigned kSkipAccess = 0x80000000u;
   constexpr uint64_t kMine = EP_SITES == 8 ? 0x0101010101010101ull : 0x0001000100010001ull;
-  auto mine = [&](uint64_t w) { return (w >> (r0 * 8 + es)) & kMine; };   // bit it * EP_SITES: site `it`
+  // c_out need not be a multiple of 32: the last block's weights are zero-padded and the threads
+  // of the channels that do not exist own no sites (they take no part in the epilogue)
+  const bool co_ok = co0 + co < Cout;
+  auto mine = [&](uint64_t w) { return co_ok ? (w >> (r0 * 8 + es)) & kMine : 0ull; };   // bit it * EP_SITES: site `it`
   auto has = [&](uint64_t sp, int it) { return ((sp >> (it * EP_SITES)) & 1ull) != 0; };
   auto out_rsrc = [&](const void* ptr) {
     return __builtin_amdgcn_make_buffer_rsrc((void*)ptr, 0, out_bytes, 0x00020000);
@@ -672,7 +675,7 @@ void conv_mfma_kernel(ConvParams p) {
   // partial sum of local site ls = it * EP_SITES + es: the part of the LDS offset that depends on
   // the thread (es < 16), the rest is a constant per `it`
   const int off_mine = ((es >> 3) * 4 + (es & 3)) * 64 + ((es >> 2) & 1) * 32 + co;
-  const float bias = (p.dense && p.bias) ? p.bias[co0 + co] : 0.0f;
+  const float bias = (p.dense && p.bias && co_ok) ? p.bias[co0 + co] : 0.0f;
 #pragma unroll
   for (int it = 0; it < EP_ITERS; ++it) {
     if (!has(site_mine, it)) continue;
@@ -773,7 +776,7 @@ int chunk_for(const ConvParams& p) {
   // low-resolution layers (few workgroups, always 8 waves): 128-channel chunks halve the number of
   // gather round trips, which is what these latency-bound launches consist of
   if (p.stride == 1 && p.k <= 3 && p.gi.c % 128 == 0 &&
-      (long long)p.go.tiles() * (p.go.c / 32) * p.st.n * 2 < 512) return 128;
+      (long long)p.go.tiles() * (p.c_out_pad / 32) * p.st.n * 2 < 512) return 128;
   if (p.stride == 1 && p.k <= 3 && p.gi.c % 64 == 0) return 64;
   if (p.stride == 1 && (p.gi.c % 32 == 0 || (p.gi.c % 16 != 0 && p.gi.c > 32))) return 32;  // ragged: fewer, padded chunks
   return 16;
@@ -791,8 +794,8 @@ void launch_variant(const ConvParams& p, hipStream_t s) {
   ConvParams q = p;
   const long long in_sites = p.upsample ? (long long)p.lo_h * p.lo_w : (long long)p.gi.h * p.gi.w;
   q.wg_swap = (long long)p.k * p.k * p.go.c > in_sites && p.go.tiles() * (2 / MB) <= 65535;
-  dim3 grid(p.go.tiles() * (2 / MB), p.go.c / 32, p.st.n);
-  if (q.wg_swap) grid = dim3(p.go.c / 32, p.go.tiles() * (2 / MB), p.st.n);
+  dim3 grid(p.go.tiles() * (2 / MB), p.c_out_pad / 32, p.st.n);
+  if (q.wg_swap) grid = dim3(p.c_out_pad / 32, p.go.tiles() * (2 / MB), p.st.n);
   if (CHUNK == 32 && p.upsample) {
     // the low-resolution source region behind the patch buffer
     lds += (size_t)(PH / 2 + 3) * (PW / 2 + 3) * (CHUNK + 4) * sizeof(float);
@@ -809,7 +812,7 @@ double fill(long long n) { return (double)n / 256.0 / (double)((n + 255) / 256);
 
 template <int CHUNK, int OPM>
 void launch_shape(const ConvParams& p, hipStream_t s) {
-  const long long n2 = (long long)p.go.tiles() * (p.go.c / 32) * p.st.n;  // workgroups with whole tiles
+  const long long n2 = (long long)p.go.tiles() * (p.c_out_pad / 32) * p.st.n;  // workgroups with whole tiles
   // Whole tiles (two accumulators per wave, every weight fragment used twice) pay off only when
   // the launch fills the chip several times over and a workgroup has a long contraction; measured
   // on the layers of the evaluation networks, half tiles win everywhere else (more, shorter
@@ -846,10 +849,10 @@ void launch_any(const ConvParams& p, hipStream_t s) {
 }  // namespace
 
 bool conv_mfma_f32_supported(const ConvParams& p) {
-  return p.gi.c >= 16 && p.go.c % 32 == 0 && p.c_out_pad == p.go.c &&
+  return p.gi.c >= 16 && p.go.c >= 16 && p.c_out_pad == (p.go.c + 31) / 32 * 32 &&
          (long long)p.gi.h * p.gi.w * p.gi.c * 4 < (1ll << 31) &&  // byte offsets of the gather fit 31 bits
          (long long)(p.go.h + 8) * p.go.w * p.go.c * 4 < (1ll << 31) &&  // those of the epilogue too
-         (long long)p.k * p.k * ((p.gi.c + 127) / 128 * 128) * p.go.c * 8 < (1ll << 31);  // and those of both weight planes
+         (long long)p.k * p.k * ((p.gi.c + 127) / 128 * 128) * p.c_out_pad * 8 < (1ll << 31);  // and those of both weight planes
 }
 // a bilinear x2 up-sampling in front of this conv can be folded into its gather
 bool conv_mfma_upsample_supported(const ConvParams& p) {

@@ -142,7 +142,8 @@ def test_unet_bf16_matrix_core_variant_reduced():
 def test_matrix_core_conv_shapes_bf16():
     _say("bf16 matrix-core conv variants")
     for k, s, ci, co in [(3, 1, 32, 32), (3, 2, 16, 64), (5, 1, 64, 32), (5, 2, 48, 96), (7, 2, 16, 32), (1, 1, 32, 64), (3, 1, 68, 32), (5, 2, 20, 32),
-                         (3, 1, 69, 32), (5, 2, 21, 32), (3, 1, 18, 64), (5, 1, 35, 64)]:   # c_in % 4 != 0
+                         (3, 1, 69, 32), (5, 2, 21, 32), (3, 1, 18, 64), (5, 1, 35, 64),   # c_in % 4 != 0
+                         (3, 1, 32, 16), (3, 1, 37, 28)]:                                   # c_out % 32 != 0
         b = wl._NetBuilder(f"conv{k}s{s}", ci, 21, 27, 100 + k * 10 + s, bf16=True, bias=True)
         b.conv(-1, co, k, s, act=wl.ACT_RELU, out=1)
         net = b.finish()
@@ -164,7 +165,8 @@ def test_matrix_core_conv_shapes():
     _say("matrix-core conv variants: k in {1,3,5,7}, stride {1,2}, c_in in {16,32,48,64}")
     for k, s, ci, co in [(3, 1, 32, 32), (3, 2, 16, 64), (5, 1, 64, 32), (5, 2, 48, 96), (7, 2, 16, 32), (1, 1, 32, 64),
                          (3, 1, 68, 32), (5, 1, 20, 32), (3, 2, 36, 64),      # ragged channel chunks
-                         (3, 1, 69, 32), (5, 2, 21, 32), (3, 1, 18, 64), (5, 1, 35, 64), (1, 1, 17, 32)]:  # c_in % 4 != 0
+                         (3, 1, 69, 32), (5, 2, 21, 32), (3, 1, 18, 64), (5, 1, 35, 64), (1, 1, 17, 32),  # c_in % 4 != 0
+                         (3, 1, 32, 16), (5, 2, 16, 48), (3, 1, 37, 28), (3, 2, 64, 100)]:   # c_out % 32 != 0
         b = wl._NetBuilder(f"conv{k}s{s}", ci, 21, 27, 100 + k * 10 + s, bias=True)
         b.conv(-1, co, k, s, act=wl.ACT_RELU, out=1)
         net = b.finish()
@@ -585,7 +587,8 @@ def test_split_bf16_conv_shapes_meet_the_fp32_bar():
     worst = 0.0
     for k, s, ci, co in [(3, 1, 32, 32), (3, 2, 16, 64), (5, 1, 64, 32), (5, 2, 48, 96), (7, 2, 16, 32), (1, 1, 32, 64),
                          (3, 1, 128, 64), (3, 1, 68, 32), (5, 2, 20, 32),
-                         (3, 1, 69, 32), (5, 2, 21, 32), (3, 1, 18, 64), (5, 1, 35, 64)]:   # c_in % 4 != 0
+                         (3, 1, 69, 32), (5, 2, 21, 32), (3, 1, 18, 64), (5, 1, 35, 64),   # c_in % 4 != 0
+                         (3, 1, 32, 16), (3, 1, 37, 28)]:                                   # c_out % 32 != 0
         b = wl._NetBuilder(f"conv{k}s{s}", ci, 21, 27, 100 + k * 10 + s, bias=True)
         b.conv(-1, co, k, s, act=wl.ACT_RELU, out=1)
         net = wl.with_weight_dtype(b.finish(), wl.WD_F32_SPLIT)
