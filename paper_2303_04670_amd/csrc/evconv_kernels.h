@@ -107,7 +107,7 @@ struct ConvParams {
   float* y; float* dy; int int_mode;
 };
 void launch_conv_valu(const ConvParams& p, hipStream_t s);
-// fp32 MFMA variant; requires c_in >= 16 and c_out >= 16 (c_out_pad = c_out rounded up to 32).  The re-laid weights
+// fp32 MFMA variant; requires c_in >= 9 and c_out >= 16 (c_out_pad = c_out rounded up to 32).  The re-laid weights
 // of all matrix-core variants carry conv_mfma_padded_cin input channels (zero rows beyond c_in).
 bool conv_mfma_f32_supported(const ConvParams& p);
 int conv_mfma_padded_cin(const ConvParams& p);

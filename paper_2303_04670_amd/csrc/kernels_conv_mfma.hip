@@ -1,6 +1,6 @@
 // Sparse incremental convolution on the matrix cores.
 //
-// Used where the per-tile channel contraction is a dense GEMM: c_in >= 16 (any count: the last
+// Used where the per-tile channel contraction is a dense GEMM: c_in >= 9 (any count: the last
 // channel chunk is zero-padded), c_out >= 16 (any count: the last block of 32 is zero-padded).
 // Implicit GEMM per touched output tile (8 x 8 sites): M = 32 * MB sites (MB = 2: the whole
 // tile as two 32-row MFMA blocks, rows 0-3 and 4-7; MB = 1: one workgroup per half tile),
@@ -849,7 +849,7 @@ void launch_any(const ConvParams& p, hipStream_t s) {
 }  // namespace
 
 bool conv_mfma_f32_supported(const ConvParams& p) {
-  return p.gi.c >= 16 && p.go.c >= 16 && p.c_out_pad == (p.go.c + 31) / 32 * 32 &&
+  return p.gi.c >= 9 && p.go.c >= 16 && p.c_out_pad == (p.go.c + 31) / 32 * 32 &&  // (fewer input channels: the narrow-input kernel)
          (long long)p.gi.h * p.gi.w * p.gi.c * 4 < (1ll << 31) &&  // byte offsets of the gather fit 31 bits
          (long long)(p.go.h + 8) * p.go.w * p.go.c * 4 < (1ll << 31) &&  // those of the epilogue too
          (long long)p.k * p.k * ((p.gi.c + 127) / 128 * 128) * p.c_out_pad * 8 < (1ll << 31);  // and those of both weight planes

@@ -166,7 +166,8 @@ def test_matrix_core_conv_shapes():
     for k, s, ci, co in [(3, 1, 32, 32), (3, 2, 16, 64), (5, 1, 64, 32), (5, 2, 48, 96), (7, 2, 16, 32), (1, 1, 32, 64),
                          (3, 1, 68, 32), (5, 1, 20, 32), (3, 2, 36, 64),      # ragged channel chunks
                          (3, 1, 69, 32), (5, 2, 21, 32), (3, 1, 18, 64), (5, 1, 35, 64), (1, 1, 17, 32),  # c_in % 4 != 0
-                         (3, 1, 32, 16), (5, 2, 16, 48), (3, 1, 37, 28), (3, 2, 64, 100)]:   # c_out % 32 != 0
+                         (3, 1, 32, 16), (5, 2, 16, 48), (3, 1, 37, 28), (3, 2, 64, 100),    # c_out % 32 != 0
+                         (3, 1, 12, 32), (5, 1, 9, 64), (3, 2, 10, 20)]:                      # fewer than 16 input channels
         b = wl._NetBuilder(f"conv{k}s{s}", ci, 21, 27, 100 + k * 10 + s, bias=True)
         b.conv(-1, co, k, s, act=wl.ACT_RELU, out=1)
         net = b.finish()
