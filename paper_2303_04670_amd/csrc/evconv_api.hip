@@ -704,7 +704,7 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
         // flattened contraction [KP][c_out], k = tap * c_in + ci, zero rows beyond taps * c_in;
         // bf16-declared weights are rounded to bf16 and widened again
         const int kp = conv_narrow_padded_k(k * k * ci_n);
-        staging.resize((size_t)kp * co_n);
+        staging.assign((size_t)kp * cop, 0.0f);  // [kp][c_out rounded up to 32]: zero columns beyond c_out
         for (int co = 0; co < co_n; ++co)
           for (int ci = 0; ci < ci_n; ++ci)
             for (int t = 0; t < k * k; ++t) {
@@ -713,7 +713,7 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
                 const uint32_t u = (uint32_t)to_bf16(w) << 16;
                 memcpy(&w, &u, 4);
               }
-              staging[((size_t)t * ci_n + ci) * co_n + co] = w;
+              staging[((size_t)t * ci_n + ci) * cop + co] = w;
             }
       } else if (n.kernel == kKernConvMfmaSplit) {
         // two bf16 planes [tap][c_in/8][c_out][8]: hi = bf16(w), then lo = bf16(w - hi)

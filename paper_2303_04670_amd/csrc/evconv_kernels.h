@@ -125,7 +125,7 @@ bool conv_pointwise_supported(const ConvParams& p);
 // public tensors (ConvParams::y, dy)
 bool conv_pointwise_integrates(const ConvParams& p);
 void launch_conv_pointwise(const ConvParams& p, hipStream_t s);
-// narrow-input variant: taps * c_in <= 128, c_out % 32 == 0; weights [padded k][c_out] fp32
+// narrow-input variant: taps * c_in <= 128, c_out >= 16; weights [padded k][c_out_pad] fp32
 bool conv_narrow_supported(const ConvParams& p);
 int conv_narrow_padded_k(int k_tot);
 void launch_conv_narrow(const ConvParams& p, hipStream_t s);

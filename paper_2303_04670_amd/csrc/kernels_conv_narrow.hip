@@ -1,7 +1,7 @@
 // Sparse incremental convolution for narrow inputs, on the matrix cores.
 //
-// For layers whose whole contraction K = taps x c_in is at most 128 and whose c_out is a multiple
-// of 32: the first convolution on the event tensor (c_in = 2..5 channels).  With so few input
+// For layers whose whole contraction K = taps x c_in is at most 128 and whose c_out is at least 16
+// (the last block of 32 output channels is zero-padded): the first convolution on the event tensor (c_in = 2..5 channels).  With so few input
 // channels a per-tap channel contraction is too thin for an MFMA, so the contraction runs over
 // the flattened index k = tap * c_in + ci (im2col by addressing, nothing is materialised):
 //   A[m][k] = patch[site(m) + tap offset(k)][ci(k)]   one ds_read_b32 through a k -> LDS-offset table
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(128 * NB) void conv_narrow_kernel(ConvParams p) {
   for (int i = 0; i < 16; ++i) {
     const int ls = 8 * (i >> 2) + hi4 + (i & 3);
     z_old[i] = 0.0f;
-    if (!p.dense && ((my_touched >> ls) & 1u)) {
+    if (!p.dense && co < Cout && ((my_touched >> ls) & 1u)) {
       const int site = half * 32 + ls;
       const int oy = tile_y * 8 + (site >> 3), ox = tile_x * 8 + (site & 7);
       z_old[i] = at_stream(p.z, so)[((size_t)oy * p.go.w + ox) * Cout + co];
@@ -149,7 +149,7 @@ __global__ __launch_bounds__(128 * NB) void conv_narrow_kernel(ConvParams p) {
       const int e = tid + j * NT;
       const int k = e / NC4, n4 = e - k * NC4;
       wreg[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (e < KP * NC4) wreg[j] = wsrc[(size_t)k * (Cout / 4) + n4];
+      if (e < KP * NC4) wreg[j] = wsrc[(size_t)k * (p.c_out_pad / 4) + n4];
     }
   }
 
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(128 * NB) void conv_narrow_kernel(ConvParams p) {
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
     const int ls = 8 * (i >> 2) + hi4 + (i & 3);
-    const bool on = (my_touched >> ls) & 1u;
+    const bool on = ((my_touched >> ls) & 1u) && co < Cout;  // (c_out rounded up to 32: surplus lanes own nothing)
     float o = 0.0f;
     if (on) {
       const int site = half * 32 + ls;
@@ -246,7 +246,7 @@ __global__ __launch_bounds__(128 * NB) void conv_narrow_kernel(ConvParams p) {
 
 bool conv_narrow_supported(const ConvParams& p) {
   const int k_tot = p.k * p.k * p.gi.c;
-  return k_tot <= kMaxK && p.gi.c <= 8 && p.go.c % 32 == 0 && p.c_out_pad == p.go.c && p.n_fused == 0 &&
+  return k_tot <= kMaxK && p.gi.c <= 8 && p.go.c >= 16 && p.c_out_pad == (p.go.c + 31) / 32 * 32 && p.n_fused == 0 &&
          (long long)p.gi.h * p.gi.w * p.gi.c * 4 < (1ll << 31);  // byte offsets of the gather fit 31 bits
 }
 
@@ -255,11 +255,11 @@ int conv_narrow_padded_k(int k_tot) { return (k_tot + 15) & ~15; }
 void launch_conv_narrow(const ConvParams& p, hipStream_t s) {
   const int P = 7 * p.stride + p.k;
   const int KP = conv_narrow_padded_k(p.k * p.k * p.gi.c);
-  const int nb = (p.go.c % 64 == 0) ? 2 : 1;
+  const int nb = (p.c_out_pad % 64 == 0) ? 2 : 1;
   const size_t lds = ((size_t)KP * 32 * nb + (size_t)P * P * (p.gi.c | 1)) * sizeof(float);
   // workgroups walk the tiles with the grid's stride; enough of them to fill the chip's resident
   // slots (a tile is one chain of dependent memory round trips, so few long walks are slow)
-  dim3 grid(std::min(p.go.tiles(), std::max(4096 / p.st.n, 256)), p.go.c / (32 * nb), p.st.n);
+  dim3 grid(std::min(p.go.tiles(), std::max(4096 / p.st.n, 256)), p.c_out_pad / (32 * nb), p.st.n);
   if (nb == 2) hipLaunchKernelGGL(conv_narrow_kernel<2>, grid, dim3(256), lds, s, p);
   else hipLaunchKernelGGL(conv_narrow_kernel<1>, grid, dim3(128), lds, s, p);
 }

@@ -159,6 +159,27 @@ def test_matrix_core_conv_shapes_bf16():
         run_stream(net, x0, incs, "increment", label=f"bf16 k{k}s{s}", tol=2e-2, frobenius=True, max_flips=20)
 
 
+def test_narrow_input_conv_shapes():
+    """First-layer kernel (2-8 input channels, taps x channels <= 128): strides, tap counts, one or
+    two blocks of output channels, output channel counts that are not multiples of 32."""
+    _say("narrow-input conv variants")
+    for k, s, ci, co in [(5, 1, 5, 32), (3, 2, 4, 64), (7, 2, 2, 64), (3, 1, 8, 96), (1, 1, 3, 32),
+                         (5, 1, 5, 16), (3, 1, 4, 48), (3, 2, 6, 100), (5, 2, 3, 24)]:
+        b = wl._NetBuilder(f"narrow{k}s{s}", ci, 21, 27, 200 + k * 10 + s, bias=True)
+        b.conv(-1, co, k, s, act=wl.ACT_RELU, out=1)
+        net = b.finish()
+        rng = np.random.default_rng(k + s + ci)
+        x0 = rng.standard_normal((ci, 21, 27)).astype(np.float32)
+        incs = []
+        for t in range(4):
+            m = rng.random((21, 27)) < (0.03 if t < 3 else 1.0)
+            incs.append(rng.standard_normal(x0.shape).astype(np.float32) * m[None])
+        g = ev.EvConvNet(net)
+        assert g.kernel_name(0) == "conv_narrow_mfma_f32", (k, s, ci, co, g.kernel_name(0))
+        g.destroy()
+        run_stream(net, x0, incs, "increment", label=f"narrow k{k}s{s} {ci}->{co}", max_flips=2)
+
+
 def test_matrix_core_conv_shapes():
     """Every (kernel, stride, channel-chunk) variant of the matrix-core conv on ragged sizes, with
     bias, dense and sparse increments."""
@@ -865,7 +886,7 @@ def test_folded_upsampling_ragged_channels_and_output_node():
     b.conv(u, 96, 5, act=wl.ACT_RELU, out=1)
     net = b.finish()
     g = ev.EvConvNet(net)
-    assert [g.kernel_name(i) for i in range(3)] == ["conv_valu_f32", "fused_into_conv_weights", "conv_mfma_f32"]
+    assert [g.kernel_name(i) for i in range(3)] == ["conv_narrow_mfma_f32", "fused_into_conv_weights", "conv_mfma_f32"]
     g.destroy()
     rng = np.random.default_rng(4242)
     x = rng.standard_normal((4, 40, 56)).astype(np.float32)
