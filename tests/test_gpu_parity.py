@@ -309,10 +309,14 @@ def test_reset_equals_stepped_state_and_dense_recompute_mode():
     np.testing.assert_array_equal(yb, yc)
 
 
-def test_run_to_run_bit_reproducible():
-    _say("determinism: the same stream twice gives identical bits")
-    net = wl.net_unet_depth(31, h=40, w=56, width=8)
-    frames = list(wl.stream_voxel(31, 40, 56, 10, 0.03, n_prim=4))
+@pytest.mark.parametrize("width,h,w", [(8, 40, 56), (32, 64, 96)])
+def test_run_to_run_bit_reproducible(width, h, w):
+    """width 8: the vector-ALU kernels; width 32: the matrix-core kernels (partial sums of up to
+    eight waves, fused epilogue adds, folded up-sampling, occupancy words OR-ed by several
+    workgroups)."""
+    _say(f"determinism: the same stream twice gives identical bits (width {width})")
+    net = wl.net_unet_depth(31, h=h, w=w, width=width)
+    frames = list(wl.stream_voxel(31, h, w, 10, 0.03, n_prim=4))
     res = []
     for _ in range(2):
         g = ev.EvConvNet(net)
