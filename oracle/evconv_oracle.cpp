@@ -112,7 +112,15 @@ struct NodeState {
   float k = 0.f;                 // sparsification layer: rounding step (z holds the residual delta)
   float k_fixed = -1.f;          // >= 0: step given by the description instead of t_p * RMS
   bool keeps_z = false, structural = false;
-  double macs_site = 0, macs_dense = 0;
+  // multiply-accumulate counters of a conv / linear node (the paper's "MFLOPs" columns, Tables I-III,
+  // under an explicit counting rule; one MAC = one weight times one input element):
+  //   macs_site          executed by the last step when only nonzero work is done: over the touched
+  //                      outputs, the (tap, output) pairs whose input site is inside the image and
+  //                      active, times c_in * c_out
+  //   macs_dense         a regular forward pass: the pairs whose input site is inside the image
+  //                      (zero padding costs nothing), times c_in * c_out
+  //   macs_dense_nominal outputs * k * k * c_in * c_out (padding counted: the usual quoted figure)
+  double macs_site = 0, macs_dense = 0, macs_dense_nominal = 0;
 };
 
 template <class T>
@@ -236,8 +244,18 @@ struct Net {
                 w_taps[i][((size_t(ky) * nd.k + kx) * nd.c_in + ci) * nd.c_out + co] =
                     T(weights[nd.w_off + ((size_t(co) * nd.c_in + ci) * nd.k + ky) * nd.k + kx]);
       }
-      if (nd.op == OP_CONV || nd.op == OP_LINEAR)
-        s.macs_dense = double(o.sites()) * nd.k * nd.k * nd.c_in * nd.c_out;  // upper bound (no border cut)
+      if (nd.op == OP_CONV || nd.op == OP_LINEAR) {
+        s.macs_dense_nominal = double(o.sites()) * nd.k * nd.k * nd.c_in * nd.c_out;
+        double pairs = 0;
+        for (int oy = 0; oy < o.h; ++oy)
+          for (int ox = 0; ox < o.w; ++ox)
+            for (int ky = 0; ky < nd.k; ++ky)
+              for (int kx = 0; kx < nd.k; ++kx) {
+                const int iy = oy * nd.stride - nd.pad + ky, ix = ox * nd.stride - nd.pad + kx;
+                if (iy >= 0 && iy < a.h && ix >= 0 && ix < a.w) pairs += 1;
+              }
+        s.macs_dense = pairs * nd.c_in * nd.c_out;
+      }
     }
     for (int i = 0; i < n_nodes; ++i)
       if (nodes[i].op == OP_DELAY) {
@@ -813,11 +831,30 @@ float evo_get_step(void* h, int node) {
   Handle* p = (Handle*)h;
   return p->fp32 ? p->f.st[node].k : p->d.st[node].k;
 }
-// executed multiply-accumulates of the last step at site granularity, and of a dense pass
-void evo_get_macs(void* h, int node, double* site, double* dense) {
+// Multiply-accumulate counts of a conv / linear node (zeros for other nodes), out[4]:
+//   [0] executed by the last step at site granularity (macs_site)
+//   [1] executed by the last step when whole mask tiles of th x tw outputs are computed: the
+//       number of tiles holding at least one touched output * th * tw * k * k * c_in * c_out
+//       ("Convolution on Sparse Inputs": filter applications are skipped per all-zero section)
+//   [2] a regular forward pass, padding taps not counted (macs_dense)
+//   [3] a regular forward pass, outputs * k * k * c_in * c_out (macs_dense_nominal)
+void evo_get_macs(void* h, int node, int th, int tw, double* out) {
   Handle* p = (Handle*)h;
-  if (p->fp32) { *site = p->f.st[node].macs_site; *dense = p->f.st[node].macs_dense; }
-  else { *site = p->d.st[node].macs_site; *dense = p->d.st[node].macs_dense; }
+  auto fill = [&](auto& net) {
+    auto& s = net.st[node];
+    const NodeDesc& nd = net.nodes[node];
+    out[0] = s.macs_site; out[2] = s.macs_dense; out[3] = s.macs_dense_nominal; out[1] = 0;
+    if (nd.op != OP_CONV && nd.op != OP_LINEAR) return;
+    const int ty = (s.shp.h + th - 1) / th, tx = (s.shp.w + tw - 1) / tw;
+    std::vector<uint8_t> hit(size_t(ty) * tx, 0);
+    for (int y = 0; y < s.shp.h; ++y)
+      for (int x = 0; x < s.shp.w; ++x)
+        if (s.touched[size_t(y) * s.shp.w + x]) hit[size_t(y / th) * tx + x / tw] = 1;
+    double tiles = 0;
+    for (uint8_t v : hit) tiles += v;
+    out[1] = tiles * th * tw * nd.k * nd.k * nd.c_in * nd.c_out;
+  };
+  if (p->fp32) fill(p->f); else fill(p->d);
 }
 
 }  // extern "C"

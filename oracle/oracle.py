@@ -56,7 +56,7 @@ def _load():
         L.evo_get_set.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
         L.evo_get_shape.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
         L.evo_get_x_prev.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
-        L.evo_get_macs.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+        L.evo_get_macs.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -163,10 +163,13 @@ class Oracle:
         """Rounding step k of a sparsification node after the last refresh."""
         return float(_load().evo_get_step(self._h, node))
 
-    def macs(self, node):
-        a, b = ctypes.c_double(), ctypes.c_double()
-        _load().evo_get_macs(self._h, node, ctypes.byref(a), ctypes.byref(b))
-        return a.value, b.value
+    def macs(self, node, tile=(8, 8)) -> dict:
+        """Multiply-accumulate counts of a conv / linear node: `site` and `tile` = executed by the
+        last step at site and at mask-tile granularity, `dense` = a regular forward pass without
+        the padding taps, `dense_nominal` = outputs * k * k * c_in * c_out."""
+        out = np.zeros(4, np.float64)
+        _load().evo_get_macs(self._h, node, int(tile[0]), int(tile[1]), out.ctypes.data_as(ctypes.c_void_p))
+        return dict(site=float(out[0]), tile=float(out[1]), dense=float(out[2]), dense_nominal=float(out[3]))
 
 
 def tile_words(mask: np.ndarray, th: int = 8, tw: int = 8):

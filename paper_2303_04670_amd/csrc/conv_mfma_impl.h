@@ -51,6 +51,9 @@
 // wave of the SIMD takes time from the MFMAs.  Hence the addressing style throughout: per-lane
 // parts of an address are computed once and kept, per-unit / per-row parts live in scalar
 // registers (buffer instructions with a scalar offset), masks are tested where their bits sit.
+// (This header holds the kernel template and its launchers; one translation unit per operand
+// mode instantiates it, so that the three modes compile in parallel.)
+#pragma once
 #include <cstdlib>
 
 #include "evconv_kernels.h"
@@ -772,7 +775,7 @@ void conv_mfma_kernel(ConvParams p) {
   }
 }
 
-int chunk_for(const ConvParams& p) {
+inline int chunk_for(const ConvParams& p) {
   // low-resolution layers (few workgroups, always 8 waves): 128-channel chunks halve the number of
   // gather round trips, which is what these latency-bound launches consist of
   if (p.stride == 1 && p.k <= 3 && p.gi.c % 128 == 0 &&
@@ -808,7 +811,7 @@ void launch_variant(const ConvParams& p, hipStream_t s) {
 }
 
 // share of the chip's 256 CUs kept busy when n equally long workgroups run at once
-double fill(long long n) { return (double)n / 256.0 / (double)((n + 255) / 256); }
+inline double fill(long long n) { return (double)n / 256.0 / (double)((n + 255) / 256); }
 
 template <int CHUNK, int OPM>
 void launch_shape(const ConvParams& p, hipStream_t s) {
@@ -820,10 +823,6 @@ void launch_shape(const ConvParams& p, hipStream_t s) {
   bool halves = !(n2 >= 512 && p.k * p.k * p.gi.c >= 1600) || fill(2 * n2) > fill(n2) + 0.1;
   const long long n = halves ? 2 * n2 : n2;
   bool eight = n < 512;  // few workgroups: 8 waves each split K further
-#ifdef EVK_TUNE  // timing sweeps of the launch shape from a stand-alone harness
-  if (const char* e = getenv("EVK_MB")) halves = atoi(e) == 1;
-  if (const char* e = getenv("EVK_NW")) eight = atoi(e) == 8;
-#endif
   if (CHUNK == 128) {  // chosen only for few workgroups: the 4-wave variants are not built
     if (halves) launch_variant<CHUNK, 8, OPM, 1>(p, s); else launch_variant<CHUNK, 8, OPM, 2>(p, s);
     return;
@@ -847,31 +846,5 @@ void launch_any(const ConvParams& p, hipStream_t s) {
 }
 
 }  // namespace
-
-bool conv_mfma_f32_supported(const ConvParams& p) {
-  return p.gi.c >= 9 && p.go.c >= 16 && p.c_out_pad == (p.go.c + 31) / 32 * 32 &&  // (fewer input channels: the narrow-input kernel)
-         (long long)p.gi.h * p.gi.w * p.gi.c * 4 < (1ll << 31) &&  // byte offsets of the gather fit 31 bits
-         (long long)(p.go.h + 8) * p.go.w * p.go.c * 4 < (1ll << 31) &&  // those of the epilogue too
-         (long long)p.k * p.k * ((p.gi.c + 127) / 128 * 128) * p.c_out_pad * 8 < (1ll << 31);  // and those of both weight planes
-}
-// a bilinear x2 up-sampling in front of this conv can be folded into its gather
-bool conv_mfma_upsample_supported(const ConvParams& p) {
-  return conv_mfma_f32_supported(p) && chunk_for(p) == 32 && p.stride == 1 && p.k <= 7;
-}
-// input channels of the re-laid weights: c_in rounded up to whole chunks of the variant that runs
-int conv_mfma_padded_cin(const ConvParams& p) {
-  const int chunk = chunk_for(p);
-  return (p.gi.c + chunk - 1) / chunk * chunk;
-}
-void launch_conv_mfma_f32(const ConvParams& p, hipStream_t s) { launch_any<kOpF32>(p, s); }
-
-// bf16 operands, fp32 accumulation; weights are [tap][c_in/8][c_out][8] bf16
-bool conv_mfma_bf16_supported(const ConvParams& p) { return conv_mfma_f32_supported(p); }
-void launch_conv_mfma_bf16(const ConvParams& p, hipStream_t s) { launch_any<kOpBf16>(p, s); }
-
-// fp32 weights and increments, each split into bf16 high + low parts: three bf16 MFMAs per
-// product with fp32 accumulation; weights are [2 planes][tap][c_in/8][c_out][8] bf16
-bool conv_mfma_split_supported(const ConvParams& p) { return conv_mfma_f32_supported(p); }
-void launch_conv_mfma_split(const ConvParams& p, hipStream_t s) { launch_any<kOpSplit>(p, s); }
 
 }  // namespace evk
