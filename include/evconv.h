@@ -9,6 +9,13 @@
  * Plain C: no C++ types, no exceptions cross this boundary.  Pointers are marked HOST or
  * DEVICE.  One handle must be used from one host thread at a time.
  *
+ * Mask tile: the paper's mask marks h x w sections of a tensor that are entirely zero
+ * ("Implementation of Increment Layers"; 6 x 6 in "Comparison to prior works") and a mask may only
+ * skip zeros, so no value depends on the section size.  This library fixes it at 8 x 8 sites over
+ * all channels: 64 sites are one gfx950 wavefront, so one ballot instruction yields a tile's 64-bit
+ * occupancy word, and every kernel's mask arithmetic is written on such words.  The section size is
+ * therefore not a parameter of the description.
+ *
  * Data layout: public tensors are C x H x W fp32 (row-major, W fastest).  Site index means
  * y*W + x.  Inside the workspace activations are H x W x C ("channels last", the notation of
  * "Implementation of Increment Layers"); evconv_get_state returns that internal layout.
@@ -64,7 +71,7 @@
 extern "C" {
 #endif
 
-#define EVCONV_ABI_VERSION 1
+#define EVCONV_ABI_VERSION 2
 
 typedef struct evconv_net evconv_net; /* opaque, library-owned; freed by evconv_destroy */
 
@@ -112,10 +119,17 @@ typedef enum {
 typedef enum { EVCONV_F32 = 0, EVCONV_BF16 = 1, EVCONV_F32_SPLIT = 2 } evconv_dtype;
 
 typedef enum {
-  EVCONV_MODE_INCREMENTAL = 0,    /* the paper's method */
-  EVCONV_MODE_DENSE_RECOMPUTE = 1 /* regular forward pass of x(n) with the same kernels (the
-                                     refresh of "Drift Errors", used as the dense comparator) */
+  EVCONV_MODE_INCREMENTAL = 0,     /* the paper's method */
+  EVCONV_MODE_DENSE_RECOMPUTE = 1, /* regular forward pass of x(n) with the same kernels (the
+                                      refresh of "Drift Errors", used as the dense comparator) */
+  EVCONV_MODE_AUTO = 2             /* whichever of the two is faster on the current stream; see
+                                      evconv_set_mode */
 } evconv_mode;
+
+/* evconv_net_desc.flags: planner switches for tests and comparisons (0 = everything on). */
+#define EVCONV_FLAG_NO_FUSION 1u  /* no node is computed by another node's kernel */
+#define EVCONV_FLAG_NO_FOLD 2u    /* an up-sampling is never folded into the consuming conv's weights */
+#define EVCONV_FLAG_FORCE_VALU 4u /* no matrix-core kernels */
 
 /* One node.  Inputs are earlier node ids; -1 is the network input; in1 is ignored by one-input
  * ops.  The activation is fused after the op. */
@@ -138,7 +152,7 @@ typedef struct {
   int32_t n_nodes;
   const evconv_node_desc* nodes; /* HOST, n_nodes entries, topological order */
   int32_t in_c, in_h, in_w;
-  int32_t tile_h, tile_w; /* mask tile; 0 = default 8 x 8 (the only size this build accepts) */
+  uint32_t flags;         /* EVCONV_FLAG_* */
   float sparsify_tp;      /* threshold parameter t_p of the SPARSIFY nodes (>= 0; 0 = lossless) */
   int32_t n_streams;      /* independent event streams (cameras) stepped together and sharing the
                            * weights, 1..256 (0 = 1).  Every stream owns a copy of the whole state;
@@ -161,8 +175,8 @@ typedef struct {
   int32_t n_sites, n_tiles;      /* of the node's output grid */
   int32_t n_touched, n_active;   /* sites in T and in S_out after the last step */
   int32_t n_touched_tiles;       /* tiles with at least one touched site */
-  double flops_executed;         /* 2 * MACs issued by the last step at tile granularity */
-  double flops_dense;            /* 2 * MACs of a regular forward pass of this node */
+  double flops_executed;         /* 2 * k*k*c_in*c_out * 64 * n_touched_tiles */
+  double flops_dense;            /* 2 * k*k*c_in*c_out * n_sites */
 } evconv_layer_stats;
 
 typedef enum {
@@ -178,10 +192,17 @@ typedef enum {
   EVCONV_STATE_Z2 = 9           /* MUL nodes: fp32 H x W x C accumulated second factor (Z: the first) */
 } evconv_state_kind;
 
-/* Bytes of device workspace a net of this description needs.  No GPU work. */
+/* Bytes of device workspace a net of this description needs.  No GPU work.  The workspace holds
+ * the state that "Implementation of Increment Layers" asks an increment layer to keep between
+ * inferences - the accumulated input x_acc of every nonlinear operator (Eq.12-14; both factors
+ * for a product, Eq.15-17; the residual delta of a sparsification layer, Eq.4-8), the previous
+ * input x(n-1) of Eq.1, the output sum of Eq.2 - plus, per node, the increment tensor, its masks
+ * (per-tile occupancy words of the active and of the touched set), the ascending site list and
+ * the re-laid weights. */
 evconv_status evconv_query_workspace(const evconv_net_desc* desc, size_t* bytes);
 
-/* Builds a net.  `weights` is HOST memory (copied and re-laid out; the caller may free it on
+/* Builds a net: one increment layer beside every forward layer of the description ("Increment
+ * tensors and increment layers").  `weights` is HOST memory (copied and re-laid out; the caller may free it on
  * return).  `workspace` is DEVICE memory, 256-byte aligned, at least the queried size, owned by
  * the caller and used exclusively by this net until evconv_destroy.  `hip_stream` is a
  * hipStream_t (NULL = the default stream); all later work of this net is enqueued on it.
@@ -204,8 +225,15 @@ int32_t evconv_num_outputs(const evconv_net* net);
  * evconv_set_refresh_period, which keeps the state. */
 evconv_status evconv_reset(evconv_net* net, const float* x0, evconv_out* out);
 
-/* One incremental step on a caller-supplied increment tensor (DEVICE, dense C x H x W fp32,
- * zeros where nothing changed).  Asynchronous.  EVCONV_ERR_STATE before the first reset.
+/* One inference step with increment layers ("Increment tensors and increment layers") on a
+ * caller-supplied increment tensor x_inc(n) (DEVICE, dense C x H x W fp32, zeros where nothing
+ * changed): the mask of the input is formed, then every
+ * node runs its increment operator in topological order - linear operators on the increment alone
+ * at the touched sites (Eq.9-10, "Convolution on Sparse Inputs"), additions with OR-ed masks
+ * (Eq.11), activations through their accumulated input (Eq.12-14), products (Eq.15-17),
+ * sparsification layers (Eq.3-8) - and the outputs are summed, y(n) = y(n-1) + y_inc(n) (Eq.2).
+ * `out` as in evconv_reset, with dy / dy_idx / dy_count describing y_inc(n).
+ * Asynchronous.  EVCONV_ERR_STATE before the first reset.
  *
  * A step only enqueues kernels (no allocation, no synchronisation, no memset), so the caller may
  * capture it into a HIP graph and replay that.  What a replay cannot see is host-side state:
@@ -222,22 +250,43 @@ evconv_status evconv_step_frame(evconv_net* net, const float* x_t, evconv_out* o
 /* NULL is accepted.  Never frees the workspace.  Synchronises the net's stream first. */
 evconv_status evconv_destroy(evconv_net* net);
 
+/* INCREMENTAL (default): every step is the paper's incremental inference.  DENSE_RECOMPUTE: every
+ * step is a regular forward pass of x(n) through the same kernels (all sites, accumulated tensors
+ * overwritten); y is the forward pass value, dy = y(n) - y(n-1) at every site.  Both leave the
+ * same state up to fp32 rounding (Eq.2), so the mode may be changed between any two steps.
+ * AUTO: the library times a few consecutive steps in each of the two modes with HIP events on the
+ * net's stream (without synchronising: the result is picked up by a later call, once the events
+ * have completed), runs the faster one for the next 256 steps, then measures again.  Incremental
+ * inference only pays while the increments stay sparse through the layers ("Mitigating Reduced
+ * Sparsity on Upsampling"; a recurrent state densifies everything behind it), and where that
+ * ends depends on the stream, not on the description.  The choice depends on measured time, so
+ * AUTO is not run-to-run bit-reproducible (results agree within fp32 rounding).  A net with
+ * active SPARSIFY nodes (sparsify_tp > 0 or a fixed step) stays incremental in AUTO mode, because
+ * a regular pass does not sparsify; so does a step that is being captured into a HIP graph.
+ * EVCONV_ERR_INVALID_ARG for another value. */
 evconv_status evconv_set_mode(evconv_net* net, int32_t mode /* evconv_mode */);
+
+/* The mode the next step would run in (AUTO resolves to INCREMENTAL or DENSE_RECOMPUTE). */
+int32_t evconv_current_mode(const evconv_net* net);
 
 /* Refresh policy of "Drift Errors": with period N > 0 every N-th call of evconv_step /
  * evconv_step_frame after a reset runs as a regular forward pass of x(n) that re-initialises
  * every accumulated tensor (for a supplied increment, x(n) = cached frame + increment), which
  * removes the rounding drift of the fp32 running sums (and the sparsification residuals).  The
- * increments and lists of such a step are empty; y and dy are the forward pass values.  0 (the
- * default) never refreshes; the count restarts at every reset and at every call of this
+ * internal increments and lists of such a step are empty; y is the forward pass value and
+ * dy = y(n) - y(n-1) at every site, listed in dy_idx, so that Eq.2 also holds across a refresh for
+ * a consumer that sums the returned increments.  0 (the default) never refreshes; the count restarts at every reset and at every call of this
  * function.  EVCONV_ERR_INVALID_ARG for a negative period. */
 evconv_status evconv_set_refresh_period(evconv_net* net, int32_t period);
 
 /* Shape (c, h, w) of a node's output; node -1 is the network input. */
 evconv_status evconv_node_shape(const evconv_net* net, int32_t node, int32_t* chw /* HOST[3] */);
 
-/* Synchronous copy of internal state to HOST memory (parity checks, checkpoints).  `bytes`
- * must be the exact size; node -1 addresses the input increment stage. */
+/* Synchronous copy of internal state to HOST memory (parity checks, checkpoints): the tensors
+ * an increment layer is defined by in "Implementation of Increment Layers" - its increment, its
+ * mask (as occupancy words, list, count, tile bitmap) and its accumulated input x_acc (Eq.14;
+ * Eq.17 for a product; the residual of Eq.8 for a sparsification layer).  `bytes` must be the
+ * exact size; node -1 addresses the input increment stage (Eq.1). */
 evconv_status evconv_get_state(evconv_net* net, int32_t node, int32_t kind, void* dst, size_t bytes);
 
 /* The same for stream `stream` of a net created with n_streams > 1 (evconv_get_state reads
@@ -249,7 +298,12 @@ evconv_status evconv_get_state_stream(evconv_net* net, int32_t stream, int32_t n
  * of streams (n_streams may be NULL).  The workspace holds n_streams such copies back to back. */
 evconv_status evconv_stream_stride(const evconv_net* net, size_t* bytes /* HOST */, int32_t* n_streams /* HOST */);
 
-/* Synchronous; counts come from the occupancy words of the last step (stream 0). */
+/* Sparsity and work of a node in the last step (stream 0): sizes of its touched and active sets
+ * (the per-layer sparsity of the "Sparsification layer" section's figure) and, for CONV2D / LINEAR,
+ * the floating-point operations of the step against those of a regular forward pass - the
+ * "MFLOPs" columns of the paper's result tables under this counting rule: 2 * k * k * c_in * c_out
+ * per output site, a mask tile with at least one touched site counted in full (64 sites), padding
+ * taps included on both sides.  Synchronous. */
 evconv_status evconv_get_stats(evconv_net* net, int32_t node, evconv_layer_stats* out);
 
 /* Per-node kernel timing with HIP events recorded on the net's stream around each node's
@@ -266,10 +320,8 @@ evconv_status evconv_get_node_time(const evconv_net* net, int32_t node, double* 
  * that another node's kernel computes reports where it went: "fused_into_conv_epilogue" (an ADD
  * applied by the producing convolution; its buffers are still written), "fused_into_conv_gather",
  * "fused_into_conv_weights", "fused_into_concat_gather" (an up-sampling that exists only inside
- * its consumer: such a node keeps no state and evconv_get_state fails for it).  The environment
- * variables EVCONV_NO_FUSION (no node is computed by another node's kernel), EVCONV_NO_FOLD (an
- * up-sampling is never folded into the consuming convolution's weights) and EVCONV_FORCE_VALU
- * (no matrix-core kernels), read by evconv_create, exist for tests and comparisons. */
+ * its consumer: such a node keeps no state and evconv_get_state fails for it).  The planner
+ * switches EVCONV_FLAG_* of the description turn these off for tests and comparisons. */
 const char* evconv_node_kernel(const evconv_net* net, int32_t node);
 
 /* Text of the last error on this net (or of the last failed create when net is NULL). */

@@ -102,8 +102,8 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
   if (desc->abi_version != EVCONV_ABI_VERSION) return fail(err, EVCONV_ERR_BAD_DESC, "abi_version mismatch");
   if (desc->n_nodes <= 0) return fail(err, EVCONV_ERR_BAD_DESC, "n_nodes must be positive");
   if (desc->in_c <= 0 || desc->in_h <= 0 || desc->in_w <= 0) return fail(err, EVCONV_ERR_SHAPE, "bad input shape");
-  if ((desc->tile_h != 0 && desc->tile_h != kTile) || (desc->tile_w != 0 && desc->tile_w != kTile))
-    return fail(err, EVCONV_ERR_UNSUPPORTED, "only 8 x 8 mask tiles are built");
+  if (desc->flags & ~(EVCONV_FLAG_NO_FUSION | EVCONV_FLAG_NO_FOLD | EVCONV_FLAG_FORCE_VALU))
+    return fail(err, EVCONV_ERR_INVALID_ARG, "unknown bits in flags");
   if (!(desc->sparsify_tp >= 0.0f)) return fail(err, EVCONV_ERR_INVALID_ARG, "sparsify_tp must be >= 0");
   if (desc->n_streams < 0 || desc->n_streams > 256) return fail(err, EVCONV_ERR_INVALID_ARG, "n_streams must be in [0, 256]");
   if ((long long)desc->in_h * desc->in_w > (1ll << 30)) return fail(err, EVCONV_ERR_SHAPE, "input too large");
@@ -290,6 +290,15 @@ struct evconv_net {
   char* ws = nullptr;
   hipStream_t stream = nullptr;
   int mode = EVCONV_MODE_INCREMENTAL;
+  uint32_t flags = 0;
+  bool has_sparsify = false;  // some SPARSIFY node has a nonzero rounding step
+  // AUTO mode: windows of kAutoProbe steps are timed in each mode with an event pair; the faster
+  // mode then runs for kAutoHold steps
+  int auto_choice = EVCONV_MODE_INCREMENTAL;
+  int auto_phase = 0;         // 0: timing incremental, 1: timing dense recompute, 2: holding auto_choice
+  int auto_count = 0;         // steps done in the current phase
+  bool auto_pending = false;  // both windows are recorded, their events may not have completed yet
+  hipEvent_t auto_ev[4] = {nullptr, nullptr, nullptr, nullptr};
   int refresh_period = 0, since_refresh = 0;
   bool has_state = false;
   bool last_dense = true;   // the previous pass was a regular forward pass (DELAY nodes)
@@ -317,12 +326,17 @@ evconv_status hip_fail(evconv_net* net, hipError_t e, const char* what) {
   return EVCONV_ERR_HIP;
 }
 
-enum PassKind { kPassStep = 0, kPassReset = 1, kPassRecompute = 2 };
+// kPassRefresh: the refresh step of "Drift Errors" in mid-stream: a reset that keeps the recurrent
+// state and returns dy = y(n) - y(n-1), so that Eq.2 holds across it
+enum PassKind { kPassStep = 0, kPassReset = 1, kPassRecompute = 2, kPassRefresh = 3 };
+constexpr int kAutoProbe = 4, kAutoHold = 256;
 
 // Enqueues one pass of the whole network.
 evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, PassKind pass) {
   hipStream_t s = net->stream;
   const int dense = pass != kPassStep;
+  const bool reinit = pass == kPassReset || pass == kPassRefresh;  // sparsification residuals and steps restart
+  const int int_mode = pass == kPassStep ? kIntStep : pass == kPassReset ? kIntReset : kIntRecompute;
   BuilderParams bp;
   bp.in = input; bp.x_prev = net->x_prev; bp.dx = net->dx; bp.occ = net->occ_in;
   bp.clear = net->occ_nodes; bp.n_clear = (int)net->L.n_occ_words;
@@ -350,7 +364,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
       if (d.is_output) {
         IntegrateParams ip;
         ip.delta = n.out; ip.occ = n.occ; ip.y = n.y; ip.dy = n.dy; ip.g = n.go;
-        ip.mode = pass == kPassStep ? kIntStep : pass == kPassReset ? kIntReset : kIntRecompute;
+        ip.mode = int_mode;
         ip.st = net->st;
         launch_integrate(ip, s);
       }
@@ -360,7 +374,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
       if (d.is_output) {
         IntegrateParams ip;
         ip.delta = n.out; ip.occ = n.occ; ip.y = n.y; ip.dy = n.dy; ip.g = n.go;
-        ip.mode = pass == kPassStep ? kIntStep : pass == kPassReset ? kIntReset : kIntRecompute;
+        ip.mode = int_mode;
         ip.st = net->st;
         launch_integrate(ip, s);
       }
@@ -408,7 +422,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
         }
         if (n.kernel == kKernConvPointwise && d.is_output && conv_pointwise_integrates(p)) {
           p.y = n.y; p.dy = n.dy;
-          p.int_mode = pass == kPassStep ? kIntStep : pass == kPassReset ? kIntReset : kIntRecompute;
+          p.int_mode = int_mode;
           integrated = true;
         }
         if (n.kernel == kKernConvMfmaF32) launch_conv_mfma_f32(p, s);
@@ -425,7 +439,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
                d.op == EVCONV_OP_UPSAMPLE_BILINEAR2X ? kEwUp2x : d.op == EVCONV_OP_SPARSIFY ? kEwSparsify : kEwAct;
         p.step = n.step;
         p.st = net->st;
-        if (d.op == EVCONV_OP_SPARSIFY && pass == kPassReset && n.step_fixed < 0.0f)
+        if (d.op == EVCONV_OP_SPARSIFY && reinit && n.step_fixed < 0.0f)
           // refresh: k = t_p * RMS of the layer input, which the producer has just written in full
           launch_rms_step(a, (size_t)n.ga.c * n.ga.sites(), net->sparsify_tp, net->rms_partial, n.step, net->st, s);
         p.act = d.act; p.dense = dense; p.keeps_z = n.keeps_z; p.structural = n.structural;
@@ -473,7 +487,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
     if (d.is_output && !integrated) {
       IntegrateParams ip;
       ip.delta = n.out; ip.occ = n.occ; ip.y = n.y; ip.dy = n.dy; ip.g = n.go;
-      ip.mode = pass == kPassStep ? kIntStep : pass == kPassReset ? kIntReset : kIntRecompute;
+      ip.mode = int_mode;
       ip.st = net->st;
       launch_integrate(ip, s);
     }
@@ -486,6 +500,18 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
   }
   net->last_dense = dense != 0;
   if (pass == kPassReset) launch_fill_u64(net->occ_nodes, net->L.n_occ_words, 0, net->st, s);
+  if (pass == kPassRefresh) {
+    // the nodes' buffers hold values, not increments: every set is emptied, except the active sets of
+    // the output nodes, whose dy = y(n) - y(n-1) is a genuine increment at every site
+    size_t from = 0;
+    for (size_t i = 0; i <= net->L.nodes.size(); ++i) {
+      const bool last = i == net->L.nodes.size();
+      if (!last && !net->L.nodes[i].d.is_output) continue;
+      const size_t to = last ? net->L.n_occ_words : (size_t)(net->L.nodes[i].occ - net->occ_nodes);
+      if (to > from) launch_fill_u64(net->occ_nodes + from, to - from, 0, net->st, s);
+      if (!last) from = to + (size_t)net->L.nodes[i].go.tiles();  // skip the S words, clear the T words behind them
+    }
+  }
   launch_build_lists(net->sets_dev, (int)net->L.nodes.size() + 1, net->L.max_ty, net->st, s);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(net, e, "kernel launch");
@@ -636,11 +662,15 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
   net->sets_dev = (SetDesc*)(ws + L.off_sets);
   net->rms_partial = (float*)(ws + L.off_rms);
   net->sparsify_tp = desc->sparsify_tp;
+  net->flags = desc->flags;
   net->st = Streams{L.stride, L.n_streams};
   net->in_stride = (size_t)L.gin.c * L.gin.sites() * sizeof(float);
 
+  // (the uploads below are blocking copies that are not ordered with a non-blocking caller stream:
+  // the clearing has to be complete before the first of them)
   hipError_t e = hipMemsetAsync(ws, 0, L.total, net->stream);
-  if (e != hipSuccess) { g_create_error = std::string("hipMemsetAsync: ") + hipGetErrorString(e); delete net; return EVCONV_ERR_HIP; }
+  if (e == hipSuccess) e = hipStreamSynchronize(net->stream);
+  if (e != hipSuccess) { g_create_error = std::string("clearing the workspace: ") + hipGetErrorString(e); delete net; return EVCONV_ERR_HIP; }
 
   std::vector<SetDesc> sets(L.nodes.size() + 1);
   sets[0] = SetDesc{net->occ_in, net->idx_in, net->count_in, net->bitmap_in, L.gin.h, L.gin.w, L.gin.tx, L.gin.ty};
@@ -652,9 +682,11 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
     n.z = (n.keeps_z || n.d.op == EVCONV_OP_MAXPOOL) ? (float*)(ws + n.off_z) : nullptr;
     if (n.d.op == EVCONV_OP_SPARSIFY) {
       n.step = (float*)(ws + n.off_step);
+      if (n.d.weight_off < 0 && desc->sparsify_tp > 0.0f) net->has_sparsify = true;
       if (n.d.weight_off >= 0) {
         memcpy(&n.step_fixed, (const char*)weights + n.d.weight_off, 4);
         if (!(n.step_fixed >= 0.0f)) { g_create_error = "negative sparsification step"; delete net; return EVCONV_ERR_BAD_DESC; }
+        if (n.step_fixed > 0.0f) net->has_sparsify = true;
         for (int sidx = 0; sidx < L.n_streams && e == hipSuccess; ++sidx)
           e = hipMemcpy((char*)n.step + (size_t)sidx * L.stride, &n.step_fixed, 4, hipMemcpyHostToDevice);
         if (e != hipSuccess) { g_create_error = std::string("upload: ") + hipGetErrorString(e); delete net; return EVCONV_ERR_HIP; }
@@ -680,7 +712,7 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
       ConvParams probe;
       probe.gi = n.ga; probe.go = n.go; probe.k = k; probe.stride = n.d.stride; probe.c_out_pad = cop;
       probe.n_fused = 0; probe.pad = n.d.pad; probe.st = Streams{L.stride, L.n_streams};
-      const bool force_valu = getenv("EVCONV_FORCE_VALU") != nullptr;
+      const bool force_valu = (net->flags & EVCONV_FLAG_FORCE_VALU) != 0;
       if (!force_valu && n.d.wdtype == EVCONV_F32 && conv_mfma_f32_supported(probe)) n.kernel = kKernConvMfmaF32;
       if (!force_valu && n.d.wdtype == EVCONV_BF16 && conv_mfma_bf16_supported(probe)) n.kernel = kKernConvMfmaBf16;
       if (!force_valu && n.d.wdtype == EVCONV_F32_SPLIT && conv_mfma_split_supported(probe)) n.kernel = kKernConvMfmaSplit;
@@ -769,7 +801,8 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
   if (net->outputs.empty()) { g_create_error = "no output node"; delete net; return EVCONV_ERR_BAD_DESC; }
   // Fold ADD nodes into the epilogue of the matrix-core conv that produces their later input
   // (residual add + activation, skip adds).  Every buffer of the ADD node is still written.
-  if (!getenv("EVCONV_NO_FUSION")) {
+  const bool fuse = !(net->flags & EVCONV_FLAG_NO_FUSION);
+  if (fuse) {
     for (size_t i = 0; i < L.nodes.size(); ++i) {
       NodePlan& a_node = L.nodes[i];
       if (a_node.d.op != EVCONV_OP_ADD) continue;
@@ -783,13 +816,20 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
           c_node.n_fused >= kMaxFusedAdds) continue;
       if (host != later && c_node.fused_nodes[c_node.n_fused - 1] != later) continue;  // chain must be contiguous
       if (other >= host) continue;  // the other input must exist before the conv runs
+      // A DELAY node between the conv and the ADD that delays this ADD reads the ADD's buffers as
+      // the previous step left them; computed in the conv's epilogue they would already hold
+      // this step's values.
+      bool delayed_between = false;
+      for (size_t dn = (size_t)host + 1; dn < i; ++dn)
+        if (L.nodes[dn].d.op == EVCONV_OP_DELAY && L.nodes[dn].d.in0 == (int)i) delayed_between = true;
+      if (delayed_between) continue;
       c_node.fused_nodes[c_node.n_fused++] = (int)i;
       a_node.fused_into = host;
     }
   }
   // Fold a bilinear x2 up-sampling into the gather of the matrix-core conv that is its only
   // consumer: the up-sampled tensor is then never written (its node keeps no state).
-  if (!getenv("EVCONV_NO_FUSION")) {
+  if (fuse) {
     std::vector<int> n_consumers(L.nodes.size(), 0);
     for (size_t i = 0; i < L.nodes.size(); ++i) {
       const evconv_node_desc& d = L.nodes[i].d;
@@ -814,7 +854,7 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
       c_node.upsampled_from = u_node.d.in0;
       // away from the image border the up-sampling goes into the weights instead (fp32 products only:
       // bf16-declared weights would be rounded a second time)
-      if (c_node.off_fold_list && c_node.kernel != kKernConvMfmaBf16 && !getenv("EVCONV_NO_FOLD")) {
+      if (c_node.off_fold_list && c_node.kernel != kKernConvMfmaBf16 && !(net->flags & EVCONV_FLAG_NO_FOLD)) {
         const Geo& lo = u_node.d.in0 < 0 ? L.gin : L.nodes[u_node.d.in0].go;
         e = prepare_fold(net, c_node, weights, lo);
         if (e != hipSuccess) { g_create_error = std::string("folded weights upload: ") + hipGetErrorString(e); delete net; return EVCONV_ERR_HIP; }
@@ -857,12 +897,45 @@ static evconv_status step_common(evconv_net* net, const float* in, int builder_m
   if (!net->has_state) { net->err = "step before reset"; return EVCONV_ERR_STATE; }
   evconv_status st;
   const bool refresh = net->refresh_period > 0 && net->since_refresh + 1 >= net->refresh_period;
+  int mode = net->mode;
+  hipEvent_t ev_after = nullptr;
+  if (mode == EVCONV_MODE_AUTO) {
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    (void)hipStreamIsCapturing(net->stream, &cap);
+    if (net->has_sparsify || cap != hipStreamCaptureStatusNone || refresh) {
+      mode = net->has_sparsify ? EVCONV_MODE_INCREMENTAL : net->auto_choice;
+      if (refresh && net->auto_phase < 2) net->auto_count = 0;  // a window holding a refresh is timed again
+    } else {
+      if (net->auto_pending && hipEventQuery(net->auto_ev[3]) == hipSuccess) {
+        float t_inc = 0.f, t_dense = 0.f;
+        if (hipEventElapsedTime(&t_inc, net->auto_ev[0], net->auto_ev[1]) == hipSuccess &&
+            hipEventElapsedTime(&t_dense, net->auto_ev[2], net->auto_ev[3]) == hipSuccess)
+          net->auto_choice = t_dense < t_inc ? EVCONV_MODE_DENSE_RECOMPUTE : EVCONV_MODE_INCREMENTAL;
+        net->auto_pending = false;
+      }
+      (void)hipGetLastError();  // (hipErrorNotReady of the query is not an error of this net)
+      if (net->auto_phase == 2 && net->auto_count >= kAutoHold && !net->auto_pending) {
+        net->auto_phase = 0;
+        net->auto_count = 0;
+      }
+      mode = net->auto_phase == 0 ? EVCONV_MODE_INCREMENTAL : net->auto_phase == 1 ? EVCONV_MODE_DENSE_RECOMPUTE : net->auto_choice;
+      if (net->auto_phase < 2) {
+        if (net->auto_count == 0) (void)hipEventRecord(net->auto_ev[2 * net->auto_phase], net->stream);
+        if (net->auto_count == kAutoProbe - 1) ev_after = net->auto_ev[2 * net->auto_phase + 1];
+      }
+      if (++net->auto_count >= kAutoProbe && net->auto_phase < 2) {
+        if (net->auto_phase == 1) net->auto_pending = true;
+        ++net->auto_phase;
+        net->auto_count = 0;
+      }
+    }
+  }
   if (refresh) {
     // "Drift Errors": every N-th step is a regular forward pass of x(n) that re-initialises every
     // accumulated tensor (and the sparsification residuals and step sizes)
-    st = run_pass(net, in, builder_mode == kBuildFrame ? kBuildReset : kBuildIncrementDense, kPassReset);
+    st = run_pass(net, in, builder_mode == kBuildFrame ? kBuildReset : kBuildIncrementDense, kPassRefresh);
     net->since_refresh = 0;
-  } else if (net->mode == EVCONV_MODE_DENSE_RECOMPUTE) {
+  } else if (mode == EVCONV_MODE_DENSE_RECOMPUTE) {
     // regular forward pass of x(n): the builder first folds the input into x_prev (and, for a
     // supplied increment, adds it), then the dense pass reads the updated frame
     st = run_pass(net, in, builder_mode == kBuildFrame ? kBuildReset : kBuildIncrementDense, kPassRecompute);
@@ -870,6 +943,7 @@ static evconv_status step_common(evconv_net* net, const float* in, int builder_m
     st = run_pass(net, in, builder_mode, kPassStep);
     ++net->since_refresh;
   }
+  if (ev_after) (void)hipEventRecord(ev_after, net->stream);
   if (st != EVCONV_OK) return st;
   fill_outputs(net, out);
   return EVCONV_OK;
@@ -887,18 +961,38 @@ evconv_status evconv_destroy(evconv_net* net) {
   if (!net) return EVCONV_OK;
   (void)hipStreamSynchronize(net->stream);
   for (hipEvent_t e : net->prof_ev) (void)hipEventDestroy(e);
+  for (hipEvent_t e : net->auto_ev)
+    if (e) (void)hipEventDestroy(e);
   delete net;
   return EVCONV_OK;
 }
 
 evconv_status evconv_set_mode(evconv_net* net, int32_t mode) {
   if (!net) return EVCONV_ERR_INVALID_ARG;
-  if (mode != EVCONV_MODE_INCREMENTAL && mode != EVCONV_MODE_DENSE_RECOMPUTE) {
+  if (mode != EVCONV_MODE_INCREMENTAL && mode != EVCONV_MODE_DENSE_RECOMPUTE && mode != EVCONV_MODE_AUTO) {
     net->err = "bad mode";
     return EVCONV_ERR_INVALID_ARG;
   }
+  if (mode == EVCONV_MODE_AUTO) {
+    for (hipEvent_t& e : net->auto_ev)
+      if (!e) {
+        hipError_t err = hipEventCreate(&e);
+        if (err != hipSuccess) return hip_fail(net, err, "hipEventCreate");
+      }
+    net->auto_phase = 0;
+    net->auto_count = 0;
+    net->auto_pending = false;
+    net->auto_choice = EVCONV_MODE_INCREMENTAL;
+  }
   net->mode = mode;
   return EVCONV_OK;
+}
+
+int32_t evconv_current_mode(const evconv_net* net) {
+  if (!net) return -1;
+  if (net->mode != EVCONV_MODE_AUTO) return net->mode;
+  if (net->has_sparsify) return EVCONV_MODE_INCREMENTAL;
+  return net->auto_phase == 0 ? EVCONV_MODE_INCREMENTAL : net->auto_phase == 1 ? EVCONV_MODE_DENSE_RECOMPUTE : net->auto_choice;
 }
 
 evconv_status evconv_set_refresh_period(evconv_net* net, int32_t period) {

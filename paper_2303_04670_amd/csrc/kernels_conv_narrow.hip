@@ -189,13 +189,16 @@ __global__ __launch_bounds__(128 * NB) void conv_narrow_kernel(ConvParams p) {
     // blocks of 8 MFMA steps: the table look-ups, then the operand reads, then the MFMAs, so that
     // the LDS latencies of a block overlap instead of forming one chain per step
     for (int k0 = kh; k0 < KP; k0 += 16) {
+      const bool full = k0 - kh + 16 <= k_tot;  // (uniform) every k of this block is a real one
       int ko[8];
       float a[8], b[8];
 #pragma unroll
       for (int j = 0; j < 8; ++j) ko[j] = s_koff[k0 + 2 * j];
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        a[j] = ap[ko[j]];
+        // (beyond taps x c_in the operand is an explicit zero, not a patch element times a zero
+        // weight: the element may be infinite or NaN)
+        a[j] = (full || k0 + 2 * j < k_tot) ? ap[ko[j]] : 0.0f;
         b[j] = bp[(k0 + 2 * j) * NC];
       }
 #pragma unroll

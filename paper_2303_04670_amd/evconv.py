@@ -15,12 +15,13 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libevconv.so")
 
-ABI_VERSION = 1
+ABI_VERSION = 2
 OK = 0
 STATUS_NAMES = ["OK", "ERR_INVALID_ARG", "ERR_BAD_DESC", "ERR_SHAPE", "ERR_STATE", "ERR_WORKSPACE",
                 "ERR_HIP", "ERR_UNSUPPORTED"]
 (ERR_INVALID_ARG, ERR_BAD_DESC, ERR_SHAPE, ERR_STATE, ERR_WORKSPACE, ERR_HIP, ERR_UNSUPPORTED) = range(1, 8)
-MODE_INCREMENTAL, MODE_DENSE_RECOMPUTE = 0, 1
+MODE_INCREMENTAL, MODE_DENSE_RECOMPUTE, MODE_AUTO = 0, 1, 2
+FLAG_NO_FUSION, FLAG_NO_FOLD, FLAG_FORCE_VALU = 1, 2, 4
 (STATE_Z, STATE_DY, STATE_IDX, STATE_COUNT, STATE_BITMAP, STATE_OCC, STATE_OCC_TOUCHED,
  STATE_X_PREV, STATE_STEP, STATE_Z2) = range(10)
 
@@ -28,7 +29,7 @@ EXPORTS = ["evconv_query_workspace", "evconv_create", "evconv_num_outputs", "evc
            "evconv_step_frame", "evconv_destroy", "evconv_set_mode", "evconv_node_shape", "evconv_get_state",
            "evconv_get_stats", "evconv_node_kernel", "evconv_last_error", "evconv_profile_begin",
            "evconv_profile_end", "evconv_get_node_time", "evconv_set_refresh_period", "evconv_get_state_stream",
-           "evconv_stream_stride"]
+           "evconv_stream_stride", "evconv_current_mode"]
 
 
 class NodeDesc(ctypes.Structure):
@@ -41,7 +42,7 @@ class NetDesc(ctypes.Structure):
     _fields_ = [("abi_version", ctypes.c_int32), ("n_nodes", ctypes.c_int32),
                 ("nodes", ctypes.POINTER(NodeDesc)),
                 ("in_c", ctypes.c_int32), ("in_h", ctypes.c_int32), ("in_w", ctypes.c_int32),
-                ("tile_h", ctypes.c_int32), ("tile_w", ctypes.c_int32),
+                ("flags", ctypes.c_uint32),
                 ("sparsify_tp", ctypes.c_float), ("n_streams", ctypes.c_int32)]
 
 
@@ -77,6 +78,7 @@ def lib() -> ctypes.CDLL:
         L.evconv_step_frame.argtypes = [vp, vp, ctypes.POINTER(Out)]
         L.evconv_destroy.argtypes = [vp]
         L.evconv_set_mode.argtypes = [vp, i32]
+        L.evconv_current_mode.argtypes = [vp]
         L.evconv_set_refresh_period.argtypes = [vp, i32]
         L.evconv_node_shape.argtypes = [vp, i32, ctypes.POINTER(i32)]
         L.evconv_get_state.argtypes = [vp, i32, i32, vp, ctypes.c_size_t]
@@ -101,7 +103,7 @@ class EvConvError(RuntimeError):
         self.status = status
 
 
-def marshal_desc(net, tile=(0, 0), sparsify_tp=None, n_streams=1):
+def marshal_desc(net, flags=0, sparsify_tp=None, n_streams=1):
     """workloads.Net -> (NetDesc, keep-alive node array).  Element offsets become byte offsets."""
     nodes = (NodeDesc * len(net.nodes))()
     for i, nd in enumerate(net.nodes):
@@ -113,7 +115,7 @@ def marshal_desc(net, tile=(0, 0), sparsify_tp=None, n_streams=1):
         n.bias_off = nd.b_off * 4 if nd.b_off >= 0 else -1
     if sparsify_tp is None:
         sparsify_tp = float(getattr(net, "sparsify_tp", 0.0))
-    d = NetDesc(ABI_VERSION, len(net.nodes), nodes, net.in_c, net.in_h, net.in_w, tile[0], tile[1],
+    d = NetDesc(ABI_VERSION, len(net.nodes), nodes, net.in_c, net.in_h, net.in_w, flags,
                 sparsify_tp, n_streams)
     return d, nodes
 
@@ -191,6 +193,9 @@ class EvConvNet:
 
     def set_mode(self, mode):
         self._check(lib().evconv_set_mode(self._h, mode))
+
+    def current_mode(self) -> int:
+        return lib().evconv_current_mode(self._h)
 
     def set_refresh_period(self, period):
         self._check(lib().evconv_set_refresh_period(self._h, int(period)))

@@ -30,6 +30,7 @@ class Report:
     flips: int = 0
     max_rel_z: float = 0.0
     max_rel_y: float = 0.0
+    max_rel_inc: float = 0.0   # frobenius mode: largest ||increment error|| / ||increment|| on the common support
     nodes_checked: int = 0
     flips_by_node: dict = dataclasses.field(default_factory=dict)
 
@@ -115,6 +116,8 @@ def compare_node(gpu, ora: Oracle, i: int, rep: Report, tol=1e-4, act_scale=None
             ref_scale = max(_accumulated_scale(ora, i), np.abs(dy_ref).max(), 1e-30)
             err = np.abs(dy_gpu[both] - dy_ref[both]).max()
             assert err <= tol * ref_scale, f"node {i}: increment error {err:g} > {tol:g} * {ref_scale:g}"
+            rel = np.linalg.norm(dy_gpu[both] - dy_ref[both]) / max(np.linalg.norm(dy_ref[both]), 1e-30)
+            rep.max_rel_inc = max(rep.max_rel_inc, rel)
         else:
             err = np.abs(dy_gpu[both] - dy_ref[both]).max()
             assert err <= tol_abs, f"node {i}: increment error {err:g} > {tol_abs:g}"
@@ -132,6 +135,19 @@ def compare_node(gpu, ora: Oracle, i: int, rep: Report, tol=1e-4, act_scale=None
         rep.max_rel_z = max(rep.max_rel_z, err / zs)
         assert err <= tol * zs, f"node {i} (op {nd.op}): accumulated tensor error {err:g} > {tol:g} * {zs:g}"
     rep.nodes_checked += 1
+
+
+def compare_outputs_value_only(gpu, ora: Oracle, rep: Report, tol=1e-4):
+    """Only y(n): for steps run as regular forward passes, whose dy is y(n) - y(n-1) at every
+    site instead of the oracle's sparse increment."""
+    gpu.torch.cuda.synchronize()
+    for o in gpu.outputs():
+        y_ref = np.transpose(ora.y(o["node"]), (2, 0, 1))
+        y = o["y"].cpu().numpy().astype(np.float64)
+        scale = max(np.abs(y_ref).max(), 1e-30)
+        err = np.abs(y - y_ref).max()
+        rep.max_rel_y = max(rep.max_rel_y, err / scale)
+        assert err <= tol * scale, f"output node {o['node']}: y error {err:g} > {tol:g} * {scale:g}"
 
 
 def compare_outputs(gpu, ora: Oracle, rep: Report, tol=1e-4):

@@ -69,10 +69,13 @@ def test_bad_descriptions_are_rejected():
     desc.sparsify_tp = -0.1
     assert _status(desc) == ev.ERR_INVALID_ARG
     desc.sparsify_tp = 0.0
-    desc.tile_h, desc.tile_w = 6, 6
-    assert _status(desc) == ev.ERR_UNSUPPORTED
-    desc.tile_h, desc.tile_w = 8, 8
+    desc.flags = 8                         # not a planner switch
+    assert _status(desc) == ev.ERR_INVALID_ARG
+    desc.flags = ev.FLAG_NO_FUSION | ev.FLAG_NO_FOLD | ev.FLAG_FORCE_VALU
     assert _status(desc) == ev.OK
+    desc.abi_version = 1                   # a description laid out for the previous ABI is refused
+    assert _status(desc) == ev.ERR_BAD_DESC
+    desc.abi_version = ev.ABI_VERSION
     assert ev.lib().evconv_query_workspace(None, None) == ev.ERR_INVALID_ARG
     assert b"" != ev.lib().evconv_last_error(None)
 
@@ -106,6 +109,7 @@ def test_null_handles():
     assert L.evconv_reset(None, None, None) == ev.ERR_INVALID_ARG
     assert L.evconv_step(None, None, None) == ev.ERR_INVALID_ARG
     assert L.evconv_set_mode(None, 0) == ev.ERR_INVALID_ARG
+    assert L.evconv_current_mode(None) == -1
 
 
 def test_product_package_does_not_import_the_oracle():
