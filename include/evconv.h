@@ -211,6 +211,21 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
                             void* workspace, size_t workspace_bytes, void* hip_stream,
                             evconv_net** out);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture set-up, tight
+ * serving loops, harnesses that forbid hipMalloc): evconv_create with the workspace taken from an
+ * array that is part of the library's code object, EVCONV_STATIC_WORKSPACE_BYTES per GPU, held
+ * from the library's load to the end of the process.  Neither this call nor any later call on
+ * the net allocates or frees device memory.  The net is built on the current device.
+ * EVCONV_ERR_WORKSPACE if the description needs more than the array holds (the text of
+ * evconv_last_error(NULL) gives both sizes); EVCONV_ERR_STATE while another net created by this
+ * call on the same device has not been destroyed: the array is one per GPU, two nets in it
+ * would overwrite each other.  The array keeps the previous net's contents; the part a new net
+ * uses is cleared by this call.  The pointers in evconv_out point into the array.  Otherwise as
+ * evconv_create. */
+#define EVCONV_STATIC_WORKSPACE_BYTES (32u << 20)
+evconv_status evconv_create_static(const evconv_net_desc* desc, const void* weights, size_t weight_bytes,
+                                   void* hip_stream, evconv_net** out);
+
 /* Number of output nodes (entries written to the `out` arrays below). */
 int32_t evconv_num_outputs(const evconv_net* net);
 

@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -17,6 +18,15 @@ using namespace evk;
 namespace {
 
 thread_local std::string g_create_error;
+
+// Workspace of evconv_create_static: one array per GPU, part of the loaded code object, so a net
+// built in it needs no device allocation by anybody.  In host code the array's name is only a
+// handle for hipGetSymbolAddress; the device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[EVCONV_STATIC_WORKSPACE_BYTES];
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};       // device address of `scratch` on each device
+evconv_net* g_static_owner[kMaxDevices] = {};  // the live net that occupies it, if any
 
 enum KernelKind { kKernConvValu = 0, kKernConvMfmaF32, kKernElementwise, kKernGap, kKernPool, kKernConvMfmaBf16,
                   kKernConvNarrow, kKernConvMfmaSplit, kKernConvPointwise, kKernDelay };
@@ -301,6 +311,7 @@ struct evconv_net {
   hipEvent_t auto_ev[4] = {nullptr, nullptr, nullptr, nullptr};
   int refresh_period = 0, since_refresh = 0;
   bool has_state = false;
+  int static_device = -1;   // >= 0: the net lives in that device's static workspace
   bool last_dense = true;   // the previous pass was a regular forward pass (DELAY nodes)
   bool zero_state = false;  // the pass being enqueued starts from the zero recurrent state (reset)
   Streams st{0, 1};
@@ -633,8 +644,11 @@ evconv_status evconv_query_workspace(const evconv_net_desc* desc, size_t* bytes)
   return EVCONV_OK;
 }
 
-evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, size_t weight_bytes,
-                            void* workspace, size_t workspace_bytes, void* hip_stream, evconv_net** out) {
+}  // extern "C"
+
+namespace {
+evconv_status create_impl(const evconv_net_desc* desc, const void* weights, size_t weight_bytes,
+                          void* workspace, size_t workspace_bytes, void* hip_stream, evconv_net** out) {
   if (!out || !workspace || (!weights && weight_bytes)) {
     g_create_error = "null argument";
     return EVCONV_ERR_INVALID_ARG;
@@ -875,6 +889,56 @@ evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, si
   *out = net;
   return EVCONV_OK;
 }
+}  // namespace
+
+extern "C" {
+
+evconv_status evconv_create(const evconv_net_desc* desc, const void* weights, size_t weight_bytes,
+                            void* workspace, size_t workspace_bytes, void* hip_stream, evconv_net** out) {
+  return create_impl(desc, weights, weight_bytes, workspace, workspace_bytes, hip_stream, out);
+}
+
+evconv_status evconv_create_static(const evconv_net_desc* desc, const void* weights, size_t weight_bytes,
+                                   void* hip_stream, evconv_net** out) {
+  if (!out) { g_create_error = "null argument"; return EVCONV_ERR_INVALID_ARG; }
+  Layout L;
+  evconv_status st = make_layout(desc, weight_bytes, true, &L, &g_create_error);
+  if (st != EVCONV_OK) return st;
+  if (L.total > (size_t)EVCONV_STATIC_WORKSPACE_BYTES) {
+    g_create_error = "this description needs " + std::to_string(L.total) + " bytes of workspace, the static workspace holds " +
+                     std::to_string((size_t)EVCONV_STATIC_WORKSPACE_BYTES);
+    return EVCONV_ERR_WORKSPACE;
+  }
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    g_create_error = e != hipSuccess ? std::string("hipGetDevice: ") + hipGetErrorString(e) : "device index out of range";
+    return EVCONV_ERR_HIP;
+  }
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  if (g_static_owner[dev]) {
+    g_create_error = "the static workspace of this device is in use by a net that has not been destroyed";
+    return EVCONV_ERR_STATE;
+  }
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      g_create_error = std::string("hipGetSymbolAddress: ") + hipGetErrorString(e);
+      return EVCONV_ERR_HIP;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  // (create_impl clears the part of the array it lays the net out in: the array keeps whatever the
+  // previous net left there)
+  evconv_net* net = nullptr;
+  st = create_impl(desc, weights, weight_bytes, g_scratch_ptr[dev], (size_t)EVCONV_STATIC_WORKSPACE_BYTES, hip_stream, &net);
+  if (st != EVCONV_OK) return st;
+  net->static_device = dev;
+  g_static_owner[dev] = net;
+  *out = net;
+  return EVCONV_OK;
+}
 
 int32_t evconv_num_outputs(const evconv_net* net) { return net ? (int32_t)net->outputs.size() : 0; }
 
@@ -963,6 +1027,10 @@ evconv_status evconv_destroy(evconv_net* net) {
   for (hipEvent_t e : net->prof_ev) (void)hipEventDestroy(e);
   for (hipEvent_t e : net->auto_ev)
     if (e) (void)hipEventDestroy(e);
+  if (net->static_device >= 0) {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (g_static_owner[net->static_device] == net) g_static_owner[net->static_device] = nullptr;
+  }
   delete net;
   return EVCONV_OK;
 }

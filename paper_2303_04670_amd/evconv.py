@@ -29,7 +29,8 @@ EXPORTS = ["evconv_query_workspace", "evconv_create", "evconv_num_outputs", "evc
            "evconv_step_frame", "evconv_destroy", "evconv_set_mode", "evconv_node_shape", "evconv_get_state",
            "evconv_get_stats", "evconv_node_kernel", "evconv_last_error", "evconv_profile_begin",
            "evconv_profile_end", "evconv_get_node_time", "evconv_set_refresh_period", "evconv_get_state_stream",
-           "evconv_stream_stride", "evconv_current_mode"]
+           "evconv_stream_stride", "evconv_current_mode", "evconv_create_static"]
+STATIC_WORKSPACE_BYTES = 32 << 20
 
 
 class NodeDesc(ctypes.Structure):
@@ -72,6 +73,7 @@ def lib() -> ctypes.CDLL:
         L.evconv_query_workspace.argtypes = [ctypes.POINTER(NetDesc), ctypes.POINTER(ctypes.c_size_t)]
         L.evconv_create.argtypes = [ctypes.POINTER(NetDesc), vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp,
                                     ctypes.POINTER(vp)]
+        L.evconv_create_static.argtypes = [ctypes.POINTER(NetDesc), vp, ctypes.c_size_t, vp, ctypes.POINTER(vp)]
         L.evconv_num_outputs.argtypes = [vp]
         L.evconv_reset.argtypes = [vp, vp, ctypes.POINTER(Out)]
         L.evconv_step.argtypes = [vp, vp, ctypes.POINTER(Out)]
@@ -128,10 +130,19 @@ def evconv_query_workspace(desc: NetDesc) -> int:
     return n.value
 
 
-class EvConvNet:
-    """Owns one evconv_net handle plus the torch tensors that back it."""
+class _DeviceBytes:
+    """A span of device memory owned by somebody else, for torch.as_tensor (no copy)."""
 
-    def __init__(self, net, device="cuda:0", stream=None, **desc_kw):
+    def __init__(self, ptr, nbytes):
+        self.__cuda_array_interface__ = {"shape": (nbytes,), "typestr": "|u1", "data": (ptr, False), "version": 2}
+
+
+class EvConvNet:
+    """Owns one evconv_net handle plus the torch tensors that back it.  static_workspace=True
+    builds the net in the library's own per-GPU array (evconv_create_static): no workspace tensor
+    is allocated."""
+
+    def __init__(self, net, device="cuda:0", stream=None, static_workspace=False, **desc_kw):
         import torch
         self.torch = torch
         self.net = net
@@ -139,17 +150,21 @@ class EvConvNet:
         desc, self._nodes_keep = marshal_desc(net, **desc_kw)
         self._desc = desc
         nbytes = evconv_query_workspace(desc)
-        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
-        base = self.workspace.data_ptr()
-        self._ws_ptr = (base + 255) // 256 * 256
         self.workspace_bytes = nbytes
         self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
         w = np.ascontiguousarray(net.weights, dtype=np.float32)
         h = ctypes.c_void_p()
         with torch.cuda.device(self.device):
-            st = lib().evconv_create(ctypes.byref(desc), w.ctypes.data_as(ctypes.c_void_p), w.nbytes,
-                                     ctypes.c_void_p(self._ws_ptr), nbytes,
-                                     ctypes.c_void_p(self.stream.cuda_stream), ctypes.byref(h))
+            if static_workspace:
+                self.workspace = None
+                st = lib().evconv_create_static(ctypes.byref(desc), w.ctypes.data_as(ctypes.c_void_p), w.nbytes,
+                                                ctypes.c_void_p(self.stream.cuda_stream), ctypes.byref(h))
+            else:
+                self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+                ws_ptr = (self.workspace.data_ptr() + 255) // 256 * 256
+                st = lib().evconv_create(ctypes.byref(desc), w.ctypes.data_as(ctypes.c_void_p), w.nbytes,
+                                         ctypes.c_void_p(ws_ptr), nbytes,
+                                         ctypes.c_void_p(self.stream.cuda_stream), ctypes.byref(h))
         if st != OK:
             raise EvConvError(st, lib().evconv_last_error(None).decode())
         self._h = h
@@ -256,13 +271,10 @@ class EvConvNet:
         until the next call on this net.  The caller synchronises the stream before reading."""
         torch = self.torch
         res = []
-        base = self._ws_ptr
-        raw = self.workspace
-        off0 = base - raw.data_ptr()
 
         def view(ptr, nbytes, dtype, shape):
-            o = ptr - base + off0 + stream * self.stream_stride
-            return raw[o:o + nbytes].view(dtype).view(*shape)
+            span = _DeviceBytes(ptr + stream * self.stream_stride, nbytes)
+            return torch.as_tensor(span, device=self.device).view(dtype).view(*shape)
         for j in range(self.n_outputs):
             o = self._outs[j]
             n = o.c * o.h * o.w
