@@ -77,9 +77,14 @@ def compare_input_stage(gpu, ora: Oracle, rep: Report):
     np.testing.assert_array_equal(gpu.state(-1, ev.STATE_X_PREV).view(np.uint32), ora.x_prev().view(np.uint32))
 
 
-def compare_node(gpu, ora: Oracle, i: int, rep: Report, tol=1e-4, act_scale=None, exact_sets=False, frobenius=False):
-    """frobenius=True: accumulated tensors and increments are compared by relative Frobenius error
-    <= tol (used for the bf16 contraction, tol = 2e-2) instead of max-abs error."""
+def compare_node(gpu, ora: Oracle, i: int, rep: Report, tol=1e-4, act_scale=None, exact_sets=False, frobenius=False,
+                 inc_rel_tol=6e-2):
+    """frobenius=True: accumulated tensors are compared by relative Frobenius error <= tol (used
+    for the bf16 contraction, tol = 2e-2) instead of max-abs error; increments element-wise
+    against tol times the accumulated tensor's scale, and in Frobenius norm against inc_rel_tol
+    times their own norm (an increment behind L bf16 layers carries each layer's 2^-8 product
+    error relative to itself, plus the sites where a ReLU's argument changes sign on one side
+    only; measured 3e-3 for a single layer, 3.4e-2 at the end of the 21-node UNet after 100 steps)."""
     from paper_2303_04670_amd import evconv as ev
     c, h, w = ora.shape(i)
     assert gpu.shape(i) == (c, h, w)
@@ -118,6 +123,7 @@ def compare_node(gpu, ora: Oracle, i: int, rep: Report, tol=1e-4, act_scale=None
             assert err <= tol * ref_scale, f"node {i}: increment error {err:g} > {tol:g} * {ref_scale:g}"
             rel = np.linalg.norm(dy_gpu[both] - dy_ref[both]) / max(np.linalg.norm(dy_ref[both]), 1e-30)
             rep.max_rel_inc = max(rep.max_rel_inc, rel)
+            assert rel <= inc_rel_tol, f"node {i}: increment error {rel:g} of its own norm > {inc_rel_tol:g}"
         else:
             err = np.abs(dy_gpu[both] - dy_ref[both]).max()
             assert err <= tol_abs, f"node {i}: increment error {err:g} > {tol_abs:g}"

@@ -593,7 +593,7 @@ def test_workload3_unet_bf16_full_size_100_steps():
     gen = wl.stream_voxel(1003, 256, 352, 100, 0.02)
     x0 = next(gen)
     run_stream(net, x0, gen, "frame", check_nodes_at={1, 50, 100}, label="w3-bf16", tol=2e-2, frobenius=True,
-               max_flips=3 * int(0.02 * 256 * 352))
+               max_flips=800)   # (measured: 378, all at the 1-channel sigmoid head and behind ReLU zero crossings)
 
 
 @pytest.mark.timeout(900)
@@ -609,7 +609,7 @@ def test_workload3_unet_full_size_100_steps():
     # the order 1e-8; fp32 drift against the fp64 oracle flips that decision at a few sites per
     # thousand.  Every other node must agree on every site.
     rep = run_stream(net, x0, gen, "frame", check_nodes_at={1, 2, 50, 100}, label="w3",
-                     max_flips=4 * int(0.005 * 256 * 352))
+                     max_flips=600)   # (measured: 170 over the 100 steps)
     assert set(rep.flips_by_node) <= {"node 20 active"}, rep.flips_by_node
 
 
@@ -869,7 +869,7 @@ def test_workload3_unet_split_bf16_full_size_100_steps():
     gen = wl.stream_voxel(1003, 256, 352, 100, 0.02)
     x0 = next(gen)
     rep = run_stream(net, x0, gen, "frame", check_nodes_at={1, 2, 50, 100}, label="w3-split",
-                     max_flips=4 * int(0.005 * 256 * 352))
+                     max_flips=600)   # (measured: 170 over the 100 steps)
     assert set(rep.flips_by_node) <= {"node 20 active"}, rep.flips_by_node
     _say(f"split-bf16 w3: max rel z err {rep.max_rel_z:.2e}, y err {rep.max_rel_y:.2e}")
 
@@ -1041,7 +1041,7 @@ def test_random_wide_graphs_all_contraction_modes(seed):
         x = (x + rng.standard_normal(x.shape).astype(np.float32) * m).astype(np.float32)
         frames.append(x)
     if mode == "bf16":
-        run_stream(net, frames[0], frames[1:], "frame", tol=2e-2, label=f"wide{seed}", max_flips=10**9, frobenius=True)
+        run_stream(net, frames[0], frames[1:], "frame", tol=2e-2, label=f"wide{seed}", max_flips=40, frobenius=True)
     else:
         run_stream(net, frames[0], frames[1:], "frame", label=f"wide{seed}", max_flips=40)
 
@@ -1073,7 +1073,7 @@ def test_upsampling_folded_into_conv_weights(seed, h, w):
         x = (x + rng.standard_normal(x.shape).astype(np.float32) * m).astype(np.float32)
         frames.append(x)
     if mode == "bf16":
-        run_stream(net, frames[0], frames[1:], "frame", tol=2e-2, label=f"fold{seed}", max_flips=10**9, frobenius=True)
+        run_stream(net, frames[0], frames[1:], "frame", tol=2e-2, label=f"fold{seed}", max_flips=40, frobenius=True)
         return
     run_stream(net, frames[0], frames[1:], "frame", label=f"fold{seed}", max_flips=40)
     folded, recomputed = ev.EvConvNet(net), ev.EvConvNet(net)
