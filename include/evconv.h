@@ -325,7 +325,9 @@ evconv_status evconv_get_stats(evconv_net* net, int32_t node, evconv_layer_stats
  * launches.  profile_begin allocates `max_records` event pairs and arms recording for the
  * following reset / step calls (recording stops silently when the pairs run out);
  * profile_end synchronises the stream and accumulates the elapsed times; get_node_time returns
- * the accumulated milliseconds and number of timed launches of a node since profile_begin. */
+ * the accumulated milliseconds and number of timed launches of a node since profile_begin; node -1
+ * is the increment builder (Eq.1 and the input mask), node n_nodes the compaction of all masks
+ * into site lists at the end of a step. */
 evconv_status evconv_profile_begin(evconv_net* net, int32_t max_records);
 evconv_status evconv_profile_end(evconv_net* net);
 evconv_status evconv_get_node_time(const evconv_net* net, int32_t node, double* ms_total /* HOST */,

@@ -353,7 +353,23 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
   bp.clear = net->occ_nodes; bp.n_clear = (int)net->L.n_occ_words;
   bp.g = net->L.gin; bp.mode = builder_mode;
   bp.st = net->st; bp.in_stride = net->in_stride;
-  launch_builder(bp, s);
+  // per-launch timing (evconv_profile_begin): record r is an event pair around the launches of
+  // prof_node[r]; -1 stands for the increment builder, n_nodes for the list compaction
+  auto timed_begin = [&]() {
+    const bool timed = net->prof && 2 * (net->prof_node.size() + 1) <= net->prof_ev.size();
+    if (timed) (void)hipEventRecord(net->prof_ev[2 * net->prof_node.size()], s);
+    return timed;
+  };
+  auto timed_end = [&](bool timed, int node) {
+    if (!timed) return;
+    (void)hipEventRecord(net->prof_ev[2 * net->prof_node.size() + 1], s);
+    net->prof_node.push_back(node);
+  };
+  {
+    const bool timed = timed_begin();
+    launch_builder(bp, s);
+    timed_end(timed, -1);
+  }
 
   for (size_t i = 0; i < net->L.nodes.size(); ++i) {
     NodePlan& n = net->L.nodes[i];
@@ -391,8 +407,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
       }
       continue;
     }
-    const bool timed = net->prof && 2 * (net->prof_node.size() + 1) <= net->prof_ev.size();
-    if (timed) (void)hipEventRecord(net->prof_ev[2 * net->prof_node.size()], s);
+    const bool timed = timed_begin();
     bool integrated = false;  // an output node whose kernel keeps the public tensors itself
     switch (n.kernel) {
       case kKernConvValu:
@@ -491,10 +506,7 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
         break;
       }
     }
-    if (timed) {
-      (void)hipEventRecord(net->prof_ev[2 * net->prof_node.size() + 1], s);
-      net->prof_node.push_back((int)i);
-    }
+    timed_end(timed, (int)i);
     if (d.is_output && !integrated) {
       IntegrateParams ip;
       ip.delta = n.out; ip.occ = n.occ; ip.y = n.y; ip.dy = n.dy; ip.g = n.go;
@@ -523,7 +535,11 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
       if (!last) from = to + (size_t)net->L.nodes[i].go.tiles();  // skip the S words, clear the T words behind them
     }
   }
-  launch_build_lists(net->sets_dev, (int)net->L.nodes.size() + 1, net->L.max_ty, net->st, s);
+  {
+    const bool timed = timed_begin();
+    launch_build_lists(net->sets_dev, (int)net->L.nodes.size() + 1, net->L.max_ty, net->st, s);
+    timed_end(timed, (int)net->L.nodes.size());
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(net, e, "kernel launch");
   return EVCONV_OK;
@@ -1158,8 +1174,8 @@ evconv_status evconv_profile_begin(evconv_net* net, int32_t max_records) {
     if (err != hipSuccess) return hip_fail(net, err, "hipEventCreate");
   }
   net->prof_node.clear();
-  net->node_ms.assign(net->L.nodes.size(), 0.0);
-  net->node_launches.assign(net->L.nodes.size(), 0);
+  net->node_ms.assign(net->L.nodes.size() + 2, 0.0);  // [node + 1]
+  net->node_launches.assign(net->L.nodes.size() + 2, 0);
   net->prof = true;
   return EVCONV_OK;
 }
@@ -1174,8 +1190,8 @@ evconv_status evconv_profile_end(evconv_net* net) {
     float ms = 0.f;
     e = hipEventElapsedTime(&ms, net->prof_ev[2 * r], net->prof_ev[2 * r + 1]);
     if (e != hipSuccess) return hip_fail(net, e, "hipEventElapsedTime");
-    net->node_ms[net->prof_node[r]] += ms;
-    net->node_launches[net->prof_node[r]] += 1;
+    net->node_ms[net->prof_node[r] + 1] += ms;
+    net->node_launches[net->prof_node[r] + 1] += 1;
   }
   for (hipEvent_t ev : net->prof_ev) (void)hipEventDestroy(ev);
   net->prof_ev.clear();
@@ -1184,10 +1200,10 @@ evconv_status evconv_profile_end(evconv_net* net) {
 }
 
 evconv_status evconv_get_node_time(const evconv_net* net, int32_t node, double* ms_total, int64_t* launches) {
-  if (!net || !ms_total || !launches || node < 0 || node >= (int)net->L.nodes.size()) return EVCONV_ERR_INVALID_ARG;
+  if (!net || !ms_total || !launches || node < -1 || node > (int)net->L.nodes.size()) return EVCONV_ERR_INVALID_ARG;
   if (net->node_ms.empty()) { *ms_total = 0; *launches = 0; return EVCONV_OK; }
-  *ms_total = net->node_ms[node];
-  *launches = net->node_launches[node];
+  *ms_total = net->node_ms[node + 1];
+  *launches = net->node_launches[node + 1];
   return EVCONV_OK;
 }
 

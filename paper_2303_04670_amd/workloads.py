@@ -91,11 +91,13 @@ class Net:
 class _NetBuilder:
     """Appends nodes and draws He-initialised weights N(0, 2/(k*k*c_in))."""
 
-    def __init__(self, name, in_c, in_h, in_w, seed, bf16=False, bias=False, sparsify=False, sparsify_k=None):
+    def __init__(self, name, in_c, in_h, in_w, seed, bf16=False, bias=False, sparsify=False, sparsify_k=None,
+                 sparsify_input=False):
         """sparsify: put a sparsification layer ahead of every convolution whose input is not the
-        network input; sparsify_k: fixed rounding step for all of them (None: the library derives
-        it from the net's threshold parameter and the layer input at refresh time)."""
-        self.sparsify, self.sparsify_k = sparsify, sparsify_k
+        network input (sparsify_input: ahead of those as well, for streams whose input increments
+        are dense but small); sparsify_k: fixed rounding step for all of them (None: the library
+        derives it from the net's threshold parameter and the layer input at refresh time)."""
+        self.sparsify, self.sparsify_k, self.sparsify_input = sparsify, sparsify_k, sparsify_input
         self.name, self.in_c, self.in_h, self.in_w = name, in_c, in_h, in_w
         self.rng = np.random.Generator(np.random.PCG64(seed))
         self.nodes: List[Node] = []
@@ -124,7 +126,7 @@ class _NetBuilder:
 
     def conv(self, src, c_out, k, stride=1, pad=None, act=ACT_RELU, out=0, op=OP_CONV2D):
         c_in = self._chan(src)
-        if self.sparsify and src >= 0 and op == OP_CONV2D:
+        if self.sparsify and (src >= 0 or self.sparsify_input) and op == OP_CONV2D:
             k_off = -1
             if self.sparsify_k is not None:
                 k_off = self._push(np.asarray([self.sparsify_k], np.float32))
@@ -201,11 +203,12 @@ def net_conv_stack(seed=1002, h=180, w=240, sparsify=False, sparsify_k=None) -> 
     return b.finish()
 
 
-def net_unet_depth(seed=1003, h=256, w=352, bf16=False, width=32, sparsify=False, sparsify_k=None) -> Net:
+def net_unet_depth(seed=1003, h=256, w=352, bf16=False, width=32, sparsify=False, sparsify_k=None,
+                   sparsify_input=False) -> Net:
     """Workload 3: UNet depth net.  head 5x5 -> 3 strided 5x5 encoders -> 2 residual blocks
     -> 3 x (skip-add, bilinear x2, conv5x5) -> skip-add with head -> 1x1 conv + sigmoid."""
     b = _NetBuilder("unet_depth" + ("_bf16" if bf16 else "") + ("_sp" if sparsify else ""), 5, h, w, seed,
-                    bf16=bf16, sparsify=sparsify, sparsify_k=sparsify_k)
+                    bf16=bf16, sparsify=sparsify, sparsify_k=sparsify_k, sparsify_input=sparsify_input)
     head = b.conv(-1, width, 5)
     e1 = b.conv(head, 2 * width, 5, 2)
     e2 = b.conv(e1, 4 * width, 5, 2)
@@ -531,6 +534,21 @@ def stream_voxel(seed, h, w, steps, density=0.02, warm=None, **kw) -> Iterator[n
         vs._emit()
     for _ in range(steps + 1):
         yield vs.frame()
+
+
+def stream_voxel_drifting_background(seed, h, w, steps, density=0.02, amplitude=0.5, drift=1e-3, event_scale=0.05, **kw):
+    """Workload-3 event frames, scaled by `event_scale`, on top of a smooth background of
+    amplitude `amplitude` (the same in every time bin) whose phase moves a little per step: every
+    pixel changes by at most `drift` at every step and event pixels change by `event_scale`,
+    both small against the values themselves.  Increments that are dense but tiny almost
+    everywhere: the situation the sparsification layer is made for ("Forward pass with increment
+    tensors": the difference of consecutive inputs is sparse *and* many of its elements have
+    small absolute values)."""
+    yy, xx = np.mgrid[0:h, 0:w]
+    phase = 2.0 * math.pi * (3.0 * xx / w + 2.0 * yy / h)
+    for t, f in enumerate(stream_voxel(seed, h, w, steps, density, **kw)):
+        bg = amplitude * np.sin(phase + t * drift / amplitude)
+        yield (event_scale * f + bg[None].astype(np.float32)).astype(np.float32)
 
 
 def density_sweep_1_5(t, period=50):
