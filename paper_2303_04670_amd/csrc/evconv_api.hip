@@ -3,6 +3,7 @@
 // happens on the host; every step of the path is a kernel launch on the caller's stream.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -268,7 +269,8 @@ evconv_status make_layout(const evconv_net_desc* desc, size_t weight_bytes, bool
     if (n.d.op == EVCONV_OP_CONV2D || n.d.op == EVCONV_OP_LINEAR) {
       const int k = n.d.kh;
       // room for input channels padded to whole chunks (at most 64) or a padded flattened contraction
-      n.off_w = b.take(((size_t)k * k * ((n.d.c_in + 63) / 64 * 64) + 16) * n.c_out_pad * 4);
+      n.off_w = b.take(std::max(((size_t)k * k * ((n.d.c_in + 63) / 64 * 64) + 16) * n.c_out_pad * 4,
+                                conv_narrow_weight_floats(n.c_out_pad) * 4));  // (the narrow-input kernel's per-lane layout)
       if (n.d.bias_off >= 0) n.off_bias = b.take((size_t)n.d.c_out * 4);
       if (n.d.op == EVCONV_OP_CONV2D && k == 5 && n.d.stride == 1 && n.d.pad == 2 && n.d.in0 >= 0 &&
           L->nodes[n.d.in0].d.op == EVCONV_OP_UPSAMPLE_BILINEAR2X) {
@@ -763,10 +765,9 @@ evconv_status create_impl(const evconv_net_desc* desc, const void* weights, size
           staging[e] = w;
         }
       } else if (n.kernel == kKernConvNarrow) {
-        // flattened contraction [KP][c_out], k = tap * c_in + ci, zero rows beyond taps * c_in;
-        // bf16-declared weights are rounded to bf16 and widened again
-        const int kp = conv_narrow_padded_k(k * k * ci_n);
-        staging.assign((size_t)kp * cop, 0.0f);  // [kp][c_out rounded up to 32]: zero columns beyond c_out
+        // flattened contraction k = tap * c_in + ci, laid out per matrix-core lane, zeros beyond
+        // taps * c_in and beyond c_out; bf16-declared weights are rounded to bf16 and widened again
+        staging.assign(conv_narrow_weight_floats(cop), 0.0f);
         for (int co = 0; co < co_n; ++co)
           for (int ci = 0; ci < ci_n; ++ci)
             for (int t = 0; t < k * k; ++t) {
@@ -775,7 +776,7 @@ evconv_status create_impl(const evconv_net_desc* desc, const void* weights, size
                 const uint32_t u = (uint32_t)to_bf16(w) << 16;
                 memcpy(&w, &u, 4);
               }
-              staging[((size_t)t * ci_n + ci) * cop + co] = w;
+              staging[conv_narrow_weight_index(t * ci_n + ci, co)] = w;
             }
       } else if (n.kernel == kKernConvMfmaSplit) {
         // two bf16 planes [tap][c_in/8][c_out][8]: hi = bf16(w), then lo = bf16(w - hi)

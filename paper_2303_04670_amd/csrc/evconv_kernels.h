@@ -125,9 +125,12 @@ bool conv_pointwise_supported(const ConvParams& p);
 // public tensors (ConvParams::y, dy)
 bool conv_pointwise_integrates(const ConvParams& p);
 void launch_conv_pointwise(const ConvParams& p, hipStream_t s);
-// narrow-input variant: taps * c_in <= 128, c_out >= 16; weights [padded k][c_out_pad] fp32
+// narrow-input variant: taps * c_in <= 128, c_out >= 16; weights re-laid per MFMA lane:
+// conv_narrow_weight_floats(c_out_pad) fp32 values, W[k = tap * c_in + ci][co] at
+// conv_narrow_weight_index(k, co), zeros elsewhere
 bool conv_narrow_supported(const ConvParams& p);
-int conv_narrow_padded_k(int k_tot);
+size_t conv_narrow_weight_floats(int c_out_pad);
+size_t conv_narrow_weight_index(int k, int co);
 void launch_conv_narrow(const ConvParams& p, hipStream_t s);
 
 // ---- elementwise / structural increment operators ---------------------------------------
