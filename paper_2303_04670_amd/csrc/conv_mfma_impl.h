@@ -736,41 +736,45 @@ void conv_mfma_kernel(ConvParams p) {
   for (int f = 0; f < kMaxFusedAdds; ++f)
     if (f < p.n_fused) lds_or(1 + f, nz_fused[f]);
   __syncthreads();
-  if (tid == 0) {
-    // site bits of this workgroup into the words of a set: its own tile's word, or (weight-folded)
-    // the words of the four up-sampled tiles over the stored tile, where site (y, x) is bit
-    // (2 * (y % 4) + fpy, 2 * (x % 4) + fpx) of tile (y / 4, x / 4)
-    auto glob_or = [&](uint64_t* words, uint64_t bits) {
-      if (!bits) return;
-      if (!fold) {
-        atomicOr((unsigned long long*)&words[tile], (unsigned long long)bits);
-        return;
-      }
-      for (int a = 0; a < 2; ++a)
-        for (int b = 0; b < 2; ++b) {
-          uint64_t spread = 0;
-          for (int r = 0; r < 4; ++r) {
-            const unsigned nib = (unsigned)(bits >> ((4 * a + r) * 8 + 4 * b)) & 0xfu;
-            const unsigned wide = (nib & 1u) | ((nib & 2u) << 1) | ((nib & 4u) << 2) | ((nib & 8u) << 3);
-            spread |= (uint64_t)wide << ((2 * r + fpy) * 8 + fpx);
-          }
-          if (spread)
-            atomicOr((unsigned long long*)&words[(2 * tile_y + a) * p.go.tx + 2 * tile_x + b], (unsigned long long)spread);
-        }
-    };
-    // S of the producer as seen by this workgroup's rows and channels; all words are pre-zeroed
-    // and the other workgroups of the tile OR their share in
+  if (tid < 4 * (2 + 2 * kMaxFusedAdds)) {
+    // Site bits of this workgroup into the words of up to 2 + 2 * (fused ADDs) sets: S and T of the
+    // conv, then T and S of each fused ADD (Eq.11b).  All words of those sets are pre-zeroed and
+    // the other workgroups of a tile OR their share in.  Four lanes per set: a weight-folded
+    // workgroup's bits go to the words of the four up-sampled tiles over its stored tile, where
+    // site (y, x) is bit (2 * (y % 4) + fpy, 2 * (x % 4) + fpx) of tile (y / 4, x / 4), one of them
+    // per lane; otherwise the first of the four lanes writes the tile's own word.
+    const int set = tid >> 2, part = tid & 3;
+    // S of the producer as seen by this workgroup's rows and channels
     uint64_t s_prev = p.dense ? touched_word : ((uint64_t)s_nz[0] | ((uint64_t)s_nz[1] << 32));
-    glob_or(at_stream(p.occ_out, so), s_prev);
-    if (wg_co == 0) glob_or(at_stream(p.occ_touched, so), touched_word);
-    for (int f = 0; f < p.n_fused; ++f) {
+    uint64_t bits = set == 0 ? s_prev : (set == 1 && wg_co == 0) ? touched_word : 0ull;
+    uint64_t* words = set == 0 ? p.occ_out : set == 1 ? p.occ_touched : nullptr;
+#pragma unroll
+    for (int f = 0; f < kMaxFusedAdds; ++f) {
+      if (f >= p.n_fused) break;
       const FusedAdd& fa = p.fused[f];
       const uint64_t t_f = s_prev | skip_word[f];  // Eq.11b
       const uint64_t nz_f = (uint64_t)s_nz[2 + 2 * f] | ((uint64_t)s_nz[3 + 2 * f] << 32);
       const uint64_t s_f = (fa.structural || p.dense) ? t_f : nz_f;
-      glob_or(at_stream(fa.occ_touched, so), t_f);
-      glob_or(at_stream(fa.occ_out, so), s_f);
+      if (set == 2 + 2 * f) { bits = t_f; words = fa.occ_touched; }
+      if (set == 3 + 2 * f) { bits = s_f; words = fa.occ_out; }
       s_prev = s_f;
+    }
+    if (bits && words) {
+      words = at_stream(words, so);
+      if (!fold) {
+        if (part == 0) atomicOr((unsigned long long*)&words[tile], (unsigned long long)bits);
+      } else {
+        const int a = part >> 1, b = part & 1;
+        uint64_t spread = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const unsigned nib = (unsigned)(bits >> ((4 * a + r) * 8 + 4 * b)) & 0xfu;
+          const unsigned wide = (nib & 1u) | ((nib & 2u) << 1) | ((nib & 4u) << 2) | ((nib & 8u) << 3);
+          spread |= (uint64_t)wide << ((2 * r + fpy) * 8 + fpx);
+        }
+        if (spread)
+          atomicOr((unsigned long long*)&words[(2 * tile_y + a) * p.go.tx + 2 * tile_x + b], (unsigned long long)spread);
+      }
     }
   }
 }
