@@ -32,7 +32,9 @@
  *   GLOBAL_AVGPOOL   y_lin = mean over sites of x_inc (1 x 1 x C), T = {0} if S_in nonempty.
  *   SPARSIFY         the sparsification layer with error feedback (Eq.3-8): residual delta (kept
  *                    as this node's accumulated tensor, zero after reset), x_corr = delta + x_inc,
- *                    y_inc = k * floor(0.5 + x_corr / k), delta = x_corr - y_inc, at S_in; S_out =
+ *                    y_inc = k * floor(0.5 + x_corr / k), delta = x_corr - y_inc, at the elements
+ *                    of S_in whose x_inc is nonzero (the others emit 0 and keep delta: the same
+ *                    formulas give that for |delta| <= k/2, so no value depends on the mask); S_out =
  *                    sites with a nonzero y_inc.  k = sparsify_tp * RMS(node input at the last
  *                    reset), kept to 8 significant bits, or the fp32 value at weight_off when
  *                    weight_off >= 0; k == 0 is the identity.  In reset and in dense-recompute

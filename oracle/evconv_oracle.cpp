@@ -33,7 +33,8 @@
 //     difference of the accumulated sums.
 //   * sparsification layer (Eq.3-8; the printed Eq.4 and Eq.8 disagree in sign and Eq.8 counts
 //     the old residual twice): delta(-1) = 0; x_corr = delta(n-1) + x_inc(n);
-//     y_inc = k * floor(0.5 + x_corr / k); delta(n) = x_corr - y_inc.  This keeps
+//     y_inc = k * floor(0.5 + x_corr / k); delta(n) = x_corr - y_inc, applied to the elements
+//     whose x_inc is nonzero (for the others the same formulas give y_inc = 0).  This keeps
 //     sum(y_inc) + delta == sum(x_inc) and -k/2 <= delta < k/2, which is what the text asks of
 //     the residual.  A refresh is a regular forward pass (the layer is the identity) and clears
 //     delta.  k = t_p * RMS(layer input at the last refresh), rounded to 8 significant bits so
@@ -537,7 +538,12 @@ struct Net {
         for (int c = 0; c < o.c; ++c) {
           const size_t e = q * o.c + c;
           T y = da[e];
-          if (k > T(0)) {
+          // An element whose input increment is zero emits nothing and keeps its residual: with
+          // -k/2 <= delta < k/2 (the bound the section asks of the residual) Eq.6-7 give
+          // floor(0.5 + delta / k) = 0 for it, and taking that for granted keeps the layer
+          // independent of the mask (which may cover such an element or not).  The zero test is the
+          // binary32 one of the masks.
+          if (k > T(0) && float(da[e]) != 0.0f) {
             const T x_corr = s.z[e] + da[e];
             y = k * std::floor(T(0.5) + x_corr / k);
             s.z[e] = x_corr - y;

@@ -326,9 +326,11 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
         const VecT<VEC> d_old = ldv<VEC>(zq);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) {
+          // (an element with a zero increment emits nothing and keeps its residual: |delta| <= k/2)
           const float x_corr = d_old.v[i] + lin.v[i];
-          o.v[i] = k * floorf(0.5f + x_corr / k);
-          d_new.v[i] = x_corr - o.v[i];
+          const bool moved = lin.v[i] != 0.0f;
+          o.v[i] = moved ? k * floorf(0.5f + x_corr / k) : 0.0f;
+          d_new.v[i] = moved ? x_corr - o.v[i] : d_old.v[i];
         }
       }
       if (p.dense || k > 0.0f) stv<VEC>(zq, d_new);  // a refresh clears the residual
