@@ -143,7 +143,7 @@ void conv_mfma_kernel(ConvParams p) {
   __shared__ uint64_t s_occ[16];
   __shared__ unsigned s_rows[24];  // bit px of s_rows[py]: patch site (py, px) is active
   __shared__ unsigned s_lrows[UPS ? LPMAX : 1];  // UPS: the same for the low-resolution source region
-  __shared__ unsigned s_nz[2 * (1 + kMaxFusedAdds)];  // nonzero-site bits: conv, then each fused ADD
+  __shared__ unsigned s_nz[2 * (2 + kMaxFusedAdds)];  // nonzero-site bits: conv, each fused ADD, fused sparsification
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // Consecutive workgroups (x fastest) go to the chip's 8 XCDs in turn, each with an L2 of its own.
@@ -213,7 +213,7 @@ void conv_mfma_kernel(ConvParams p) {
       w = p.dense ? ~0ull : at_stream(p.occ_in, so)[ty * s_tx + tx];
     s_occ[tid] = w;
   }
-  if (tid < 2 * (1 + kMaxFusedAdds)) s_nz[tid] = 0;
+  if (tid < 2 * (2 + kMaxFusedAdds)) s_nz[tid] = 0;
   __syncthreads();
   if (tid < GH) {  // one bit row per row of the region; out-of-image sites are 0
     const int gy = gy0 + tid;
@@ -644,6 +644,18 @@ void conv_mfma_kernel(ConvParams p) {
     }
   }
 
+  // residuals and rounding step of a fused sparsification layer
+  float sp_delta[EP_ITERS];
+  float sp_k = 0.0f;
+#pragma unroll
+  for (int it = 0; it < EP_ITERS; ++it) sp_delta[it] = 0.0f;
+  if (p.sp.delta && !p.dense) {
+    sp_k = *at_stream(p.sp.step, so);
+    const __amdgpu_buffer_rsrc_t d_rsrc = out_rsrc(at_stream(p.sp.delta, so));
+#pragma unroll
+    for (int it = 0; it < EP_ITERS; ++it) sp_delta[it] = ep_load(d_rsrc, sp_k > 0.0f && has(site_mine, it), it);
+  }
+
   // ---- reduce the NW partial sums through LDS: slots [4][block*16 + reg][lane]
   auto spill = [&](float* part) {
 #pragma unroll
@@ -674,6 +686,7 @@ void conv_mfma_kernel(ConvParams p) {
   // their place in the tile word once)
   uint64_t nz_mine = 0;
   uint64_t nz_fused_mine[kMaxFusedAdds] = {0, 0};
+  uint64_t nz_sp_mine = 0;
   const __amdgpu_buffer_rsrc_t o_rsrc = out_rsrc(at_stream(p.out, so));
   // partial sum of local site ls = it * EP_SITES + es: the part of the LDS offset that depends on
   // the thread (es < 16), the rest is a constant per `it`
@@ -722,6 +735,25 @@ void conv_mfma_kernel(ConvParams p) {
       ep_store(out_rsrc(at_stream(fa.out, so)), it, o);
       if (o != 0.0f) nz_fused_mine[f] |= 1ull << (it * EP_SITES);
     }
+    // fused sparsification layer on the last stage's increment (Eq.3-8): x_corr = delta + x_inc,
+    // y_inc = k floor(0.5 + x_corr / k), delta = x_corr - y_inc where x_inc is nonzero; elsewhere
+    // y_inc = 0 and the residual stays.  A regular pass: identity, residual cleared.
+    if (p.sp.delta) {
+#pragma clang fp contract(off)  // the residual is x_corr minus the rounded product, not a fused form
+      float y = o;
+      if (p.dense) {
+        ep_store(out_rsrc(at_stream(p.sp.delta, so)), it, 0.0f);
+      } else if (sp_k > 0.0f) {
+        const float x_corr = sp_delta[it] + o;
+        y = 0.0f;
+        if (o != 0.0f) {
+          y = sp_k * floorf(0.5f + x_corr / sp_k);
+          ep_store(out_rsrc(at_stream(p.sp.delta, so)), it, x_corr - y);
+        }
+      }
+      ep_store(out_rsrc(at_stream(p.sp.out, so)), it, y);
+      if (y != 0.0f) nz_sp_mine |= 1ull << (it * EP_SITES);
+    }
   }
   const uint64_t nz_sites = nz_mine << (r0 * 8 + es);
   uint64_t nz_fused[kMaxFusedAdds];
@@ -735,10 +767,12 @@ void conv_mfma_kernel(ConvParams p) {
 #pragma unroll
   for (int f = 0; f < kMaxFusedAdds; ++f)
     if (f < p.n_fused) lds_or(1 + f, nz_fused[f]);
+  if (p.sp.delta) lds_or(1 + kMaxFusedAdds, nz_sp_mine << (r0 * 8 + es));
   __syncthreads();
-  if (tid < 4 * (2 + 2 * kMaxFusedAdds)) {
-    // Site bits of this workgroup into the words of up to 2 + 2 * (fused ADDs) sets: S and T of the
-    // conv, then T and S of each fused ADD (Eq.11b).  All words of those sets are pre-zeroed and
+  if (tid < 4 * (4 + 2 * kMaxFusedAdds)) {
+    // Site bits of this workgroup into the words of up to 4 + 2 * (fused ADDs) sets: S and T of the
+    // conv, then T and S of each fused ADD (Eq.11b), then T and S of a fused sparsification layer
+    // (its T is the active set of the stage it reads).  All words of those sets are pre-zeroed and
     // the other workgroups of a tile OR their share in.  Four lanes per set: a weight-folded
     // workgroup's bits go to the words of the four up-sampled tiles over its stored tile, where
     // site (y, x) is bit (2 * (y % 4) + fpy, 2 * (x % 4) + fpx) of tile (y / 4, x / 4), one of them
@@ -758,6 +792,11 @@ void conv_mfma_kernel(ConvParams p) {
       if (set == 2 + 2 * f) { bits = t_f; words = fa.occ_touched; }
       if (set == 3 + 2 * f) { bits = s_f; words = fa.occ_out; }
       s_prev = s_f;
+    }
+    if (p.sp.delta) {
+      const uint64_t nz_sp = (uint64_t)s_nz[2 + 2 * kMaxFusedAdds] | ((uint64_t)s_nz[3 + 2 * kMaxFusedAdds] << 32);
+      if (set == 2 + 2 * kMaxFusedAdds) { bits = s_prev; words = p.sp.occ_touched; }
+      if (set == 3 + 2 * kMaxFusedAdds) { bits = p.dense ? s_prev : nz_sp; words = p.sp.occ_out; }
     }
     if (bits && words) {
       words = at_stream(words, so);

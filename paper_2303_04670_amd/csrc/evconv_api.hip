@@ -49,7 +49,8 @@ struct NodePlan {
   bool keeps_z = false, structural = false;
   int kernel = 0;
   int c_out_pad = 0;
-  int fused_into = -1;      // ADD node executed in the epilogue of that conv node
+  int fused_into = -1;      // ADD or SPARSIFY node executed in the epilogue of that conv node
+  int fused_sp = -1;        // conv node: the SPARSIFY node it executes behind its last epilogue stage
   int n_fused = 0;          // conv node: ADD nodes it executes, in order
   int fused_nodes[kMaxFusedAdds] = {-1, -1};
   int gather_fused_into = -1;  // UPSAMPLE node computed inside the gather of that conv node, never stored
@@ -400,6 +401,9 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
       continue;
     }
     if (n.fused_into >= 0) {  // computed by the producing conv's epilogue
+      if (d.op == EVCONV_OP_SPARSIFY && reinit && n.step_fixed < 0.0f)
+        // refresh: k = t_p * RMS of the layer input, which the producer has just written in full
+        launch_rms_step(a, (size_t)n.ga.c * n.ga.sites(), net->sparsify_tp, net->rms_partial, n.step, net->st, s);
       if (d.is_output) {
         IntegrateParams ip;
         ip.delta = n.out; ip.occ = n.occ; ip.y = n.y; ip.dy = n.dy; ip.g = n.go;
@@ -435,6 +439,11 @@ evconv_status run_pass(evconv_net* net, const float* input, int builder_mode, Pa
           p.occ_in = src < 0 ? net->occ_in : net->L.nodes[src].occ;
           const Geo& gl = src < 0 ? net->L.gin : net->L.nodes[src].go;
           p.upsample = 1; p.lo_h = gl.h; p.lo_w = gl.w;
+        }
+        p.sp = FusedSparsify{};
+        if (n.fused_sp >= 0) {
+          const NodePlan& sp = net->L.nodes[n.fused_sp];
+          p.sp.delta = sp.z; p.sp.out = sp.out; p.sp.occ_out = sp.occ; p.sp.occ_touched = sp.touched; p.sp.step = sp.step;
         }
         for (int f = 0; f < kMaxFusedAdds; ++f) p.fused[f] = FusedAdd{};
         for (int f = 0; f < n.n_fused; ++f) {
@@ -856,6 +865,31 @@ evconv_status create_impl(const evconv_net_desc* desc, const void* weights, size
       if (delayed_between) continue;
       c_node.fused_nodes[c_node.n_fused++] = (int)i;
       a_node.fused_into = host;
+    }
+  }
+  // Fold a sparsification layer into the epilogue of the matrix-core conv that produces its input,
+  // directly or through the last ADD folded into that conv: the layer then reads the increment
+  // where it is made (no launch, no re-read).  One layer per conv; every buffer of the layer is
+  // still written.
+  if (fuse) {
+    for (size_t i = 0; i < L.nodes.size(); ++i) {
+      NodePlan& s_node = L.nodes[i];
+      if (s_node.d.op != EVCONV_OP_SPARSIFY || s_node.d.in0 < 0 || s_node.d.is_output) continue;
+      const NodePlan& x = L.nodes[s_node.d.in0];
+      int host = -1;
+      if (x.fused_into >= 0) {
+        const NodePlan& h = L.nodes[x.fused_into];
+        if (x.d.op == EVCONV_OP_ADD && h.n_fused > 0 && h.fused_nodes[h.n_fused - 1] == s_node.d.in0) host = x.fused_into;
+      } else if (x.n_fused == 0 && (x.kernel == kKernConvMfmaF32 || x.kernel == kKernConvMfmaBf16 || x.kernel == kKernConvMfmaSplit)) {
+        host = s_node.d.in0;
+      }
+      if (host < 0 || L.nodes[host].fused_sp >= 0) continue;
+      bool delayed_between = false;  // (a DELAY of this layer placed before it must see last step's buffers)
+      for (size_t dn = (size_t)host + 1; dn < i; ++dn)
+        if (L.nodes[dn].d.op == EVCONV_OP_DELAY && L.nodes[dn].d.in0 == (int)i) delayed_between = true;
+      if (delayed_between) continue;
+      L.nodes[host].fused_sp = (int)i;
+      s_node.fused_into = host;
     }
   }
   // Fold a bilinear x2 up-sampling into the gather of the matrix-core conv that is its only

@@ -69,6 +69,16 @@ struct FusedAdd {
   int act, keeps_z, structural;
 };
 constexpr int kMaxFusedAdds = 2;
+// A sparsification layer (Eq.3-8) folded into the same epilogue: it reads the increment the last
+// stage of the epilogue has just produced (the conv's, or the last fused ADD's), at the sites the
+// workgroup visits, and writes its own buffers.  Its touched set is that stage's active set.
+struct FusedSparsify {
+  float* delta;             // its residual (accumulated tensor); null = no such layer
+  float* out;               // its increment buffer (the value in a regular pass, where it is the identity)
+  uint64_t* occ_out;        // its S words (pre-zeroed; OR-ed in)
+  uint64_t* occ_touched;    // its T words (pre-zeroed; OR-ed in)
+  const float* step;        // device scalar: the rounding step k (0 = identity)
+};
 
 struct ConvParams {
   const float* in;          // H x W x C increment of the input node (full values if dense)
@@ -85,6 +95,7 @@ struct ConvParams {
   int dense;                // 1: regular forward pass (all sites, z overwritten with bias)
   int n_fused;              // matrix-core kernel only: ADD nodes applied in the epilogue, in order
   FusedAdd fused[kMaxFusedAdds];
+  FusedSparsify sp;         // matrix-core kernel only: applied behind the last stage of the epilogue
   Streams st;               // w and bias are shared by all streams
   // matrix-core kernel only: the input is the bilinear x2 up-sampling of `in` (lo_h x lo_w stored
   // sites, occ_in their occupancy words); gi describes the up-sampled tensor

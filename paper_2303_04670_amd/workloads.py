@@ -124,14 +124,22 @@ class _NetBuilder:
         self.n_w += arr.size
         return off
 
-    def conv(self, src, c_out, k, stride=1, pad=None, act=ACT_RELU, out=0, op=OP_CONV2D):
+    def sparsify_node(self, src):
+        """A sparsification layer on node `src` (if this builder places such layers at all)."""
+        if not self.sparsify:
+            return src
         c_in = self._chan(src)
-        if self.sparsify and (src >= 0 or self.sparsify_input) and op == OP_CONV2D:
-            k_off = -1
-            if self.sparsify_k is not None:
-                k_off = self._push(np.asarray([self.sparsify_k], np.float32))
-            self.nodes.append(Node(OP_SPARSIFY, ACT_NONE, src, -2, c_in, c_in, 1, 1, 0, k_off, -1, 0))
-            src = len(self.nodes) - 1
+        k_off = -1
+        if self.sparsify_k is not None:
+            k_off = self._push(np.asarray([self.sparsify_k], np.float32))
+        self.nodes.append(Node(OP_SPARSIFY, ACT_NONE, src, -2, c_in, c_in, 1, 1, 0, k_off, -1, 0))
+        return len(self.nodes) - 1
+
+    def conv(self, src, c_out, k, stride=1, pad=None, act=ACT_RELU, out=0, op=OP_CONV2D, sparsify_input=True):
+        """sparsify_input=False: the caller has placed this conv's sparsification layer itself."""
+        c_in = self._chan(src)
+        if sparsify_input and (src >= 0 or self.sparsify_input) and op == OP_CONV2D:
+            src = self.sparsify_node(src)
         pad = k // 2 if pad is None else pad
         std = math.sqrt(2.0 / (k * k * c_in))
         w = self.rng.standard_normal((c_out, c_in, k, k)) * std
@@ -220,8 +228,11 @@ def net_unet_depth(seed=1003, h=256, w=352, bf16=False, width=32, sparsify=False
         x = b.simple(OP_ADD, x, r, act=ACT_RELU)
     for skip, c_out in ((e3, 4 * width), (e2, 2 * width), (e1, width)):
         x = b.simple(OP_ADD, x, skip)
+        # (the decoder conv's sparsification layer sits ahead of the up-sampling: conv o up-sampling
+        # is one linear operator, and its input is the tensor at the lower resolution)
+        x = b.sparsify_node(x)
         x = b.simple(OP_UPSAMPLE2X, x)
-        x = b.conv(x, c_out, 5)
+        x = b.conv(x, c_out, 5, sparsify_input=False)
     x = b.simple(OP_ADD, x, head)
     b.conv(x, 1, 1, 1, 0, ACT_SIGMOID, out=1)
     return b.finish()

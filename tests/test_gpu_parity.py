@@ -672,6 +672,56 @@ def test_sparsified_conv_net_exact_arithmetic():
     assert rep.flips == 0
 
 
+def test_sparsification_layers_folded_into_conv_epilogues_exact_arithmetic():
+    """Sparsification layers whose input comes from a matrix-core conv, directly or through an ADD
+    folded into that conv, run inside its epilogue.  Exact arithmetic again (dyadic weights and
+    inputs, k = 0.5), so the GPU must equal the fp64 oracle on every tensor and every list, with
+    the layers folded and with every fusion switched off."""
+    _say("sparsification layers inside conv epilogues (behind the conv and behind a folded ADD), exact arithmetic")
+    b = wl._NetBuilder("sp_fused_exact", 16, 21, 27, 5, sparsify=True, sparsify_k=0.5)
+    c1 = b.conv(-1, 32, 3)
+    c2 = b.conv(c1, 32, 3)                       # its layer reads c1: behind the conv stage
+    c3 = b.conv(c2, 32, 3, act=wl.ACT_NONE)      # its layer reads c2
+    a = b.simple(wl.OP_ADD, c1, c3, act=wl.ACT_RELU)   # folded into c3's epilogue
+    b.conv(a, 32, 3, out=1)                      # its layer reads the ADD: behind the folded ADD stage
+    net = b.finish()
+    rng = np.random.default_rng(8)
+    wts = net.weights.copy()
+    for nd in net.nodes:
+        if nd.op == wl.OP_CONV2D:
+            n = nd.c_out * nd.c_in * 9
+            wts[nd.w_off:nd.w_off + n] = rng.integers(-1, 2, n) / 8.0
+    net.weights = wts
+    x0 = (rng.integers(-8, 9, (16, 21, 27)) / 4.0).astype(np.float32)
+    incs = [((rng.integers(-4, 5, x0.shape) / 4.0) * (rng.random((1, 21, 27)) < 0.1)).astype(np.float32)
+            for _ in range(8)]
+    incs.append(np.zeros_like(x0))
+    sp_nodes = [i for i, nd in enumerate(net.nodes) if nd.op == wl.OP_SPARSIFY]
+    assert len(sp_nodes) == 3
+    g = ev.EvConvNet(net)
+    names = [g.kernel_name(i) for i in range(len(net.nodes))]
+    g.destroy()
+    assert all(names[i] == "fused_into_conv_epilogue" for i in sp_nodes), names
+    assert names[a] == "fused_into_conv_epilogue"
+    for flags in (0, ev.FLAG_NO_FUSION):
+        gpu, ora, rep = ev.EvConvNet(net, flags=flags), Oracle(net), cmp.Report()
+        gpu.reset(_dev(x0))
+        ora.reset(x0)
+        for d in incs:
+            gpu.step(_dev(d))
+            ora.step_increment(d)
+            cmp.compare_outputs(gpu, ora, rep, 1e-7)
+            for i in range(len(net.nodes)):
+                cmp.compare_node(gpu, ora, i, rep, tol=1e-7, exact_sets=True)
+        # a refresh clears the residuals and leaves the layers' buffers holding values
+        gpu.set_refresh_period(1)
+        gpu.step(_dev(incs[0]))
+        for i in sp_nodes:
+            assert not gpu.state(i, ev.STATE_Z).any(), f"residual of node {i} after a refresh"
+        assert rep.flips == 0
+        gpu.destroy()
+
+
 def test_sparsified_unet_properties_and_speed_of_convergence():
     """Lossy path on a reduced UNet with t_p = 0.3: what must hold whatever the rounding
     decisions were - residual bounded by k/2, emitted increments multiples of k, fewer active
