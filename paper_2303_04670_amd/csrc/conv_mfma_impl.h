@@ -120,8 +120,9 @@ void conv_mfma_kernel(ConvParams p) {
   constexpr bool BF16 = OPM != kOpF32;     // bf16 MFMA, 16 channels per unit
   constexpr bool SPLIT = OPM == kOpSplit;  // operands as bf16 high + low parts, three products
   constexpr int NT = NW * 64;
-  // LDS site stride in 4-byte words; stride / 4 is odd => conflict-free ds_read_b128.  Split
-  // mode keeps a high plane and a low plane of CHUNK bf16 each per site.
+  // LDS site stride in 4-byte words; stride / 4 is odd (the eight sites of a patch row fall into
+  // eight distinct 16-byte slots of the banks).  Split mode keeps a high plane and a low plane of
+  // CHUNK bf16 each per site.
   constexpr int CS = (BF16 && !SPLIT) ? CHUNK / 2 + 4 : CHUNK + 4;
   constexpr int LO = CHUNK / 2;  // word offset of the low plane inside a site (split mode)
   constexpr int UCH = BF16 ? 16 : 8;  // channels per unit
@@ -332,7 +333,14 @@ void conv_mfma_kernel(ConvParams p) {
   // The gathered region is the patch itself, or (UPS) its low-resolution source region, which
   // goes to a second fp32 buffer behind the patch buffer.
   constexpr unsigned kOob = 0x80000000u;
-  float* const s_low = s_mem + PH * PW * CS;  // UPS only
+  // Row pitch of the patch in LDS (4-byte words).  The LDS serves a 16-byte read per lane in
+  // groups of 16 lanes over 64 banks; the 16 lanes of an A-fragment read are two rows of eight
+  // sites.  The site stride (an odd number of 16-byte slots) spreads a row's eight sites over
+  // eight distinct slots; a row pitch of 128 bytes modulo 256 puts the next row's sites on the
+  // other eight.  (Stride-2 layers read every other site and row: no pitch frees them of
+  // conflicts, they keep the dense pitch.)
+  const int RP = s == 1 ? ((PW * CS + 31) / 64) * 64 + 32 : PW * CS;
+  float* const s_low = s_mem + PH * RP;  // UPS only
   const int total_v = GH * GW * NV;
   const int gw_magic = (65536 + GW - 1) / GW;  // site / GW == (site * gw_magic) >> 16 for site < 441
   int lds_off[MAXG];
@@ -345,7 +353,7 @@ void conv_mfma_kernel(ConvParams p) {
     if (e < total_v) {
       const int site = e / NV, v = e - site * NV;
       const int py = (site * gw_magic) >> 16, px = site - py * GW;
-      lds_off[j] = ups ? site * CSL + v * 4 : (BF16 ? site * CS + v * 2 : site * CS + v * 4);
+      lds_off[j] = ups ? site * CSL + v * 4 : py * RP + px * CS + v * (BF16 ? 2 : 4);
       const unsigned row = ups ? s_lrows[py] : s_rows[py];
       if ((row >> px) & 1u) g_off[j] = (unsigned)((((gy0 + py) * SW + gx0 + px) * Cin + v * 4) * 4);
     }
@@ -442,7 +450,7 @@ void conv_mfma_kernel(ConvParams p) {
         ib_src[b] = (((cy0 - gy0) * GW + (cx0 - gx0)) * CSL + v * 4) | (((cy1 - cy0) * GW * CSL) << 12) |
                     (((cx1 - cx0) * CSL) << 22);
         const int py = 2 * i + 1 - iy0, px = 2 * j + 1 - ix0;  // patch coordinates of the block, -1 at least
-        const int dst = (py * PW + px) * CS + v * (BF16 ? 2 : 4) + 4096;
+        const int dst = py * RP + px * CS + v * (BF16 ? 2 : 4) + 4096;
         int mask = 0;
 #pragma unroll
         for (int r = 0; r < 2; ++r)
@@ -477,8 +485,8 @@ void conv_mfma_kernel(ConvParams p) {
       const int dst = (ib_dst[b] & 0xffff) - 4096;
       if (mask & 1) put(dst, (mask & 16) ? hsum(0.75f, a0, 0.25f, a1) : zero);
       if (mask & 2) put(dst + CS, (mask & 32) ? hsum(0.75f, b0, 0.25f, b1) : zero);
-      if (mask & 4) put(dst + PW * CS, (mask & 64) ? hsum(0.25f, a0, 0.75f, a1) : zero);
-      if (mask & 8) put(dst + (PW + 1) * CS, (mask & 128) ? hsum(0.25f, b0, 0.75f, b1) : zero);
+      if (mask & 4) put(dst + RP, (mask & 64) ? hsum(0.25f, a0, 0.75f, a1) : zero);
+      if (mask & 8) put(dst + RP + CS, (mask & 128) ? hsum(0.25f, b0, 0.75f, b1) : zero);
     }
   };
 
@@ -491,8 +499,8 @@ void conv_mfma_kernel(ConvParams p) {
   const int n_units = K * K * KG;
   const int cin_pad = (Cin + CHUNK - 1) / CHUNK * CHUNK;    // the weights are zero-padded to whole chunks
   const int cin_rows = BF16 ? cin_pad >> 3 : cin_pad >> 2;  // 16-byte weight rows per tap: 8 bf16 or 4 floats
-  const int a_lane_off = (mly * s * PW + mlx * s) * CS + half * 4;
-  const int a_blk1 = 4 * s * PW * CS;
+  const int a_lane_off = mly * s * RP + mlx * s * CS + half * 4;
+  const int a_blk1 = 4 * s * RP;
   // units of this wave: u_j = wave + j * NW, j < n_mine
   const int n_mine = (n_units - wave + NW - 1) / NW;
   const int last = n_mine - 1;
@@ -525,7 +533,7 @@ void conv_mfma_kernel(ConvParams p) {
     const int u = wave + j * NW;
     const int tap = u / KG, kg = u % KG;
     const int ky = (tap * k_magic) >> 16, kx = tap - ky * K;
-    return a_lane_off + __builtin_amdgcn_readfirstlane((ky * PW + kx) * CS + kg * 8);  // 8 words = 8 floats or 16 bf16
+    return a_lane_off + __builtin_amdgcn_readfirstlane(ky * RP + kx * CS + kg * 8);  // 8 words = 8 floats or 16 bf16
   };
   // A fragment of unit j (clamped like the B fragments): the patch values of this lane's site
   // for both 32-row blocks, and their low parts in split mode; unused members cost nothing
@@ -831,7 +839,8 @@ inline int chunk_for(const ConvParams& p) {
 template <int CHUNK, int NW, int OPM, int MB>
 void launch_variant(const ConvParams& p, hipStream_t s) {
   const int PH = (4 * MB - 1) * p.stride + p.k, PW = 7 * p.stride + p.k;
-  size_t lds = (size_t)PH * PW * (OPM == kOpBf16 ? CHUNK / 2 + 4 : CHUNK + 4) * sizeof(float);
+  // (rows of the patch are padded to a pitch of 32 modulo 64 words: at most 64 more per row)
+  size_t lds = (size_t)PH * (PW * (OPM == kOpBf16 ? CHUNK / 2 + 4 : CHUNK + 4) + 64) * sizeof(float);
   const size_t part = (size_t)4 * MB * 16 * 64 * sizeof(float);  // partial sums reuse the patch
   // The operand that is read by every XCD in full should be the smaller one: the weights of the
   // high-resolution layers, the input of the low-resolution ones (k * k * c_out weights per input
