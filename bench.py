@@ -531,45 +531,53 @@ def sparsified_leg(args, np, torch, ev, wl, dev):
     little at every step, event pixels change by order one).  Lossless incremental inference sees
     every site active; with a layer ahead of every convolution, including the first, the small
     changes stay in the residuals until they add up to half a rounding step.  Threshold sweep of the
-    paper's sensitivity study, t_p in {0.01, 0.05, 0.1, 0.3}: step time against the lossless
-    incremental step and against dense recompute, touched-site fraction, tile-level operation
-    fraction, deviation of the output from the lossless run."""
+    paper's sensitivity study, t_p in {0.01, 0.05, 0.1, 0.3}, at two drift rates: step time against
+    the lossless incremental step and against dense recompute, touched-site and touched-tile
+    fractions, tile-level operation fraction, deviation of the output from the lossless run.
+
+    Measured in the steady state: the residuals start at zero at the reset and the drift is
+    coherent, so nothing but events is emitted until the first residuals reach half a rounding
+    step (50 steps and more at t_p = 0.3); timing that quiet stretch would flatter the layer.  The
+    warm-up is 300 steps, longer than the first crossing at every threshold of the sweep."""
     H, W = 256, 352
-    warm, steps = 5, max(20, args.steps // 2)
-    frames = list(wl.stream_voxel_drifting_background(1003, H, W, warm + steps, args.density))
-    dfr = [torch.from_numpy(f).to(dev) for f in frames]
-    plain = wl.net_unet_depth(1003, h=H, w=W)
-    inc, dense, frac = mode_pair(torch, ev, plain, dfr, warm, steps)
-    res = {"stream": "0.05 x event voxel grid + smooth background of amplitude 0.5 drifting by at most 1e-3 per step at every pixel",
-           "lossless_incremental_ms": inc, "dense_recompute_ms": dense, "lossless_tile_flop_fraction": frac, "unit": "ms/step",
-           "rows": []}
-    # lossless output for the deviation column
-    g = ev.EvConvNet(plain, device="cuda:0")
-    g.reset(dfr[0])
-    for i in range(1, warm + steps + 1):
-        g.step_frame(dfr[i])
-    torch.cuda.synchronize()
-    y_ref = g.outputs()[0]["y"].clone()
-    g.destroy()
-    for tp in (0.01, 0.05, 0.1, 0.3):
-        net = wl.net_unet_depth(1003, h=H, w=W, sparsify=True, sparsify_input=True)
-        net.sparsify_tp = tp
-        g = ev.EvConvNet(net, device="cuda:0")
+    warm, steps = 300, max(20, args.steps // 2)
+    base = list(wl.stream_voxel(1003, H, W, warm + steps, args.density))
+    res = {"unit": "ms/step", "warmup_steps": warm, "timed_steps": steps, "streams": []}
+    for drift in (1e-3, 2e-4):
+        dfr = [torch.from_numpy(f).to(dev)
+               for f in wl.drifting_background(base, amplitude=0.5, drift=drift, event_scale=0.05)]
+        plain = wl.net_unet_depth(1003, h=H, w=W)
+        inc, dense, frac = mode_pair(torch, ev, plain, dfr, warm, steps)
+        leg = {"stream": f"0.05 x event voxel grid + smooth background of amplitude 0.5 drifting by at most {drift:g} per step at every pixel",
+               "lossless_incremental_ms": inc, "dense_recompute_ms": dense, "lossless_tile_flop_fraction": frac, "rows": []}
+        # lossless output for the deviation column
+        g = ev.EvConvNet(plain, device="cuda:0")
         g.reset(dfr[0])
-        for i in range(1, warm + 1):
+        for i in range(1, warm + steps + 1):
             g.step_frame(dfr[i])
-        per, wall = timed_steps(torch, g, dfr, warm + 1, steps)
-        conv = [i for i, nd in enumerate(net.nodes) if nd.op == wl.OP_CONV2D]
-        touched = sum(g.stats(i).n_touched for i in conv)
-        sites = sum(g.stats(i).n_sites for i in conv)
-        ex = sum(g.stats(i).flops_executed for i in conv)
-        de = sum(g.stats(i).flops_dense for i in conv)
-        dev_out = float((g.outputs()[0]["y"] - y_ref).abs().max())
+        torch.cuda.synchronize()
+        y_ref = g.outputs()[0]["y"].clone()
         g.destroy()
-        med = statistics.median(per)
-        res["rows"].append(dict(t_p=tp, ms_per_step=med, speedup_vs_lossless=inc / med, speedup_vs_dense=dense / med,
-                                touched_site_fraction=touched / sites, tile_flop_fraction=ex / de,
-                                max_abs_output_deviation_from_lossless=dev_out))
+        for tp in (0.01, 0.05, 0.1, 0.3):
+            net = wl.net_unet_depth(1003, h=H, w=W, sparsify=True, sparsify_input=True)
+            net.sparsify_tp = tp
+            g = ev.EvConvNet(net, device="cuda:0")
+            g.reset(dfr[0])
+            for i in range(1, warm + 1):
+                g.step_frame(dfr[i])
+            per, wall = timed_steps(torch, g, dfr, warm + 1, steps)
+            conv = [i for i, nd in enumerate(net.nodes) if nd.op == wl.OP_CONV2D]
+            st = [g.stats(i) for i in conv]
+            dev_out = float((g.outputs()[0]["y"] - y_ref).abs().max())
+            g.destroy()
+            med = statistics.median(per)
+            leg["rows"].append(dict(t_p=tp, ms_per_step=med, speedup_vs_lossless=inc / med, speedup_vs_dense=dense / med,
+                                    touched_site_fraction=sum(x.n_touched for x in st) / sum(x.n_sites for x in st),
+                                    touched_tile_fraction=sum(x.n_touched_tiles for x in st) / sum(x.n_tiles for x in st),
+                                    tile_flop_fraction=sum(x.flops_executed for x in st) / sum(x.flops_dense for x in st),
+                                    max_abs_output_deviation_from_lossless=dev_out))
+        res["streams"].append(leg)
+        del dfr
     return res
 
 

@@ -144,7 +144,7 @@ void conv_mfma_kernel(ConvParams p) {
   __shared__ uint64_t s_occ[16];
   __shared__ unsigned s_rows[24];  // bit px of s_rows[py]: patch site (py, px) is active
   __shared__ unsigned s_lrows[UPS ? LPMAX : 1];  // UPS: the same for the low-resolution source region
-  __shared__ unsigned s_nz[2 * (2 + kMaxFusedAdds)];  // nonzero-site bits: conv, each fused ADD, fused sparsification
+  __shared__ uint64_t s_nz[(2 + kMaxFusedAdds) * NW];  // nonzero-site bits per wave: conv, each fused ADD, fused sparsification
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // Consecutive workgroups (x fastest) go to the chip's 8 XCDs in turn, each with an L2 of its own.
@@ -206,15 +206,94 @@ void conv_mfma_kernel(ConvParams p) {
       skip_raw[f] = at_stream(p.fused[f].occ_skip, so)[tile];
     }
   }
+  uint64_t occ_w = 0;
   if (tid < 16) {
     const int ry = tid >> 2, rx = tid & 3;
     const int ty = rty0 + ry, tx = rtx0 + rx;
-    uint64_t w = 0;
     if (ry < rny && rx < rnx && ty >= 0 && ty < s_ty && tx >= 0 && tx < s_tx)
-      w = p.dense ? ~0ull : at_stream(p.occ_in, so)[ty * s_tx + tx];
-    s_occ[tid] = w;
+      occ_w = p.dense ? ~0ull : at_stream(p.occ_in, so)[ty * s_tx + tx];
   }
-  if (tid < 2 * (2 + kMaxFusedAdds)) s_nz[tid] = 0;
+
+  // While the occupancy words are on their way: everything about the gather that depends on the
+  // tile's position only.
+  // ---- patch gather: per thread a fixed list of (LDS offset, byte offset into the input)
+  // The gathered region is the patch itself, or (UPS) its low-resolution source region, which
+  // goes to a second fp32 buffer behind the patch buffer.
+  constexpr unsigned kOob = 0x80000000u;
+  // Row pitch of the patch in LDS (4-byte words).  The LDS serves a 16-byte read per lane in
+  // groups of 16 lanes over 64 banks; the 16 lanes of an A-fragment read are two rows of eight
+  // sites.  The site stride (an odd number of 16-byte slots) spreads a row's eight sites over
+  // eight distinct slots; a row pitch of 128 bytes modulo 256 puts the next row's sites on the
+  // other eight.  (Stride-2 layers read every other site and row: no pitch frees them of
+  // conflicts, they keep the dense pitch.)
+  const int RP = s == 1 ? ((PW * CS + 31) / 64) * 64 + 32 : PW * CS;
+  float* const s_low = s_mem + PH * RP;  // UPS only
+  const int total_v = GH * GW * NV;
+  const int gw_magic = (65536 + GW - 1) / GW;  // site / GW == (site * gw_magic) >> 16 for site < 441
+  int lds_off[MAXG];     // (until the occupancy is known: patch row and column in bits 16-23 and 24-31)
+  unsigned g_off[MAXG];
+#pragma unroll
+  for (int j = 0; j < MAXG; ++j) {
+    const int e = tid + j * NT;
+    lds_off[j] = -1;
+    g_off[j] = kOob;
+    if (e < total_v) {
+      const int site = e / NV, v = e - site * NV;
+      const int py = (site * gw_magic) >> 16, px = site - py * GW;
+      lds_off[j] = (ups ? site * CSL + v * 4 : py * RP + px * CS + v * (BF16 ? 2 : 4)) | (py << 16) | (px << 24);
+      g_off[j] = (unsigned)((((gy0 + py) * SW + gx0 + px) * Cin + v * 4) * 4);
+    }
+  }
+  // UPS: every patch element from its four sources in the low-resolution buffer, with the
+  // weights and the summation order of the stand-alone up-sampling operator
+  //
+  // Work item = one 2 x 2 block of up-sampled sites (rows 2i+1, 2i+2, columns 2j+1, 2j+2) x four
+  // channels: its four values come from the same four stored sites (rows i, i+1, columns j, j+1,
+  // clamped to the image), so the four reads and the two horizontal sums per stored row are
+  // shared; a site without an active source comes out as zero because inactive sources are
+  // stored as zeros.  The items of a thread are the same for every chunk: offsets and masks are
+  // worked out once (this arithmetic would otherwise take vector-ALU time from the fp32 matrix
+  // instructions, which run on the same pipeline).
+  constexpr int MAXB = UPS ? (8 * (MB == 2 ? 8 : 6) * NV + NT - 1) / NT : 1;  // <= 8 x 8 blocks (K <= 7)
+  // per item two packed words: ib_src = source offset (12 bits) | row step (10) | column step (6);
+  // ib_dst = patch offset + 4096 (16 bits) | write mask (4) | inside-the-image mask (4)
+  int ib_src[MAXB], ib_dst[MAXB];
+#pragma unroll
+  for (int b = 0; b < MAXB; ++b) ib_src[b] = ib_dst[b] = 0;
+  if (ups) {
+    const int by0 = (iy0 - 1) >> 1, bx0 = (ix0 - 1) >> 1;
+    const int nby = ((iy0 + PH - 2) >> 1) - by0 + 1, nbx = ((ix0 + PW - 2) >> 1) - bx0 + 1;
+    const int nbx_magic = (65536 + nbx - 1) / nbx;  // blk / nbx == (blk * nbx_magic) >> 16 for blk < 64
+#pragma unroll
+    for (int b = 0; b < MAXB; ++b) {
+      const int e = tid + b * NT;
+      const int blk = e / NV, v = e - blk * NV;
+      ib_src[b] = ib_dst[b] = 0;
+      if (blk < nby * nbx) {
+        const int bi = (blk * nbx_magic) >> 16, bj = blk - bi * nbx;
+        const int i = by0 + bi, j = bx0 + bj;
+        const int cy0 = min(max(i, 0), SH - 1), cy1 = min(max(i + 1, 0), SH - 1);
+        const int cx0 = min(max(j, 0), SW - 1), cx1 = min(max(j + 1, 0), SW - 1);
+        ib_src[b] = (((cy0 - gy0) * GW + (cx0 - gx0)) * CSL + v * 4) | (((cy1 - cy0) * GW * CSL) << 12) |
+                    (((cx1 - cx0) * CSL) << 22);
+        const int py = 2 * i + 1 - iy0, px = 2 * j + 1 - ix0;  // patch coordinates of the block, -1 at least
+        const int dst = py * RP + px * CS + v * (BF16 ? 2 : 4) + 4096;
+        int mask = 0;
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+          for (int c = 0; c < 2; ++c) {
+            const bool in_patch = py + r >= 0 && py + r < PH && px + c >= 0 && px + c < PW;
+            const bool in_image = (unsigned)(iy0 + py + r) < (unsigned)H && (unsigned)(ix0 + px + c) < (unsigned)W;
+            if (in_patch) mask |= 1 << (r * 2 + c);
+            if (in_patch && in_image) mask |= 16 << (r * 2 + c);
+          }
+        ib_dst[b] = dst | (mask << 16);
+      }
+    }
+  }
+
+  if (tid < 16) s_occ[tid] = occ_w;
   __syncthreads();
   if (tid < GH) {  // one bit row per row of the region; out-of-image sites are 0
     const int gy = gy0 + tid;
@@ -318,9 +397,6 @@ void conv_mfma_kernel(ConvParams p) {
   auto ep_load = [&](const __amdgpu_buffer_rsrc_t& r, bool on, int it) {
     return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, on ? ep_voff : kSkipAccess, it * ep_step, 0));
   };
-  auto ep_store = [&](const __amdgpu_buffer_rsrc_t& r, int it, float v) {
-    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, ep_voff, it * ep_step, 0);
-  };
   const uint64_t touched_mine = mine(touched_word), site_mine = mine(site_word);
   const __amdgpu_buffer_rsrc_t z_rsrc = out_rsrc(at_stream(p.z, so));
 
@@ -329,34 +405,14 @@ void conv_mfma_kernel(ConvParams p) {
 #pragma unroll
   for (int it = 0; it < EP_ITERS; ++it) z_old[it] = ep_load(z_rsrc, !p.dense && has(touched_mine, it), it);
 
-  // ---- patch gather: per thread a fixed list of (LDS offset, byte offset into the input)
-  // The gathered region is the patch itself, or (UPS) its low-resolution source region, which
-  // goes to a second fp32 buffer behind the patch buffer.
-  constexpr unsigned kOob = 0x80000000u;
-  // Row pitch of the patch in LDS (4-byte words).  The LDS serves a 16-byte read per lane in
-  // groups of 16 lanes over 64 banks; the 16 lanes of an A-fragment read are two rows of eight
-  // sites.  The site stride (an odd number of 16-byte slots) spreads a row's eight sites over
-  // eight distinct slots; a row pitch of 128 bytes modulo 256 puts the next row's sites on the
-  // other eight.  (Stride-2 layers read every other site and row: no pitch frees them of
-  // conflicts, they keep the dense pitch.)
-  const int RP = s == 1 ? ((PW * CS + 31) / 64) * 64 + 32 : PW * CS;
-  float* const s_low = s_mem + PH * RP;  // UPS only
-  const int total_v = GH * GW * NV;
-  const int gw_magic = (65536 + GW - 1) / GW;  // site / GW == (site * gw_magic) >> 16 for site < 441
-  int lds_off[MAXG];
-  unsigned g_off[MAXG];
+  // the gather's offsets, now conditioned on the occupancy (out of range where the site is inactive)
 #pragma unroll
   for (int j = 0; j < MAXG; ++j) {
-    const int e = tid + j * NT;
-    lds_off[j] = -1;
-    g_off[j] = kOob;
-    if (e < total_v) {
-      const int site = e / NV, v = e - site * NV;
-      const int py = (site * gw_magic) >> 16, px = site - py * GW;
-      lds_off[j] = ups ? site * CSL + v * 4 : py * RP + px * CS + v * (BF16 ? 2 : 4);
-      const unsigned row = ups ? s_lrows[py] : s_rows[py];
-      if ((row >> px) & 1u) g_off[j] = (unsigned)((((gy0 + py) * SW + gx0 + px) * Cin + v * 4) * 4);
-    }
+    if (lds_off[j] < 0) continue;
+    const int py = (lds_off[j] >> 16) & 0xff, px = lds_off[j] >> 24;
+    lds_off[j] &= 0xffff;
+    const unsigned row = ups ? s_lrows[py] : s_rows[py];
+    if (!((row >> px) & 1u)) g_off[j] = kOob;
   }
   // c_in need not be a multiple of four: the 16-byte load of a site's last channel group then
   // runs into the next site (buffer loads of dwords need dword alignment only); the foreign
@@ -417,54 +473,6 @@ void conv_mfma_kernel(ConvParams p) {
         else put(lds_off[j], pre[j]);
       }
   };
-  // UPS: every patch element from its four sources in the low-resolution buffer, with the
-  // weights and the summation order of the stand-alone up-sampling operator
-  //
-  // Work item = one 2 x 2 block of up-sampled sites (rows 2i+1, 2i+2, columns 2j+1, 2j+2) x four
-  // channels: its four values come from the same four stored sites (rows i, i+1, columns j, j+1,
-  // clamped to the image), so the four reads and the two horizontal sums per stored row are
-  // shared; a site without an active source comes out as zero because inactive sources are
-  // stored as zeros.  The items of a thread are the same for every chunk: offsets and masks are
-  // worked out once (this arithmetic would otherwise take vector-ALU time from the fp32 matrix
-  // instructions, which run on the same pipeline).
-  constexpr int MAXB = UPS ? (8 * (MB == 2 ? 8 : 6) * NV + NT - 1) / NT : 1;  // <= 8 x 8 blocks (K <= 7)
-  // per item two packed words: ib_src = source offset (12 bits) | row step (10) | column step (6);
-  // ib_dst = patch offset + 4096 (16 bits) | write mask (4) | inside-the-image mask (4)
-  int ib_src[MAXB], ib_dst[MAXB];
-#pragma unroll
-  for (int b = 0; b < MAXB; ++b) ib_src[b] = ib_dst[b] = 0;
-  if (ups) {
-    const int by0 = (iy0 - 1) >> 1, bx0 = (ix0 - 1) >> 1;
-    const int nby = ((iy0 + PH - 2) >> 1) - by0 + 1, nbx = ((ix0 + PW - 2) >> 1) - bx0 + 1;
-    const int nbx_magic = (65536 + nbx - 1) / nbx;  // blk / nbx == (blk * nbx_magic) >> 16 for blk < 64
-#pragma unroll
-    for (int b = 0; b < MAXB; ++b) {
-      const int e = tid + b * NT;
-      const int blk = e / NV, v = e - blk * NV;
-      ib_src[b] = ib_dst[b] = 0;
-      if (blk < nby * nbx) {
-        const int bi = (blk * nbx_magic) >> 16, bj = blk - bi * nbx;
-        const int i = by0 + bi, j = bx0 + bj;
-        const int cy0 = min(max(i, 0), SH - 1), cy1 = min(max(i + 1, 0), SH - 1);
-        const int cx0 = min(max(j, 0), SW - 1), cx1 = min(max(j + 1, 0), SW - 1);
-        ib_src[b] = (((cy0 - gy0) * GW + (cx0 - gx0)) * CSL + v * 4) | (((cy1 - cy0) * GW * CSL) << 12) |
-                    (((cx1 - cx0) * CSL) << 22);
-        const int py = 2 * i + 1 - iy0, px = 2 * j + 1 - ix0;  // patch coordinates of the block, -1 at least
-        const int dst = py * RP + px * CS + v * (BF16 ? 2 : 4) + 4096;
-        int mask = 0;
-#pragma unroll
-        for (int r = 0; r < 2; ++r)
-#pragma unroll
-          for (int c = 0; c < 2; ++c) {
-            const bool in_patch = py + r >= 0 && py + r < PH && px + c >= 0 && px + c < PW;
-            const bool in_image = (unsigned)(iy0 + py + r) < (unsigned)H && (unsigned)(ix0 + px + c) < (unsigned)W;
-            if (in_patch) mask |= 1 << (r * 2 + c);
-            if (in_patch && in_image) mask |= 16 << (r * 2 + c);
-          }
-        ib_dst[b] = dst | (mask << 16);
-      }
-    }
-  }
   auto interpolate = [&]() {
 #pragma unroll
     for (int b = 0; b < MAXB; ++b) {
@@ -700,24 +708,37 @@ void conv_mfma_kernel(ConvParams p) {
   // the thread (es < 16), the rest is a constant per `it`
   const int off_mine = ((es >> 3) * 4 + (es & 3)) * 64 + ((es >> 2) & 1) * 32 + co;
   const float bias = (p.dense && p.bias && co_ok) ? p.bias[co0 + co] : 0.0f;
+  // Straight-line code: a site this thread does not own gets an out-of-range offset (its stores
+  // are dropped) instead of a branch around it, and the partial sums of all passes are read from
+  // LDS up front, so that the passes are not a chain of LDS round trips.
+  float v_sum[EP_ITERS];
 #pragma unroll
   for (int it = 0; it < EP_ITERS; ++it) {
-    if (!has(site_mine, it)) continue;
-    float o = 0.0f;
-    if (has(touched_mine, it)) {
-      constexpr int kRow = EP_SITES / 8;  // tile rows per `it`
-      const int off = off_mine + (((it * kRow) >> 2) * 16 + ((it * kRow) & 3) * 4) * 64;
-      const float v = (s_mem[off] + s_mem[off + SLOT]) + (s_mem[off + 2 * SLOT] + s_mem[off + 3 * SLOT]);
+    constexpr int kRow = EP_SITES / 8;  // tile rows per `it`
+    const int off = off_mine + (((it * kRow) >> 2) * 16 + ((it * kRow) & 3) * 4) * 64;
+    v_sum[it] = (s_mem[off] + s_mem[off + SLOT]) + (s_mem[off + 2 * SLOT] + s_mem[off + 3 * SLOT]);
+  }
+  auto ep_store_at = [&](const __amdgpu_buffer_rsrc_t& r, unsigned voff, int it, float v) {
+    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, voff, it * ep_step, 0);
+  };
+#pragma unroll
+  for (int it = 0; it < EP_ITERS; ++it) {
+    const bool on_site = has(site_mine, it), on_conv = has(touched_mine, it);
+    const unsigned at_site = on_site ? ep_voff : kSkipAccess, at_conv = on_conv ? ep_voff : kSkipAccess;
+    float o;
+    {
+      const float v = v_sum[it];
       if (p.dense) {
         const float z = v + bias;
-        ep_store(z_rsrc, it, z);
+        ep_store_at(z_rsrc, at_conv, it, z);
         o = act_m(p.act, z);
       } else {
         const float z_new = z_old[it] + v;
-        ep_store(z_rsrc, it, z_new);
+        ep_store_at(z_rsrc, at_conv, it, z_new);
         o = (p.act == kActNone) ? v : act_m(p.act, z_new) - act_m(p.act, z_old[it]);
       }
-      ep_store(o_rsrc, it, o);
+      o = on_conv ? o : 0.0f;
+      ep_store_at(o_rsrc, at_conv, it, o);
       if (o != 0.0f) nz_mine |= 1ull << (it * EP_SITES);
     }
     // fused ADD nodes (Eq.11 followed by Eq.12-14): a = the value just produced, b = skip input
@@ -729,18 +750,19 @@ void conv_mfma_kernel(ConvParams p) {
       if (fa.keeps_z) {
         const __amdgpu_buffer_rsrc_t fz_rsrc = out_rsrc(at_stream(fa.z, so));
         if (p.dense) {
-          ep_store(fz_rsrc, it, lin);
+          ep_store_at(fz_rsrc, at_site, it, lin);
           o = act_m(fa.act, lin);
         } else {
           const float z2_old = f_zold[f][it];
           const float z2_new = z2_old + lin;
-          ep_store(fz_rsrc, it, z2_new);
+          ep_store_at(fz_rsrc, at_site, it, z2_new);
           o = (fa.act == kActNone) ? lin : act_m(fa.act, z2_new) - act_m(fa.act, z2_old);
         }
       } else {
         o = lin;
       }
-      ep_store(out_rsrc(at_stream(fa.out, so)), it, o);
+      o = on_site ? o : 0.0f;
+      ep_store_at(out_rsrc(at_stream(fa.out, so)), at_site, it, o);
       if (o != 0.0f) nz_fused_mine[f] |= 1ull << (it * EP_SITES);
     }
     // fused sparsification layer on the last stage's increment (Eq.3-8): x_corr = delta + x_inc,
@@ -750,32 +772,40 @@ void conv_mfma_kernel(ConvParams p) {
 #pragma clang fp contract(off)  // the residual is x_corr minus the rounded product, not a fused form
       float y = o;
       if (p.dense) {
-        ep_store(out_rsrc(at_stream(p.sp.delta, so)), it, 0.0f);
+        ep_store_at(out_rsrc(at_stream(p.sp.delta, so)), at_site, it, 0.0f);
       } else if (sp_k > 0.0f) {
         const float x_corr = sp_delta[it] + o;
-        y = 0.0f;
-        if (o != 0.0f) {
-          y = sp_k * floorf(0.5f + x_corr / sp_k);
-          ep_store(out_rsrc(at_stream(p.sp.delta, so)), it, x_corr - y);
-        }
+        y = (o != 0.0f) ? sp_k * floorf(0.5f + x_corr / sp_k) : 0.0f;
+        ep_store_at(out_rsrc(at_stream(p.sp.delta, so)), (o != 0.0f) ? at_site : kSkipAccess, it, x_corr - y);
       }
-      ep_store(out_rsrc(at_stream(p.sp.out, so)), it, y);
+      ep_store_at(out_rsrc(at_stream(p.sp.out, so)), at_site, it, y);
       if (y != 0.0f) nz_sp_mine |= 1ull << (it * EP_SITES);
     }
   }
-  const uint64_t nz_sites = nz_mine << (r0 * 8 + es);
-  uint64_t nz_fused[kMaxFusedAdds];
+  // A site is nonzero where one of its 32 channels is: lanes 0-31 of a wave hold site es = 2 * wave
+  // of every pass, lanes 32-63 site 2 * wave + 1, so one ballot per pass gives the wave's two site
+  // bits; the waves' words meet in LDS (no atomics: 64 lanes hitting one LDS word are served one
+  // after the other and hold up the LDS for every workgroup of the CU).
+  auto lds_or = [&](int slot, uint64_t mine_bits) {
+    uint64_t w = 0;
 #pragma unroll
-  for (int f = 0; f < kMaxFusedAdds; ++f) nz_fused[f] = nz_fused_mine[f] << (r0 * 8 + es);
-  auto lds_or = [&](int slot, uint64_t bits) {
-    if ((unsigned)bits) atomicOr(&s_nz[2 * slot], (unsigned)bits);
-    if ((unsigned)(bits >> 32)) atomicOr(&s_nz[2 * slot + 1], (unsigned)(bits >> 32));
+    for (int it = 0; it < EP_ITERS; ++it) {
+      const uint64_t b = __ballot(((mine_bits >> (it * EP_SITES)) & 1ull) != 0);
+      w |= (uint64_t)(((unsigned)b != 0 ? 1u : 0u) | ((unsigned)(b >> 32) != 0 ? 2u : 0u)) << (it * EP_SITES);
+    }
+    if (lane == 0) s_nz[slot * NW + wave] = w << (r0 * 8 + 2 * wave);
   };
-  lds_or(0, nz_sites);
+  auto nz_word = [&](int slot) {
+    uint64_t w = 0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) w |= s_nz[slot * NW + i];
+    return w;
+  };
+  lds_or(0, nz_mine);
 #pragma unroll
   for (int f = 0; f < kMaxFusedAdds; ++f)
-    if (f < p.n_fused) lds_or(1 + f, nz_fused[f]);
-  if (p.sp.delta) lds_or(1 + kMaxFusedAdds, nz_sp_mine << (r0 * 8 + es));
+    if (f < p.n_fused) lds_or(1 + f, nz_fused_mine[f]);
+  if (p.sp.delta) lds_or(1 + kMaxFusedAdds, nz_sp_mine);
   __syncthreads();
   if (tid < 4 * (4 + 2 * kMaxFusedAdds)) {
     // Site bits of this workgroup into the words of up to 4 + 2 * (fused ADDs) sets: S and T of the
@@ -787,7 +817,7 @@ void conv_mfma_kernel(ConvParams p) {
     // per lane; otherwise the first of the four lanes writes the tile's own word.
     const int set = tid >> 2, part = tid & 3;
     // S of the producer as seen by this workgroup's rows and channels
-    uint64_t s_prev = p.dense ? touched_word : ((uint64_t)s_nz[0] | ((uint64_t)s_nz[1] << 32));
+    uint64_t s_prev = p.dense ? touched_word : nz_word(0);
     uint64_t bits = set == 0 ? s_prev : (set == 1 && wg_co == 0) ? touched_word : 0ull;
     uint64_t* words = set == 0 ? p.occ_out : set == 1 ? p.occ_touched : nullptr;
 #pragma unroll
@@ -795,14 +825,14 @@ void conv_mfma_kernel(ConvParams p) {
       if (f >= p.n_fused) break;
       const FusedAdd& fa = p.fused[f];
       const uint64_t t_f = s_prev | skip_word[f];  // Eq.11b
-      const uint64_t nz_f = (uint64_t)s_nz[2 + 2 * f] | ((uint64_t)s_nz[3 + 2 * f] << 32);
+      const uint64_t nz_f = nz_word(1 + f);
       const uint64_t s_f = (fa.structural || p.dense) ? t_f : nz_f;
       if (set == 2 + 2 * f) { bits = t_f; words = fa.occ_touched; }
       if (set == 3 + 2 * f) { bits = s_f; words = fa.occ_out; }
       s_prev = s_f;
     }
     if (p.sp.delta) {
-      const uint64_t nz_sp = (uint64_t)s_nz[2 + 2 * kMaxFusedAdds] | ((uint64_t)s_nz[3 + 2 * kMaxFusedAdds] << 32);
+      const uint64_t nz_sp = nz_word(1 + kMaxFusedAdds);
       if (set == 2 + 2 * kMaxFusedAdds) { bits = s_prev; words = p.sp.occ_touched; }
       if (set == 3 + 2 * kMaxFusedAdds) { bits = p.dense ? s_prev : nz_sp; words = p.sp.occ_out; }
     }

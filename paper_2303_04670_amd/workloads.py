@@ -547,19 +547,27 @@ def stream_voxel(seed, h, w, steps, density=0.02, warm=None, **kw) -> Iterator[n
         yield vs.frame()
 
 
-def stream_voxel_drifting_background(seed, h, w, steps, density=0.02, amplitude=0.5, drift=1e-3, event_scale=0.05, **kw):
-    """Workload-3 event frames, scaled by `event_scale`, on top of a smooth background of
-    amplitude `amplitude` (the same in every time bin) whose phase moves a little per step: every
-    pixel changes by at most `drift` at every step and event pixels change by `event_scale`,
-    both small against the values themselves.  Increments that are dense but tiny almost
-    everywhere: the situation the sparsification layer is made for ("Forward pass with increment
-    tensors": the difference of consecutive inputs is sparse *and* many of its elements have
-    small absolute values)."""
-    yy, xx = np.mgrid[0:h, 0:w]
-    phase = 2.0 * math.pi * (3.0 * xx / w + 2.0 * yy / h)
-    for t, f in enumerate(stream_voxel(seed, h, w, steps, density, **kw)):
+def drifting_background(frames, amplitude=0.5, drift=1e-3, event_scale=0.05):
+    """The given frames, scaled by `event_scale`, on top of a smooth background of amplitude
+    `amplitude` (the same in every channel) whose phase moves a little per step: every pixel
+    changes by at most `drift` at every step and event pixels change by `event_scale`, both small
+    against the values themselves.  Increments that are dense but tiny almost everywhere: the
+    situation the sparsification layer is made for ("Forward pass with increment tensors": the
+    difference of consecutive inputs is sparse *and* many of its elements have small absolute
+    values)."""
+    phase = None
+    for t, f in enumerate(frames):
+        if phase is None:
+            h, w = f.shape[-2:]
+            yy, xx = np.mgrid[0:h, 0:w]
+            phase = 2.0 * math.pi * (3.0 * xx / w + 2.0 * yy / h)
         bg = amplitude * np.sin(phase + t * drift / amplitude)
         yield (event_scale * f + bg[None].astype(np.float32)).astype(np.float32)
+
+
+def stream_voxel_drifting_background(seed, h, w, steps, density=0.02, amplitude=0.5, drift=1e-3, event_scale=0.05, **kw):
+    """Workload-3 event frames under drifting_background()."""
+    return drifting_background(stream_voxel(seed, h, w, steps, density, **kw), amplitude, drift, event_scale)
 
 
 def density_sweep_1_5(t, period=50):
