@@ -55,6 +55,7 @@
 // mode instantiates it, so that the three modes compile in parallel.)
 #pragma once
 #include <cstdlib>
+#include <type_traits>
 
 #include "evconv_kernels.h"
 
@@ -721,6 +722,75 @@ void conv_mfma_kernel(ConvParams p) {
   auto ep_store_at = [&](const __amdgpu_buffer_rsrc_t& r, unsigned voff, int it, float v) {
     __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, voff, it * ep_step, 0);
   };
+  // Activations other than none / ReLU need branches (exp, tanh); nets made of the two simple
+  // ones, the usual case, take a loop without any: every decision that is the same for the whole
+  // workgroup becomes a select, so that the passes can be interleaved freely (a branch per
+  // decision and pass made each pass a chain of kernel-argument loads and waits).
+  bool simple_acts = p.act == kActNone || p.act == kActRelu;
+#pragma unroll
+  for (int f = 0; f < kMaxFusedAdds; ++f)
+    if (f < p.n_fused && p.fused[f].keeps_z && !(p.fused[f].act == kActNone || p.fused[f].act == kActRelu))
+      simple_acts = false;
+  auto epilogue_simple = [&](auto sp_tag) {
+    constexpr bool HAS_SP = decltype(sp_tag)::value;
+    const bool dense = p.dense != 0;
+    const bool relu0 = p.act == kActRelu;
+    bool f_on[kMaxFusedAdds], f_kz[kMaxFusedAdds], f_relu[kMaxFusedAdds];
+    __amdgpu_buffer_rsrc_t f_out_r[kMaxFusedAdds], f_z_r[kMaxFusedAdds];
+#pragma unroll
+    for (int f = 0; f < kMaxFusedAdds; ++f) {
+      f_on[f] = f < p.n_fused;
+      f_kz[f] = f_on[f] && p.fused[f].keeps_z;
+      f_relu[f] = f_kz[f] && p.fused[f].act == kActRelu;
+      // (a stage that does not exist stores nowhere: its offsets are out of range)
+      f_out_r[f] = out_rsrc(at_stream(f_on[f] ? p.fused[f].out : p.out, so));
+      f_z_r[f] = out_rsrc(at_stream(f_kz[f] ? p.fused[f].z : p.out, so));
+    }
+    const __amdgpu_buffer_rsrc_t sp_delta_r = out_rsrc(at_stream(HAS_SP ? p.sp.delta : p.out, so));
+    const __amdgpu_buffer_rsrc_t sp_out_r = out_rsrc(at_stream(HAS_SP ? p.sp.out : p.out, so));
+#pragma unroll
+    for (int it = 0; it < EP_ITERS; ++it) {
+      const bool on_site = has(site_mine, it), on_conv = has(touched_mine, it);
+      const unsigned at_site = on_site ? ep_voff : kSkipAccess, at_conv = on_conv ? ep_voff : kSkipAccess;
+      // regular pass: z = v + bias, o = act(z); incremental: z += v, o = act(z_new) - act(z_old)
+      // (z_old reads as 0 in a regular pass, so ReLU's difference form serves both)
+      const float v = v_sum[it];
+      const float z_new = (dense ? bias : z_old[it]) + v;
+      ep_store_at(z_rsrc, at_conv, it, z_new);
+      float o = relu0 ? fmaxf(z_new, 0.0f) - fmaxf(z_old[it], 0.0f) : (dense ? z_new : v);
+      o = on_conv ? o : 0.0f;
+      ep_store_at(o_rsrc, at_conv, it, o);
+      if (o != 0.0f) nz_mine |= 1ull << (it * EP_SITES);
+      // fused ADD nodes (Eq.11 followed by Eq.12-14): a = the value just produced, b = skip input
+#pragma unroll
+      for (int f = 0; f < kMaxFusedAdds; ++f) {
+        const float lin = o + f_skip[f][it];
+        const float z2_new = dense ? lin : f_zold[f][it] + lin;
+        ep_store_at(f_z_r[f], f_kz[f] ? at_site : kSkipAccess, it, z2_new);
+        float o2 = f_relu[f] ? fmaxf(z2_new, 0.0f) - fmaxf(f_zold[f][it], 0.0f) : lin;
+        o2 = on_site ? o2 : 0.0f;
+        ep_store_at(f_out_r[f], f_on[f] ? at_site : kSkipAccess, it, o2);
+        if (f_on[f] && o2 != 0.0f) nz_fused_mine[f] |= 1ull << (it * EP_SITES);
+        o = f_on[f] ? o2 : o;
+      }
+      // fused sparsification layer on the last stage's increment (Eq.3-8): x_corr = delta + x_inc,
+      // y_inc = k floor(0.5 + x_corr / k), delta = x_corr - y_inc where x_inc is nonzero; elsewhere
+      // y_inc = 0 and the residual stays.  A regular pass: identity, residual cleared.
+      if (HAS_SP) {
+#pragma clang fp contract(off)  // the residual is x_corr minus the rounded product, not a fused form
+        const bool sp_on = sp_k > 0.0f, moved = o != 0.0f;   // (sp_k is 0 in a regular pass)
+        const float x_corr = sp_delta[it] + o;
+        const float q = sp_k * floorf(0.5f + x_corr / sp_k);
+        const float y = sp_on ? (moved ? q : 0.0f) : o;
+        ep_store_at(sp_delta_r, (dense || (sp_on && moved)) ? at_site : kSkipAccess, it, dense ? 0.0f : x_corr - y);
+        ep_store_at(sp_out_r, at_site, it, y);
+        if (y != 0.0f) nz_sp_mine |= 1ull << (it * EP_SITES);
+      }
+    }
+  };
+  if (simple_acts) {
+    if (p.sp.delta) epilogue_simple(std::true_type{}); else epilogue_simple(std::false_type{});
+  } else {
 #pragma unroll
   for (int it = 0; it < EP_ITERS; ++it) {
     const bool on_site = has(site_mine, it), on_conv = has(touched_mine, it);
@@ -781,6 +851,7 @@ void conv_mfma_kernel(ConvParams p) {
       ep_store_at(out_rsrc(at_stream(p.sp.out, so)), at_site, it, y);
       if (y != 0.0f) nz_sp_mine |= 1ull << (it * EP_SITES);
     }
+  }
   }
   // A site is nonzero where one of its 32 channels is: lanes 0-31 of a wave hold site es = 2 * wave
   // of every pass, lanes 32-63 site 2 * wave + 1, so one ballot per pass gives the wave's two site
