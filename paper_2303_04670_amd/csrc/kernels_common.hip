@@ -212,6 +212,10 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
   const int cv = min(kEwVecPerBlock, cv_all - v0);
   const int total = n_sites * cv;
 
+  // sites at which this thread produced a nonzero element; the waves' ORs meet in LDS afterwards
+  // (one LDS atomic per element would be served lane by lane where the lanes share a site, and
+  // the LDS serves nobody else on the CU meanwhile)
+  uint64_t nz_sites = 0;
   for (int e = tid; e < total; e += 256) {
     const int r = e / cv, v = v0 + (e - r * cv);
     const int site = s_sites[r];
@@ -266,6 +270,23 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
     } else {  // kEwPoolMax: p.a is the accumulated pool input, p.z the cached window maximum
 #pragma unroll
       for (int i = 0; i < VEC; ++i) lin.v[i] = -INFINITY;
+      if (p.k == 3) {
+        // the usual window: nine loads requested together (an out-of-image tap reads the window's
+        // centre instead and is left out of the maximum), then the maxima in the same order
+        VecT<VEC> t[9];
+        bool ok[9];
+        const int cy = min(max(oy * p.stride - p.pad + 1, 0), p.ga.h - 1), cx = min(max(ox * p.stride - p.pad + 1, 0), p.ga.w - 1);
+#pragma unroll
+        for (int j = 0; j < 9; ++j) {
+          const int iy = oy * p.stride - p.pad + j / 3, ix = ox * p.stride - p.pad + j % 3;
+          ok[j] = (unsigned)iy < (unsigned)p.ga.h && (unsigned)ix < (unsigned)p.ga.w;
+          t[j] = ldv<VEC>(&p.a[((size_t)(ok[j] ? iy : cy) * p.ga.w + (ok[j] ? ix : cx)) * C + c]);
+        }
+#pragma unroll
+        for (int j = 0; j < 9; ++j)
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) lin.v[i] = ok[j] ? fmaxf(lin.v[i], t[j].v[i]) : lin.v[i];
+      } else
       for (int ky = 0; ky < p.k; ++ky) {
         const int iy = oy * p.stride - p.pad + ky;
         if ((unsigned)iy >= (unsigned)p.ga.h) continue;
@@ -360,9 +381,21 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
     stv<VEC>(&p.out[q * C + c], o);
 #pragma unroll
     for (int i = 0; i < VEC; ++i) nz |= (o.v[i] != 0.0f);
-    if (nz && !p.structural) atomicOr(&s_flags[site >> 5], 1u << (site & 31));
+    if (nz) nz_sites |= 1ull << site;
   }
   if (p.op == kEwPoolAcc) return;
+  if (!p.structural) {
+    unsigned lo = (unsigned)nz_sites, hi = (unsigned)(nz_sites >> 32);
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+      lo |= __shfl_xor(lo, m);
+      hi |= __shfl_xor(hi, m);
+    }
+    if ((tid & 63) == 0) {
+      if (lo) atomicOr(&s_flags[0], lo);
+      if (hi) atomicOr(&s_flags[1], hi);
+    }
+  }
   __syncthreads();
   if (tid == 0) {
     const uint64_t flags = (uint64_t)s_flags[0] | ((uint64_t)s_flags[1] << 32);
@@ -385,33 +418,45 @@ void launch_elementwise(const EwParams& p, hipStream_t s) {
 }
 
 // =============================================================================== global avg pool
-// One thread per channel; active sites are visited in tile order (ascending tiles, ascending
-// bits), a fixed order, so the fp32 sum is reproducible.
+// Workgroup = 64 channels x 4 row slices: slice s sums the active sites of tile rows s and s + 4
+// of every tile, a row's eight loads in flight together; the four partial sums are added in a
+// fixed order.  Sites are visited in a fixed order throughout, so the fp32 sum is reproducible.
 __global__ __launch_bounds__(256) void gap_kernel(GapParams p) {
   {
     const size_t so = (size_t)blockIdx.z * p.st.stride;
     p.a = at_stream(p.a, so); p.occ_a = at_stream(p.occ_a, so); p.z = at_stream(p.z, so);
     p.out = at_stream(p.out, so); p.occ_out = at_stream(p.occ_out, so); p.occ_touched = at_stream(p.occ_touched, so);
   }
-  const int c = blockIdx.x * 256 + threadIdx.x;
+  __shared__ float s_part[4][64];
+  const int cl = threadIdx.x & 63, slice = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl;
   const int C = p.ga.c;
+  const bool c_ok = c < C;
   bool any = false;
   float sum = 0.0f;
   for (int t = 0; t < p.ga.tiles(); ++t) {
     const int tile_y = t / p.ga.tx, tile_x = t - tile_y * p.ga.tx;
-    uint64_t w = p.dense ? inbounds_word(p.ga.h, p.ga.w, tile_y, tile_x) : p.occ_a[t];
+    const uint64_t w = p.dense ? inbounds_word(p.ga.h, p.ga.w, tile_y, tile_x) : p.occ_a[t];
     any |= (w != 0);
-    while (w) {
-      const int bit = __ffsll((unsigned long long)w) - 1;
-      w &= w - 1;
-      const int y = tile_y * 8 + (bit >> 3), x = tile_x * 8 + (bit & 7);
-      if (c < C) sum += p.a[((size_t)y * p.ga.w + x) * C + c];
+    for (int r = slice; r < 8; r += 4) {
+      const unsigned bits = (unsigned)(w >> (8 * r)) & 0xffu;
+      if (bits == 0) continue;
+      const int y = tile_y * 8 + r;
+      float v[8];
+#pragma unroll
+      for (int x = 0; x < 8; ++x)
+        v[x] = (((bits >> x) & 1u) && c_ok) ? p.a[((size_t)y * p.ga.w + tile_x * 8 + x) * C + c] : 0.0f;
+#pragma unroll
+      for (int x = 0; x < 8; ++x) sum += v[x];
     }
   }
-  if (!any) return;
+  if (!any) return;  // (the same for every thread)
+  s_part[slice][cl] = sum;
+  __syncthreads();
+  if (slice != 0) return;
   bool nz = false;
-  if (c < C) {
-    const float lin = sum / (float)(p.ga.h * p.ga.w);
+  if (c_ok) {
+    const float lin = ((s_part[0][cl] + s_part[1][cl]) + (s_part[2][cl] + s_part[3][cl])) / (float)(p.ga.h * p.ga.w);
     float o;
     if (p.dense) {
       p.z[c] = lin;
@@ -426,7 +471,7 @@ __global__ __launch_bounds__(256) void gap_kernel(GapParams p) {
   }
   const bool structural = (p.act == kActNone) || p.dense;
   const uint64_t b = __ballot(nz);
-  if ((threadIdx.x & 63) == 0) {
+  if (cl == 0) {
     if (structural) { if (c == 0) p.occ_out[0] = 1ull; }
     else if (b) atomicOr((unsigned long long*)p.occ_out, 1ull);
     if (c == 0) p.occ_touched[0] = 1ull;
@@ -434,7 +479,7 @@ __global__ __launch_bounds__(256) void gap_kernel(GapParams p) {
 }
 
 void launch_gap(const GapParams& p, hipStream_t s) {
-  hipLaunchKernelGGL(gap_kernel, dim3((p.ga.c + 255) / 256, 1, p.st.n), dim3(256), 0, s, p);
+  hipLaunchKernelGGL(gap_kernel, dim3((p.ga.c + 63) / 64, 1, p.st.n), dim3(256), 0, s, p);
 }
 
 // =============================================================================== Eq.2
