@@ -415,6 +415,46 @@ def test_delay_of_an_add_that_follows_its_conv_is_not_fused():
         gpu.destroy()
 
 
+def test_pooling_windows_other_than_3x3_and_a_global_mean_over_many_ragged_tiles():
+    """Max-pool with 2 x 2 / stride 2 / no padding and with 5 x 5 / stride 1 / padding 2 windows
+    (the kernel has a path of its own for 3 x 3), and a global mean over a 27 x 43 map (4 x 6 tiles,
+    ragged last row and column, most of them inactive at any step) feeding a linear layer; sparse
+    and dense steps, a refresh in between."""
+    _say("max-pool 2x2 / 5x5 and a global mean over ragged tiles")
+    b = wl._NetBuilder("pools", 6, 27, 43, 57)
+    c0 = b.conv(-1, 32, 3, act=wl.ACT_RELU)
+    p5 = b.simple(wl.OP_MAXPOOL, c0, k=5, stride=1, pad=2)
+    g = b.simple(wl.OP_GAP, p5)
+    b.linear(g, 10, out=1)
+    p2 = b.simple(wl.OP_MAXPOOL, c0, k=2, stride=2, pad=0)
+    b.conv(p2, 16, 3, act=wl.ACT_RELU, out=1)
+    net = b.finish()
+    rng = np.random.default_rng(57)
+    x = rng.standard_normal((6, 27, 43)).astype(np.float32)
+    frames = [x]
+    for t in range(8):
+        dens = 1.0 if t == 4 else 0.02
+        m = rng.random((1, 27, 43)) < dens
+        x = (x + rng.standard_normal(x.shape).astype(np.float32) * m).astype(np.float32)
+        frames.append(x)
+    gpu, ora, rep = ev.EvConvNet(net), Oracle(net), cmp.Report()
+    assert gpu.kernel_name(g) == "global_avgpool" and gpu.kernel_name(p2) == "maxpool"
+    gpu.reset(_dev(frames[0]))
+    ora.reset(frames[0])
+    for t, f in enumerate(frames[1:]):
+        if t == 6:
+            gpu.reset(_dev(f))
+            ora.reset(f)
+        else:
+            gpu.step_frame(_dev(f))
+            ora.step_frame(f)
+        cmp.compare_outputs(gpu, ora, rep)
+        for i in range(len(net.nodes)):
+            cmp.compare_node(gpu, ora, i, rep)
+    assert rep.flips <= 4
+    gpu.destroy()
+
+
 def test_auto_mode_times_both_modes_and_keeps_the_state():
     """AUTO runs windows of incremental and of dense-recompute steps, then holds the faster mode;
     whatever it picks, the state follows the same frames (Eq.2), so outputs and accumulated
