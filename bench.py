@@ -252,6 +252,8 @@ def main():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense-recompute and AUTO legs")
     ap.add_argument("--no-second-variant", action="store_true", help="skip the other contraction modes")
     ap.add_argument("--no-sparsified", action="store_true", help="skip the sparsification-layer leg")
+    ap.add_argument("--chip-probes", action="store_true",
+                    help="run the library's timing probes of the chip (evconv_debug_chip_probes), print them as a table and exit")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay leg")
     ap.add_argument("--no-recurrent", action="store_true", help="skip the ConvLSTM leg")
     ap.add_argument("--no-extras", action="store_true", help="skip the single-object, short density-sweep and drift legs")
@@ -282,6 +284,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
+    if args.chip_probes:
+        print(chip_probe_table(ev.chip_probes()))
+        return
     if args.sweep:
         out = {"metric": "density sweep: incremental vs dense recompute (flow encoder-decoder 4x256x256 and its "
                          "delayed-integration variant)",
@@ -400,6 +405,25 @@ def cpu_baseline(args, np, net, frames):
                                      "incremental_tile_level": 2 * tile / k / 1e6,
                                      "reduction_site_level": 1 - site / k / dense, "reduction_tile_level": 1 - tile / k / dense,
                                      "rule": "2 x multiply-accumulates of the conv layers; a tap on a zero-padding or inactive site costs nothing at site level"}}
+
+
+def chip_probe_table(v):
+    """The values of evconv_debug_chip_probes as a markdown table (layout: include/evconv.h)."""
+    rows = [("one wave per SIMD, per iteration one fp32 MFMA (64 cycles of the pipeline) + k independent vector instructions",
+             "cycles / iteration for k = 0, 4, 16, 32", f"{v[0]:.0f}, {v[1]:.0f}, {v[2]:.0f}, {v[3]:.0f}"),
+            ("two waves per SIMD: vector loop | fp32 MFMA chain", "us alone", f"{v[4]:.0f} | {v[5]:.0f}"),
+            ("", "us side by side", f"{v[6]:.0f} | {v[7]:.0f}"),
+            ("two waves per SIMD: vector loop | bf16 MFMA chain", "us alone", f"{v[4]:.0f} | {v[8]:.0f}"),
+            ("", "us side by side", f"{v[9]:.0f} | {v[10]:.0f}"),
+            ("chain of 100 dependent global loads, one wave per SIMD", "us alone / beside three fp32 MFMA chain waves per SIMD",
+             f"{v[11]:.0f} / {v[12]:.0f}"),
+            ("chain of 1000 dependent LDS reads", "us alone / beside them", f"{v[13]:.0f} / {v[14]:.0f}"),
+            ("LDS atomic OR, 64 lanes", "ns per instruction: one word / 64 words", f"{v[15]:.0f} / {v[16]:.0f}"),
+            ("20000 16-byte LDS reads of one wave per SIMD", "us alone / beside one-word atomics / beside 64-word atomics",
+             f"{v[17]:.0f} / {v[18]:.0f} / {v[19]:.0f}")]
+    out = ["| Probe | Quantity | Measured |", "|---|---|---|"]
+    out += [f"| {a} | {b} | {c} |" for a, b, c in rows]
+    return "\n".join(out)
 
 
 def graph_leg(args, np, torch, ev, wl, dframes):

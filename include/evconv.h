@@ -335,6 +335,28 @@ evconv_status evconv_profile_end(evconv_net* net);
 evconv_status evconv_get_node_time(const evconv_net* net, int32_t node, double* ms_total /* HOST */,
                                    int64_t* launches /* HOST */);
 
+/* Measurement aid, not part of the method: small timing probes of the properties of the chip that
+ * the matrix-core kernels are designed around ("Convolution on Sparse Inputs" leaves the kernel
+ * design to the hardware at hand).  Runs on hip_stream in `scratch` (DEVICE, at least
+ * EVCONV_CHIP_PROBE_SCRATCH_BYTES, overwritten) and writes EVCONV_CHIP_PROBE_VALUES floats to out
+ * (HOST):
+ *   [0..3]   cycles per iteration (at 2.4 GHz) of one wave per SIMD issuing one fp32 MFMA plus 0, 4,
+ *            16, 32 independent vector instructions
+ *   [4..7]   us, one wave each on every SIMD: vector loop alone, fp32 MFMA chain alone, the loop
+ *            beside the chain, the chain beside the loop
+ *   [8..10]  us: bf16 MFMA chain alone, the vector loop beside it, the chain beside the loop
+ *   [11..14] us: a chain of dependent global loads alone / beside three fp32 MFMA chain waves per
+ *            SIMD; a chain of dependent LDS reads alone / beside them
+ *   [15..16] ns per LDS atomic instruction whose 64 lanes hit one word / 64 different words
+ *   [17..19] us: a loop of 16-byte LDS reads alone / beside another wave's one-word atomics /
+ *            beside its 64-word atomics
+ * Synchronous (a few milliseconds).  EVCONV_ERR_INVALID_ARG for a null pointer or too little
+ * room, EVCONV_ERR_HIP if a launch or copy fails. */
+#define EVCONV_CHIP_PROBE_VALUES 20
+#define EVCONV_CHIP_PROBE_SCRATCH_BYTES (1u << 20)
+evconv_status evconv_debug_chip_probes(void* scratch /* DEVICE */, size_t scratch_bytes, void* hip_stream,
+                                       float* out /* HOST */, int32_t n_out);
+
 /* Name of the kernel family that executes a node ("conv_valu_f32", "conv_mfma_f32", ...).  A node
  * that another node's kernel computes reports where it went: "fused_into_conv_epilogue" (an ADD
  * applied by the producing convolution; its buffers are still written), "fused_into_conv_gather",

@@ -1254,6 +1254,15 @@ const char* evconv_node_kernel(const evconv_net* net, int32_t node) {
   return kKernelNames[net->L.nodes[node].kernel];
 }
 
+evconv_status evconv_debug_chip_probes(void* scratch, size_t scratch_bytes, void* hip_stream, float* out, int32_t n_out) {
+  if (!scratch || !out || scratch_bytes < EVCONV_CHIP_PROBE_SCRATCH_BYTES || n_out < EVCONV_CHIP_PROBE_VALUES)
+    return EVCONV_ERR_INVALID_ARG;
+  static_assert(EVCONV_CHIP_PROBE_VALUES == evk::kChipProbeValues && EVCONV_CHIP_PROBE_SCRATCH_BYTES == evk::kChipProbeScratch,
+                "header and probes disagree");
+  return evk::chip_probes(scratch, scratch_bytes, (hipStream_t)hip_stream, out, n_out) == evk::kChipProbeValues ? EVCONV_OK
+                                                                                                                 : EVCONV_ERR_HIP;
+}
+
 const char* evconv_last_error(const evconv_net* net) { return net ? net->err.c_str() : g_create_error.c_str(); }
 
 }  // extern "C"

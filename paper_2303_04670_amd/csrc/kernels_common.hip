@@ -213,8 +213,7 @@ __global__ __launch_bounds__(256) void elementwise_kernel(EwParams p) {
   const int total = n_sites * cv;
 
   // sites at which this thread produced a nonzero element; the waves' ORs meet in LDS afterwards
-  // (one LDS atomic per element would be served lane by lane where the lanes share a site, and
-  // the LDS serves nobody else on the CU meanwhile)
+  // (one LDS atomic per element would be served lane by lane where the lanes share a site)
   uint64_t nz_sites = 0;
   for (int e = tid; e < total; e += 256) {
     const int r = e / cv, v = v0 + (e - r * cv);

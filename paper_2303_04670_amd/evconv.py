@@ -29,7 +29,7 @@ EXPORTS = ["evconv_query_workspace", "evconv_create", "evconv_num_outputs", "evc
            "evconv_step_frame", "evconv_destroy", "evconv_set_mode", "evconv_node_shape", "evconv_get_state",
            "evconv_get_stats", "evconv_node_kernel", "evconv_last_error", "evconv_profile_begin",
            "evconv_profile_end", "evconv_get_node_time", "evconv_set_refresh_period", "evconv_get_state_stream",
-           "evconv_stream_stride", "evconv_current_mode", "evconv_create_static"]
+           "evconv_stream_stride", "evconv_current_mode", "evconv_create_static", "evconv_debug_chip_probes"]
 STATIC_WORKSPACE_BYTES = 32 << 20
 
 
@@ -95,8 +95,26 @@ def lib() -> ctypes.CDLL:
         L.evconv_profile_end.argtypes = [vp]
         L.evconv_get_node_time.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double),
                                            ctypes.POINTER(ctypes.c_int64)]
+        L.evconv_debug_chip_probes.argtypes = [vp, ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_float), i32]
         _lib = L
     return _lib
+
+
+CHIP_PROBE_VALUES = 20
+CHIP_PROBE_SCRATCH_BYTES = 1 << 20
+
+
+def chip_probes(device="cuda:0"):
+    """evconv_debug_chip_probes on a scratch tensor of its own: the list of probe values."""
+    import torch
+    scratch = torch.empty(CHIP_PROBE_SCRATCH_BYTES, dtype=torch.uint8, device=device)
+    out = (ctypes.c_float * CHIP_PROBE_VALUES)()
+    with torch.cuda.device(scratch.device):
+        st = lib().evconv_debug_chip_probes(scratch.data_ptr(), scratch.numel(), torch.cuda.current_stream().cuda_stream,
+                                            out, CHIP_PROBE_VALUES)
+    if st != 0:
+        raise EvConvError(st, "evconv_debug_chip_probes failed")
+    return list(out)
 
 
 class EvConvError(RuntimeError):
