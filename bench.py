@@ -252,6 +252,9 @@ def main():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense-recompute and AUTO legs")
     ap.add_argument("--no-second-variant", action="store_true", help="skip the other contraction modes")
     ap.add_argument("--no-sparsified", action="store_true", help="skip the sparsification-layer leg")
+    ap.add_argument("--phase-times", action="store_true",
+                    help="per-phase times of the matrix-core conv workgroups on the headline workload, from the library "
+                         "built with `python -m paper_2303_04670_amd.build --phase-stamps`; prints tables and exits")
     ap.add_argument("--chip-probes", action="store_true",
                     help="run the library's timing probes of the chip (evconv_debug_chip_probes), print them as a table and exit")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay leg")
@@ -286,6 +289,11 @@ def main():
     dev = torch.device("cuda:0")
     if args.chip_probes:
         print(chip_probe_table(ev.chip_probes()))
+        return
+    if args.phase_times:
+        from paper_2303_04670_amd import build as evbuild
+        ev.use_library(evbuild.PHASE_LIB_PATH)
+        print(phase_time_tables(args, np, torch, ev, wl, dev))
         return
     if args.sweep:
         out = {"metric": "density sweep: incremental vs dense recompute (flow encoder-decoder 4x256x256 and its "
@@ -405,6 +413,54 @@ def cpu_baseline(args, np, net, frames):
                                      "incremental_tile_level": 2 * tile / k / 1e6,
                                      "reduction_site_level": 1 - site / k / dense, "reduction_tile_level": 1 - tile / k / dense,
                                      "rule": "2 x multiply-accumulates of the conv layers; a tap on a zero-padding or inactive site costs nothing at site level"}}
+
+
+def phase_time_tables(args, np, torch, ev, wl, dev):
+    """One step of the headline workload per weight type on the library with phase stamps: per
+    conv layer the mean time a workgroup spends in each phase (field names: PhaseField in
+    csrc/conv_mfma_impl.h), the workgroup's life and the span of the launch."""
+    frames = [torch.from_numpy(f).to(dev) for f in wl.stream_voxel(1003, 256, 352, 10, args.density)]
+    order = [0, 1, 2, 3, 4, 5, 6, 10, 7, 14, 8, 11, 12, 13, 9]   # the stamps in program order
+    names = ["occupancy words", "bit rows", "touched set, old z, gather predicates", "first requests",
+             "first patch in LDS", "chunk loop", "fused operands requested", "partial sums reduced", "operands arrived",
+             "epilogue passes", "flag ballots", "flags to LDS", "barrier", "tile words"]
+    out = []
+    for variant, mode in (("f32", 0), ("f32_split", 2), ("bf16", 1)):
+        net = make_net(wl, variant)
+        g = ev.EvConvNet(net, device="cuda:0")
+        g.reset(frames[0])
+        for i in range(1, 9):
+            g.step_frame(frames[i])
+        torch.cuda.synchronize()
+        ev.phase_stamps(mode, reset=True, max_records=0)
+        g.step_frame(frames[9])
+        torch.cuda.synchronize()
+        rec, n = ev.phase_stamps(mode)
+        g.destroy()
+        rec = rec.astype(np.int64)
+        out.append(f"## {variant}: {n} workgroups of the matrix-core conv in one step\n")
+        out.append("Mean microseconds per workgroup that ran the chunk loop.\n")
+        out.append("| layer (out rows, c_in, k, c_out) | workgroups (active) | launch span | life | " + " | ".join(names) +
+                   " | inside contraction loops | between them |")
+        out.append("|" + "---|" * (len(names) + 6))
+        layers = []
+        for key in rec[:, 27]:
+            if key not in layers:
+                layers.append(key)
+        for key in layers:
+            r = rec[rec[:, 27] == key]
+            full = r[r[:, 6] > 0]
+            if len(full) == 0:
+                continue
+            d = np.diff(full[:, order], axis=1) / 100.0
+            life = (full[:, 9] - full[:, 0]) / 100.0
+            span = (r[:, [0, 9]].max() - r[:, 0].min()) / 100.0
+            desc = f"{key & 0xffff}, {(key >> 16) & 0xffff}, {(key >> 32) & 0xff}, {key >> 40}"
+            out.append(f"| {desc} | {len(r)} ({len(full)}) | {span:.1f} | {life.mean():.1f} | " +
+                       " | ".join(f"{d[:, i].mean():.2f}" for i in range(len(names))) +
+                       f" | {full[:, 20].mean() / 100:.2f} | {full[:, 21].mean() / 100:.2f} |")
+        out.append("")
+    return "\n".join(out)
 
 
 def chip_probe_table(v):

@@ -335,6 +335,19 @@ evconv_status evconv_profile_end(evconv_net* net);
 evconv_status evconv_get_node_time(const evconv_net* net, int32_t node, double* ms_total /* HOST */,
                                    int64_t* launches /* HOST */);
 
+/* Measurement aid, not part of the method: where the time of a matrix-core convolution workgroup
+ * goes ("Convolution on Sparse Inputs": mask test, conditioned fetch, contraction, write-back are
+ * the phases of the paper's kernel as well).  In a library built with -DEVCONV_PHASE_STAMPS
+ * (python -m paper_2303_04670_amd.build --phase-stamps; the regular build has none of this and
+ * returns EVCONV_ERR_UNSUPPORTED) one lane of every such workgroup writes a 100 MHz wall-clock stamp
+ * at each phase boundary.  Copies the records of the kernels of one operand mode (evconv_dtype)
+ * written since the last reset to out (HOST, max_records records of 32 x uint64; field meanings:
+ * PhaseField in csrc/conv_mfma_impl.h), stores the number written in n_records (it may exceed
+ * max_records and the 32768 the library keeps) and, if reset != 0, starts a new collection.
+ * Synchronises the device. */
+evconv_status evconv_debug_phase_stamps(int32_t operand_mode, uint64_t* out /* HOST */, int32_t max_records,
+                                        int32_t reset, int32_t* n_records /* HOST */);
+
 /* Measurement aid, not part of the method: small timing probes of the properties of the chip that
  * the matrix-core kernels are designed around ("Convolution on Sparse Inputs" leaves the kernel
  * design to the hardware at hand).  Runs on hip_stream in `scratch` (DEVICE, at least

@@ -54,6 +54,7 @@
 // (This header holds the kernel template and its launchers; one translation unit per operand
 // mode instantiates it, so that the three modes compile in parallel.)
 #pragma once
+#include <algorithm>
 #include <cstdlib>
 #include <type_traits>
 
@@ -64,6 +65,39 @@ namespace evk {
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+// Phase stamps.  In a build with -DEVCONV_PHASE_STAMPS (never the product build) one lane per
+// workgroup writes the 100 MHz wall clock at the boundaries of the kernel's phases into a device
+// array of the translation unit; evconv_debug_phase_stamps copies the records out.  Without the
+// define EVK_PHASE expands to nothing.  A record is 32 x u64:
+enum PhaseField {
+  kPhStart = 0,            // first instruction of the workgroup
+  kPhOccInLds = 1,         // occupancy words arrived and in LDS (the gather addressing is worked out meanwhile)
+  kPhBitRows = 2,          // bit rows of the patch built
+  kPhAddressed = 3,        // touched words, old z requested, gather offsets conditioned
+  kPhFirstIssued = 4,      // first patch chunk and first weight fragments requested
+  kPhFirstPatchInLds = 5,  // first chunk arrived, in LDS (and interpolated), next chunk requested
+  kPhChunksDone = 6,       // end of the chunk loop
+  kPhFusedRequested = 10,  // operands of the fused stages requested
+  kPhReduced = 7,          // partial sums of the waves in LDS
+  kPhArrived = 14,         // everything requested so far has arrived
+  kPhEpilogueDone = 8,     // all passes of the epilogue issued
+  kPhFlagsBallot = 11,     // (start of the nonzero-flag collection)
+  kPhFlagsInLds = 12,      // the waves' flag words written
+  kPhFlagsBarrier = 13,    // ... and visible to the workgroup
+  kPhEnd = 9,              // tile words OR-ed into memory
+  kPhContractionTicks = 20,  // ticks inside the contraction loops, all chunks
+  kPhChunkChangeTicks = 21,  // ticks in barriers, LDS stores and interpolation between them
+  kPhGrid = 24, kPhBlock = 25, kPhHwId = 26,  // workgroups of the launch, this one's index, HW_ID | XCC_ID << 32
+  kPhLayer = 27,           // output height | c_in << 16 | k << 32 | c_out << 40
+};
+#ifdef EVCONV_PHASE_STAMPS
+constexpr unsigned kPhaseRecords = 1u << 15;
+static __device__ unsigned long long g_phase[kPhaseRecords][32];
+static __device__ unsigned g_phase_n;
+#define EVK_PHASE(i) do { if (tid == 0 && ph_slot < kPhaseRecords) g_phase[ph_slot][i] = wall_clock64(); } while (0)
+#else
+#define EVK_PHASE(i) do {} while (0)
+#endif
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 // operand modes of the contraction
@@ -148,6 +182,22 @@ void conv_mfma_kernel(ConvParams p) {
   __shared__ uint64_t s_nz[(2 + kMaxFusedAdds) * NW];  // nonzero-site bits per wave: conv, each fused ADD, fused sparsification
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+#ifdef EVCONV_PHASE_STAMPS
+  unsigned ph_slot = 0xffffffffu;
+  if (tid == 0) {
+    ph_slot = atomicAdd(&g_phase_n, 1u);
+    if (ph_slot < kPhaseRecords) {
+      unsigned long long* r = g_phase[ph_slot];
+      for (int i = 1; i < 24; ++i) r[i] = 0;
+      r[kPhGrid] = (unsigned long long)gridDim.x * gridDim.y;
+      r[kPhBlock] = blockIdx.x + (unsigned long long)blockIdx.y * gridDim.x;
+      r[kPhHwId] = __builtin_amdgcn_s_getreg(4 | (31 << 11)) | ((unsigned long long)__builtin_amdgcn_s_getreg(20 | (31 << 11)) << 32);
+      r[kPhLayer] = (unsigned long long)p.go.h | ((unsigned long long)p.gi.c << 16) | ((unsigned long long)p.k << 32) |
+                    ((unsigned long long)p.go.c << 40);
+    }
+  }
+#endif
+  EVK_PHASE(kPhStart);
   // Consecutive workgroups (x fastest) go to the chip's 8 XCDs in turn, each with an L2 of its own.
   // x over tiles: an XCD sees every eighth tile and all of the weights; x over the blocks of
   // output channels (wg_swap): an XCD sees all tiles and one in eight (four, two) of the weight
@@ -296,6 +346,7 @@ void conv_mfma_kernel(ConvParams p) {
 
   if (tid < 16) s_occ[tid] = occ_w;
   __syncthreads();
+  EVK_PHASE(kPhOccInLds);
   if (tid < GH) {  // one bit row per row of the region; out-of-image sites are 0
     const int gy = gy0 + tid;
     unsigned bits = 0;
@@ -339,6 +390,7 @@ void conv_mfma_kernel(ConvParams p) {
     __syncthreads();
   }
 
+  EVK_PHASE(kPhBitRows);
   // touched word of this workgroup's rows (identical in all waves): OR of the K bit rows under a
   // site, then any of the K columns
   uint64_t touched_word;
@@ -598,6 +650,7 @@ void conv_mfma_kernel(ConvParams p) {
   bq0.h = bq0.l = make_float4(0.f, 0.f, 0.f, 0.f);
   bq1 = bq0;
   bq2 = bq0;
+  EVK_PHASE(kPhAddressed);
   if (conv_on) {
     fetch(0);
     if (n_mine > 0) {
@@ -605,7 +658,14 @@ void conv_mfma_kernel(ConvParams p) {
       bq1 = b_load(0, 1);
     }
   }
+  EVK_PHASE(kPhFirstIssued);
+#ifdef EVCONV_PHASE_STAMPS
+  unsigned long long ph_contract = 0, ph_change = 0;
+#endif
   for (int c0 = 0; conv_on && c0 < Cin; c0 += CHUNK) {
+#ifdef EVCONV_PHASE_STAMPS
+    const unsigned long long ph_a = wall_clock64();
+#endif
     __syncthreads();  // all waves are done reading the previous chunk
     stash(c0);
     __syncthreads();
@@ -615,6 +675,11 @@ void conv_mfma_kernel(ConvParams p) {
     }
     const bool more = c0 + CHUNK < Cin;
     if (more) fetch(c0 + CHUNK);  // next chunk's patch, in flight during the contraction
+#ifdef EVCONV_PHASE_STAMPS
+    const unsigned long long ph_b = wall_clock64();
+    ph_change += ph_b - ph_a;
+    if (c0 == 0) EVK_PHASE(kPhFirstPatchInLds);
+#endif
     if (n_mine <= 0) continue;    // more waves than units (1 x 1 taps): only help with the gather
     // fp32 and bf16 modes: the A fragments run one unit ahead of their use (three names, two alive
     // at a time), so that an LDS read is in flight during the matrix instructions of the unit
@@ -640,7 +705,17 @@ void conv_mfma_kernel(ConvParams p) {
       bq0 = b_load(c0 + CHUNK, 0);
       bq1 = b_load(c0 + CHUNK, 1);
     }
+#ifdef EVCONV_PHASE_STAMPS
+    ph_contract += wall_clock64() - ph_b;
+#endif
   }
+  EVK_PHASE(kPhChunksDone);
+#ifdef EVCONV_PHASE_STAMPS
+  if (tid == 0 && ph_slot < kPhaseRecords) {
+    g_phase[ph_slot][kPhContractionTicks] = ph_contract;
+    g_phase[ph_slot][kPhChunkChangeTicks] = ph_change;
+  }
+#endif
 
   // operands of the fused ADD stages, requested together now so that one memory latency covers
   // all of them and the reduction below hides part of it
@@ -673,6 +748,7 @@ void conv_mfma_kernel(ConvParams p) {
     for (int it = 0; it < EP_ITERS; ++it) sp_delta[it] = ep_load(d_rsrc, sp_k > 0.0f && has(site_mine, it), it);
   }
 
+  EVK_PHASE(kPhFusedRequested);
   // ---- reduce the NW partial sums through LDS: slots [4][block*16 + reg][lane]
   auto spill = [&](float* part) {
 #pragma unroll
@@ -696,6 +772,11 @@ void conv_mfma_kernel(ConvParams p) {
   }
   if (wave < 4) spill(s_mem + wave * SLOT);
   __syncthreads();
+  EVK_PHASE(kPhReduced);
+#ifdef EVCONV_PHASE_STAMPS
+  __builtin_amdgcn_s_waitcnt(0);  // (separates waiting for the operands from the epilogue's own time)
+  EVK_PHASE(kPhArrived);
+#endif
 
   // epilogue: thread -> (output channel = tid % 32, EP_ITERS sites); accumulator element
   // (block b, register i, lane l) is local site b*32 + 8*(i/4) + 4*(l/32) + i%4, channel l%32
@@ -853,6 +934,7 @@ void conv_mfma_kernel(ConvParams p) {
     }
   }
   }
+  EVK_PHASE(kPhEpilogueDone);
   // A site is nonzero where one of its 32 channels is: lanes 0-31 of a wave hold site es = 2 * wave
   // of every pass, lanes 32-63 site 2 * wave + 1, so one ballot per pass gives the wave's two site
   // bits; the waves' words meet in LDS (no atomics: 64 lanes hitting one LDS word are served one
@@ -872,12 +954,15 @@ void conv_mfma_kernel(ConvParams p) {
     for (int i = 0; i < NW; ++i) w |= s_nz[slot * NW + i];
     return w;
   };
+  EVK_PHASE(kPhFlagsBallot);
   lds_or(0, nz_mine);
 #pragma unroll
   for (int f = 0; f < kMaxFusedAdds; ++f)
     if (f < p.n_fused) lds_or(1 + f, nz_fused_mine[f]);
   if (p.sp.delta) lds_or(1 + kMaxFusedAdds, nz_sp_mine);
+  EVK_PHASE(kPhFlagsInLds);
   __syncthreads();
+  EVK_PHASE(kPhFlagsBarrier);
   if (tid < 4 * (4 + 2 * kMaxFusedAdds)) {
     // Site bits of this workgroup into the words of up to 4 + 2 * (fused ADDs) sets: S and T of the
     // conv, then T and S of each fused ADD (Eq.11b), then T and S of a fused sparsification layer
@@ -925,6 +1010,7 @@ void conv_mfma_kernel(ConvParams p) {
       }
     }
   }
+  EVK_PHASE(kPhEnd);
 }
 
 inline int chunk_for(const ConvParams& p) {
@@ -996,6 +1082,27 @@ void launch_any(const ConvParams& p, hipStream_t s) {
     case 32: launch_shape<32, OPM>(p, s); break;
     default: launch_shape<16, OPM>(p, s); break;
   }
+}
+
+// Copies the phase records of this translation unit's kernels to `host` (32 x u64 each, at most
+// max_records); returns how many workgroups have written one since the last reset, or -1 in a
+// build without phase stamps.
+inline int phase_stamps_read(unsigned long long* host, int max_records, bool reset) {
+#ifdef EVCONV_PHASE_STAMPS
+  unsigned n = 0;
+  if (hipDeviceSynchronize() != hipSuccess) return -2;
+  if (hipMemcpyFromSymbol(&n, HIP_SYMBOL(g_phase_n), sizeof(n)) != hipSuccess) return -2;
+  const unsigned take = std::min(std::min(n, kPhaseRecords), (unsigned)std::max(max_records, 0));
+  if (host && take && hipMemcpyFromSymbol(host, HIP_SYMBOL(g_phase), sizeof(unsigned long long) * 32 * take) != hipSuccess) return -2;
+  if (reset) {
+    const unsigned zero = 0;
+    if (hipMemcpyToSymbol(HIP_SYMBOL(g_phase_n), &zero, sizeof(zero)) != hipSuccess) return -2;
+  }
+  return (int)n;
+#else
+  (void)host; (void)max_records; (void)reset;
+  return -1;
+#endif
 }
 
 }  // namespace

@@ -1254,6 +1254,21 @@ const char* evconv_node_kernel(const evconv_net* net, int32_t node) {
   return kKernelNames[net->L.nodes[node].kernel];
 }
 
+evconv_status evconv_debug_phase_stamps(int32_t operand_mode, uint64_t* out, int32_t max_records, int32_t reset,
+                                        int32_t* n_records) {
+  if (!n_records || max_records < 0 || (max_records > 0 && !out)) return EVCONV_ERR_INVALID_ARG;
+  int n;
+  unsigned long long* dst = (unsigned long long*)out;
+  if (operand_mode == EVCONV_F32) n = evk::conv_mfma_f32_phase_stamps(dst, max_records, reset != 0);
+  else if (operand_mode == EVCONV_BF16) n = evk::conv_mfma_bf16_phase_stamps(dst, max_records, reset != 0);
+  else if (operand_mode == EVCONV_F32_SPLIT) n = evk::conv_mfma_split_phase_stamps(dst, max_records, reset != 0);
+  else return EVCONV_ERR_INVALID_ARG;
+  if (n == -1) return EVCONV_ERR_UNSUPPORTED;
+  if (n < 0) return EVCONV_ERR_HIP;
+  *n_records = n;
+  return EVCONV_OK;
+}
+
 evconv_status evconv_debug_chip_probes(void* scratch, size_t scratch_bytes, void* hip_stream, float* out, int32_t n_out) {
   if (!scratch || !out || scratch_bytes < EVCONV_CHIP_PROBE_SCRATCH_BYTES || n_out < EVCONV_CHIP_PROBE_VALUES)
     return EVCONV_ERR_INVALID_ARG;

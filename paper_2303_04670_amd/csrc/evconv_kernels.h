@@ -130,6 +130,12 @@ void launch_conv_mfma_bf16(const ConvParams& p, hipStream_t s);
 // fp32 operands contracted as bf16 high/low parts (three bf16 MFMAs per product)
 bool conv_mfma_split_supported(const ConvParams& p);
 void launch_conv_mfma_split(const ConvParams& p, hipStream_t s);
+// phase records of the matrix-core kernels of one operand mode (conv_mfma_impl.h: PhaseField): copies
+// at most max_records records of 32 x u64 to host, returns the number written since the last
+// reset; -1 in a build without -DEVCONV_PHASE_STAMPS, -2 if a copy fails
+int conv_mfma_f32_phase_stamps(unsigned long long* host, int max_records, bool reset);
+int conv_mfma_bf16_phase_stamps(unsigned long long* host, int max_records, bool reset);
+int conv_mfma_split_phase_stamps(unsigned long long* host, int max_records, bool reset);
 // 1 x 1 taps with at most 8 output channels, or LINEAR on a 1 x 1 grid; weights [c_out][c_in] fp32
 bool conv_pointwise_supported(const ConvParams& p);
 // true if launch_conv_pointwise(p) runs the per-tile kernel, which can also keep an output node's

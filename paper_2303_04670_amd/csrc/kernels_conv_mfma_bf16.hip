@@ -6,5 +6,8 @@ namespace evk {
 
 bool conv_mfma_bf16_supported(const ConvParams& p) { return conv_mfma_f32_supported(p); }
 void launch_conv_mfma_bf16(const ConvParams& p, hipStream_t s) { launch_any<kOpBf16>(p, s); }
+int conv_mfma_bf16_phase_stamps(unsigned long long* host, int max_records, bool reset) {
+  return phase_stamps_read(host, max_records, reset);
+}
 
 }  // namespace evk

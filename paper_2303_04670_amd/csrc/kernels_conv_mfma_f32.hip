@@ -20,5 +20,8 @@ int conv_mfma_padded_cin(const ConvParams& p) {
   return (p.gi.c + chunk - 1) / chunk * chunk;
 }
 void launch_conv_mfma_f32(const ConvParams& p, hipStream_t s) { launch_any<kOpF32>(p, s); }
+int conv_mfma_f32_phase_stamps(unsigned long long* host, int max_records, bool reset) {
+  return phase_stamps_read(host, max_records, reset);
+}
 
 }  // namespace evk

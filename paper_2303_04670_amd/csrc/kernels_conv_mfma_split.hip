@@ -7,5 +7,8 @@ namespace evk {
 
 bool conv_mfma_split_supported(const ConvParams& p) { return conv_mfma_f32_supported(p); }
 void launch_conv_mfma_split(const ConvParams& p, hipStream_t s) { launch_any<kOpSplit>(p, s); }
+int conv_mfma_split_phase_stamps(unsigned long long* host, int max_records, bool reset) {
+  return phase_stamps_read(host, max_records, reset);
+}
 
 }  // namespace evk

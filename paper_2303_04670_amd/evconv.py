@@ -29,7 +29,8 @@ EXPORTS = ["evconv_query_workspace", "evconv_create", "evconv_num_outputs", "evc
            "evconv_step_frame", "evconv_destroy", "evconv_set_mode", "evconv_node_shape", "evconv_get_state",
            "evconv_get_stats", "evconv_node_kernel", "evconv_last_error", "evconv_profile_begin",
            "evconv_profile_end", "evconv_get_node_time", "evconv_set_refresh_period", "evconv_get_state_stream",
-           "evconv_stream_stride", "evconv_current_mode", "evconv_create_static", "evconv_debug_chip_probes"]
+           "evconv_stream_stride", "evconv_current_mode", "evconv_create_static", "evconv_debug_chip_probes",
+           "evconv_debug_phase_stamps"]
 STATIC_WORKSPACE_BYTES = 32 << 20
 
 
@@ -96,8 +97,28 @@ def lib() -> ctypes.CDLL:
         L.evconv_get_node_time.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double),
                                            ctypes.POINTER(ctypes.c_int64)]
         L.evconv_debug_chip_probes.argtypes = [vp, ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_float), i32]
+        L.evconv_debug_phase_stamps.argtypes = [i32, vp, i32, i32, ctypes.POINTER(i32)]
         _lib = L
     return _lib
+
+
+def use_library(path):
+    """Load another build of the library (the one with phase stamps) instead of libevconv.so; to
+    be called before anything else of this module."""
+    global LIB_PATH, _lib
+    assert _lib is None, "the library is already loaded"
+    LIB_PATH = path
+
+
+def phase_stamps(operand_mode, reset=True, max_records=1 << 15):
+    """evconv_debug_phase_stamps: (records as a uint64 array [n][32], number of workgroups that wrote
+    one).  Raises EvConvError(UNSUPPORTED) on a library built without phase stamps."""
+    buf = np.zeros((max_records, 32), np.uint64)
+    n = ctypes.c_int32(0)
+    st = lib().evconv_debug_phase_stamps(operand_mode, buf.ctypes.data, max_records, 1 if reset else 0, ctypes.byref(n))
+    if st != 0:
+        raise EvConvError(st, "evconv_debug_phase_stamps (library built without --phase-stamps?)")
+    return buf[:min(n.value, max_records)], n.value
 
 
 CHIP_PROBE_VALUES = 20
