@@ -36,7 +36,7 @@
  *                    of S_in whose x_inc is nonzero (the others emit 0 and keep delta: the same
  *                    formulas give that for |delta| <= k/2, so no value depends on the mask); S_out =
  *                    sites with a nonzero y_inc.  k = sparsify_tp * RMS(node input at the last
- *                    reset), kept to 8 significant bits, or the fp32 value at weight_off when
+ *                    reset), kept to 8 fraction bits, or the fp32 value at weight_off when
  *                    weight_off >= 0; k == 0 is the identity.  In reset and in dense-recompute
  *                    mode the node is the identity.  Lossy: y no longer equals the forward pass.
  *   MUL              elementwise product of two nodes of equal shape (Eq.15-17): keeps the

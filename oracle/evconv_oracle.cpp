@@ -37,7 +37,7 @@
 //     whose x_inc is nonzero (for the others the same formulas give y_inc = 0).  This keeps
 //     sum(y_inc) + delta == sum(x_inc) and -k/2 <= delta < k/2, which is what the text asks of
 //     the residual.  A refresh is a regular forward pass (the layer is the identity) and clears
-//     delta.  k = t_p * RMS(layer input at the last refresh), rounded to 8 significant bits so
+//     delta.  k = t_p * RMS(layer input at the last refresh), rounded to 8 fraction bits so
 //     that both sides of a comparison use the identical step (the paper says "t_p times the L2
 //     norm of a rolling average of the input" without giving window or normalisation);
 //     k == 0 makes the layer the identity.
@@ -467,7 +467,7 @@ struct Net {
     last_dense = false;
   }
 
-  // rounding step kept to 8 significant bits (round to nearest on the 16th mantissa bit)
+  // rounding step kept to 8 fraction bits (round to nearest on the 16th mantissa bit)
   static float quantise_step(float k) {
     uint32_t u;
     std::memcpy(&u, &k, 4);

@@ -658,7 +658,7 @@ void launch_build_lists(const SetDesc* sets_dev, int n_sets, int max_ty, Streams
 // =============================================================================== rounding step
 // stage 1: block b sums the squares of its contiguous slice in a fixed order (thread-strided
 // partials, then a shared-memory tree); stage 2: one block adds the kRmsBlocks partials the same
-// way and writes k = tp * sqrt(sum / n) kept to 8 significant bits.
+// way and writes k = tp * sqrt(sum / n) kept to 8 fraction bits.
 __global__ __launch_bounds__(256) void rms_stage1_kernel(const float* x, size_t n, float* partial, size_t stream_stride) {
   x = at_stream(x, (size_t)blockIdx.y * stream_stride);
   partial = at_stream(partial, (size_t)blockIdx.y * stream_stride);

@@ -98,8 +98,32 @@ def test_step_is_tp_times_rms_of_layer_input_at_refresh():
         if nd.op == wl.OP_SPARSIFY:
             rms = np.sqrt(np.mean(ref[nd.in0] ** 2))
             k = o.step_size(i)
-            assert abs(k - 0.1 * rms) <= 0.1 * rms * 2.0 ** -8        # kept to 8 significant bits
+            assert abs(k - 0.1 * rms) <= 0.1 * rms * 2.0 ** -8        # kept to 8 fraction bits
             assert (np.float32(k).view(np.uint32) & 0x7fff) == 0
+
+
+def test_step_size_closed_forms_and_a_hand_quantised_value():
+    """k = t_p * sqrt(mean(x^2)) over the layer input at the reset, kept to the nine leading bits of
+    its significand (round to nearest at the 16th fraction bit).  Inputs whose root mean square is
+    known without arithmetic: a constant, +-c, a 6-8-0 pattern (36 + 64 over 100 elements: mean
+    square 1); and 0.3 quantised by hand: 0.3f = 0x3e99999a -> + 0x4000 -> 0x3e99d99a -> low 15 bits
+    cleared -> 0x3e998000 = 0.2998046875."""
+    def k_of(x, tp):
+        net = sp_only_net(c=x.shape[0], h=x.shape[1], w=x.shape[2])
+        net.sparsify_tp = tp
+        o = Oracle(net)
+        o.reset(x.astype(np.float32))
+        return o.step_size(0)
+    assert k_of(np.full((3, 6, 7), 2.0), 0.25) == 0.5
+    pm = np.where((np.arange(3 * 6 * 7) % 2) == 0, 3.0, -3.0).reshape(3, 6, 7)
+    assert k_of(pm, 0.5) == 1.5
+    x = np.zeros((1, 10, 10))
+    x[0, 2, 3], x[0, 7, 1] = 6.0, -8.0
+    assert k_of(x, 0.125) == 0.125
+    assert k_of(np.ones((2, 5, 5)), 0.3) == 0.2998046875
+    assert np.float32(0.2998046875).view(np.uint32) == 0x3e998000
+    # zero input: k = 0, the layer is the identity
+    assert k_of(np.zeros((2, 5, 5)), 0.3) == 0.0
 
 
 def torch_forward_sp(net, x):
