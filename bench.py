@@ -476,7 +476,9 @@ def chip_probe_table(v):
             ("chain of 1000 dependent LDS reads", "us alone / beside them", f"{v[13]:.0f} / {v[14]:.0f}"),
             ("LDS atomic OR, 64 lanes", "ns per instruction: one word / 64 words", f"{v[15]:.0f} / {v[16]:.0f}"),
             ("20000 16-byte LDS reads of one wave per SIMD", "us alone / beside one-word atomics / beside 64-word atomics",
-             f"{v[17]:.0f} / {v[18]:.0f} / {v[19]:.0f}")]
+             f"{v[17]:.0f} / {v[18]:.0f} / {v[19]:.0f}"),
+            ("fp32 MFMA chain with a 16-cycle s_nop after every MFMA", "us alone (chain without: %.0f)" % v[5], f"{v[20]:.0f}"),
+            ("the two dependent chains beside three such waves per SIMD", "us global loads / LDS reads", f"{v[21]:.0f} / {v[22]:.0f}")]
     out = ["| Probe | Quantity | Measured |", "|---|---|---|"]
     out += [f"| {a} | {b} | {c} |" for a, b, c in rows]
     return "\n".join(out)

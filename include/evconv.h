@@ -363,9 +363,11 @@ evconv_status evconv_debug_phase_stamps(int32_t operand_mode, uint64_t* out /* H
  *   [15..16] ns per LDS atomic instruction whose 64 lanes hit one word / 64 different words
  *   [17..19] us: a loop of 16-byte LDS reads alone / beside another wave's one-word atomics /
  *            beside its 64-word atomics
+ *   [20..22] us: the fp32 MFMA chain with a 16-cycle s_nop after every MFMA, alone; the global-load
+ *            chain and the LDS chain beside three such waves per SIMD
  * Synchronous (a few milliseconds).  EVCONV_ERR_INVALID_ARG for a null pointer or too little
  * room, EVCONV_ERR_HIP if a launch or copy fails. */
-#define EVCONV_CHIP_PROBE_VALUES 20
+#define EVCONV_CHIP_PROBE_VALUES 23
 #define EVCONV_CHIP_PROBE_SCRATCH_BYTES (1u << 20)
 evconv_status evconv_debug_chip_probes(void* scratch /* DEVICE */, size_t scratch_bytes, void* hip_stream,
                                        float* out /* HOST */, int32_t n_out);

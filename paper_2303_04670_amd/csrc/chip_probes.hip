@@ -37,6 +37,7 @@ enum Role {
   kLdsAtomicSame,  // 64 lanes OR a bit into one LDS word
   kLdsAtomicOwn,   // 64 lanes OR a bit into 64 different words
   kLdsRead,        // independent 16-byte LDS reads
+  kMfmaF32Nop,     // the fp32 chain with a 16-cycle s_nop after every MFMA
 };
 
 struct ProbeParams {
@@ -72,6 +73,15 @@ __global__ __launch_bounds__(1024) void probe_kernel(ProbeParams p) {
     for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
     const float a = 1.0f + lane, b = 2.0f;
     for (int it = 0; it < iters; ++it) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+    for (int i = 0; i < 16; ++i) res += acc[i];
+  } else if (role == kMfmaF32Nop) {
+    floatx16 acc;
+    for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+    const float a = 1.0f + lane, b = 2.0f;
+    for (int it = 0; it < iters; ++it) {
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+      asm volatile("s_nop 15");
+    }
     for (int i = 0; i < 16; ++i) res += acc[i];
   } else if (role == kMfmaBf16) {
     floatx16 acc;
@@ -191,6 +201,8 @@ bool same_wave_cycles(hipStream_t s, float* sink, float& cycles) {
 // out[11..14] us: chain of dependent global loads alone / beside three fp32 MFMA chain waves per SIMD; LDS chain likewise
 // out[15..16] ns per LDS atomic instruction: 64 lanes on one word / on 64 words
 // out[17..19] us: 16-byte LDS read loop alone / beside same-word atomics of another wave / beside 64-word atomics
+// out[20..22] us: fp32 MFMA chain with a 16-cycle s_nop after every MFMA, alone; the global-load chain and the LDS
+//             chain beside three such waves per SIMD
 int chip_probes(void* scratch, size_t scratch_bytes, hipStream_t s, float* out, int n) {
   if (!scratch || scratch_bytes < kChipProbeScratch || !out || n < kChipProbeValues) return -1;
   launch_fill_u64((uint64_t*)scratch, kChipProbeScratch / 8, 0, Streams{0, 1}, s);
@@ -218,6 +230,9 @@ int chip_probes(void* scratch, size_t scratch_bytes, hipStream_t s, float* out, 
   ok = ok && r.run({kIdle, kLdsRead, kIdle, kIdle}, {0, kR, 0, 0}, t); out[17] = t[1];
   ok = ok && r.run({kLdsAtomicSame, kLdsRead, kIdle, kIdle}, {8 * kA, kR, 0, 0}, t); out[18] = t[1];
   ok = ok && r.run({kLdsAtomicOwn, kLdsRead, kIdle, kIdle}, {8 * kA, kR, 0, 0}, t); out[19] = t[1];
+  ok = ok && r.run({kIdle, kMfmaF32Nop, kIdle, kIdle}, {0, kM, 0, 0}, t); out[20] = t[1];
+  ok = ok && r.run({kGlobalChain, kMfmaF32Nop, kMfmaF32Nop, kMfmaF32Nop}, {100, kM, kM, kM}, t); out[21] = t[0];
+  ok = ok && r.run({kLdsChain, kMfmaF32Nop, kMfmaF32Nop, kMfmaF32Nop}, {1000, kM, kM, kM}, t); out[22] = t[0];
   return ok ? kChipProbeValues : -2;
 }
 

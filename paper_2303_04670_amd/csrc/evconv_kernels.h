@@ -222,7 +222,7 @@ void launch_build_lists(const SetDesc* sets_dev, int n_sets, int max_ty, Streams
 void launch_fill_u64(uint64_t* p, size_t n, uint64_t v, Streams st, hipStream_t s);
 
 // timing probes of the chip (chip_probes.hip); number of values written, or < 0
-constexpr int kChipProbeValues = 20;
+constexpr int kChipProbeValues = 23;
 constexpr size_t kChipProbeScratch = 1u << 20;
 int chip_probes(void* scratch, size_t scratch_bytes, hipStream_t s, float* out, int n);
 

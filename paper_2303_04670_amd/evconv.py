@@ -121,7 +121,7 @@ def phase_stamps(operand_mode, reset=True, max_records=1 << 15):
     return buf[:min(n.value, max_records)], n.value
 
 
-CHIP_PROBE_VALUES = 20
+CHIP_PROBE_VALUES = 23
 CHIP_PROBE_SCRATCH_BYTES = 1 << 20
 
 
