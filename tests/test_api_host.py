@@ -112,6 +112,24 @@ def test_null_handles():
     assert L.evconv_current_mode(None) == -1
 
 
+def test_measurement_aids_reject_bad_arguments_before_any_gpu_work():
+    L = ev.lib()
+    out = (ctypes.c_float * ev.CHIP_PROBE_VALUES)()
+    INVALID, UNSUPPORTED = ev.STATUS_NAMES.index("ERR_INVALID_ARG"), ev.STATUS_NAMES.index("ERR_UNSUPPORTED")
+    assert L.evconv_debug_chip_probes(None, ev.CHIP_PROBE_SCRATCH_BYTES, None, out, ev.CHIP_PROBE_VALUES) == INVALID
+    dummy = ctypes.c_void_p(4096)  # (never dereferenced: the size check comes first)
+    assert L.evconv_debug_chip_probes(dummy, ev.CHIP_PROBE_SCRATCH_BYTES - 1, None, out, ev.CHIP_PROBE_VALUES) == INVALID
+    assert L.evconv_debug_chip_probes(dummy, ev.CHIP_PROBE_SCRATCH_BYTES, None, out, ev.CHIP_PROBE_VALUES - 1) == INVALID
+    # phase stamps exist only in the measurement build; the product library says so
+    n = ctypes.c_int32(-5)
+    for mode in (0, 1, 2):
+        assert L.evconv_debug_phase_stamps(mode, None, 0, 0, ctypes.byref(n)) == UNSUPPORTED
+    assert L.evconv_debug_phase_stamps(3, None, 0, 0, ctypes.byref(n)) == INVALID
+    assert L.evconv_debug_phase_stamps(0, None, 0, 0, None) == INVALID
+    assert L.evconv_debug_phase_stamps(0, None, 8, 0, ctypes.byref(n)) == INVALID
+    assert n.value == -5
+
+
 def test_product_package_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2303_04670_amd")
     for dirpath, _, files in os.walk(pkg):
