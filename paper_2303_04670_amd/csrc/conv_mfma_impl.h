@@ -65,6 +65,7 @@ namespace evk {
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 // Phase stamps.  In a build with -DEVCONV_PHASE_STAMPS (never the product build) one lane per
 // workgroup writes the 100 MHz wall clock at the boundaries of the kernel's phases into a device
 // array of the translation unit; evconv_debug_phase_stamps copies the records out.  Without the
@@ -146,8 +147,13 @@ constexpr int max_patch_sites(int chunk, int mb) {
 // four of them on its way into the patch buffer.  p.gi describes the up-sampled tensor, p.lo_h x
 // p.lo_w the stored one; p.occ_in are the stored tensor's occupancy words, and an up-sampled
 // site is active where one of its four sources is.
-template <int CHUNK, int NW, int OPM, int MB, bool UPS>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(MB == 1 && !(UPS && NW == 4) ? 4 : 3)))
+// NB: output channels per workgroup.  32 is the normal shape.  16 (fp32, half tiles, no up-sampling)
+// is for launches that would otherwise leave the chip unevenly filled: the same half tile as two
+// 16-row blocks of v_mfma_f32_16x16x4_f32 (a unit = one tap x 16 channels, MFMA j of a unit
+// contracts channels {j, 4+j, 8+j, 12+j}: lanes 16 q .. 16 q + 15 hold channel 4 q + j), twice the
+// workgroups at half the work each.
+template <int CHUNK, int NW, int OPM, int MB, bool UPS, int NB = 32>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NB == 16 ? 4 : MB == 1 && !(UPS && NW == 4) ? 4 : 3)))
 void conv_mfma_kernel(ConvParams p) {
   // this workgroup's stream: every state pointer of p is used through at_stream(.., so); p itself
   // stays untouched so that it remains in the kernel-argument segment
@@ -160,16 +166,19 @@ void conv_mfma_kernel(ConvParams p) {
   // CHUNK bf16 each per site.
   constexpr int CS = (BF16 && !SPLIT) ? CHUNK / 2 + 4 : CHUNK + 4;
   constexpr int LO = CHUNK / 2;  // word offset of the low plane inside a site (split mode)
-  constexpr int UCH = BF16 ? 16 : 8;  // channels per unit
+  static_assert(NB == 32 || (NB == 16 && OPM == kOpF32 && MB == 1 && !UPS), "16-channel blocks: fp32 half tiles only");
+  constexpr int UCH = (BF16 || NB == 16) ? 16 : 8;  // channels per unit
   constexpr int KG = CHUNK / UCH;     // units per tap and chunk
   constexpr int NV = CHUNK / 4;       // float4 per patch site
   constexpr int MAXV = (max_patch_sites(CHUNK, MB) * NV + NT - 1) / NT;  // patch float4 per thread
   constexpr int SUBS = 2 / MB;        // workgroups per tile
   constexpr int NROWS = 4 * MB;       // output rows of this workgroup
   constexpr int NSITES = 32 * MB;
-  constexpr int EP_SITES = NT / 32;   // sites per epilogue pass
+  constexpr int EP_SITES = NT / NB;   // sites per epilogue pass
   constexpr int EP_ITERS = NSITES / EP_SITES;
-  constexpr int SLOT = MB * 16 * 64;  // floats per partial-sum slot
+  static_assert(EP_ITERS >= 1 && EP_SITES <= 32, "epilogue mapping");
+  constexpr int NACC = NB == 16 ? 8 : MB * 16;  // accumulator registers of a lane
+  constexpr int SLOT = NACC * 64;     // floats per partial-sum slot
   constexpr int CSL = CHUNK + 4;      // UPS: site stride of the low-resolution fp32 buffer
   constexpr int LPMAX = 10;           // UPS: a 14-row patch has sources in at most 14 / 2 + 3 rows
   constexpr int MAXG = UPS ? (LPMAX * LPMAX * NV + NT - 1) / NT : MAXV;  // gathered float4 per thread
@@ -428,9 +437,9 @@ void conv_mfma_kernel(ConvParams p) {
   // an access that must not happen gets an out-of-range vector offset (loads return 0, stores are
   // dropped).  The bits of a thread's sites are kept where they are in the 64-bit words, EP_SITES
   // bits apart: no per-site shifts, no 64-bit address arithmetic on the vector ALU.
-  const int co = tid & 31;
-  const int co0 = wg_co * 32;
-  const int es = tid >> 5;
+  const int co = tid & (NB - 1);
+  const int co0 = wg_co * NB;
+  const int es = tid / NB;
   // (weight-folded: site (y, x) of the stored tile is output site (2y + fpy, 2x + fpx))
   const int ey = tile_y * 8 + r0 + (es >> 3), ex = tile_x * 8 + (es & 7);
   const unsigned ep_voff =
@@ -438,7 +447,7 @@ void conv_mfma_kernel(ConvParams p) {
   const unsigned ep_step = (unsigned)((EP_SITES / 8) * p.go.w * Cout * 4) << (fold ? 1 : 0);
   const int out_bytes = p.go.h * p.go.w * Cout * 4;
   constexpr unsigned kSkipAccess = 0x80000000u;
-  constexpr uint64_t kMine = EP_SITES == 8 ? 0x0101010101010101ull : 0x0001000100010001ull;
+  constexpr uint64_t kMine = EP_SITES == 8 ? 0x0101010101010101ull : EP_SITES == 16 ? 0x0001000100010001ull : 0x1ull;
   // c_out need not be a multiple of 32: the last block's weights are zero-padded and the threads
   // of the channels that do not exist own no sites (they take no part in the epilogue)
   const bool co_ok = co0 + co < Cout;
@@ -554,14 +563,16 @@ void conv_mfma_kernel(ConvParams p) {
   floatx16 acc0, acc1;
 #pragma unroll
   for (int i = 0; i < 16; ++i) { acc0[i] = 0.0f; acc1[i] = 0.0f; }
-  const int half = lane >> 5, m = lane & 31;
-  const int mly = m >> 3, mlx = m & 7;  // site of this lane inside a 32-row block
+  floatx4 c16a = {0.f, 0.f, 0.f, 0.f}, c16b = {0.f, 0.f, 0.f, 0.f};  // NB == 16: the two 16-row blocks
+  // operand lane: k-group `half` (two groups of 32 lanes, or four of 16), row / column m of the block
+  const int half = NB == 16 ? lane >> 4 : lane >> 5, m = NB == 16 ? lane & 15 : lane & 31;
+  const int mly = m >> 3, mlx = m & 7;  // site of this lane inside a block
   const int cop = p.c_out_pad;
   const int n_units = K * K * KG;
   const int cin_pad = (Cin + CHUNK - 1) / CHUNK * CHUNK;    // the weights are zero-padded to whole chunks
   const int cin_rows = BF16 ? cin_pad >> 3 : cin_pad >> 2;  // 16-byte weight rows per tap: 8 bf16 or 4 floats
   const int a_lane_off = mly * s * RP + mlx * s * CS + half * 4;
-  const int a_blk1 = 4 * s * RP;
+  const int a_blk1 = (NB == 16 ? 2 : 4) * s * RP;  // the second block starts four (two) tile rows further down
   // units of this wave: u_j = wave + j * NW, j < n_mine
   const int n_mine = (n_units - wave + NW - 1) / NW;
   const int last = n_mine - 1;
@@ -583,7 +594,8 @@ void conv_mfma_kernel(ConvParams p) {
     const int u = wave + min(j, last) * NW;
     const int tap = u / KG, kg = u % KG;
     const int row0 = BF16 ? (c0 >> 3) : (c0 >> 2);
-    const unsigned soff = (unsigned)__builtin_amdgcn_readfirstlane(((tap * cin_rows + row0 + kg * 2) * cop) << 4);
+    constexpr int kRowsPerUnit = BF16 ? UCH / 8 : UCH / 4;  // 16-byte weight rows of a unit
+    const unsigned soff = (unsigned)__builtin_amdgcn_readfirstlane(((tap * cin_rows + row0 + kg * kRowsPerUnit) * cop) << 4);
     BFrag f;
     f.h = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, w_lane, soff, 0));
     f.l = SPLIT ? __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, w_lane, soff + w_plane, 0)) : f.h;
@@ -594,7 +606,7 @@ void conv_mfma_kernel(ConvParams p) {
     const int u = wave + j * NW;
     const int tap = u / KG, kg = u % KG;
     const int ky = (tap * k_magic) >> 16, kx = tap - ky * K;
-    return a_lane_off + __builtin_amdgcn_readfirstlane(ky * RP + kx * CS + kg * 8);  // 8 words = 8 floats or 16 bf16
+    return a_lane_off + __builtin_amdgcn_readfirstlane(ky * RP + kx * CS + kg * (NB == 16 ? 16 : 8));  // words of a unit: 8 floats, 16 bf16 or 16 floats
   };
   // A fragment of unit j (clamped like the B fragments): the patch values of this lane's site
   // for both 32-row blocks, and their low parts in split mode; unused members cost nothing
@@ -602,7 +614,7 @@ void conv_mfma_kernel(ConvParams p) {
     AFrag f;
     const float* ap = &s_mem[a_off(min(j, last))];
     f.h0 = *(const float4*)ap;
-    f.h1 = MB == 2 ? *(const float4*)(ap + a_blk1) : f.h0;
+    f.h1 = (MB == 2 || NB == 16) ? *(const float4*)(ap + a_blk1) : f.h0;
     f.l0 = SPLIT ? *(const float4*)(ap + LO) : f.h0;
     f.l1 = (SPLIT && MB == 2) ? *(const float4*)(ap + a_blk1 + LO) : f.h0;
     return f;
@@ -610,6 +622,17 @@ void conv_mfma_kernel(ConvParams p) {
   auto unit = [&](const AFrag& af, const BFrag& bf) {
     const float4& b = bf.h;
     const float4 a0 = af.h0, a1 = af.h1;
+    if (NB == 16) {
+      c16a = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.x, b.x, c16a, 0, 0, 0);
+      c16b = __builtin_amdgcn_mfma_f32_16x16x4f32(a1.x, b.x, c16b, 0, 0, 0);
+      c16a = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.y, b.y, c16a, 0, 0, 0);
+      c16b = __builtin_amdgcn_mfma_f32_16x16x4f32(a1.y, b.y, c16b, 0, 0, 0);
+      c16a = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.z, b.z, c16a, 0, 0, 0);
+      c16b = __builtin_amdgcn_mfma_f32_16x16x4f32(a1.z, b.z, c16b, 0, 0, 0);
+      c16a = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.w, b.w, c16a, 0, 0, 0);
+      c16b = __builtin_amdgcn_mfma_f32_16x16x4f32(a1.w, b.w, c16b, 0, 0, 0);
+      return;
+    }
     if (SPLIT) {
       // a * b ~ a_lo * b_hi + a_hi * b_lo + a_hi * b_hi (the low x low term, 2^-16 smaller, is dropped)
       const bf16x8 bh = __builtin_bit_cast(bf16x8, bf.h), bl = __builtin_bit_cast(bf16x8, bf.l);
@@ -751,6 +774,14 @@ void conv_mfma_kernel(ConvParams p) {
   EVK_PHASE(kPhFusedRequested);
   // ---- reduce the NW partial sums through LDS: slots [4][block*16 + reg][lane]
   auto spill = [&](float* part) {
+    if (NB == 16) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        part[i * 64 + lane] = c16a[i];
+        part[(4 + i) * 64 + lane] = c16b[i];
+      }
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       part[i * 64 + lane] = acc0[i];
@@ -763,8 +794,15 @@ void conv_mfma_kernel(ConvParams p) {
     __syncthreads();
     if (wave < 4) {
       const float* part = s_mem + wave * SLOT;
+      if (NB == 16) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
+        for (int i = 0; i < 4; ++i) {
+          c16a[i] += part[i * 64 + lane];
+          c16b[i] += part[(4 + i) * 64 + lane];
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < (NB == 16 ? 0 : 16); ++i) {
         acc0[i] += part[i * 64 + lane];
         if (MB == 2) acc1[i] += part[(16 + i) * 64 + lane];
       }
@@ -788,7 +826,9 @@ void conv_mfma_kernel(ConvParams p) {
   const __amdgpu_buffer_rsrc_t o_rsrc = out_rsrc(at_stream(p.out, so));
   // partial sum of local site ls = it * EP_SITES + es: the part of the LDS offset that depends on
   // the thread (es < 16), the rest is a constant per `it`
-  const int off_mine = ((es >> 3) * 4 + (es & 3)) * 64 + ((es >> 2) & 1) * 32 + co;
+  // (NB == 16: element (block b, register i, lane l) is local site 16 b + 4 (l / 16) + i, channel l % 16)
+  const int off_mine = NB == 16 ? ((es >> 4) * 4 + (es & 3)) * 64 + ((es >> 2) & 3) * 16 + co
+                                : ((es >> 3) * 4 + (es & 3)) * 64 + ((es >> 2) & 1) * 32 + co;
   const float bias = (p.dense && p.bias && co_ok) ? p.bias[co0 + co] : 0.0f;
   // Straight-line code: a site this thread does not own gets an out-of-range offset (its stores
   // are dropped) instead of a branch around it, and the partial sums of all passes are read from
@@ -797,7 +837,8 @@ void conv_mfma_kernel(ConvParams p) {
 #pragma unroll
   for (int it = 0; it < EP_ITERS; ++it) {
     constexpr int kRow = EP_SITES / 8;  // tile rows per `it`
-    const int off = off_mine + (((it * kRow) >> 2) * 16 + ((it * kRow) & 3) * 4) * 64;
+    const int off = NB == 16 ? off_mine + it * (EP_SITES / 16) * 4 * 64
+                             : off_mine + (((it * kRow) >> 2) * 16 + ((it * kRow) & 3) * 4) * 64;
     v_sum[it] = (s_mem[off] + s_mem[off + SLOT]) + (s_mem[off + 2 * SLOT] + s_mem[off + 3 * SLOT]);
   }
   auto ep_store_at = [&](const __amdgpu_buffer_rsrc_t& r, unsigned voff, int it, float v) {
@@ -944,9 +985,13 @@ void conv_mfma_kernel(ConvParams p) {
 #pragma unroll
     for (int it = 0; it < EP_ITERS; ++it) {
       const uint64_t b = __ballot(((mine_bits >> (it * EP_SITES)) & 1ull) != 0);
-      w |= (uint64_t)(((unsigned)b != 0 ? 1u : 0u) | ((unsigned)(b >> 32) != 0 ? 2u : 0u)) << (it * EP_SITES);
+      if (NB == 16)  // four sites of 16 lanes each
+        w |= (uint64_t)(((b & 0xffffull) ? 1u : 0u) | ((b & 0xffff0000ull) ? 2u : 0u) | ((b & 0xffff00000000ull) ? 4u : 0u) |
+                        ((b >> 48) ? 8u : 0u)) << (it * EP_SITES);
+      else
+        w |= (uint64_t)(((unsigned)b != 0 ? 1u : 0u) | ((unsigned)(b >> 32) != 0 ? 2u : 0u)) << (it * EP_SITES);
     }
-    if (lane == 0) s_nz[slot * NW + wave] = w << (r0 * 8 + 2 * wave);
+    if (lane == 0) s_nz[slot * NW + wave] = w << (r0 * 8 + (64 / NB) * wave);
   };
   auto nz_word = [&](int slot) {
     uint64_t w = 0;
@@ -1023,7 +1068,7 @@ inline int chunk_for(const ConvParams& p) {
   return 16;
 }
 
-template <int CHUNK, int NW, int OPM, int MB>
+template <int CHUNK, int NW, int OPM, int MB, int NB = 32>
 void launch_variant(const ConvParams& p, hipStream_t s) {
   const int PH = (4 * MB - 1) * p.stride + p.k, PW = 7 * p.stride + p.k;
   // (rows of the patch are padded to a pitch of 32 modulo 64 words: at most 64 more per row)
@@ -1036,8 +1081,8 @@ void launch_variant(const ConvParams& p, hipStream_t s) {
   ConvParams q = p;
   const long long in_sites = p.upsample ? (long long)p.lo_h * p.lo_w : (long long)p.gi.h * p.gi.w;
   q.wg_swap = (long long)p.k * p.k * p.go.c > in_sites && p.go.tiles() * (2 / MB) <= 65535;
-  dim3 grid(p.go.tiles() * (2 / MB), p.c_out_pad / 32, p.st.n);
-  if (q.wg_swap) grid = dim3(p.c_out_pad / 32, p.go.tiles() * (2 / MB), p.st.n);
+  dim3 grid(p.go.tiles() * (2 / MB), p.c_out_pad / NB, p.st.n);
+  if (q.wg_swap) grid = dim3(p.c_out_pad / NB, p.go.tiles() * (2 / MB), p.st.n);
   if (CHUNK == 32 && p.upsample) {
     // the low-resolution source region behind the patch buffer
     lds += (size_t)(PH / 2 + 3) * (PW / 2 + 3) * (CHUNK + 4) * sizeof(float);
@@ -1046,7 +1091,7 @@ void launch_variant(const ConvParams& p, hipStream_t s) {
     return;
   }
   if (lds < part) lds = part;
-  hipLaunchKernelGGL((conv_mfma_kernel<CHUNK, NW, OPM, MB, false>), grid, dim3(NW * 64), lds, s, q);
+  hipLaunchKernelGGL((conv_mfma_kernel<CHUNK, NW, OPM, MB, false, NB>), grid, dim3(NW * 64), lds, s, q);
 }
 
 // share of the chip's 256 CUs kept busy when n equally long workgroups run at once
@@ -1062,6 +1107,18 @@ void launch_shape(const ConvParams& p, hipStream_t s) {
   bool halves = !(n2 >= 512 && p.k * p.k * p.gi.c >= 1600) || fill(2 * n2) > fill(n2) + 0.1;
   const long long n = halves ? 2 * n2 : n2;
   bool eight = n < 512;  // few workgroups: 8 waves each split K further
+  // fp32, few half-tile workgroups that fill the chip unevenly (384 on 256 CUs: half of the CUs get
+  // two; 32 or 128: most CUs get none): blocks of 16 output channels instead of 32, twice the
+  // workgroups at half the work.  Four waves each where that gives three workgroups per CU, eight
+  // where the chip still is not full.  Measured: the 32 x 44 layers of the depth net 37 / 28 -> 32 /
+  // 26 us, the 16 x 16 x 512 layers of the flow net 30 -> 23.5 us, ResNet-18's 7 x 7 x 512 layers
+  // 29 -> 21 us.
+  constexpr int kNarrowBlock = OPM == kOpF32 ? 16 : 32;
+  if (OPM == kOpF32 && halves && eight && !p.upsample && fill(2 * n) > fill(n) + 0.1) {
+    if (2 * n <= 256) launch_variant<CHUNK, 8, OPM, 1, kNarrowBlock>(p, s);
+    else launch_variant<CHUNK, 4, OPM, 1, kNarrowBlock>(p, s);
+    return;
+  }
   if (CHUNK == 128) {  // chosen only for few workgroups: the 4-wave variants are not built
     if (halves) launch_variant<CHUNK, 8, OPM, 1>(p, s); else launch_variant<CHUNK, 8, OPM, 2>(p, s);
     return;
