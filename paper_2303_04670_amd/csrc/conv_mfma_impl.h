@@ -4,7 +4,8 @@
 // channel chunk is zero-padded), c_out >= 16 (any count: the last block of 32 is zero-padded).
 // Implicit GEMM per touched output tile (8 x 8 sites): M = 32 * MB sites (MB = 2: the whole
 // tile as two 32-row MFMA blocks, rows 0-3 and 4-7; MB = 1: one workgroup per half tile),
-// N = 32 output channels per workgroup, K = taps x c_in.
+// N = 32 output channels per workgroup (16 in the fp32 variant for launches that fill the chip
+// unevenly, see NB below), K = taps x c_in.
 //
 //   fp32 mode : fp32 operands, v_mfma_f32_32x32x2_f32; a unit = one tap x 8 channels (4 MFMA
 //               steps per block); MFMA j of a unit contracts channels {j, 4+j}: lanes 0-31 hold
