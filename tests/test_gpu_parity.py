@@ -457,6 +457,48 @@ def test_pooling_windows_other_than_3x3_and_a_global_mean_over_many_ragged_tiles
     gpu.destroy()
 
 
+@pytest.mark.parametrize("hw", [(20, 28), (40, 56)], ids=["few_workgroups_8_waves", "more_workgroups_4_waves"])
+def test_fp32_blocks_of_16_output_channels_with_ragged_channel_counts(hw):
+    """Small maps make the fp32 matrix-core conv take blocks of 16 output channels (eight waves
+    per workgroup on the smaller map, four on the larger).  Output channel counts that are not
+    multiples of 16, a residual ADD + ReLU folded into the epilogue, a stride-2 layer and a 1 x 1
+    layer; sparse steps, one dense step, a refresh."""
+    _say(f"16-channel blocks of the fp32 matrix-core conv, {hw[0]} x {hw[1]}")
+    h, w = hw
+    b = wl._NetBuilder("nb16", 12, h, w, 77)
+    c0 = b.conv(-1, 40, 3, act=wl.ACT_RELU)
+    c1 = b.conv(c0, 40, 3, act=wl.ACT_NONE)
+    r = b.simple(wl.OP_ADD, c1, c0, act=wl.ACT_RELU)
+    c2 = b.conv(r, 24, 5, stride=2, act=wl.ACT_RELU)
+    c3 = b.conv(c2, 72, 1, pad=0, act=wl.ACT_RELU)
+    b.conv(c3, 16, 3, act=wl.ACT_NONE, out=1)
+    net = b.finish()
+    rng = np.random.default_rng(77)
+    x = rng.standard_normal((12, h, w)).astype(np.float32)
+    frames = [x]
+    for t in range(7):
+        m = rng.random((1, h, w)) < (1.0 if t == 3 else 0.03)
+        x = (x + rng.standard_normal(x.shape).astype(np.float32) * m).astype(np.float32)
+        frames.append(x)
+    gpu, ora, rep = ev.EvConvNet(net), Oracle(net), cmp.Report()
+    assert all(gpu.kernel_name(i) == "conv_mfma_f32" for i in (c0, c1, c2, c3)), [gpu.kernel_name(i) for i in range(len(net.nodes))]
+    assert gpu.kernel_name(r) == "fused_into_conv_epilogue"
+    gpu.reset(_dev(frames[0]))
+    ora.reset(frames[0])
+    for t, f in enumerate(frames[1:]):
+        if t == 5:
+            gpu.reset(_dev(f))
+            ora.reset(f)
+        else:
+            gpu.step_frame(_dev(f))
+            ora.step_frame(f)
+        cmp.compare_outputs(gpu, ora, rep)
+        for i in range(len(net.nodes)):
+            cmp.compare_node(gpu, ora, i, rep)
+    assert rep.flips <= 4
+    gpu.destroy()
+
+
 def test_auto_mode_times_both_modes_and_keeps_the_state():
     """AUTO runs windows of incremental and of dense-recompute steps, then holds the faster mode;
     whatever it picks, the state follows the same frames (Eq.2), so outputs and accumulated
